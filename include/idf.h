@@ -1,0 +1,173 @@
+/*
+ * idf -- incremental depth-first CNN inference on one AMD MI355X (gfx950).
+ *
+ * C ABI of the streaming core described in Binas & Bengio, "Low-memory
+ * convolutional neural networks through incremental depth-first processing":
+ * input arrives in small segments (single samples of a 1-D signal, rows of an
+ * image); every non-zero value of a segment is an event that is added,
+ * weighted, into the stateful pre-activations c of every convolution layer it
+ * can influence (Sec. 3: stateful neuron, event definition, event-delivery
+ * rule); a row of c that no future input can change is activated, emitted to
+ * the next layer and forgotten, so each layer keeps only a rolling buffer of
+ * K_h rows (Sec. 3 last two paragraphs, Fig. 1, Fig. 2): constant state for
+ * 1-D input, state proportional to the row width for 2-D input.  The result
+ * equals the conventional layer-by-layer network (Sec. 1, Sec. 4, Sec. 5).
+ *
+ * Conventions
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device
+ *     memory of the GPU that is current when idf_open_streams is called.
+ *   - The library never allocates or frees device memory: the caller hands in
+ *     one workspace (size from idf_query_sizes) and keeps it alive until
+ *     idf_close_streams.
+ *   - All device work is enqueued on the hipStream_t given to idf_open_streams
+ *     and is asynchronous to the host; calls return after enqueueing.
+ *   - Layouts are row-major with channels last: rows [row][x][channel].
+ *     1-D signals use in_w = 1, k_w = 1; the streaming axis is always "row".
+ *   - Every function returns IDF_OK (0) or a negative IDF_E* code and never
+ *     throws or aborts; idf_last_error() gives the text for the calling thread.
+ *     On any error nothing has been enqueued.
+ *   - A handle must not be used from two threads at once.
+ */
+#ifndef IDF_H
+#define IDF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct idf_net idf_net;          /* immutable network: layers + packed weights (host side) */
+typedef struct idf_streams idf_streams;  /* B independent streams of one net on one GPU            */
+
+enum { IDF_OK = 0, IDF_EINVAL = -1, IDF_ENOMEM = -2, IDF_ESTATE = -3, IDF_EDEVICE = -4, IDF_EUNSUPPORTED = -5 };
+
+/* Arithmetic of a network.
+ *   IDF_PREC_F32   input, weights, events, state and output are float32.
+ *   IDF_PREC_BF16  input, weights and the events passed between layers are bfloat16 (16-bit
+ *                  patterns, events rounded to nearest-even when emitted); state c is float32;
+ *                  the last layer's output is float32, not rounded.
+ *   IDF_PREC_I8    input, weights and events are int8; state c and bias are int32; output int32.
+ */
+enum { IDF_PREC_F32 = 0, IDF_PREC_BF16 = 1, IDF_PREC_I8 = 2 };
+
+enum { IDF_CONV = 0, IDF_MAXPOOL = 1 };
+
+/* f of the stateful neuron h^ = f(c) (Sec. 3).  All have f(0) = 0, as the paper assumes.
+ *   IDF_ACT_RELU_SHR_CLAMP (IDF_PREC_I8 only): min(clamp_hi, max(c, 0) >> shr). */
+enum { IDF_ACT_NONE = 0, IDF_ACT_RELU = 1, IDF_ACT_RELU_SHR_CLAMP = 2 };
+
+typedef struct {
+    int kind;          /* IDF_CONV | IDF_MAXPOOL (window 2 rows x k_w columns, stride = window, no padding) */
+    int c_in, c_out;   /* pool: equal */
+    int k_h, k_w;      /* conv: any >= 1.  pool: k_h = 2 and k_w in {1, 2} */
+    int s_h, s_w;      /* conv: any >= 1.  pool: s_h = 2, s_w = k_w */
+    int p_h, p_w;      /* zero padding, same amount on both sides.  pool: 0 */
+    int act;           /* IDF_ACT_* (conv only) */
+    int shr, clamp_hi; /* parameters of IDF_ACT_RELU_SHR_CLAMP */
+} idf_layer;
+
+typedef struct {
+    int precision;     /* IDF_PREC_* */
+    int in_h;          /* rows per sample; after row in_h-1 every layer completes its remaining rows
+                          (bottom padding) and the stream starts the next sample at row 0.
+                          0 = unbounded stream: then every p_h must be 0. */
+    int in_w, in_c;    /* row width and channels of the network input */
+    int n_layers;
+    const idf_layer *layers;   /* host */
+} idf_net_desc;
+
+typedef struct {
+    size_t workspace_bytes;          /* device memory idf_open_streams needs                        */
+    size_t weights_bytes;            /* of which: packed weights and biases (shared by all streams) */
+    size_t state_bytes_per_stream;   /* of which, per stream: the retained state -- the rolling rows of
+                                        c of every conv layer and the held row of every pool.  This is
+                                        the footprint the paper bounds; it does not depend on in_h.  */
+    size_t transit_bytes_per_stream; /* per stream: rows in flight between layers during one push   */
+    size_t output_bytes_per_stream;  /* per stream: completed rows waiting for idf_read_outputs      */
+    int    out_w, out_c;             /* shape of one output row                                      */
+    int64_t out_h;                   /* output rows per sample (0 if unbounded)                      */
+} idf_sizes;
+
+/* Build a network.
+ *   weights[i] (host): for conv layer i an array [c_out][c_in][k_h][k_w] of float32 (F32),
+ *                      bfloat16 bit patterns as uint16 (BF16) or int8 (I8); ignored for pools.
+ *   biases  (host):    NULL, or per layer NULL / [c_out] float32 (F32, BF16) or int32 (I8).  A row
+ *                      of c starts at the bias; the paper's "b = 0 without loss of generality" is
+ *                      the special case NULL.
+ * Everything is copied and repacked; the caller keeps ownership of its arrays.
+ * IDF_EINVAL: inconsistent description (channel chain, kernel larger than its input, pool shape,
+ *             padding on an unbounded stream, unknown enum).  IDF_EUNSUPPORTED: a valid network
+ *             this build cannot run (shr/clamp activation outside I8). */
+int idf_create_net(const idf_net_desc *desc, const void *const *weights, const void *const *biases,
+                   idf_net **out);
+int idf_destroy_net(idf_net *net);
+
+/* Sizes for n_streams streams that are pushed at most max_seg_rows rows per call and may hold up
+ * to out_cap_rows completed output rows per stream between reads (0 = one whole sample; must be
+ * > 0 for an unbounded net). */
+int idf_query_sizes(const idf_net *net, int n_streams, int max_seg_rows, int64_t out_cap_rows,
+                    idf_sizes *out);
+
+/* Open n_streams streams, all at row 0 with zero state (Sec. 3: "initial state of the network
+ * to be zero").  dev_workspace (device, 256-byte aligned, >= workspace_bytes) stays owned by
+ * the caller.  hip_stream: a hipStream_t (NULL = the default stream).  Enqueues the upload of
+ * the packed weights. */
+int idf_open_streams(idf_net *net, int n_streams, int max_seg_rows, int64_t out_cap_rows,
+                     void *dev_workspace, size_t workspace_bytes, void *hip_stream,
+                     idf_streams **out);
+int idf_close_streams(idf_streams *s);
+
+/* Present the next n_rows rows to n_ids streams and push them depth-first through every layer
+ * they can influence (Sec. 3 first paragraph; Sec. 5 "streaming core, taking inputs as they
+ * arrive").
+ *   stream_ids (host): n_ids distinct ids in [0, n_streams), or NULL for 0 .. n_ids-1.
+ *   dev_rows (device): [n_ids][n_rows][in_w][in_c] in the input type; entry i belongs to
+ *                      stream_ids[i].  It is read by the enqueued kernels: keep it unchanged
+ *                      until the work has run (stream order).
+ *   1 <= n_rows <= max_seg_rows.
+ * Zero values are not events: they cause no arithmetic (Sec. 1).  Completed rows of the last
+ * layer are appended to the stream's output area.
+ * IDF_EINVAL: bad id, duplicate id, n_rows out of range.  IDF_ESTATE: the rows would run past row
+ * in_h-1 of the current sample, or the completed output rows would not fit the output area
+ * (read first). */
+int idf_push_segment(idf_streams *s, const int32_t *stream_ids, int n_ids, const void *dev_rows,
+                     int n_rows);
+
+/* Hand over the output rows completed since the previous read.
+ *   dev_out (device): [n_ids][max_rows][out_w][out_c] float32 (F32, BF16) or int32 (I8); for
+ *                     stream i rows 0 .. n_rows[i]-1 are written.
+ *   first_row, n_rows (host, length n_ids): index of the first row within its sample, and how
+ *                     many rows.  These follow from the number of rows pushed alone (the schedule
+ *                     does not depend on the data), so no device synchronisation happens here; the
+ *                     copy itself is enqueued on the stream.
+ * At most max_rows rows per stream are taken; the rest stay for the next read. */
+int idf_read_outputs(idf_streams *s, const int32_t *stream_ids, int n_ids, void *dev_out,
+                     int64_t max_rows, int64_t *first_row, int32_t *n_rows);
+
+/* Forget everything about these streams (state, pending output): next row is row 0. */
+int idf_reset_streams(idf_streams *s, const int32_t *stream_ids, int n_ids);
+
+/* Counters of one stream since open/reset, per layer (host arrays of n_layers; any may be NULL):
+ *   events_in      non-zero values delivered to the layer
+ *   macs_executed  multiply-adds those events caused (taps landing inside the layer's output
+ *                  x c_out); 0 for pools
+ *   state_bytes    retained state of the layer for one stream
+ * Synchronises the stream. */
+int idf_get_stats(idf_streams *s, int stream_id, uint64_t *events_in, uint64_t *macs_executed,
+                  uint64_t *state_bytes);
+
+/* Rows of the current sample a stream has been given so far (host bookkeeping, no device work). */
+int idf_rows_pushed(const idf_streams *s, int stream_id, int64_t *rows);
+
+/* Which kernel family serves layer i of an open stream set: a short static name such as
+ * "generic", for reports.  NULL on a bad index. */
+const char *idf_layer_kernel(const idf_streams *s, int layer);
+
+const char *idf_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,233 @@
+"""ctypes binding of libidf.so: same names as the C ABI, argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+IDF_OK, IDF_EINVAL, IDF_ENOMEM, IDF_ESTATE, IDF_EDEVICE, IDF_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
+PREC = {"f32": 0, "bf16": 1, "i8": 2}
+KIND = {"conv": 0, "maxpool": 1}
+ACT = {"none": 0, "relu": 1, "relu_shr_clamp": 2}
+
+EXPORTS = ["idf_create_net", "idf_destroy_net", "idf_query_sizes", "idf_open_streams", "idf_close_streams",
+           "idf_push_segment", "idf_read_outputs", "idf_reset_streams", "idf_get_stats", "idf_rows_pushed",
+           "idf_layer_kernel", "idf_last_error"]
+
+
+class IdfError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__(f"idf error {code}: {text}")
+        self.code = code
+
+
+class _Layer(C.Structure):
+    _fields_ = [(n, C.c_int) for n in
+                ("kind", "c_in", "c_out", "k_h", "k_w", "s_h", "s_w", "p_h", "p_w", "act", "shr", "clamp_hi")]
+
+
+class _NetDesc(C.Structure):
+    _fields_ = [("precision", C.c_int), ("in_h", C.c_int), ("in_w", C.c_int), ("in_c", C.c_int),
+                ("n_layers", C.c_int), ("layers", C.POINTER(_Layer))]
+
+
+class Sizes(C.Structure):
+    _fields_ = [("workspace_bytes", C.c_size_t), ("weights_bytes", C.c_size_t),
+                ("state_bytes_per_stream", C.c_size_t), ("transit_bytes_per_stream", C.c_size_t),
+                ("output_bytes_per_stream", C.c_size_t), ("out_w", C.c_int), ("out_c", C.c_int),
+                ("out_h", C.c_int64)]
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libidf.so")
+
+
+def load_library():
+    """Load libidf.so, building it first only if it is not there.  No fallback: without the
+    HIP library nothing in this package works."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    if not os.path.exists(lib_path()):
+        from . import build as _build
+        _build.build()
+    L = C.CDLL(lib_path())
+    L.idf_last_error.restype = C.c_char_p
+    L.idf_layer_kernel.restype = C.c_char_p
+    L.idf_layer_kernel.argtypes = [C.c_void_p, C.c_int]
+    L.idf_create_net.argtypes = [C.POINTER(_NetDesc), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
+                                 C.POINTER(C.c_void_p)]
+    L.idf_destroy_net.argtypes = [C.c_void_p]
+    L.idf_query_sizes.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int64, C.POINTER(Sizes)]
+    L.idf_open_streams.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int64, C.c_void_p, C.c_size_t,
+                                   C.c_void_p, C.POINTER(C.c_void_p)]
+    L.idf_close_streams.argtypes = [C.c_void_p]
+    L.idf_push_segment.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int]
+    L.idf_read_outputs.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int64,
+                                   C.c_void_p, C.c_void_p]
+    L.idf_reset_streams.argtypes = [C.c_void_p, C.c_void_p, C.c_int]
+    L.idf_get_stats.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.idf_rows_pushed.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_int64)]
+    _LIB = L
+    return L
+
+
+def _check(rc):
+    if rc != IDF_OK:
+        raise IdfError(rc, load_library().idf_last_error().decode())
+
+
+def _ids(stream_ids):
+    if stream_ids is None:
+        return None, None
+    a = np.ascontiguousarray(stream_ids, dtype=np.int32)
+    return a, a.ctypes.data
+
+
+class Net:
+    """idf_create_net / idf_destroy_net."""
+
+    def __init__(self, precision, in_h, in_w, in_c, layers, weights, biases=None):
+        L = load_library()
+        self.precision = precision
+        self.layers = layers
+        n = len(layers)
+        arr = (_Layer * n)()
+        for i, d in enumerate(layers):
+            arr[i] = _Layer(KIND[d["kind"]], d["c_in"], d["c_out"], d["k_h"], d["k_w"], d["s_h"], d["s_w"],
+                            d["p_h"], d["p_w"], ACT[d.get("act", "none")], d.get("shr", 0), d.get("clamp_hi", 0))
+        desc = _NetDesc(PREC[precision], in_h, in_w, in_c, n, arr)
+        wdt = {"f32": np.float32, "bf16": np.uint16, "i8": np.int8}[precision]
+        bdt = np.int32 if precision == "i8" else np.float32
+        keep = []
+
+        def table(arrays, dt):
+            t = (C.c_void_p * n)()
+            for i, a in enumerate(arrays):
+                if a is None:
+                    t[i] = None
+                else:
+                    a = np.ascontiguousarray(a, dtype=dt)
+                    keep.append(a)
+                    t[i] = a.ctypes.data
+            return t
+        wt = table(weights, wdt)
+        bt = table(biases, bdt) if biases is not None else None
+        h = C.c_void_p()
+        _check(L.idf_create_net(C.byref(desc), wt, bt, C.byref(h)))
+        self._h = h
+
+    def query_sizes(self, n_streams, max_seg_rows=1, out_cap_rows=0) -> Sizes:
+        s = Sizes()
+        _check(load_library().idf_query_sizes(self._h, n_streams, max_seg_rows, out_cap_rows, C.byref(s)))
+        return s
+
+    def destroy(self):
+        if self._h:
+            _check(load_library().idf_destroy_net(self._h))
+            self._h = None
+
+
+class Streams:
+    """idf_open_streams ... idf_close_streams.  Tensors are torch CUDA tensors; only their
+    data pointers cross the boundary."""
+
+    def __init__(self, net: Net, n_streams, max_seg_rows=1, out_cap_rows=0, device="cuda:0", stream=None):
+        import torch
+        self.net = net
+        self.n_streams = n_streams
+        self.sizes = net.query_sizes(n_streams, max_seg_rows, out_cap_rows)
+        self.device = torch.device(device)
+        with torch.cuda.device(self.device):
+            self.workspace = torch.empty(self.sizes.workspace_bytes + 256, dtype=torch.uint8, device=self.device)
+            base = self.workspace.data_ptr()
+            self._ws_ptr = (base + 255) // 256 * 256
+            self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+            h = C.c_void_p()
+            _check(load_library().idf_open_streams(net._h, n_streams, max_seg_rows, out_cap_rows,
+                                                   C.c_void_p(self._ws_ptr), self.sizes.workspace_bytes,
+                                                   C.c_void_p(self.stream.cuda_stream), C.byref(h)))
+        self._h = h
+        self.out_dtype = torch.int32 if net.precision == "i8" else torch.float32
+
+    def push_segment(self, rows, stream_ids=None, n_rows=None):
+        """rows: device tensor [n_ids][n_rows][in_w][in_c] (float32 / bfloat16 / int8)."""
+        keep, ptr = _ids(stream_ids)
+        n_ids = rows.shape[0] if stream_ids is None else len(keep)
+        n_rows = rows.shape[1] if n_rows is None else n_rows
+        assert rows.is_contiguous() and rows.is_cuda
+        _check(load_library().idf_push_segment(self._h, ptr, n_ids, C.c_void_p(rows.data_ptr()), n_rows))
+
+    def read_outputs(self, max_rows, stream_ids=None, n_ids=None, out=None):
+        import torch
+        keep, ptr = _ids(stream_ids)
+        n_ids = (self.n_streams if n_ids is None else n_ids) if stream_ids is None else len(keep)
+        if out is None:
+            out = torch.empty((n_ids, max_rows, self.sizes.out_w, self.sizes.out_c), dtype=self.out_dtype,
+                              device=self.device)
+        first = np.zeros(n_ids, dtype=np.int64)
+        cnt = np.zeros(n_ids, dtype=np.int32)
+        _check(load_library().idf_read_outputs(self._h, ptr, n_ids, C.c_void_p(out.data_ptr()), max_rows,
+                                               first.ctypes.data, cnt.ctypes.data))
+        return out, first, cnt
+
+    def reset(self, stream_ids=None, n_ids=None):
+        keep, ptr = _ids(stream_ids)
+        n_ids = (self.n_streams if n_ids is None else n_ids) if stream_ids is None else len(keep)
+        _check(load_library().idf_reset_streams(self._h, ptr, n_ids))
+
+    def get_stats(self, stream_id):
+        n = len(self.net.layers)
+        ev = np.zeros(n, dtype=np.uint64); macs = np.zeros(n, dtype=np.uint64); sb = np.zeros(n, dtype=np.uint64)
+        _check(load_library().idf_get_stats(self._h, stream_id, ev.ctypes.data, macs.ctypes.data, sb.ctypes.data))
+        return dict(events_in=ev, macs=macs, state_bytes=sb)
+
+    def rows_pushed(self, stream_id):
+        r = C.c_int64()
+        _check(load_library().idf_rows_pushed(self._h, stream_id, C.byref(r)))
+        return r.value
+
+    def layer_kernels(self):
+        L = load_library()
+        return [L.idf_layer_kernel(self._h, i).decode() for i in range(len(self.net.layers))]
+
+    def close(self):
+        if self._h:
+            _check(load_library().idf_close_streams(self._h))
+            self._h = None
+
+
+def create_net(precision, in_h, in_w, in_c, layers, weights, biases=None) -> Net:
+    return Net(precision, in_h, in_w, in_c, layers, weights, biases)
+
+
+def open_streams(net, n_streams, **kw) -> Streams:
+    return Streams(net, n_streams, **kw)
+
+
+def _bf16_bits(a):
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    return (u >> 16).astype(np.uint16)
+
+
+def net_from_workload(wl) -> Net:
+    """Net from a workload dict (see the workloads module): only dtype marshalling."""
+    prec = wl["precision"]
+    if prec == "bf16":
+        ws = [None if w is None else _bf16_bits(w) for w in wl["weights"]]
+    else:
+        ws = wl["weights"]
+    return Net(prec, wl["in_h"], wl["in_w"], wl["in_c"], wl["layers"], ws, wl["biases"])
+
+
+def input_tensor(wl, device="cuda:0"):
+    """The workload's input as a device tensor of the net's input type: [streams][H][W][C]."""
+    import torch
+    x = wl["x"]
+    if wl["precision"] == "bf16":
+        return torch.from_numpy(np.ascontiguousarray(x)).to(device).to(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(x)).to(device)

@@ -1,0 +1,131 @@
+// Shared between the host side of the library and its kernels: layer geometry, the
+// data-independent row schedule, and the argument blocks handed to the kernels.
+#pragma once
+
+#include <stddef.h>
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#include <hip/hip_runtime.h>
+#define IDF_HD __host__ __device__ inline
+#else
+#define IDF_HD inline
+#endif
+
+namespace idf {
+
+constexpr int kMaxLayers = 32;
+constexpr int kSelIds = 256;   // stream ids carried by value in one launch
+
+struct Geom {
+    int kind;            // IDF_CONV / IDF_MAXPOOL
+    int c_in, c_out, k_h, k_w, s_h, s_w, p_h, p_w;
+    int act, shr, clamp_hi;
+    int h_in, w_in;      // h_in = 0: unbounded
+    int h_out, w_out;    // h_out = 0: unbounded
+};
+
+IDF_HD int out_size(int n, int k, int s, int p)
+{
+    int t = n + 2 * p - k;
+    return t < 0 ? 0 : t / s + 1;
+}
+
+// Number of output rows of a layer that are final once it has received rows 0..y-1 of its
+// input.  Output row o needs input rows o*s-p .. o*s-p+k-1 (clipped to the sample), so it is
+// final when y >= o*s-p+k, and every row is final once the whole sample (h_in rows) is in:
+// the bottom padding contributes nothing.
+IDF_HD int64_t rows_final(const Geom &g, int64_t y)
+{
+    if (g.h_in > 0 && y >= g.h_in) return g.h_out;
+    int64_t t = y + g.p_h - g.k_h;
+    int64_t n = t < 0 ? 0 : t / g.s_h + 1;
+    if (g.h_out > 0 && n > g.h_out) n = g.h_out;
+    return n;
+}
+
+// One past the last output row that input rows 0..y-1 have contributed to (first input row
+// of output row o is o*s-p).
+IDF_HD int64_t rows_touched(const Geom &g, int64_t y)
+{
+    if (y <= 0) return 0;
+    int64_t n = (y - 1 + g.p_h) / g.s_h + 1;
+    if (g.h_out > 0 && n > g.h_out) n = g.h_out;
+    return n;
+}
+
+// Stream selection of one launch: either the contiguous ids base .. base+n-1 or n ids by value.
+struct StreamSel {
+    int n;
+    int base;            // >= 0: contiguous; -1: use ids[]
+    int pos0;            // position of the first selected stream in the caller's id list
+    int ids[kSelIds];
+};
+
+__host__ __device__ inline int sel_stream(const StreamSel &s, int i) { return s.base >= 0 ? s.base + i : s.ids[i]; }
+
+// One step of one conv layer for a group of streams that are all at the same row:
+// input rows [y0, y0+cnt) arrive; output rows [o_lo, o_hi) are touched; of those
+// [o_lo, o_fin) become final and are emitted, the rest go back to the ring.
+struct ConvStep {
+    Geom g;
+    int layer;
+    int64_t y0;
+    int cnt;
+    int64_t o_lo, o_fin, o_hi;
+    int ring_rows;               // slots of the ring (k_h)
+    // input rows: [stream or position][row - in_row0][w_in][c_in]
+    const void *in;
+    int64_t in_stream_stride;    // elements
+    int64_t in_row0;             // input row held in slot 0
+    int in_by_position;          // 1: index by position in the caller's list (network input)
+    // state ring [stream][slot][w_out][c_out], slot = o mod ring_rows
+    void *ring;
+    int64_t ring_stream_stride;
+    // destination of emitted rows: next layer's transit rows (slot = o - dst_row0) or, for the
+    // last layer, the output area (slot = (dst_slot0 + o - dst_row0) mod out_cap)
+    void *dst;
+    int64_t dst_stream_stride;
+    int64_t dst_row0, dst_slot0;
+    int to_output;
+    int64_t out_cap;
+    const void *w;               // [k_h][k_w][c_in][c_out]
+    const void *bias;            // [c_out] or null
+    unsigned long long *stats;   // [stream][layer][2]: events_in, macs
+    int n_layers;
+    int tile_x, tile_c, cells_per_thread;
+};
+
+struct PoolStep {
+    Geom g;
+    int layer;
+    int64_t y0;
+    int cnt;
+    int64_t o_lo, o_fin;         // output rows emitted: [o_lo, o_fin)
+    int hold_new;                // 1: the last new row is the even row of a pair: hold it
+    const void *in;
+    int64_t in_stream_stride;
+    int64_t in_row0;
+    int in_by_position;
+    void *held;                  // [stream][w_in][c]
+    int64_t held_stream_stride;
+    void *dst;
+    int64_t dst_stream_stride;
+    int64_t dst_row0, dst_slot0;
+    int to_output;
+    int64_t out_cap;
+    unsigned long long *stats;
+    int n_layers;
+};
+
+struct CopyOut {
+    const void *src;             // output area [stream][out_cap][row_elems]
+    int64_t src_stream_stride;
+    int64_t out_cap;
+    void *dst;                   // [position][max_rows][row_elems]
+    int64_t dst_stream_stride;
+    int64_t row_elems;
+    int elem_bytes;
+};
+
+}  // namespace idf

@@ -1,0 +1,558 @@
+// Host side of the library: network description, workspace layout, the data-independent
+// row schedule of a push (which layer receives which rows, which rows become final), and the
+// kernel launches.  All arithmetic of the method runs in the kernels.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "idf.h"
+#include "idf_common.h"
+#include "idf_kernels.h"
+
+using namespace idf;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof(buf), fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+int ev_bytes(int prec) { return prec == IDF_PREC_F32 ? 4 : prec == IDF_PREC_BF16 ? 2 : 1; }
+int w_bytes(int prec) { return ev_bytes(prec); }
+
+}  // namespace
+
+struct idf_net {
+    int precision = 0;
+    int in_h = 0, in_w = 0, in_c = 0;
+    std::vector<Geom> g;
+    // device images: per conv layer weights [k_h][k_w][c_in][c_out] and bias [c_out] (4-byte)
+    std::vector<std::vector<unsigned char>> w_img, b_img;
+    int out_w = 0, out_c = 0;
+    int64_t out_h = 0;
+    int open_count = 0;
+};
+
+struct StreamHost {
+    int64_t r = 0;            // rows of the current sample received
+    int64_t out_written = 0;  // output rows completed since open/reset
+    int64_t out_read = 0;     // output rows handed over
+};
+
+struct idf_streams {
+    idf_net *net = nullptr;
+    int B = 0, max_seg = 0;
+    int64_t out_cap = 0;
+    hipStream_t st = nullptr;
+    char *ws = nullptr;
+    size_t ws_bytes = 0;
+    std::vector<size_t> w_off, b_off, ring_off, held_off, transit_off;
+    std::vector<int64_t> ring_stride, held_stride, transit_stride;   // elements per stream
+    std::vector<int> transit_cap;                                    // rows per stream
+    size_t out_off = 0, stats_off = 0;
+    int64_t out_stride = 0;
+    std::vector<StreamHost> h;
+    std::vector<int> stamp;
+    int stamp_gen = 0;
+    idf_sizes sizes{};
+};
+
+namespace {
+
+// Rows the last layer completes when a stream at row r receives n more rows.
+int64_t output_rows_of_push(const idf_net &net, int64_t r, int n)
+{
+    int64_t y0 = r, cnt = n;
+    for (const Geom &g : net.g) {
+        int64_t a = rows_final(g, y0), b = rows_final(g, y0 + cnt);
+        y0 = a;
+        cnt = b - a;
+        if (cnt == 0) return 0;
+    }
+    return cnt;
+}
+
+// Most rows a layer can emit in one step when it receives at most cap_in rows.
+int max_emit(const Geom &g, int cap_in)
+{
+    int64_t best = 0;
+    auto probe = [&](int64_t y0) {
+        if (y0 < 0) return;
+        int64_t cnt = cap_in;
+        if (g.h_in > 0) {
+            if (y0 >= g.h_in) return;
+            cnt = std::min<int64_t>(cnt, g.h_in - y0);
+        }
+        best = std::max(best, rows_final(g, y0 + cnt) - rows_final(g, y0));
+    };
+    int64_t span = (int64_t)4 * g.k_h * g.s_h + cap_in + 4;
+    for (int64_t y0 = 0; y0 <= span; ++y0) probe(y0);
+    if (g.h_in > 0)
+        for (int64_t y0 = g.h_in - span; y0 < g.h_in; ++y0) probe(y0);
+    return (int)best;
+}
+
+struct Layout {
+    std::vector<size_t> w_off, b_off, ring_off, held_off, transit_off;
+    std::vector<int64_t> ring_stride, held_stride, transit_stride;
+    std::vector<int> transit_cap;
+    size_t out_off = 0, stats_off = 0, total = 0;
+    int64_t out_stride = 0;
+    idf_sizes sizes{};
+};
+
+int make_layout(const idf_net &net, int B, int max_seg, int64_t out_cap, Layout &L)
+{
+    const int n = (int)net.g.size();
+    const int eb = ev_bytes(net.precision);
+    size_t off = 0;
+    L.w_off.assign(n, 0); L.b_off.assign(n, 0);
+    L.ring_off.assign(n, 0); L.held_off.assign(n, 0); L.transit_off.assign(n, 0);
+    L.ring_stride.assign(n, 0); L.held_stride.assign(n, 0); L.transit_stride.assign(n, 0);
+    L.transit_cap.assign(n, 0);
+    for (int l = 0; l < n; ++l) {
+        if (net.g[l].kind != IDF_CONV) continue;
+        L.w_off[l] = off; off = align_up(off + net.w_img[l].size());
+        L.b_off[l] = off; off = align_up(off + net.b_img[l].size());
+    }
+    L.sizes.weights_bytes = off;
+    size_t state_per_stream = 0, transit_per_stream = 0;
+    int cap = max_seg;
+    for (int l = 0; l < n; ++l) {
+        const Geom &g = net.g[l];
+        if (g.kind == IDF_CONV) {
+            L.ring_stride[l] = (int64_t)g.k_h * g.w_out * g.c_out;
+            L.ring_off[l] = off; off = align_up(off + (size_t)L.ring_stride[l] * 4 * B);
+            state_per_stream += (size_t)L.ring_stride[l] * 4;
+        } else {
+            L.held_stride[l] = (int64_t)g.w_in * g.c_out;
+            L.held_off[l] = off; off = align_up(off + (size_t)L.held_stride[l] * eb * B);
+            state_per_stream += (size_t)L.held_stride[l] * eb;
+        }
+        cap = max_emit(g, cap);
+        if (cap < 1) cap = 1;
+        L.transit_cap[l] = cap;
+        if (l < n - 1) {
+            L.transit_stride[l] = (int64_t)cap * g.w_out * g.c_out;
+            L.transit_off[l] = off; off = align_up(off + (size_t)L.transit_stride[l] * eb * B);
+            transit_per_stream += (size_t)L.transit_stride[l] * eb;
+        }
+    }
+    if (out_cap <= 0) {
+        if (net.out_h <= 0) return fail(IDF_EINVAL, "an unbounded net needs out_cap_rows > 0");
+        out_cap = net.out_h;
+    }
+    if (out_cap < L.transit_cap[n - 1])
+        return fail(IDF_EINVAL, "out_cap_rows %lld is smaller than the %d rows one push can complete",
+                    (long long)out_cap, L.transit_cap[n - 1]);
+    L.out_stride = out_cap * net.out_w * net.out_c;
+    L.out_off = off; off = align_up(off + (size_t)L.out_stride * 4 * B);
+    L.stats_off = off; off = align_up(off + (size_t)B * n * 2 * sizeof(unsigned long long));
+    L.total = off;
+    L.sizes.workspace_bytes = off;
+    L.sizes.state_bytes_per_stream = state_per_stream;
+    L.sizes.transit_bytes_per_stream = transit_per_stream;
+    L.sizes.output_bytes_per_stream = (size_t)L.out_stride * 4;
+    L.sizes.out_w = net.out_w; L.sizes.out_c = net.out_c; L.sizes.out_h = net.out_h;
+    return IDF_OK;
+}
+
+int check_ids(idf_streams *s, const int32_t *ids, int n_ids)
+{
+    if (n_ids < 1 || n_ids > s->B) return fail(IDF_EINVAL, "n_ids %d outside [1, %d]", n_ids, s->B);
+    if (!ids) return IDF_OK;
+    if (++s->stamp_gen == 0x7fffffff) { std::fill(s->stamp.begin(), s->stamp.end(), 0); s->stamp_gen = 1; }
+    for (int i = 0; i < n_ids; ++i) {
+        if (ids[i] < 0 || ids[i] >= s->B) return fail(IDF_EINVAL, "stream id %d outside [0, %d)", ids[i], s->B);
+        if (s->stamp[ids[i]] == s->stamp_gen) return fail(IDF_EINVAL, "stream id %d given twice", ids[i]);
+        s->stamp[ids[i]] = s->stamp_gen;
+    }
+    return IDF_OK;
+}
+
+// Splits a list of (position, id) pairs into launch selections: maximal runs that are
+// contiguous in both position and id go by base, the rest by value in blocks of kSelIds.
+template <class F> int for_each_selection(const std::vector<std::pair<int, int>> &members, F &&f)
+{
+    size_t i = 0;
+    while (i < members.size()) {
+        size_t j = i + 1;
+        while (j < members.size() && members[j].first == members[j - 1].first + 1 &&
+               members[j].second == members[j - 1].second + 1 && j - i < 65535)
+            ++j;
+        StreamSel sel{};
+        if (j - i >= 2 || members.size() - i == 1) {
+            sel.n = (int)(j - i); sel.base = members[i].second; sel.pos0 = members[i].first;
+            int rc = f(sel);
+            if (rc != IDF_OK) return rc;
+            i = j;
+            continue;
+        }
+        // by value: positions must still be consecutive within one selection
+        j = i + 1;
+        while (j < members.size() && members[j].first == members[j - 1].first + 1 && j - i < (size_t)kSelIds) ++j;
+        sel.n = (int)(j - i); sel.base = -1; sel.pos0 = members[i].first;
+        for (size_t k = i; k < j; ++k) sel.ids[k - i] = members[k].second;
+        int rc = f(sel);
+        if (rc != IDF_OK) return rc;
+        i = j;
+    }
+    return IDF_OK;
+}
+
+int dev_fail(hipError_t e, const char *what)
+{
+    return fail(IDF_EDEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+// Enqueue everything one group of streams (all at row r, n new rows) needs.
+int enqueue_cascade(idf_streams *s, const StreamSel &sel, const void *dev_rows, int n_rows, int64_t r,
+                    int64_t out_slot0)
+{
+    const idf_net &net = *s->net;
+    const int n = (int)net.g.size();
+    const int eb = ev_bytes(net.precision);
+    unsigned long long *stats = (unsigned long long *)(s->ws + s->stats_off);
+    const void *in = dev_rows;
+    int64_t in_stride = (int64_t)n_rows * net.in_w * net.in_c;
+    int64_t in_row0 = r;
+    int by_pos = 1;
+    int64_t y0 = r;
+    int64_t cnt = n_rows;
+    for (int l = 0; l < n && cnt > 0; ++l) {
+        const Geom &g = net.g[l];
+        const bool last = l == n - 1;
+        const int64_t o_lo = rows_final(g, y0), o_fin = rows_final(g, y0 + cnt);
+        void *dst = last ? (void *)(s->ws + s->out_off) : (void *)(s->ws + s->transit_off[l]);
+        const int64_t dst_stride = last ? s->out_stride : s->transit_stride[l];
+        if (!last && o_fin - o_lo > s->transit_cap[l])
+            return fail(IDF_ESTATE, "internal: layer %d would emit %lld rows, room for %d", l,
+                        (long long)(o_fin - o_lo), s->transit_cap[l]);
+        if (g.kind == IDF_CONV) {
+            const int max_rows = conv_generic_max_rows(g.c_out);
+            int64_t yy = y0;
+            while (yy < y0 + cnt) {
+                int64_t c = y0 + cnt - yy;
+                auto touched = [&](int64_t cc) {
+                    return std::max(rows_touched(g, yy + cc), rows_final(g, yy + cc)) - rows_final(g, yy);
+                };
+                while (c > 1 && touched(c) > max_rows) c = (c + 1) / 2;
+                ConvStep a{};
+                a.g = g; a.layer = l; a.y0 = yy; a.cnt = (int)c;
+                a.o_lo = rows_final(g, yy); a.o_fin = rows_final(g, yy + c);
+                a.o_hi = std::max(rows_touched(g, yy + c), a.o_fin);
+                a.ring_rows = g.k_h;
+                a.in = in; a.in_stream_stride = in_stride; a.in_row0 = in_row0; a.in_by_position = by_pos;
+                a.ring = s->ws + s->ring_off[l]; a.ring_stream_stride = s->ring_stride[l];
+                a.dst = dst; a.dst_stream_stride = dst_stride; a.dst_row0 = o_lo; a.dst_slot0 = out_slot0;
+                a.to_output = last; a.out_cap = s->out_cap;
+                a.w = s->ws + s->w_off[l];
+                a.bias = net.b_img[l].empty() ? nullptr : s->ws + s->b_off[l];
+                a.stats = stats; a.n_layers = n;
+                conv_generic_plan(a);
+                hipError_t e = launch_conv_generic(net.precision, a, sel, s->st);
+                if (e != hipSuccess) return dev_fail(e, "conv launch");
+                yy += c;
+            }
+        } else {
+            PoolStep a{};
+            a.g = g; a.layer = l; a.y0 = y0; a.cnt = (int)cnt; a.o_lo = o_lo; a.o_fin = o_fin;
+            const int64_t y_last = y0 + cnt - 1;
+            a.hold_new = (y_last % 2 == 0) && (g.h_out == 0 || y_last / 2 < g.h_out);
+            a.in = in; a.in_stream_stride = in_stride; a.in_row0 = in_row0; a.in_by_position = by_pos;
+            a.held = s->ws + s->held_off[l]; a.held_stream_stride = s->held_stride[l];
+            a.dst = dst; a.dst_stream_stride = dst_stride; a.dst_row0 = o_lo; a.dst_slot0 = out_slot0;
+            a.to_output = last; a.out_cap = s->out_cap;
+            a.stats = stats; a.n_layers = n;
+            hipError_t e = launch_pool_generic(net.precision, a, sel, s->st);
+            if (e != hipSuccess) return dev_fail(e, "pool launch");
+        }
+        in = dst; in_stride = dst_stride; in_row0 = o_lo; by_pos = 0;
+        y0 = o_lo; cnt = o_fin - o_lo;
+        (void)eb;
+    }
+    return IDF_OK;
+}
+
+}  // namespace
+
+// -----------------------------------------------------------------------------------------
+extern "C" {
+
+const char *idf_last_error(void) { return g_err.c_str(); }
+
+int idf_create_net(const idf_net_desc *d, const void *const *weights, const void *const *biases,
+                   idf_net **out)
+{
+    if (!d || !out || !d->layers) return fail(IDF_EINVAL, "null argument");
+    *out = nullptr;
+    if (d->precision < IDF_PREC_F32 || d->precision > IDF_PREC_I8) return fail(IDF_EINVAL, "unknown precision %d", d->precision);
+    if (d->n_layers < 1 || d->n_layers > kMaxLayers) return fail(IDF_EINVAL, "n_layers %d outside [1, %d]", d->n_layers, kMaxLayers);
+    if (d->in_h < 0 || d->in_w < 1 || d->in_c < 1) return fail(IDF_EINVAL, "bad input shape %d x %d x %d", d->in_h, d->in_w, d->in_c);
+    idf_net *net = new (std::nothrow) idf_net;
+    if (!net) return fail(IDF_ENOMEM, "out of host memory");
+    net->precision = d->precision; net->in_h = d->in_h; net->in_w = d->in_w; net->in_c = d->in_c;
+    int h = d->in_h, w = d->in_w, c = d->in_c;
+    int rc = IDF_OK;
+    for (int l = 0; l < d->n_layers && rc == IDF_OK; ++l) {
+        const idf_layer &L = d->layers[l];
+        Geom g{};
+        g.kind = L.kind; g.c_in = L.c_in; g.c_out = L.c_out; g.k_h = L.k_h; g.k_w = L.k_w;
+        g.s_h = L.s_h; g.s_w = L.s_w; g.p_h = L.p_h; g.p_w = L.p_w; g.act = L.act; g.shr = L.shr; g.clamp_hi = L.clamp_hi;
+        g.h_in = h; g.w_in = w;
+        if (L.kind != IDF_CONV && L.kind != IDF_MAXPOOL) rc = fail(IDF_EINVAL, "layer %d: unknown kind %d", l, L.kind);
+        else if (L.c_in != c || L.c_out < 1) rc = fail(IDF_EINVAL, "layer %d: c_in %d does not follow %d channels", l, L.c_in, c);
+        else if (L.k_h < 1 || L.k_w < 1 || L.s_h < 1 || L.s_w < 1 || L.p_h < 0 || L.p_w < 0) rc = fail(IDF_EINVAL, "layer %d: bad kernel/stride/padding", l);
+        else if (d->in_h == 0 && L.p_h != 0) rc = fail(IDF_EINVAL, "layer %d: row padding on an unbounded stream", l);
+        else if (L.kind == IDF_MAXPOOL && !(L.c_out == L.c_in && L.k_h == 2 && L.s_h == 2 && L.p_h == 0 && L.p_w == 0 &&
+                                            ((L.k_w == 2 && L.s_w == 2) || (L.k_w == 1 && L.s_w == 1))))
+            rc = fail(IDF_EINVAL, "layer %d: pool must be 2 x {1,2}, stride = window, no padding", l);
+        else if (L.kind == IDF_CONV && (L.act < IDF_ACT_NONE || L.act > IDF_ACT_RELU_SHR_CLAMP)) rc = fail(IDF_EINVAL, "layer %d: unknown activation", l);
+        else if (L.kind == IDF_CONV && (!weights || !weights[l])) rc = fail(IDF_EINVAL, "layer %d: no weights", l);
+        if (rc != IDF_OK) break;
+        g.h_out = d->in_h ? out_size(h, L.k_h, L.s_h, L.p_h) : 0;
+        g.w_out = out_size(w, L.k_w, L.s_w, L.p_w);
+        if ((d->in_h && g.h_out < 1) || g.w_out < 1) { rc = fail(IDF_EINVAL, "layer %d: window larger than its input", l); break; }
+        const bool last = l == d->n_layers - 1;
+        if (L.kind == IDF_CONV) {
+            if (L.act == IDF_ACT_RELU_SHR_CLAMP && d->precision != IDF_PREC_I8) { rc = fail(IDF_EUNSUPPORTED, "layer %d: shift/clamp activation needs int8 precision", l); break; }
+            if (L.act == IDF_ACT_RELU_SHR_CLAMP && (L.shr < 0 || L.shr > 30 || L.clamp_hi < 0 || L.clamp_hi > 127)) { rc = fail(IDF_EINVAL, "layer %d: shr/clamp_hi out of range", l); break; }
+            if (d->precision == IDF_PREC_I8 && !last && L.act != IDF_ACT_RELU_SHR_CLAMP) { rc = fail(IDF_EUNSUPPORTED, "layer %d: int8 events between layers need the shift/clamp activation", l); break; }
+            if (L.k_h > conv_generic_max_rows(L.c_out)) { rc = fail(IDF_EUNSUPPORTED, "layer %d: kernel height %d too large", l, L.k_h); break; }
+        } else if (last && d->precision != IDF_PREC_F32) { rc = fail(IDF_EUNSUPPORTED, "a pool as the last layer needs float32 precision"); break; }
+        net->g.push_back(g);
+        net->w_img.emplace_back(); net->b_img.emplace_back();
+        if (L.kind == IDF_CONV) {
+            const int wb = w_bytes(d->precision);
+            std::vector<unsigned char> &img = net->w_img.back();
+            img.resize((size_t)L.k_h * L.k_w * L.c_in * L.c_out * wb);
+            const unsigned char *src = (const unsigned char *)weights[l];
+            for (int co = 0; co < L.c_out; ++co)
+            for (int ci = 0; ci < L.c_in; ++ci)
+            for (int ky = 0; ky < L.k_h; ++ky)
+            for (int kx = 0; kx < L.k_w; ++kx) {
+                size_t s_idx = (((size_t)co * L.c_in + ci) * L.k_h + ky) * L.k_w + kx;
+                size_t d_idx = (((size_t)ky * L.k_w + kx) * L.c_in + ci) * L.c_out + co;
+                memcpy(&img[d_idx * wb], src + s_idx * wb, wb);
+            }
+            if (biases && biases[l]) {
+                net->b_img.back().resize((size_t)L.c_out * 4);
+                memcpy(net->b_img.back().data(), biases[l], (size_t)L.c_out * 4);
+            }
+        }
+        h = g.h_out; w = g.w_out; c = L.c_out;
+    }
+    if (rc != IDF_OK) { delete net; return rc; }
+    net->out_h = h; net->out_w = w; net->out_c = c;
+    *out = net;
+    return IDF_OK;
+}
+
+int idf_destroy_net(idf_net *net)
+{
+    if (!net) return IDF_OK;
+    if (net->open_count > 0) return fail(IDF_ESTATE, "net still has %d open stream sets", net->open_count);
+    delete net;
+    return IDF_OK;
+}
+
+int idf_query_sizes(const idf_net *net, int n_streams, int max_seg_rows, int64_t out_cap_rows, idf_sizes *out)
+{
+    if (!net || !out) return fail(IDF_EINVAL, "null argument");
+    if (n_streams < 1 || max_seg_rows < 1) return fail(IDF_EINVAL, "n_streams and max_seg_rows must be >= 1");
+    Layout L;
+    int rc = make_layout(*net, n_streams, max_seg_rows, out_cap_rows, L);
+    if (rc != IDF_OK) return rc;
+    *out = L.sizes;
+    return IDF_OK;
+}
+
+int idf_open_streams(idf_net *net, int n_streams, int max_seg_rows, int64_t out_cap_rows, void *dev_workspace,
+                     size_t workspace_bytes, void *hip_stream, idf_streams **out)
+{
+    if (!net || !out || !dev_workspace) return fail(IDF_EINVAL, "null argument");
+    *out = nullptr;
+    if (n_streams < 1 || max_seg_rows < 1) return fail(IDF_EINVAL, "n_streams and max_seg_rows must be >= 1");
+    if (((uintptr_t)dev_workspace & 255) != 0) return fail(IDF_EINVAL, "workspace must be 256-byte aligned");
+    Layout L;
+    int rc = make_layout(*net, n_streams, max_seg_rows, out_cap_rows, L);
+    if (rc != IDF_OK) return rc;
+    if (workspace_bytes < L.total) return fail(IDF_EINVAL, "workspace of %zu bytes, %zu needed", workspace_bytes, L.total);
+    idf_streams *s = new (std::nothrow) idf_streams;
+    if (!s) return fail(IDF_ENOMEM, "out of host memory");
+    s->net = net; s->B = n_streams; s->max_seg = max_seg_rows;
+    s->out_cap = out_cap_rows > 0 ? out_cap_rows : net->out_h;
+    s->st = (hipStream_t)hip_stream; s->ws = (char *)dev_workspace; s->ws_bytes = workspace_bytes;
+    s->w_off = L.w_off; s->b_off = L.b_off; s->ring_off = L.ring_off; s->held_off = L.held_off;
+    s->transit_off = L.transit_off; s->ring_stride = L.ring_stride; s->held_stride = L.held_stride;
+    s->transit_stride = L.transit_stride; s->transit_cap = L.transit_cap;
+    s->out_off = L.out_off; s->stats_off = L.stats_off; s->out_stride = L.out_stride; s->sizes = L.sizes;
+    s->h.assign(n_streams, StreamHost{});
+    s->stamp.assign(n_streams, 0);
+    hipError_t e = hipSuccess;
+    for (size_t l = 0; l < net->g.size() && e == hipSuccess; ++l) {
+        if (net->g[l].kind != IDF_CONV) continue;
+        e = hipMemcpyAsync(s->ws + s->w_off[l], net->w_img[l].data(), net->w_img[l].size(), hipMemcpyHostToDevice, s->st);
+        if (e == hipSuccess && !net->b_img[l].empty())
+            e = hipMemcpyAsync(s->ws + s->b_off[l], net->b_img[l].data(), net->b_img[l].size(), hipMemcpyHostToDevice, s->st);
+    }
+    // State needs no clearing for correctness (a row of c is initialised when first touched);
+    // it is zeroed once so that the workspace never exposes stale bytes.
+    if (e == hipSuccess)
+        e = hipMemsetAsync(s->ws + L.sizes.weights_bytes, 0, L.total - L.sizes.weights_bytes, s->st);
+    if (e != hipSuccess) { delete s; return dev_fail(e, "open_streams"); }
+    net->open_count++;
+    *out = s;
+    return IDF_OK;
+}
+
+int idf_close_streams(idf_streams *s)
+{
+    if (!s) return IDF_OK;
+    hipError_t e = hipStreamSynchronize(s->st);
+    s->net->open_count--;
+    delete s;
+    return e == hipSuccess ? IDF_OK : dev_fail(e, "close_streams");
+}
+
+int idf_push_segment(idf_streams *s, const int32_t *stream_ids, int n_ids, const void *dev_rows, int n_rows)
+{
+    if (!s || !dev_rows) return fail(IDF_EINVAL, "null argument");
+    int rc = check_ids(s, stream_ids, n_ids);
+    if (rc != IDF_OK) return rc;
+    if (n_rows < 1 || n_rows > s->max_seg) return fail(IDF_EINVAL, "n_rows %d outside [1, %d]", n_rows, s->max_seg);
+    const idf_net &net = *s->net;
+    // validate everything before anything is enqueued
+    std::map<std::pair<int64_t, int64_t>, std::vector<std::pair<int, int>>> groups;
+    for (int i = 0; i < n_ids; ++i) {
+        const int id = stream_ids ? stream_ids[i] : i;
+        const StreamHost &h = s->h[id];
+        if (net.in_h > 0 && h.r + n_rows > net.in_h)
+            return fail(IDF_ESTATE, "stream %d: rows %lld..%lld run past the sample of %d rows", id,
+                        (long long)h.r, (long long)(h.r + n_rows - 1), net.in_h);
+        const int64_t fresh = output_rows_of_push(net, h.r, n_rows);
+        if (h.out_written - h.out_read + fresh > s->out_cap)
+            return fail(IDF_ESTATE, "stream %d: output area full (%lld rows waiting, %lld more would complete, room for %lld)",
+                        id, (long long)(h.out_written - h.out_read), (long long)fresh, (long long)s->out_cap);
+        groups[{h.r, h.out_written % s->out_cap}].push_back({i, id});
+    }
+    for (auto &kv : groups) {
+        const int64_t r = kv.first.first, slot0 = kv.first.second;
+        rc = for_each_selection(kv.second, [&](const StreamSel &sel) {
+            return enqueue_cascade(s, sel, dev_rows, n_rows, r, slot0);
+        });
+        if (rc != IDF_OK) return rc;
+    }
+    for (int i = 0; i < n_ids; ++i) {
+        const int id = stream_ids ? stream_ids[i] : i;
+        StreamHost &h = s->h[id];
+        h.out_written += output_rows_of_push(net, h.r, n_rows);
+        h.r += n_rows;
+        if (net.in_h > 0 && h.r == net.in_h) h.r = 0;      // next sample
+    }
+    return IDF_OK;
+}
+
+int idf_read_outputs(idf_streams *s, const int32_t *stream_ids, int n_ids, void *dev_out, int64_t max_rows,
+                     int64_t *first_row, int32_t *n_rows)
+{
+    if (!s || !dev_out || !first_row || !n_rows) return fail(IDF_EINVAL, "null argument");
+    int rc = check_ids(s, stream_ids, n_ids);
+    if (rc != IDF_OK) return rc;
+    if (max_rows < 1) return fail(IDF_EINVAL, "max_rows must be >= 1");
+    const idf_net &net = *s->net;
+    std::map<std::pair<int64_t, int>, std::vector<std::pair<int, int>>> groups;
+    for (int i = 0; i < n_ids; ++i) {
+        const int id = stream_ids ? stream_ids[i] : i;
+        const StreamHost &h = s->h[id];
+        const int64_t n = std::min<int64_t>(h.out_written - h.out_read, max_rows);
+        first_row[i] = net.out_h > 0 ? h.out_read % net.out_h : h.out_read;
+        n_rows[i] = (int32_t)n;
+        if (n > 0) groups[{h.out_read % s->out_cap, (int)n}].push_back({i, id});
+    }
+    CopyOut a{};
+    a.src = s->ws + s->out_off; a.src_stream_stride = s->out_stride; a.out_cap = s->out_cap;
+    a.dst = dev_out; a.row_elems = (int64_t)net.out_w * net.out_c; a.dst_stream_stride = max_rows * a.row_elems;
+    a.elem_bytes = 4;
+    for (auto &kv : groups) {
+        const int64_t slot = kv.first.first;
+        const int n = kv.first.second;
+        rc = for_each_selection(kv.second, [&](const StreamSel &sel) {
+            hipError_t e = launch_copy_out(a, sel, slot, n, s->st);
+            return e == hipSuccess ? IDF_OK : dev_fail(e, "copy launch");
+        });
+        if (rc != IDF_OK) return rc;
+    }
+    for (int i = 0; i < n_ids; ++i) s->h[stream_ids ? stream_ids[i] : i].out_read += n_rows[i];
+    return IDF_OK;
+}
+
+int idf_reset_streams(idf_streams *s, const int32_t *stream_ids, int n_ids)
+{
+    if (!s) return fail(IDF_EINVAL, "null argument");
+    int rc = check_ids(s, stream_ids, n_ids);
+    if (rc != IDF_OK) return rc;
+    const size_t per = s->net->g.size() * 2 * sizeof(unsigned long long);
+    for (int i = 0; i < n_ids; ++i) {
+        const int id = stream_ids ? stream_ids[i] : i;
+        hipError_t e = hipMemsetAsync(s->ws + s->stats_off + per * id, 0, per, s->st);
+        if (e != hipSuccess) return dev_fail(e, "reset_streams");
+        s->h[id] = StreamHost{};
+    }
+    return IDF_OK;
+}
+
+int idf_get_stats(idf_streams *s, int stream_id, uint64_t *events_in, uint64_t *macs_executed, uint64_t *state_bytes)
+{
+    if (!s) return fail(IDF_EINVAL, "null argument");
+    if (stream_id < 0 || stream_id >= s->B) return fail(IDF_EINVAL, "stream id %d outside [0, %d)", stream_id, s->B);
+    const int n = (int)s->net->g.size();
+    std::vector<unsigned long long> buf((size_t)n * 2);
+    hipError_t e = hipStreamSynchronize(s->st);
+    if (e == hipSuccess)
+        e = hipMemcpy(buf.data(), s->ws + s->stats_off + (size_t)stream_id * n * 2 * sizeof(unsigned long long),
+                      buf.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return dev_fail(e, "get_stats");
+    const int eb = ev_bytes(s->net->precision);
+    for (int l = 0; l < n; ++l) {
+        if (events_in) events_in[l] = buf[2 * l];
+        if (macs_executed) macs_executed[l] = buf[2 * l + 1];
+        if (state_bytes)
+            state_bytes[l] = s->net->g[l].kind == IDF_CONV ? (uint64_t)s->ring_stride[l] * 4 : (uint64_t)s->held_stride[l] * eb;
+    }
+    return IDF_OK;
+}
+
+int idf_rows_pushed(const idf_streams *s, int stream_id, int64_t *rows)
+{
+    if (!s || !rows) return fail(IDF_EINVAL, "null argument");
+    if (stream_id < 0 || stream_id >= s->B) return fail(IDF_EINVAL, "stream id %d outside [0, %d)", stream_id, s->B);
+    *rows = s->h[stream_id].r;
+    return IDF_OK;
+}
+
+const char *idf_layer_kernel(const idf_streams *s, int layer)
+{
+    if (!s || layer < 0 || layer >= (int)s->net->g.size()) return nullptr;
+    return "generic";
+}
+
+}  // extern "C"

@@ -1,0 +1,345 @@
+// Generic event-propagation kernels: any layer shape, any precision.  They are the fallback
+// for shapes the specialised kernels do not cover and the simplest statement of the update:
+//
+//   Every workgroup owns a band of cells (x_out, c_out) of one stream's layer, across all the
+//   output rows the arriving input rows touch.  Each cell starts from its retained
+//   pre-activation c (or from the bias when this step is the first to touch its row), adds
+//   w * dh for every non-zero dh in its kernel footprint among the new rows (Sec. 3, the
+//   event-delivery rule; zero values are skipped, Sec. 1), and then either goes back to the
+//   ring or -- when no future row can reach it -- is activated and emitted (Sec. 3, stateful
+//   neuron and event definition; Fig. 2 "fully processed and can be forgotten").
+//
+// Ownership instead of scatter: two events never race for one cell, so float results are
+// reproducible run to run.
+#include "idf.h"
+#include "idf_kernels.h"
+
+namespace idf {
+
+// ---------------------------------------------------------------------------------------
+// Per-precision value handling
+// ---------------------------------------------------------------------------------------
+template <int PREC> struct Prec;
+
+template <> struct Prec<IDF_PREC_F32> {
+    using ev_t = float; using w_t = float; using st_t = float; using out_t = float;
+    static __device__ __forceinline__ bool nz(ev_t v) { return v != 0.0f; }
+    static __device__ __forceinline__ st_t val(ev_t v) { return v; }
+    static __device__ __forceinline__ st_t wval(w_t v) { return v; }
+    static __device__ __forceinline__ st_t mac(st_t acc, st_t v, st_t w) { return fmaf(v, w, acc); }
+    static __device__ __forceinline__ ev_t to_ev(st_t h) { return h; }
+    static __device__ __forceinline__ out_t ev_to_out(ev_t v) { return v; }
+};
+
+template <> struct Prec<IDF_PREC_BF16> {
+    using ev_t = uint16_t; using w_t = uint16_t; using st_t = float; using out_t = float;
+    static __device__ __forceinline__ bool nz(ev_t v) { return (v & 0x7fffu) != 0; }
+    static __device__ __forceinline__ st_t val(ev_t v) { return __uint_as_float((uint32_t)v << 16); }
+    static __device__ __forceinline__ st_t wval(w_t v) { return __uint_as_float((uint32_t)v << 16); }
+    static __device__ __forceinline__ st_t mac(st_t acc, st_t v, st_t w) { return fmaf(v, w, acc); }
+    // round to nearest, ties to even, on the upper 16 bits of the binary32 pattern
+    static __device__ __forceinline__ ev_t to_ev(st_t h)
+    {
+        uint32_t u = __float_as_uint(h);
+        u += 0x7fffu + ((u >> 16) & 1u);
+        return (ev_t)(u >> 16);
+    }
+    static __device__ __forceinline__ out_t ev_to_out(ev_t v) { return val(v); }
+};
+
+template <> struct Prec<IDF_PREC_I8> {
+    using ev_t = int8_t; using w_t = int8_t; using st_t = int32_t; using out_t = int32_t;
+    static __device__ __forceinline__ bool nz(ev_t v) { return v != 0; }
+    static __device__ __forceinline__ st_t val(ev_t v) { return v; }
+    static __device__ __forceinline__ st_t wval(w_t v) { return v; }
+    static __device__ __forceinline__ st_t mac(st_t acc, st_t v, st_t w) { return acc + v * w; }
+    static __device__ __forceinline__ ev_t to_ev(st_t h) { return (ev_t)h; }
+    static __device__ __forceinline__ out_t ev_to_out(ev_t v) { return v; }
+};
+
+__device__ __forceinline__ float activate(const Geom &g, float c)
+{
+    return g.act == IDF_ACT_NONE ? c : fmaxf(c, 0.0f);
+}
+
+__device__ __forceinline__ int32_t activate(const Geom &g, int32_t c)
+{
+    if (g.act == IDF_ACT_NONE) return c;
+    int32_t r = c > 0 ? c : 0;
+    if (g.act == IDF_ACT_RELU_SHR_CLAMP) {
+        r >>= g.shr;
+        r = r > g.clamp_hi ? g.clamp_hi : r;
+    }
+    return r;
+}
+
+// Taps of a conv layer that an input row y / column x lands on inside the output.
+__device__ __forceinline__ int taps_1d(int64_t pos, int k, int s, int p, int64_t n_out)
+{
+    int n = 0;
+    for (int kk = 0; kk < k; ++kk) {
+        int64_t t = pos + p - kk;
+        if (t < 0 || t % s != 0) continue;
+        if (n_out > 0 && t / s >= n_out) continue;
+        ++n;
+    }
+    return n;
+}
+
+// Adds (events, macs) of one workgroup's threads into the per-stream per-layer counters.
+__device__ __forceinline__ void block_add_stats(unsigned long long ev, unsigned long long macs,
+                                                unsigned long long *dst)
+{
+    __shared__ unsigned long long red[2][4];
+    for (int off = 32; off > 0; off >>= 1) {
+        ev += __shfl_down(ev, off);
+        macs += __shfl_down(macs, off);
+    }
+    int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if (lane == 0) { red[0][wave] = ev; red[1][wave] = macs; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long e = 0, m = 0;
+        for (int w = 0; w < (int)(blockDim.x >> 6); ++w) { e += red[0][w]; m += red[1][w]; }
+        if (e) atomicAdd(dst, e);
+        if (m) atomicAdd(dst + 1, m);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Convolution step
+// ---------------------------------------------------------------------------------------
+constexpr int kGenThreads = 256;
+constexpr int kGenCells = 8;                     // cells per thread at most
+constexpr int kGenMaxTile = kGenThreads * kGenCells;
+
+template <int PREC>
+__global__ void __launch_bounds__(kGenThreads) k_conv_generic(const ConvStep a, const StreamSel sel)
+{
+    using T = Prec<PREC>;
+    using ev_t = typename T::ev_t; using w_t = typename T::w_t;
+    using st_t = typename T::st_t; using out_t = typename T::out_t;
+    const Geom &g = a.g;
+    const int si = blockIdx.z;
+    const int stream = sel_stream(sel, si);
+    const int64_t in_idx = a.in_by_position ? (int64_t)(sel.pos0 + si) : (int64_t)stream;
+    const ev_t *in = (const ev_t *)a.in + in_idx * a.in_stream_stride;
+    st_t *ring = (st_t *)a.ring + (int64_t)stream * a.ring_stream_stride;
+    const w_t *w = (const w_t *)a.w;
+    const st_t *bias = (const st_t *)a.bias;
+    const int row_in = g.w_in * g.c_in, row_out = g.w_out * g.c_out;
+
+    if (blockIdx.x == 0 && blockIdx.y == 0 && a.stats) {
+        unsigned long long ev = 0, macs = 0;
+        const ev_t *rows = in + (a.y0 - a.in_row0) * row_in;
+        for (int i = threadIdx.x; i < a.cnt * row_in; i += kGenThreads) {
+            if (!T::nz(rows[i])) continue;
+            int r = i / row_in, x = (i % row_in) / g.c_in;
+            int ty = taps_1d(a.y0 + r, g.k_h, g.s_h, g.p_h, g.h_out);
+            int tx = taps_1d(x, g.k_w, g.s_w, g.p_w, g.w_out);
+            ev += 1;
+            macs += (unsigned long long)(ty * tx) * g.c_out;
+        }
+        block_add_stats(ev, macs, a.stats + ((int64_t)stream * a.n_layers + a.layer) * 2);
+    }
+
+    const int x_base = blockIdx.x * a.tile_x, c_base = blockIdx.y * a.tile_c;
+    const int n_t = (int)(a.o_hi - a.o_lo);
+    const int cells = n_t * a.tile_x * a.tile_c;
+
+    st_t acc[kGenCells];
+    // Phase 1: every cell fetches its starting value before any cell of the band writes, since
+    // a row that is about to be forgotten and a row that is new can share a ring slot.
+#pragma unroll
+    for (int j = 0; j < kGenCells; ++j) {
+        int idx = threadIdx.x + j * kGenThreads;
+        acc[j] = 0;
+        if (j >= a.cells_per_thread || idx >= cells) continue;
+        int co = c_base + idx % a.tile_c;
+        int xo = x_base + (idx / a.tile_c) % a.tile_x;
+        int64_t o = a.o_lo + idx / (a.tile_c * a.tile_x);
+        if (co >= g.c_out || xo >= g.w_out) continue;
+        int64_t first = o * g.s_h - g.p_h;
+        if (first < 0) first = 0;
+        if (first >= a.y0) acc[j] = bias ? bias[co] : (st_t)0;
+        else acc[j] = ring[(o % a.ring_rows) * row_out + xo * g.c_out + co];
+    }
+    __syncthreads();
+    // Phase 2: deliver the events of the new rows, then emit or retain.
+#pragma unroll
+    for (int j = 0; j < kGenCells; ++j) {
+        int idx = threadIdx.x + j * kGenThreads;
+        if (j >= a.cells_per_thread || idx >= cells) continue;
+        int co = c_base + idx % a.tile_c;
+        int xo = x_base + (idx / a.tile_c) % a.tile_x;
+        int64_t o = a.o_lo + idx / (a.tile_c * a.tile_x);
+        if (co >= g.c_out || xo >= g.w_out) continue;
+        st_t c = acc[j];
+        for (int ky = 0; ky < g.k_h; ++ky) {
+            int64_t y = o * g.s_h - g.p_h + ky;
+            if (y < a.y0 || y >= a.y0 + a.cnt) continue;
+            const ev_t *row = in + (y - a.in_row0) * row_in;
+            for (int kx = 0; kx < g.k_w; ++kx) {
+                int x = xo * g.s_w - g.p_w + kx;
+                if (x < 0 || x >= g.w_in) continue;
+                const ev_t *px = row + x * g.c_in;
+                const w_t *wp = w + ((int64_t)(ky * g.k_w + kx) * g.c_in) * g.c_out + co;
+                for (int ci = 0; ci < g.c_in; ++ci) {
+                    ev_t v = px[ci];
+                    if (T::nz(v)) c = T::mac(c, T::val(v), T::wval(wp[(int64_t)ci * g.c_out]));
+                }
+            }
+        }
+        if (o < a.o_fin) {
+            st_t h = activate(g, c);
+            if (a.to_output) {
+                int64_t slot = (a.dst_slot0 + (o - a.dst_row0)) % a.out_cap;
+                ((out_t *)a.dst)[(int64_t)stream * a.dst_stream_stride + slot * row_out + xo * g.c_out + co] = (out_t)h;
+            } else {
+                int64_t slot = o - a.dst_row0;
+                ((ev_t *)a.dst)[(int64_t)stream * a.dst_stream_stride + slot * row_out + xo * g.c_out + co] = T::to_ev(h);
+            }
+        } else {
+            ring[(o % a.ring_rows) * row_out + xo * g.c_out + co] = c;
+        }
+    }
+}
+
+int conv_generic_max_rows(int c_out)
+{
+    int tile_c = c_out < 64 ? c_out : 64;
+    return kGenMaxTile / tile_c;
+}
+
+void conv_generic_plan(ConvStep &a)
+{
+    int n_t = (int)(a.o_hi - a.o_lo);
+    if (n_t < 1) n_t = 1;
+    a.tile_c = a.g.c_out < 64 ? a.g.c_out : 64;
+    int tx = kGenMaxTile / (n_t * a.tile_c);
+    if (tx < 1) tx = 1;
+    if (tx > a.g.w_out) tx = a.g.w_out;
+    // prefer more workgroups over long per-thread loops when the row is wide
+    while (tx > 1 && n_t * tx * a.tile_c > 2 * kGenThreads && (a.g.w_out + tx - 1) / tx < 8) tx = (tx + 1) / 2;
+    a.tile_x = tx;
+    a.cells_per_thread = (n_t * a.tile_x * a.tile_c + kGenThreads - 1) / kGenThreads;
+}
+
+hipError_t launch_conv_generic(int prec, const ConvStep &a, const StreamSel &sel, hipStream_t st)
+{
+    dim3 grid((a.g.w_out + a.tile_x - 1) / a.tile_x, (a.g.c_out + a.tile_c - 1) / a.tile_c, sel.n);
+    dim3 block(kGenThreads);
+    switch (prec) {
+    case IDF_PREC_F32: hipLaunchKernelGGL(k_conv_generic<IDF_PREC_F32>, grid, block, 0, st, a, sel); break;
+    case IDF_PREC_BF16: hipLaunchKernelGGL(k_conv_generic<IDF_PREC_BF16>, grid, block, 0, st, a, sel); break;
+    case IDF_PREC_I8: hipLaunchKernelGGL(k_conv_generic<IDF_PREC_I8>, grid, block, 0, st, a, sel); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Max-pool step: rows arrive final, so this is the ordinary maximum over a pair of rows; the
+// even row of a pair waits in the held row until the odd one arrives.
+// ---------------------------------------------------------------------------------------
+template <int PREC>
+__global__ void __launch_bounds__(kGenThreads) k_pool_generic(const PoolStep a, const StreamSel sel)
+{
+    using T = Prec<PREC>;
+    using ev_t = typename T::ev_t; using st_t = typename T::st_t; using out_t = typename T::out_t;
+    const Geom &g = a.g;
+    const int si = blockIdx.z;
+    const int stream = sel_stream(sel, si);
+    const int64_t in_idx = a.in_by_position ? (int64_t)(sel.pos0 + si) : (int64_t)stream;
+    const ev_t *in = (const ev_t *)a.in + in_idx * a.in_stream_stride;
+    ev_t *held = (ev_t *)a.held + (int64_t)stream * a.held_stream_stride;
+    const int C = g.c_out, row_in = g.w_in * C, row_out = g.w_out * C;
+
+    if (blockIdx.x == 0 && a.stats) {
+        unsigned long long ev = 0;
+        const ev_t *rows = in + (a.y0 - a.in_row0) * row_in;
+        for (int i = threadIdx.x; i < a.cnt * row_in; i += kGenThreads) ev += T::nz(rows[i]) ? 1 : 0;
+        block_add_stats(ev, 0, a.stats + ((int64_t)stream * a.n_layers + a.layer) * 2);
+    }
+
+    const int n_out = (int)(a.o_fin - a.o_lo);
+    const int rows = n_out > 0 ? n_out : 1;
+    const int idx = blockIdx.x * kGenThreads + threadIdx.x;
+    if (idx >= rows * row_out) return;
+    const int c = idx % C, ox = (idx / C) % g.w_out, oi = idx / row_out;
+    if (oi < n_out) {
+        int64_t o = a.o_lo + oi, y_even = 2 * o, y_odd = 2 * o + 1;
+        st_t m = 0;
+        for (int kx = 0; kx < g.k_w; ++kx) {
+            int x = ox * g.s_w + kx;
+            ev_t e = y_even >= a.y0 ? in[(y_even - a.in_row0) * row_in + x * C + c] : held[x * C + c];
+            ev_t d = in[(y_odd - a.in_row0) * row_in + x * C + c];
+            st_t ve = T::val(e), vd = T::val(d);
+            st_t mm = ve > vd ? ve : vd;
+            m = (kx == 0 || mm > m) ? mm : m;
+        }
+        if (a.to_output) {
+            int64_t slot = (a.dst_slot0 + (o - a.dst_row0)) % a.out_cap;
+            ((out_t *)a.dst)[(int64_t)stream * a.dst_stream_stride + slot * row_out + ox * C + c] = (out_t)m;
+        } else {
+            ((ev_t *)a.dst)[(int64_t)stream * a.dst_stream_stride + (o - a.dst_row0) * row_out + ox * C + c] = T::to_ev(m);
+        }
+    }
+    // The thread that consumed the old held values of its window is the one that replaces them.
+    if (oi == 0 && a.hold_new) {
+        int64_t y_last = a.y0 + a.cnt - 1;
+        for (int kx = 0; kx < g.k_w; ++kx) {
+            int x = ox * g.s_w + kx;
+            held[x * C + c] = in[(y_last - a.in_row0) * row_in + x * C + c];
+        }
+    }
+}
+
+hipError_t launch_pool_generic(int prec, const PoolStep &a, const StreamSel &sel, hipStream_t st)
+{
+    int n_out = (int)(a.o_fin - a.o_lo);
+    int rows = n_out > 0 ? n_out : 1;
+    int total = rows * a.g.w_out * a.g.c_out;
+    dim3 grid((total + kGenThreads - 1) / kGenThreads, 1, sel.n);
+    dim3 block(kGenThreads);
+    switch (prec) {
+    case IDF_PREC_F32: hipLaunchKernelGGL(k_pool_generic<IDF_PREC_F32>, grid, block, 0, st, a, sel); break;
+    case IDF_PREC_BF16: hipLaunchKernelGGL(k_pool_generic<IDF_PREC_BF16>, grid, block, 0, st, a, sel); break;
+    case IDF_PREC_I8: hipLaunchKernelGGL(k_pool_generic<IDF_PREC_I8>, grid, block, 0, st, a, sel); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Output hand-over: rows [first_slot, first_slot + n_rows) of the output ring -> caller.
+// Output elements are always 4 bytes (float32 / int32).
+// ---------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kGenThreads) k_copy_out(const CopyOut a, const StreamSel sel,
+                                                          int64_t first_slot, int n_rows)
+{
+    const int si = blockIdx.z;
+    const int stream = sel_stream(sel, si);
+    const uint32_t *src = (const uint32_t *)a.src + (int64_t)stream * a.src_stream_stride;
+    uint32_t *dst = (uint32_t *)a.dst + (int64_t)(sel.pos0 + si) * a.dst_stream_stride;
+    const int64_t total = (int64_t)n_rows * a.row_elems;
+    for (int64_t i = (int64_t)blockIdx.x * kGenThreads + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * kGenThreads) {
+        int64_t r = i / a.row_elems, e = i % a.row_elems;
+        dst[i] = src[((first_slot + r) % a.out_cap) * a.row_elems + e];
+    }
+}
+
+hipError_t launch_copy_out(const CopyOut &a, const StreamSel &sel, int64_t first_slot, int n_rows,
+                           hipStream_t st)
+{
+    int64_t total = (int64_t)n_rows * a.row_elems;
+    int64_t blocks = (total + kGenThreads - 1) / kGenThreads;
+    if (blocks > 1024) blocks = 1024;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(k_copy_out, dim3((unsigned)blocks, 1, sel.n), dim3(kGenThreads), 0, st, a, sel,
+                       first_slot, n_rows);
+    return hipGetLastError();
+}
+
+}  // namespace idf

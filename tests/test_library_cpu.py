@@ -1,0 +1,108 @@
+"""Host-only checks of the HIP library: it loads, exports the declared C ABI, validates
+network descriptions and reports sizes.  No GPU needed (no compute call is made)."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_1804_10727_amd as idf
+from paper_1804_10727_amd import binding
+import workloads as wl_mod
+from workloads import conv, maxpool
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_exports_every_declared_symbol():
+    L = idf.load_library()
+    header = open(os.path.join(ROOT, "include", "idf.h")).read()
+    declared = set(re.findall(r"\b(idf_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_create_net_validation():
+    w = [np.zeros((4, 2, 3, 3), np.float32)]
+    with pytest.raises(idf.IdfError) as e:
+        idf.Net("f32", 8, 8, 3, [conv(2, 4, 3, 3)], w)             # channel chain
+    assert e.value.code == binding.IDF_EINVAL
+    with pytest.raises(idf.IdfError) as e:
+        idf.Net("f32", 0, 1, 2, [conv(2, 4, 3, 1, p_h=1)], [np.zeros((4, 2, 3, 1), np.float32)])   # unbounded + padding
+    assert e.value.code == binding.IDF_EINVAL
+    with pytest.raises(idf.IdfError) as e:
+        idf.Net("f32", 2, 8, 2, [conv(2, 4, 3, 3)], w)             # kernel larger than input
+    assert e.value.code == binding.IDF_EINVAL
+    with pytest.raises(idf.IdfError) as e:
+        idf.Net("f32", 8, 8, 2, [conv(2, 4, 3, 3, act="relu_shr_clamp", shr=4, clamp_hi=15)], w)
+    assert e.value.code == binding.IDF_EUNSUPPORTED
+    with pytest.raises(idf.IdfError) as e:                          # int8 events need the clamp
+        idf.Net("i8", 8, 8, 2, [conv(2, 4, 3, 3), conv(4, 4, 1, 1)],
+                [np.zeros((4, 2, 3, 3), np.int8), np.zeros((4, 4, 1, 1), np.int8)])
+    assert e.value.code == binding.IDF_EUNSUPPORTED
+    bad_pool = maxpool(4); bad_pool["k_h"] = 3
+    with pytest.raises(idf.IdfError):
+        idf.Net("f32", 8, 8, 2, [conv(2, 4, 3, 3), bad_pool], w + [None])
+    with pytest.raises(idf.IdfError):
+        idf.Net("f32", 8, 8, 2, [conv(2, 4, 3, 3)], [None])        # missing weights
+    net = idf.Net("f32", 8, 8, 2, [conv(2, 4, 3, 3)], w)
+    net.destroy()
+
+
+# retained state per stream the build is held to: K_h rows of c (4 bytes) per conv layer plus
+# one held row of activations per pool
+def bound_bytes(wl):
+    eb = {"f32": 4, "bf16": 2, "i8": 1}[wl["precision"]]
+    h, w = wl["in_h"], wl["in_w"]
+    total = 0
+    for L in wl["layers"]:
+        w_in = w
+        h = wl_mod.out_size(h, L["k_h"], L["s_h"], L["p_h"])
+        w = wl_mod.out_size(w, L["k_w"], L["s_w"], L["p_w"])
+        total += L["k_h"] * w * L["c_out"] * 4 if L["kind"] == "conv" else w_in * L["c_out"] * eb
+    return total
+
+
+@pytest.mark.parametrize("cfg,kw", [(1, dict(streams=1, length=64)), (2, dict(streams=1, length=400)),
+                                    (3, dict(streams=1)), (4, dict(streams=1, size=64)), (5, dict(streams=1, size=32))])
+def test_state_footprint_within_bound_and_independent_of_height(cfg, kw):
+    wl = wl_mod.make(cfg, **kw)
+    net = idf.net_from_workload(wl)
+    s = net.query_sizes(4, wl["seg_rows"], 0)
+    assert s.state_bytes_per_stream <= bound_bytes(wl)
+    assert (s.out_h, s.out_w, s.out_c) == wl_mod.output_shape(wl)
+    net.destroy()
+    # a sample twice as tall (1-D: twice as long) needs exactly the same state
+    key = "length" if cfg in (1, 2) else None
+    if key:
+        wl2 = wl_mod.make(cfg, **dict(kw, length=2 * kw["length"]))
+        net2 = idf.net_from_workload(wl2)
+        assert net2.query_sizes(4, wl["seg_rows"], 0).state_bytes_per_stream == s.state_bytes_per_stream
+        net2.destroy()
+
+
+def test_full_size_state_figures():
+    # per-stream retained state of the five full-size configurations never exceeds
+    # K_h rows per conv layer + one row per pool
+    expect = {1: 288, 2: 11520, 3: 53248}
+    for cfg, want in expect.items():
+        kw = dict(streams=1)
+        wl = wl_mod.make(cfg, **kw)
+        net = idf.net_from_workload(wl)
+        s = net.query_sizes(1, wl["seg_rows"], 0)
+        assert s.state_bytes_per_stream <= want
+        net.destroy()
+
+
+def test_query_sizes_errors():
+    wl = wl_mod.make(1, streams=1, length=64)
+    net = idf.net_from_workload(wl)
+    with pytest.raises(idf.IdfError):
+        net.query_sizes(0, 1, 0)
+    net.destroy()
+    un = idf.Net("f32", 0, 1, 1, [conv(1, 4, 3, 1)], [np.zeros((4, 1, 3, 1), np.float32)])
+    with pytest.raises(idf.IdfError):
+        un.query_sizes(1, 4, 0)          # unbounded needs an explicit output capacity
+    assert un.query_sizes(1, 4, 64).out_h == 0
+    un.destroy()
