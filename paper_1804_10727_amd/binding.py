@@ -55,6 +55,11 @@ def load_library():
     if not os.path.exists(lib_path()):
         from . import build as _build
         _build.build()
+    # PyTorch ships its own copy of the HIP runtime (same soname).  Device pointers and streams
+    # are only meaningful inside the runtime instance that made them, so that copy must be the
+    # one this library binds to: import torch first, then the loader resolves our dependency
+    # to the runtime already in the process.
+    import torch  # noqa: F401
     L = C.CDLL(lib_path())
     L.idf_last_error.restype = C.c_char_p
     L.idf_layer_kernel.restype = C.c_char_p

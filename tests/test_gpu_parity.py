@@ -184,12 +184,12 @@ def test_two_samples_back_to_back():
     import torch
     import paper_1804_10727_amd as idf
     from paper_1804_10727_amd.binding import input_tensor
-    wl = wl_mod.make(4, streams=4, size=20, channels=(4, 4, 4, 4, 8, 8, 8, 8))
+    wl = wl_mod.make(4, streams=4, size=40, channels=(4, 4, 8, 8, 16, 16, 16, 16))
     net = idf.net_from_workload(wl)
     st = idf.Streams(net, 2)
     x = input_tensor(wl)
     for sample in range(2):
-        for r in range(20):
+        for r in range(40):
             st.push_segment(x[2 * sample:2 * sample + 2, r:r + 1].contiguous())
         out, first, cnt = st.read_outputs(int(st.sizes.out_h))
         torch.cuda.synchronize()
