@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the incremental depth-first CNN update on one MI355X.
+
+One "step" is one whole batch of the workload: every stream's sample is pushed segment by
+segment (each segment goes depth-first through every layer it can influence), then the
+completed outputs are read.  Inputs are resident in HBM before the timed region starts.
+
+Prints one JSON line: input pixels per second (a pixel = one spatial position of the network
+input), with the dense-equivalent and the actually executed multiply-add rates, the roofline
+position of the dominant kernel and the CPU oracle timed on the host cores of the same box.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X published peaks
+PEAK_HBM = 8.0e12
+PEAK = {"f32_valu": 157.3e12, "f32_mfma": 157.3e12, "bf16_mfma": 2.5e15, "i8_mfma": 5.0e15, "i32_valu": 157.3e12 / 2}
+WORKLOADS = {1: "cfg1_1d_k3_1stream", 2: "cfg2_1d_audio_k9_64streams", 3: "cfg3_2d_small_256streams",
+             4: "cfg4_2d_int8_events_32streams", 5: "cfg5_2d_vgg_bf16_64streams"}
+DTYPE = {"f32": "f32", "bf16": "bf16", "i8": "int8"}
+# kernel family -> (bound kind, peak key per precision)
+KERNEL_PEAK = {
+    "conv_generic": {"f32": ("alu", "f32_valu"), "bf16": ("alu", "f32_valu"), "i8": ("alu", "i32_valu")},
+    "pool_generic": None, "copy_out": None,
+}
+
+
+def cpu_baseline(wl, budget_s=20.0):
+    """The CPU oracle's event-by-event streaming scheme, as it stands, on this machine's cores."""
+    import oracle
+    from concurrent.futures import ThreadPoolExecutor
+    integer = wl["precision"] == "i8"
+    emit = "bf16" if wl["precision"] == "bf16" else None
+
+    def one(b):
+        oracle.stream_run(wl["layers"], wl["x"][b], wl["weights"], wl["biases"], seg_rows=wl["seg_rows"],
+                          integer=integer, emit_round=emit)
+    oracle.lib()
+    t0 = time.perf_counter(); one(0); t1 = time.perf_counter() - t0
+    cores = max(1, min(16, os.cpu_count() or 1))
+    n = int(max(1, min(wl["streams"], (budget_s / max(t1, 1e-6)) * cores * 0.7)))
+    threads = min(cores, n)
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        list(ex.map(one, range(n)))
+    dt = time.perf_counter() - t0
+    px = n * wl["in_h"] * wl["in_w"]
+    return {"value": px / dt, "unit": "pixels/s", "cores": threads, "kind": "oracle",
+            "sample": f"{n} of {wl['streams']} streams, whole samples, seg_rows={wl['seg_rows']}, "
+                      f"scalar event-by-event fp64/int64, one stream per thread, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (streams are independent: more GPUs "
+              "would each take a share of the streams, no figure for that is produced here)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads
+    import paper_1804_10727_amd as idf
+    from paper_1804_10727_amd.binding import input_tensor, load_library
+    import ctypes as C
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = "cuda:0"
+    wl = workloads.make(args.config)
+    B, H, W, C0, seg = wl["streams"], wl["in_h"], wl["in_w"], wl["in_c"], wl["seg_rows"]
+    n_seg = (H + seg - 1) // seg
+    assert H % seg == 0
+    steps = args.steps if args.steps is not None else {1: 5, 2: 10, 3: 50, 4: 10, 5: 5}[args.config]
+    warmup = args.warmup if args.warmup is not None else 2
+
+    net = idf.net_from_workload(wl)
+    st = idf.Streams(net, B, max_seg_rows=seg, device=dev)
+    x = input_tensor(wl, dev)
+    # segment-major copy in HBM: xs[i] is the contiguous block [B][seg][W][C] of push i
+    xs = x.view(B, n_seg, seg, W, C0).permute(1, 0, 2, 3, 4).contiguous()
+    del x
+    out_h = int(st.sizes.out_h)
+    out = torch.empty((B, out_h, st.sizes.out_w, st.sizes.out_c), dtype=st.out_dtype, device=dev)
+    L = load_library()
+    h = st._h
+    seg_ptrs = [C.c_void_p(xs[i].data_ptr()) for i in range(n_seg)]
+    first = np.zeros(B, dtype=np.int64); cnt = np.zeros(B, dtype=np.int32)
+    out_ptr = C.c_void_p(out.data_ptr())
+    push = L.idf_push_segment
+    read = L.idf_read_outputs
+
+    def step():
+        for p in seg_ptrs:
+            rc = push(h, None, B, p, seg)
+            if rc:
+                raise RuntimeError(L.idf_last_error().decode())
+        rc = read(h, None, B, out_ptr, out_h, first.ctypes.data, cnt.ctypes.data)
+        if rc:
+            raise RuntimeError(L.idf_last_error().decode())
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / steps * 1e3
+    pixels = B * H * W
+    value = pixels / (dt / steps)
+
+    # executed work and kernel times of one more step, bracketed kernel by kernel
+    def macs_total():
+        ev = np.zeros(len(wl["layers"]), dtype=np.float64); mc = np.zeros(len(wl["layers"]), dtype=np.float64)
+        for b in range(B):
+            s = st.get_stats(b)
+            ev += s["events_in"]; mc += s["macs"]
+        return ev, mc
+    ev0, mc0 = macs_total()
+    st.profile_begin()
+    step()
+    prof = st.profile_end()
+    ev1, mc1 = macs_total()
+    macs_exec_layer = mc1 - mc0
+    macs_exec = float(macs_exec_layer.sum())
+    macs_dense = float(workloads.dense_equivalent_macs(wl)) * B
+    kinds = st.layer_kernels()
+
+    dom = max(prof, key=lambda p: p["total_ms"])
+    avg_s = dom["total_ms"] * 1e-3 / dom["launches"]
+    bytes_per_launch = dom["algorithmic_bytes"] / dom["launches"]
+    layer_idx = [i for i, k in enumerate(kinds) if k == dom["name"] or dom["name"].startswith(k)]
+    flops_per_launch = 2.0 * float(sum(macs_exec_layer[i] for i in layer_idx)) / dom["launches"]
+    pk = KERNEL_PEAK.get(dom["name"])
+    kind_peak = pk[wl["precision"]] if pk else None
+    t_hbm = bytes_per_launch / PEAK_HBM
+    t_alu = flops_per_launch / PEAK[kind_peak[1]] if kind_peak else 0.0
+    if kind_peak and t_alu > t_hbm:
+        roof = {"bound": kind_peak[0], "achieved": flops_per_launch / avg_s / 1e12, "peak": PEAK[kind_peak[1]] / 1e12,
+                "unit": "TFLOP/s"}
+    else:
+        roof = {"bound": "hbm", "achieved": bytes_per_launch / avg_s / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof.update({"kernel": dom["name"], "avg_launch_us": avg_s * 1e6, "launches_per_step": dom["launches"],
+                 "algorithmic_bytes_per_launch": bytes_per_launch, "executed_flops_per_launch": flops_per_launch,
+                 "kernel_time_share": dom["total_ms"] / sum(p["total_ms"] for p in prof),
+                 "gpu_busy_ms_per_step": sum(p["total_ms"] for p in prof)})
+
+    res = {
+        "metric": "input_pixels_per_s", "value": value, "unit": "pixels/s", "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": DTYPE[wl["precision"]], "data": "synthetic",
+        "config": {"workload": WORKLOADS[args.config], "streams": B, "rows_per_sample": H, "row_width": W,
+                   "in_channels": C0, "rows_per_push": seg, "pushes_per_step": n_seg,
+                   "layers": len(wl["layers"]), "state_bytes_per_stream": int(st.sizes.state_bytes_per_stream)},
+        "gmacs_dense_equivalent": macs_dense / (dt / steps) / 1e9,
+        "gmacs_executed": macs_exec / (dt / steps) / 1e9,
+        "executed_over_dense": macs_exec / macs_dense,
+        "kernels": {p["name"]: {"launches": p["launches"], "total_ms": p["total_ms"]} for p in prof},
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(wl)
+    st.close()
+    net.destroy()
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -165,6 +165,22 @@ int idf_rows_pushed(const idf_streams *s, int stream_id, int64_t *rows);
  * "generic", for reports.  NULL on a bad index. */
 const char *idf_layer_kernel(const idf_streams *s, int layer);
 
+/* Kernel timing, for benchmarks and reports (the paper gives no timings; this is how the build
+ * measures itself).  Between idf_profile_begin and idf_profile_end every kernel the library
+ * launches for this stream set is bracketed by a HIP event pair that the runtime stamps at the
+ * kernel's own start and end.  idf_profile_end synchronises the stream and returns, per kernel
+ * family, the number of launches, the summed execution time and the summed algorithmic bytes
+ * (rows read and written, retained state read and written, weights once per launch).
+ * out: host array of max_kinds entries; *n_kinds receives how many were filled. */
+typedef struct {
+    char name[32];
+    uint64_t launches;
+    double total_ms;
+    double algorithmic_bytes;
+} idf_kernel_profile;
+int idf_profile_begin(idf_streams *s);
+int idf_profile_end(idf_streams *s, int max_kinds, idf_kernel_profile *out, int *n_kinds);
+
 const char *idf_last_error(void);
 
 #ifdef __cplusplus

@@ -16,7 +16,7 @@ ACT = {"none": 0, "relu": 1, "relu_shr_clamp": 2}
 
 EXPORTS = ["idf_create_net", "idf_destroy_net", "idf_query_sizes", "idf_open_streams", "idf_close_streams",
            "idf_push_segment", "idf_read_outputs", "idf_reset_streams", "idf_get_stats", "idf_rows_pushed",
-           "idf_layer_kernel", "idf_last_error"]
+           "idf_layer_kernel", "idf_last_error", "idf_profile_begin", "idf_profile_end"]
 
 
 class IdfError(RuntimeError):
@@ -33,6 +33,11 @@ class _Layer(C.Structure):
 class _NetDesc(C.Structure):
     _fields_ = [("precision", C.c_int), ("in_h", C.c_int), ("in_w", C.c_int), ("in_c", C.c_int),
                 ("n_layers", C.c_int), ("layers", C.POINTER(_Layer))]
+
+
+class KernelProfile(C.Structure):
+    _fields_ = [("name", C.c_char * 32), ("launches", C.c_uint64), ("total_ms", C.c_double),
+                ("algorithmic_bytes", C.c_double)]
 
 
 class Sizes(C.Structure):
@@ -77,6 +82,8 @@ def load_library():
     L.idf_reset_streams.argtypes = [C.c_void_p, C.c_void_p, C.c_int]
     L.idf_get_stats.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
     L.idf_rows_pushed.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_int64)]
+    L.idf_profile_begin.argtypes = [C.c_void_p]
+    L.idf_profile_end.argtypes = [C.c_void_p, C.c_int, C.POINTER(KernelProfile), C.POINTER(C.c_int)]
     _LIB = L
     return L
 
@@ -195,6 +202,16 @@ class Streams:
         r = C.c_int64()
         _check(load_library().idf_rows_pushed(self._h, stream_id, C.byref(r)))
         return r.value
+
+    def profile_begin(self):
+        _check(load_library().idf_profile_begin(self._h))
+
+    def profile_end(self):
+        arr = (KernelProfile * 16)()
+        n = C.c_int()
+        _check(load_library().idf_profile_end(self._h, 16, arr, C.byref(n)))
+        return [dict(name=arr[i].name.decode(), launches=int(arr[i].launches), total_ms=float(arr[i].total_ms),
+                     algorithmic_bytes=float(arr[i].algorithmic_bytes)) for i in range(n.value)]
 
     def layer_kernels(self):
         L = load_library()

@@ -15,7 +15,7 @@
 namespace idf {
 
 constexpr int kMaxLayers = 32;
-constexpr int kSelIds = 256;   // stream ids carried by value in one launch
+constexpr int kSelIds = 16;    // stream ids carried by value in one launch (kept small: kernel arguments are fetched from memory)
 
 struct Geom {
     int kind;            // IDF_CONV / IDF_MAXPOOL
@@ -116,6 +116,40 @@ struct PoolStep {
     int64_t out_cap;
     unsigned long long *stats;
     int n_layers;
+};
+
+// Whole-net cascade for 1-D nets (one launch per push).
+constexpr int kCasThreads = 512;
+constexpr int kCasKMax = 9;        // kernel height at most
+constexpr int kCasRowsMax = 16;    // rows a layer receives per push at most
+constexpr int kCasMaxLayers = 8;
+
+// One layer's step in small integers.  Accumulator slot t stands for output row o_base + t.
+struct CascadeLayer {
+    int cnt;                 // new input rows (0: the layer does not fire)
+    int t_lo, t_fin, t_hi;   // slots [t_lo, t_hi) are live; those below t_fin become final
+    int slot0;               // ring slot of o_base (slot of t is (slot0 + t) mod k_h)
+    int d0;                  // first input row of slot 0 minus the first new row
+    int at_start;            // 1: the first new row is row 0 of the sample
+    int rho;                 // (first new row + padding) mod stride
+    int cp_log;              // log2 of c_out rounded up to a power of two
+    unsigned char taps[kCasRowsMax];   // per new row: kernel taps landing inside the output
+};
+
+struct CascadeArgs {
+    int n_layers;
+    Geom g[kCasMaxLayers];
+    CascadeLayer sched[kCasMaxLayers];
+    const void *w[kCasMaxLayers];        // [k_h][c_in][c_out]
+    const void *bias[kCasMaxLayers];
+    void *ring[kCasMaxLayers];           // [stream][slot = o mod k_h][c_out]
+    int64_t ring_stride[kCasMaxLayers];
+    const void *in;                      // [position][n_rows][c0]
+    int64_t in_stream_stride;
+    int n_rows;
+    void *out;                           // output area [stream][out_cap][c_out]
+    int64_t out_stride, out_cap, out_slot0;
+    unsigned long long *stats;
 };
 
 struct CopyOut {

@@ -2,16 +2,45 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include "idf_common.h"
 
 namespace idf {
 
+// Where and how a kernel is launched: plain, or bracketed by an event pair stamped at the
+// kernel's own start and end (profiling).
+struct LaunchCtx {
+    hipStream_t st = nullptr;
+    hipEvent_t start = nullptr, stop = nullptr;
+};
+
+template <class K, class... A>
+inline hipError_t launch(K kernel, dim3 grid, dim3 block, size_t lds, const LaunchCtx &c, A... args)
+{
+    if (c.start) hipExtLaunchKernelGGL(kernel, grid, block, lds, c.st, c.start, c.stop, 0, args...);
+    else hipLaunchKernelGGL(kernel, grid, block, lds, c.st, args...);
+    return hipGetLastError();
+}
+
+enum KernelKind { kKindConvGeneric = 0, kKindPoolGeneric, kKindCopyOut, kKindCascade1d, kKindCount };
+inline const char *kind_name(int k)
+{
+    static const char *names[kKindCount] = {"conv_generic", "pool_generic", "copy_out", "cascade1d"};
+    return k >= 0 && k < kKindCount ? names[k] : "?";
+}
+
 // Generic kernels: any layer shape, any precision (prec = IDF_PREC_*).
-hipError_t launch_conv_generic(int prec, const ConvStep &a, const StreamSel &sel, hipStream_t st);
-hipError_t launch_pool_generic(int prec, const PoolStep &a, const StreamSel &sel, hipStream_t st);
+hipError_t launch_conv_generic(int prec, const ConvStep &a, const StreamSel &sel, const LaunchCtx &lc);
+hipError_t launch_pool_generic(int prec, const PoolStep &a, const StreamSel &sel, const LaunchCtx &lc);
 hipError_t launch_copy_out(const CopyOut &a, const StreamSel &sel, int64_t first_slot, int n_rows,
-                           hipStream_t st);
+                           const LaunchCtx &lc);
+
+// Whole-net cascade for 1-D float32 nets: can it serve this net (rows_cap[l] = most rows layer
+// l emits per push)?
+bool cascade1d_eligible(int prec, const Geom *g, int n_layers, const int *rows_cap, int max_seg_rows);
+int cascade1d_slot_off(int S, int rho);   // accumulator slot 0 relative to floor((y0 + p) / S)
+hipError_t launch_cascade1d(const CascadeArgs &a, const StreamSel &sel, const LaunchCtx &lc);
 
 // Largest number of touched output rows one generic conv step can take for a layer with
 // c_out output channels (the host splits longer steps).

@@ -57,7 +57,17 @@ struct StreamHost {
     int64_t out_read = 0;     // output rows handed over
 };
 
+struct ProfRec {
+    int kind;
+    hipEvent_t a, b;
+    double bytes;
+};
+
 struct idf_streams {
+    bool use_cascade1d = false;      // whole-net kernel for 1-D nets instead of one launch per layer
+    bool prof_on = false;
+    std::vector<ProfRec> prof;
+    std::vector<hipEvent_t> ev_pool;
     idf_net *net = nullptr;
     int B = 0, max_seg = 0;
     int64_t out_cap = 0;
@@ -116,6 +126,7 @@ struct Layout {
     std::vector<int> transit_cap;
     size_t out_off = 0, stats_off = 0, total = 0;
     int64_t out_stride = 0;
+    bool cascade1d = false;          // the whole-net 1-D kernel serves this stream set
     idf_sizes sizes{};
 };
 
@@ -128,9 +139,20 @@ int make_layout(const idf_net &net, int B, int max_seg, int64_t out_cap, Layout 
     L.ring_off.assign(n, 0); L.held_off.assign(n, 0); L.transit_off.assign(n, 0);
     L.ring_stride.assign(n, 0); L.held_stride.assign(n, 0); L.transit_stride.assign(n, 0);
     L.transit_cap.assign(n, 0);
+    {
+        int cap = max_seg;
+        for (int l = 0; l < n; ++l) {
+            cap = std::max(1, max_emit(net.g[l], cap));
+            L.transit_cap[l] = cap;
+        }
+    }
+    L.cascade1d = cascade1d_eligible(net.precision, net.g.data(), n, L.transit_cap.data(), max_seg);
     for (int l = 0; l < n; ++l) {
         if (net.g[l].kind != IDF_CONV) continue;
-        L.w_off[l] = off; off = align_up(off + net.w_img[l].size());
+        // the 1-D cascade reads weights zero-padded to kCasKMax taps (same layout, longer)
+        size_t wsz = net.w_img[l].size();
+        if (L.cascade1d) wsz = wsz / net.g[l].k_h * kCasKMax;
+        L.w_off[l] = off; off = align_up(off + wsz);
         L.b_off[l] = off; off = align_up(off + net.b_img[l].size());
     }
     L.sizes.weights_bytes = off;
@@ -147,9 +169,7 @@ int make_layout(const idf_net &net, int B, int max_seg, int64_t out_cap, Layout 
             L.held_off[l] = off; off = align_up(off + (size_t)L.held_stride[l] * eb * B);
             state_per_stream += (size_t)L.held_stride[l] * eb;
         }
-        cap = max_emit(g, cap);
-        if (cap < 1) cap = 1;
-        L.transit_cap[l] = cap;
+        cap = L.transit_cap[l];
         if (l < n - 1) {
             L.transit_stride[l] = (int64_t)cap * g.w_out * g.c_out;
             L.transit_off[l] = off; off = align_up(off + (size_t)L.transit_stride[l] * eb * B);
@@ -223,10 +243,103 @@ int dev_fail(hipError_t e, const char *what)
     return fail(IDF_EDEVICE, "%s: %s", what, hipGetErrorString(e));
 }
 
+// Launch context of the next kernel: plain, or with a fresh event pair while profiling.
+LaunchCtx launch_ctx(idf_streams *s, int kind, double bytes)
+{
+    LaunchCtx c;
+    c.st = s->st;
+    if (!s->prof_on) return c;
+    hipEvent_t ev[2] = {nullptr, nullptr};
+    for (int i = 0; i < 2; ++i) {
+        if (!s->ev_pool.empty()) { ev[i] = s->ev_pool.back(); s->ev_pool.pop_back(); }
+        else if (hipEventCreate(&ev[i]) != hipSuccess) { ev[i] = nullptr; }
+    }
+    if (!ev[0] || !ev[1]) {            // out of events: run this launch unprofiled
+        for (int i = 0; i < 2; ++i) if (ev[i]) s->ev_pool.push_back(ev[i]);
+        return c;
+    }
+    c.start = ev[0]; c.stop = ev[1];
+    s->prof.push_back(ProfRec{kind, ev[0], ev[1], bytes});
+    return c;
+}
+
+// Bytes one conv step has to move by the definition of the method: the new input rows, the
+// retained rows of c it continues (read) and leaves unfinished (written), the rows it emits,
+// per stream; the layer's weights once.
+double conv_step_bytes(const idf_net &net, const ConvStep &a, int n_streams)
+{
+    const int eb = ev_bytes(net.precision);
+    const double row_in = (double)a.g.w_in * a.g.c_in * eb, row_out = (double)a.g.w_out * a.g.c_out;
+    const int64_t old_rows = std::max<int64_t>(0, std::min(rows_touched(a.g, a.y0), a.o_hi) - a.o_lo);
+    // rows handed from layer to layer are not counted: the method does not require them to
+    // leave the chip
+    double per_stream = (a.in_by_position ? a.cnt * row_in : 0.0) + old_rows * row_out * 4 +
+                        (double)(a.o_hi - a.o_fin) * row_out * 4 +
+                        (a.to_output ? (double)(a.o_fin - a.o_lo) * row_out * 4 : 0.0);
+    double weights = (double)a.g.k_h * a.g.k_w * a.g.c_in * a.g.c_out * w_bytes(net.precision) + (a.bias ? a.g.c_out * 4.0 : 0.0);
+    return per_stream * n_streams + weights;
+}
+
 // Enqueue everything one group of streams (all at row r, n new rows) needs.
+int enqueue_cascade1d(idf_streams *s, const StreamSel &sel, const void *dev_rows, int n_rows, int64_t r,
+                      int64_t out_slot0)
+{
+    const idf_net &net = *s->net;
+    const int n = (int)net.g.size();
+    CascadeArgs a{};
+    a.n_layers = n;
+    double bytes = 0;
+    int64_t y0 = r, cnt = n_rows;
+    for (int l = 0; l < n; ++l) {
+        const Geom &g = net.g[l];
+        a.g[l] = g;
+        a.w[l] = s->ws + s->w_off[l];
+        a.bias[l] = net.b_img[l].empty() ? nullptr : s->ws + s->b_off[l];
+        a.ring[l] = s->ws + s->ring_off[l];
+        a.ring_stride[l] = s->ring_stride[l];
+        if (cnt > 0) {
+            ConvStep c{};
+            c.g = g; c.y0 = y0; c.cnt = (int)cnt; c.o_lo = rows_final(g, y0); c.o_fin = rows_final(g, y0 + cnt);
+            c.o_hi = std::max(rows_touched(g, y0 + cnt), c.o_fin);
+            c.in_by_position = l == 0; c.to_output = l == n - 1; c.bias = a.bias[l];
+            bytes += conv_step_bytes(net, c, sel.n);
+            CascadeLayer &L = a.sched[l];
+            const int64_t y0p = y0 + g.p_h;
+            L.rho = (int)(y0p % g.s_h);
+            const int64_t o_base = y0p / g.s_h + cascade1d_slot_off(g.s_h, L.rho);
+            L.cnt = (int)cnt;
+            L.t_lo = (int)(c.o_lo - o_base); L.t_fin = (int)(c.o_fin - o_base); L.t_hi = (int)(c.o_hi - o_base);
+            L.slot0 = (int)(((o_base % g.k_h) + g.k_h) % g.k_h);
+            L.d0 = (int)(o_base * g.s_h - g.p_h - y0);
+            L.at_start = y0 == 0;
+            L.cp_log = 0;
+            while ((1 << L.cp_log) < g.c_out) ++L.cp_log;
+            for (int j = 0; j < cnt && j < kCasRowsMax; ++j) {
+                int t = 0;
+                for (int ky = 0; ky < g.k_h; ++ky) {
+                    const int64_t u = y0 + j + g.p_h - ky;
+                    if (u < 0 || u % g.s_h != 0) continue;
+                    if (g.h_out > 0 && u / g.s_h >= g.h_out) continue;
+                    ++t;
+                }
+                L.taps[j] = (unsigned char)t;
+            }
+            if (cnt > kCasRowsMax || L.t_lo < 0 || L.t_hi > kCasRowsMax + kCasKMax - 1)
+                return fail(IDF_ESTATE, "internal: cascade schedule of layer %d out of range", l);
+            y0 = c.o_lo; cnt = c.o_fin - c.o_lo;
+        }
+    }
+    a.in = dev_rows; a.in_stream_stride = (int64_t)n_rows * net.in_c; a.n_rows = n_rows;
+    a.out = s->ws + s->out_off; a.out_stride = s->out_stride; a.out_cap = s->out_cap; a.out_slot0 = out_slot0;
+    a.stats = (unsigned long long *)(s->ws + s->stats_off);
+    hipError_t e = launch_cascade1d(a, sel, launch_ctx(s, kKindCascade1d, bytes));
+    return e == hipSuccess ? IDF_OK : dev_fail(e, "cascade launch");
+}
+
 int enqueue_cascade(idf_streams *s, const StreamSel &sel, const void *dev_rows, int n_rows, int64_t r,
                     int64_t out_slot0)
 {
+    if (s->use_cascade1d) return enqueue_cascade1d(s, sel, dev_rows, n_rows, r, out_slot0);
     const idf_net &net = *s->net;
     const int n = (int)net.g.size();
     const int eb = ev_bytes(net.precision);
@@ -268,7 +381,8 @@ int enqueue_cascade(idf_streams *s, const StreamSel &sel, const void *dev_rows, 
                 a.bias = net.b_img[l].empty() ? nullptr : s->ws + s->b_off[l];
                 a.stats = stats; a.n_layers = n;
                 conv_generic_plan(a);
-                hipError_t e = launch_conv_generic(net.precision, a, sel, s->st);
+                hipError_t e = launch_conv_generic(net.precision, a, sel,
+                                                   launch_ctx(s, kKindConvGeneric, conv_step_bytes(net, a, sel.n)));
                 if (e != hipSuccess) return dev_fail(e, "conv launch");
                 yy += c;
             }
@@ -282,12 +396,14 @@ int enqueue_cascade(idf_streams *s, const StreamSel &sel, const void *dev_rows, 
             a.dst = dst; a.dst_stream_stride = dst_stride; a.dst_row0 = o_lo; a.dst_slot0 = out_slot0;
             a.to_output = last; a.out_cap = s->out_cap;
             a.stats = stats; a.n_layers = n;
-            hipError_t e = launch_pool_generic(net.precision, a, sel, s->st);
+            const double row_in = (double)g.w_in * g.c_out * eb, row_out = (double)g.w_out * g.c_out;
+            const double bytes = sel.n * (cnt * row_in + (a.hold_new ? row_in : 0) + (y0 % 2 ? row_in : 0) +
+                                          (double)(o_fin - o_lo) * row_out * (last ? 4 : eb));
+            hipError_t e = launch_pool_generic(net.precision, a, sel, launch_ctx(s, kKindPoolGeneric, bytes));
             if (e != hipSuccess) return dev_fail(e, "pool launch");
         }
         in = dst; in_stride = dst_stride; in_row0 = o_lo; by_pos = 0;
         y0 = o_lo; cnt = o_fin - o_lo;
-        (void)eb;
     }
     return IDF_OK;
 }
@@ -405,9 +521,10 @@ int idf_open_streams(idf_net *net, int n_streams, int max_seg_rows, int64_t out_
     s->transit_off = L.transit_off; s->ring_stride = L.ring_stride; s->held_stride = L.held_stride;
     s->transit_stride = L.transit_stride; s->transit_cap = L.transit_cap;
     s->out_off = L.out_off; s->stats_off = L.stats_off; s->out_stride = L.out_stride; s->sizes = L.sizes;
+    s->use_cascade1d = L.cascade1d;
     s->h.assign(n_streams, StreamHost{});
     s->stamp.assign(n_streams, 0);
-    hipError_t e = hipSuccess;
+    hipError_t e = hipMemsetAsync(s->ws, 0, L.sizes.weights_bytes, s->st);     // zero padding of the weights
     for (size_t l = 0; l < net->g.size() && e == hipSuccess; ++l) {
         if (net->g[l].kind != IDF_CONV) continue;
         e = hipMemcpyAsync(s->ws + s->w_off[l], net->w_img[l].data(), net->w_img[l].size(), hipMemcpyHostToDevice, s->st);
@@ -428,6 +545,8 @@ int idf_close_streams(idf_streams *s)
 {
     if (!s) return IDF_OK;
     hipError_t e = hipStreamSynchronize(s->st);
+    for (ProfRec &r : s->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+    for (hipEvent_t ev : s->ev_pool) (void)hipEventDestroy(ev);
     s->net->open_count--;
     delete s;
     return e == hipSuccess ? IDF_OK : dev_fail(e, "close_streams");
@@ -496,7 +615,8 @@ int idf_read_outputs(idf_streams *s, const int32_t *stream_ids, int n_ids, void 
         const int64_t slot = kv.first.first;
         const int n = kv.first.second;
         rc = for_each_selection(kv.second, [&](const StreamSel &sel) {
-            hipError_t e = launch_copy_out(a, sel, slot, n, s->st);
+            hipError_t e = launch_copy_out(a, sel, slot, n,
+                                           launch_ctx(s, kKindCopyOut, 8.0 * n * a.row_elems * sel.n));
             return e == hipSuccess ? IDF_OK : dev_fail(e, "copy launch");
         });
         if (rc != IDF_OK) return rc;
@@ -549,10 +669,46 @@ int idf_rows_pushed(const idf_streams *s, int stream_id, int64_t *rows)
     return IDF_OK;
 }
 
+int idf_profile_begin(idf_streams *s)
+{
+    if (!s) return fail(IDF_EINVAL, "null argument");
+    if (s->prof_on) return fail(IDF_ESTATE, "profiling already on");
+    s->prof_on = true;
+    return IDF_OK;
+}
+
+int idf_profile_end(idf_streams *s, int max_kinds, idf_kernel_profile *out, int *n_kinds)
+{
+    if (!s || !out || !n_kinds || max_kinds < 1) return fail(IDF_EINVAL, "null argument");
+    if (!s->prof_on) return fail(IDF_ESTATE, "profiling is not on");
+    s->prof_on = false;
+    hipError_t e = hipStreamSynchronize(s->st);
+    if (e != hipSuccess) return dev_fail(e, "profile_end");
+    double ms[kKindCount] = {0}, bytes[kKindCount] = {0};
+    uint64_t cnt[kKindCount] = {0};
+    for (ProfRec &r : s->prof) {
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, r.a, r.b) == hipSuccess) { ms[r.kind] += t; bytes[r.kind] += r.bytes; cnt[r.kind]++; }
+        s->ev_pool.push_back(r.a); s->ev_pool.push_back(r.b);
+    }
+    s->prof.clear();
+    int n = 0;
+    for (int k = 0; k < kKindCount && n < max_kinds; ++k) {
+        if (!cnt[k]) continue;
+        memset(&out[n], 0, sizeof(out[n]));
+        snprintf(out[n].name, sizeof(out[n].name), "%s", kind_name(k));
+        out[n].launches = cnt[k]; out[n].total_ms = ms[k]; out[n].algorithmic_bytes = bytes[k];
+        ++n;
+    }
+    *n_kinds = n;
+    return IDF_OK;
+}
+
 const char *idf_layer_kernel(const idf_streams *s, int layer)
 {
     if (!s || layer < 0 || layer >= (int)s->net->g.size()) return nullptr;
-    return "generic";
+    if (s->use_cascade1d) return kind_name(kKindCascade1d);
+    return s->net->g[layer].kind == IDF_CONV ? kind_name(kKindConvGeneric) : kind_name(kKindPoolGeneric);
 }
 
 }  // extern "C"

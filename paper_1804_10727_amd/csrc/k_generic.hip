@@ -146,6 +146,15 @@ __global__ void __launch_bounds__(kGenThreads) k_conv_generic(const ConvStep a, 
     const int x_base = blockIdx.x * a.tile_x, c_base = blockIdx.y * a.tile_c;
     const int n_t = (int)(a.o_hi - a.o_lo);
     const int cells = n_t * a.tile_x * a.tile_c;
+    // Everything below works in small integers relative to the first touched output row o_lo and
+    // the first new input row y0 (64-bit row numbers are only needed to get these offsets).
+    const int slot_lo = (int)(a.o_lo % a.ring_rows);          // ring slot of o_lo
+    const int d0 = (int)(a.o_lo * g.s_h - g.p_h - a.y0);      // first input row of o_lo, relative to y0
+    const bool at_start = a.y0 == 0;
+    const int n_fin = (int)(a.o_fin - a.o_lo);
+    const int in_off = (int)(a.y0 - a.in_row0);
+    const int64_t dst_rel0 = a.o_lo - a.dst_row0;
+    const int plane = a.tile_c * a.tile_x;
 
     st_t acc[kGenCells];
     // Phase 1: every cell fetches its starting value before any cell of the band writes, since
@@ -155,14 +164,13 @@ __global__ void __launch_bounds__(kGenThreads) k_conv_generic(const ConvStep a, 
         int idx = threadIdx.x + j * kGenThreads;
         acc[j] = 0;
         if (j >= a.cells_per_thread || idx >= cells) continue;
-        int co = c_base + idx % a.tile_c;
-        int xo = x_base + (idx / a.tile_c) % a.tile_x;
-        int64_t o = a.o_lo + idx / (a.tile_c * a.tile_x);
+        int oi = idx / plane, rem = idx - oi * plane;
+        int xi = rem / a.tile_c;
+        int co = c_base + rem - xi * a.tile_c, xo = x_base + xi;
         if (co >= g.c_out || xo >= g.w_out) continue;
-        int64_t first = o * g.s_h - g.p_h;
-        if (first < 0) first = 0;
-        if (first >= a.y0) acc[j] = bias ? bias[co] : (st_t)0;
-        else acc[j] = ring[(o % a.ring_rows) * row_out + xo * g.c_out + co];
+        const bool fresh = d0 + oi * g.s_h >= 0 || at_start;
+        if (fresh) acc[j] = bias ? bias[co] : (st_t)0;
+        else acc[j] = ring[((slot_lo + oi) % a.ring_rows) * row_out + xo * g.c_out + co];
     }
     __syncthreads();
     // Phase 2: deliver the events of the new rows, then emit or retain.
@@ -170,15 +178,15 @@ __global__ void __launch_bounds__(kGenThreads) k_conv_generic(const ConvStep a, 
     for (int j = 0; j < kGenCells; ++j) {
         int idx = threadIdx.x + j * kGenThreads;
         if (j >= a.cells_per_thread || idx >= cells) continue;
-        int co = c_base + idx % a.tile_c;
-        int xo = x_base + (idx / a.tile_c) % a.tile_x;
-        int64_t o = a.o_lo + idx / (a.tile_c * a.tile_x);
+        int oi = idx / plane, rem = idx - oi * plane;
+        int xi = rem / a.tile_c;
+        int co = c_base + rem - xi * a.tile_c, xo = x_base + xi;
         if (co >= g.c_out || xo >= g.w_out) continue;
         st_t c = acc[j];
         for (int ky = 0; ky < g.k_h; ++ky) {
-            int64_t y = o * g.s_h - g.p_h + ky;
-            if (y < a.y0 || y >= a.y0 + a.cnt) continue;
-            const ev_t *row = in + (y - a.in_row0) * row_in;
+            int yr = d0 + oi * g.s_h + ky;                    // input row relative to y0
+            if (yr < 0 || yr >= a.cnt) continue;
+            const ev_t *row = in + (int64_t)(yr + in_off) * row_in;
             for (int kx = 0; kx < g.k_w; ++kx) {
                 int x = xo * g.s_w - g.p_w + kx;
                 if (x < 0 || x >= g.w_in) continue;
@@ -186,21 +194,21 @@ __global__ void __launch_bounds__(kGenThreads) k_conv_generic(const ConvStep a, 
                 const w_t *wp = w + ((int64_t)(ky * g.k_w + kx) * g.c_in) * g.c_out + co;
                 for (int ci = 0; ci < g.c_in; ++ci) {
                     ev_t v = px[ci];
-                    if (T::nz(v)) c = T::mac(c, T::val(v), T::wval(wp[(int64_t)ci * g.c_out]));
+                    if (T::nz(v)) c = T::mac(c, T::val(v), T::wval(wp[ci * g.c_out]));
                 }
             }
         }
-        if (o < a.o_fin) {
+        if (oi < n_fin) {
             st_t h = activate(g, c);
             if (a.to_output) {
-                int64_t slot = (a.dst_slot0 + (o - a.dst_row0)) % a.out_cap;
+                int64_t slot = a.dst_slot0 + dst_rel0 + oi;
+                if (slot >= a.out_cap) slot -= a.out_cap;
                 ((out_t *)a.dst)[(int64_t)stream * a.dst_stream_stride + slot * row_out + xo * g.c_out + co] = (out_t)h;
             } else {
-                int64_t slot = o - a.dst_row0;
-                ((ev_t *)a.dst)[(int64_t)stream * a.dst_stream_stride + slot * row_out + xo * g.c_out + co] = T::to_ev(h);
+                ((ev_t *)a.dst)[(int64_t)stream * a.dst_stream_stride + (dst_rel0 + oi) * row_out + xo * g.c_out + co] = T::to_ev(h);
             }
         } else {
-            ring[(o % a.ring_rows) * row_out + xo * g.c_out + co] = c;
+            ring[((slot_lo + oi) % a.ring_rows) * row_out + xo * g.c_out + co] = c;
         }
     }
 }
@@ -225,17 +233,16 @@ void conv_generic_plan(ConvStep &a)
     a.cells_per_thread = (n_t * a.tile_x * a.tile_c + kGenThreads - 1) / kGenThreads;
 }
 
-hipError_t launch_conv_generic(int prec, const ConvStep &a, const StreamSel &sel, hipStream_t st)
+hipError_t launch_conv_generic(int prec, const ConvStep &a, const StreamSel &sel, const LaunchCtx &lc)
 {
     dim3 grid((a.g.w_out + a.tile_x - 1) / a.tile_x, (a.g.c_out + a.tile_c - 1) / a.tile_c, sel.n);
     dim3 block(kGenThreads);
     switch (prec) {
-    case IDF_PREC_F32: hipLaunchKernelGGL(k_conv_generic<IDF_PREC_F32>, grid, block, 0, st, a, sel); break;
-    case IDF_PREC_BF16: hipLaunchKernelGGL(k_conv_generic<IDF_PREC_BF16>, grid, block, 0, st, a, sel); break;
-    case IDF_PREC_I8: hipLaunchKernelGGL(k_conv_generic<IDF_PREC_I8>, grid, block, 0, st, a, sel); break;
+    case IDF_PREC_F32: return launch(k_conv_generic<IDF_PREC_F32>, grid, block, 0, lc, a, sel);
+    case IDF_PREC_BF16: return launch(k_conv_generic<IDF_PREC_BF16>, grid, block, 0, lc, a, sel);
+    case IDF_PREC_I8: return launch(k_conv_generic<IDF_PREC_I8>, grid, block, 0, lc, a, sel);
     default: return hipErrorInvalidValue;
     }
-    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------
@@ -267,35 +274,38 @@ __global__ void __launch_bounds__(kGenThreads) k_pool_generic(const PoolStep a, 
     const int idx = blockIdx.x * kGenThreads + threadIdx.x;
     if (idx >= rows * row_out) return;
     const int c = idx % C, ox = (idx / C) % g.w_out, oi = idx / row_out;
+    const int e0 = (int)(2 * a.o_lo - a.y0);       // even row of the first pair, relative to y0 (-1: held)
+    const int in_off = (int)(a.y0 - a.in_row0);
+    const int64_t dst_rel0 = a.o_lo - a.dst_row0;
     if (oi < n_out) {
-        int64_t o = a.o_lo + oi, y_even = 2 * o, y_odd = 2 * o + 1;
+        const int y_even = e0 + 2 * oi, y_odd = y_even + 1;
         st_t m = 0;
         for (int kx = 0; kx < g.k_w; ++kx) {
             int x = ox * g.s_w + kx;
-            ev_t e = y_even >= a.y0 ? in[(y_even - a.in_row0) * row_in + x * C + c] : held[x * C + c];
-            ev_t d = in[(y_odd - a.in_row0) * row_in + x * C + c];
+            ev_t e = y_even >= 0 ? in[(int64_t)(y_even + in_off) * row_in + x * C + c] : held[x * C + c];
+            ev_t d = in[(int64_t)(y_odd + in_off) * row_in + x * C + c];
             st_t ve = T::val(e), vd = T::val(d);
             st_t mm = ve > vd ? ve : vd;
             m = (kx == 0 || mm > m) ? mm : m;
         }
         if (a.to_output) {
-            int64_t slot = (a.dst_slot0 + (o - a.dst_row0)) % a.out_cap;
+            int64_t slot = a.dst_slot0 + dst_rel0 + oi;
+            if (slot >= a.out_cap) slot -= a.out_cap;
             ((out_t *)a.dst)[(int64_t)stream * a.dst_stream_stride + slot * row_out + ox * C + c] = (out_t)m;
         } else {
-            ((ev_t *)a.dst)[(int64_t)stream * a.dst_stream_stride + (o - a.dst_row0) * row_out + ox * C + c] = T::to_ev(m);
+            ((ev_t *)a.dst)[(int64_t)stream * a.dst_stream_stride + (dst_rel0 + oi) * row_out + ox * C + c] = T::to_ev(m);
         }
     }
     // The thread that consumed the old held values of its window is the one that replaces them.
     if (oi == 0 && a.hold_new) {
-        int64_t y_last = a.y0 + a.cnt - 1;
         for (int kx = 0; kx < g.k_w; ++kx) {
             int x = ox * g.s_w + kx;
-            held[x * C + c] = in[(y_last - a.in_row0) * row_in + x * C + c];
+            held[x * C + c] = in[(int64_t)(a.cnt - 1 + in_off) * row_in + x * C + c];
         }
     }
 }
 
-hipError_t launch_pool_generic(int prec, const PoolStep &a, const StreamSel &sel, hipStream_t st)
+hipError_t launch_pool_generic(int prec, const PoolStep &a, const StreamSel &sel, const LaunchCtx &lc)
 {
     int n_out = (int)(a.o_fin - a.o_lo);
     int rows = n_out > 0 ? n_out : 1;
@@ -303,12 +313,11 @@ hipError_t launch_pool_generic(int prec, const PoolStep &a, const StreamSel &sel
     dim3 grid((total + kGenThreads - 1) / kGenThreads, 1, sel.n);
     dim3 block(kGenThreads);
     switch (prec) {
-    case IDF_PREC_F32: hipLaunchKernelGGL(k_pool_generic<IDF_PREC_F32>, grid, block, 0, st, a, sel); break;
-    case IDF_PREC_BF16: hipLaunchKernelGGL(k_pool_generic<IDF_PREC_BF16>, grid, block, 0, st, a, sel); break;
-    case IDF_PREC_I8: hipLaunchKernelGGL(k_pool_generic<IDF_PREC_I8>, grid, block, 0, st, a, sel); break;
+    case IDF_PREC_F32: return launch(k_pool_generic<IDF_PREC_F32>, grid, block, 0, lc, a, sel);
+    case IDF_PREC_BF16: return launch(k_pool_generic<IDF_PREC_BF16>, grid, block, 0, lc, a, sel);
+    case IDF_PREC_I8: return launch(k_pool_generic<IDF_PREC_I8>, grid, block, 0, lc, a, sel);
     default: return hipErrorInvalidValue;
     }
-    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------
@@ -322,24 +331,26 @@ __global__ void __launch_bounds__(kGenThreads) k_copy_out(const CopyOut a, const
     const int stream = sel_stream(sel, si);
     const uint32_t *src = (const uint32_t *)a.src + (int64_t)stream * a.src_stream_stride;
     uint32_t *dst = (uint32_t *)a.dst + (int64_t)(sel.pos0 + si) * a.dst_stream_stride;
-    const int64_t total = (int64_t)n_rows * a.row_elems;
-    for (int64_t i = (int64_t)blockIdx.x * kGenThreads + threadIdx.x; i < total;
-         i += (int64_t)gridDim.x * kGenThreads) {
-        int64_t r = i / a.row_elems, e = i % a.row_elems;
-        dst[i] = src[((first_slot + r) % a.out_cap) * a.row_elems + e];
+    for (int r = blockIdx.y; r < n_rows; r += gridDim.y) {
+        int64_t slot = first_slot + r;
+        if (slot >= a.out_cap) slot -= a.out_cap;
+        const uint32_t *s_row = src + slot * a.row_elems;
+        uint32_t *d_row = dst + (int64_t)r * a.row_elems;
+        for (int64_t e = (int64_t)blockIdx.x * kGenThreads + threadIdx.x; e < a.row_elems;
+             e += (int64_t)gridDim.x * kGenThreads)
+            d_row[e] = s_row[e];
     }
 }
 
 hipError_t launch_copy_out(const CopyOut &a, const StreamSel &sel, int64_t first_slot, int n_rows,
-                           hipStream_t st)
+                           const LaunchCtx &lc)
 {
-    int64_t total = (int64_t)n_rows * a.row_elems;
-    int64_t blocks = (total + kGenThreads - 1) / kGenThreads;
-    if (blocks > 1024) blocks = 1024;
+    int64_t blocks = (a.row_elems + kGenThreads - 1) / kGenThreads;
+    if (blocks > 64) blocks = 64;
     if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL(k_copy_out, dim3((unsigned)blocks, 1, sel.n), dim3(kGenThreads), 0, st, a, sel,
-                       first_slot, n_rows);
-    return hipGetLastError();
+    int rows = n_rows < 1024 ? n_rows : 1024;
+    return launch(k_copy_out, dim3((unsigned)blocks, (unsigned)rows, sel.n), dim3(kGenThreads), 0, lc, a, sel,
+                  first_slot, n_rows);
 }
 
 }  // namespace idf
