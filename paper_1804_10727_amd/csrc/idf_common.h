@@ -152,6 +152,43 @@ struct CascadeArgs {
     unsigned long long *stats;
 };
 
+// One arriving row of a 3x3 / stride 1 / same-padded conv layer on the matrix cores.
+// Tap ky of input row y lands on output row o = y + 1 - ky.
+enum { kEmitNone = 0,      // row not final: back to the rolling buffer
+       kEmitDirect,        // final: activate and emit
+       kEmitHold,          // final, even row of a pool pair: becomes the pool's held row
+       kEmitPoolHeld,      // final, odd row of a pool pair: max with the held row, emit pooled row
+       kEmitPoolReg };     // final, odd row whose even partner became final in the same launch
+enum { kMfmaTile64x64 = 0, kMfmaTile128x32, kMfmaTile32x64, kMfmaTile32x32 };
+
+struct MfmaTap {
+    int valid;             // output row exists
+    int fresh;             // first touched by this input row: starts from the bias
+    int emit;              // kEmit*
+    int store_held;        // kEmitHold: write the held row (not needed when its partner follows at once)
+    int ring_slot;
+    int64_t dst_slot;      // row slot in the destination (pooled row slot for the pool cases)
+};
+
+struct MfmaStep {
+    int w, c_in, c_out, c_out_pad;
+    int act, shr, clamp_hi;
+    int layer, pool_layer, n_layers;   // pool_layer < 0: no fused pool
+    int taps_y;                        // taps of this input row that land inside the output (for the counters)
+    int tile;                          // kMfmaTile*
+    MfmaTap t[3];
+    const void *in;                    // input rows
+    int64_t in_stream_stride, in_row_off;   // elements
+    int in_by_position;
+    void *ring;  int64_t ring_stream_stride;
+    void *held;  int64_t held_stream_stride;
+    void *dst;   int64_t dst_stream_stride;
+    int to_output;
+    const void *wfrag;                 // fragment-ordered weights
+    const void *bias;
+    unsigned long long *stats;
+};
+
 struct CopyOut {
     const void *src;             // output area [stream][out_cap][row_elems]
     int64_t src_stream_stride;

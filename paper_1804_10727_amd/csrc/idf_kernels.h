@@ -23,10 +23,10 @@ inline hipError_t launch(K kernel, dim3 grid, dim3 block, size_t lds, const Laun
     return hipGetLastError();
 }
 
-enum KernelKind { kKindConvGeneric = 0, kKindPoolGeneric, kKindCopyOut, kKindCascade1d, kKindCount };
+enum KernelKind { kKindConvGeneric = 0, kKindPoolGeneric, kKindCopyOut, kKindCascade1d, kKindConvMfma, kKindCount };
 inline const char *kind_name(int k)
 {
-    static const char *names[kKindCount] = {"conv_generic", "pool_generic", "copy_out", "cascade1d"};
+    static const char *names[kKindCount] = {"conv_generic", "pool_generic", "copy_out", "cascade1d", "conv3x3_mfma"};
     return k >= 0 && k < kKindCount ? names[k] : "?";
 }
 
@@ -41,6 +41,13 @@ hipError_t launch_copy_out(const CopyOut &a, const StreamSel &sel, int64_t first
 bool cascade1d_eligible(int prec, const Geom *g, int n_layers, const int *rows_cap, int max_seg_rows);
 int cascade1d_slot_off(int S, int rho);   // accumulator slot 0 relative to floor((y0 + p) / S)
 hipError_t launch_cascade1d(const CascadeArgs &a, const StreamSel &sel, const LaunchCtx &lc);
+
+// Matrix-core kernel for 3x3 / stride 1 / same-padded conv layers (bf16 and int8 nets).
+bool conv3x3_mfma_eligible(int prec, const Geom &g);
+int conv3x3_mfma_tile(const Geom &g, int n_streams);
+// Packs weights [k_h][k_w][c_in][c_out] into fragment order; returns the size (out may be null).
+size_t conv3x3_mfma_pack(int prec, const Geom &g, const void *w_khkwcico, void *out);
+hipError_t launch_conv3x3_mfma(int prec, const MfmaStep &a, const StreamSel &sel, const LaunchCtx &lc);
 
 // Largest number of touched output rows one generic conv step can take for a layer with
 // c_out output channels (the host splits longer steps).

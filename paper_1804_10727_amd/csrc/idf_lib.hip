@@ -6,6 +6,7 @@
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <new>
@@ -46,6 +47,8 @@ struct idf_net {
     std::vector<Geom> g;
     // device images: per conv layer weights [k_h][k_w][c_in][c_out] and bias [c_out] (4-byte)
     std::vector<std::vector<unsigned char>> w_img, b_img;
+    // per conv layer the matrix-core kernel can serve: weights in its fragment order (else empty)
+    std::vector<std::vector<unsigned char>> wm_img;
     int out_w = 0, out_c = 0;
     int64_t out_h = 0;
     int open_count = 0;
@@ -74,7 +77,8 @@ struct idf_streams {
     hipStream_t st = nullptr;
     char *ws = nullptr;
     size_t ws_bytes = 0;
-    std::vector<size_t> w_off, b_off, ring_off, held_off, transit_off;
+    std::vector<size_t> w_off, b_off, wm_off, ring_off, held_off, transit_off;
+    std::vector<int> mfma;           // per layer: 1 = matrix-core conv kernel, 2 = pool fused into the conv before it
     std::vector<int64_t> ring_stride, held_stride, transit_stride;   // elements per stream
     std::vector<int> transit_cap;                                    // rows per stream
     size_t out_off = 0, stats_off = 0;
@@ -121,7 +125,7 @@ int max_emit(const Geom &g, int cap_in)
 }
 
 struct Layout {
-    std::vector<size_t> w_off, b_off, ring_off, held_off, transit_off;
+    std::vector<size_t> w_off, b_off, wm_off, ring_off, held_off, transit_off;
     std::vector<int64_t> ring_stride, held_stride, transit_stride;
     std::vector<int> transit_cap;
     size_t out_off = 0, stats_off = 0, total = 0;
@@ -135,7 +139,7 @@ int make_layout(const idf_net &net, int B, int max_seg, int64_t out_cap, Layout 
     const int n = (int)net.g.size();
     const int eb = ev_bytes(net.precision);
     size_t off = 0;
-    L.w_off.assign(n, 0); L.b_off.assign(n, 0);
+    L.w_off.assign(n, 0); L.b_off.assign(n, 0); L.wm_off.assign(n, 0);
     L.ring_off.assign(n, 0); L.held_off.assign(n, 0); L.transit_off.assign(n, 0);
     L.ring_stride.assign(n, 0); L.held_stride.assign(n, 0); L.transit_stride.assign(n, 0);
     L.transit_cap.assign(n, 0);
@@ -154,6 +158,7 @@ int make_layout(const idf_net &net, int B, int max_seg, int64_t out_cap, Layout 
         if (L.cascade1d) wsz = wsz / net.g[l].k_h * kCasKMax;
         L.w_off[l] = off; off = align_up(off + wsz);
         L.b_off[l] = off; off = align_up(off + net.b_img[l].size());
+        L.wm_off[l] = off; off = align_up(off + net.wm_img[l].size());
     }
     L.sizes.weights_bytes = off;
     size_t state_per_stream = 0, transit_per_stream = 0;
@@ -359,7 +364,74 @@ int enqueue_cascade(idf_streams *s, const StreamSel &sel, const void *dev_rows, 
         if (!last && o_fin - o_lo > s->transit_cap[l])
             return fail(IDF_ESTATE, "internal: layer %d would emit %lld rows, room for %d", l,
                         (long long)(o_fin - o_lo), s->transit_cap[l]);
-        if (g.kind == IDF_CONV) {
+        if (g.kind == IDF_CONV && s->mfma[l] == 1) {
+            // one launch per arriving row; a pool that follows is done in the epilogue
+            const bool pool = l + 1 < n && s->mfma[l + 1] == 2;
+            const int lp = pool ? l + 1 : l;                        // layer whose rows leave this step
+            const bool last_out = lp == n - 1;
+            const Geom &gp = net.g[lp];
+            const int64_t e_lo = pool ? rows_final(gp, o_lo) : o_lo, e_fin = pool ? rows_final(gp, o_fin) : o_fin;
+            void *edst = last_out ? (void *)(s->ws + s->out_off) : (void *)(s->ws + s->transit_off[lp]);
+            const int64_t edst_stride = last_out ? s->out_stride : s->transit_stride[lp];
+            if (!last_out && e_fin - e_lo > s->transit_cap[lp])
+                return fail(IDF_ESTATE, "internal: layer %d would emit %lld rows, room for %d", lp,
+                            (long long)(e_fin - e_lo), s->transit_cap[lp]);
+            for (int64_t y = y0; y < y0 + cnt; ++y) {
+                MfmaStep a{};
+                a.w = g.w_out; a.c_in = g.c_in; a.c_out = g.c_out; a.c_out_pad = (g.c_out + 63) / 64 * 64;
+                a.act = g.act; a.shr = g.shr; a.clamp_hi = g.clamp_hi;
+                a.layer = l; a.pool_layer = pool ? l + 1 : -1; a.n_layers = n;
+                a.tile = conv3x3_mfma_tile(g, sel.n);
+                const int64_t fin_after = rows_final(g, y + 1);
+                int taps_y = 0;
+                for (int ky = 0; ky < 3; ++ky) {
+                    MfmaTap &t = a.t[ky];
+                    const int64_t o = y + 1 - ky;
+                    t.valid = o >= 0 && o < g.h_out;
+                    if (!t.valid) continue;
+                    ++taps_y;
+                    t.fresh = std::max<int64_t>(0, o - 1) >= y;
+                    t.ring_slot = (int)(o % 3);
+                    const bool fin = o < fin_after;
+                    if (!fin) { t.emit = kEmitNone; continue; }
+                    int64_t row = o;                                // row index in the leaving layer
+                    if (!pool) t.emit = kEmitDirect;
+                    else if (o % 2 == 0) {
+                        t.emit = kEmitHold;
+                        t.store_held = (o / 2 < gp.h_out) && !(o + 1 < fin_after);
+                        continue;
+                    } else {
+                        t.emit = (o - 1 >= rows_final(g, y)) ? kEmitPoolReg : kEmitPoolHeld;
+                        row = o / 2;
+                        if (row >= gp.h_out) { t.emit = kEmitHold; t.store_held = 0; continue; }
+                    }
+                    t.dst_slot = row - e_lo;
+                    if (last_out) t.dst_slot = (out_slot0 + t.dst_slot) % s->out_cap;
+                }
+                a.taps_y = taps_y;
+                a.in = in; a.in_stream_stride = in_stride; a.in_by_position = by_pos;
+                a.in_row_off = (y - in_row0) * (int64_t)g.w_in * g.c_in;
+                a.ring = s->ws + s->ring_off[l]; a.ring_stream_stride = s->ring_stride[l];
+                a.held = pool ? s->ws + s->held_off[l + 1] : nullptr;
+                a.held_stream_stride = pool ? s->held_stride[l + 1] : 0;
+                a.dst = edst; a.dst_stream_stride = edst_stride; a.to_output = last_out;
+                a.wfrag = s->ws + s->wm_off[l];
+                a.bias = net.b_img[l].empty() ? nullptr : s->ws + s->b_off[l];
+                a.stats = stats;
+                ConvStep c{};
+                c.g = g; c.y0 = y; c.cnt = 1; c.o_lo = rows_final(g, y); c.o_fin = fin_after;
+                c.o_hi = std::max(rows_touched(g, y + 1), c.o_fin);
+                c.in_by_position = by_pos; c.to_output = !pool && last_out; c.bias = a.bias;
+                double bytes = conv_step_bytes(net, c, sel.n);
+                if (pool) bytes += sel.n * (double)g.w_out * g.c_out * eb;      // the held row, written or read
+                hipError_t e = launch_conv3x3_mfma(net.precision, a, sel, launch_ctx(s, kKindConvMfma, bytes));
+                if (e != hipSuccess) return dev_fail(e, "mfma conv launch");
+            }
+            in = edst; in_stride = edst_stride; in_row0 = e_lo; by_pos = 0;
+            y0 = e_lo; cnt = e_fin - e_lo;
+            if (pool) ++l;
+            continue;
+        } else if (g.kind == IDF_CONV) {
             const int max_rows = conv_generic_max_rows(g.c_out);
             int64_t yy = y0;
             while (yy < y0 + cnt) {
@@ -455,7 +527,7 @@ int idf_create_net(const idf_net_desc *d, const void *const *weights, const void
             if (L.k_h > conv_generic_max_rows(L.c_out)) { rc = fail(IDF_EUNSUPPORTED, "layer %d: kernel height %d too large", l, L.k_h); break; }
         } else if (last && d->precision != IDF_PREC_F32) { rc = fail(IDF_EUNSUPPORTED, "a pool as the last layer needs float32 precision"); break; }
         net->g.push_back(g);
-        net->w_img.emplace_back(); net->b_img.emplace_back();
+        net->w_img.emplace_back(); net->b_img.emplace_back(); net->wm_img.emplace_back();
         if (L.kind == IDF_CONV) {
             const int wb = w_bytes(d->precision);
             std::vector<unsigned char> &img = net->w_img.back();
@@ -468,6 +540,10 @@ int idf_create_net(const idf_net_desc *d, const void *const *weights, const void
                 size_t s_idx = (((size_t)co * L.c_in + ci) * L.k_h + ky) * L.k_w + kx;
                 size_t d_idx = (((size_t)ky * L.k_w + kx) * L.c_in + ci) * L.c_out + co;
                 memcpy(&img[d_idx * wb], src + s_idx * wb, wb);
+            }
+            if (conv3x3_mfma_eligible(d->precision, g)) {
+                net->wm_img.back().resize(conv3x3_mfma_pack(d->precision, g, nullptr, nullptr));
+                conv3x3_mfma_pack(d->precision, g, img.data(), net->wm_img.back().data());
             }
             if (biases && biases[l]) {
                 net->b_img.back().resize((size_t)L.c_out * 4);
@@ -517,11 +593,19 @@ int idf_open_streams(idf_net *net, int n_streams, int max_seg_rows, int64_t out_
     s->net = net; s->B = n_streams; s->max_seg = max_seg_rows;
     s->out_cap = out_cap_rows > 0 ? out_cap_rows : net->out_h;
     s->st = (hipStream_t)hip_stream; s->ws = (char *)dev_workspace; s->ws_bytes = workspace_bytes;
-    s->w_off = L.w_off; s->b_off = L.b_off; s->ring_off = L.ring_off; s->held_off = L.held_off;
+    s->w_off = L.w_off; s->b_off = L.b_off; s->wm_off = L.wm_off; s->ring_off = L.ring_off; s->held_off = L.held_off;
     s->transit_off = L.transit_off; s->ring_stride = L.ring_stride; s->held_stride = L.held_stride;
     s->transit_stride = L.transit_stride; s->transit_cap = L.transit_cap;
     s->out_off = L.out_off; s->stats_off = L.stats_off; s->out_stride = L.out_stride; s->sizes = L.sizes;
     s->use_cascade1d = L.cascade1d;
+    s->mfma.assign(net->g.size(), 0);
+    if (!getenv("IDF_NO_MFMA")) {
+        for (size_t l = 0; l < net->g.size(); ++l) {
+            if (net->wm_img[l].empty()) continue;
+            s->mfma[l] = 1;
+            if (l + 1 < net->g.size() && net->g[l + 1].kind == IDF_MAXPOOL && net->g[l + 1].k_w == 2) s->mfma[l + 1] = 2;
+        }
+    }
     s->h.assign(n_streams, StreamHost{});
     s->stamp.assign(n_streams, 0);
     hipError_t e = hipMemsetAsync(s->ws, 0, L.sizes.weights_bytes, s->st);     // zero padding of the weights
@@ -530,6 +614,8 @@ int idf_open_streams(idf_net *net, int n_streams, int max_seg_rows, int64_t out_
         e = hipMemcpyAsync(s->ws + s->w_off[l], net->w_img[l].data(), net->w_img[l].size(), hipMemcpyHostToDevice, s->st);
         if (e == hipSuccess && !net->b_img[l].empty())
             e = hipMemcpyAsync(s->ws + s->b_off[l], net->b_img[l].data(), net->b_img[l].size(), hipMemcpyHostToDevice, s->st);
+        if (e == hipSuccess && !net->wm_img[l].empty())
+            e = hipMemcpyAsync(s->ws + s->wm_off[l], net->wm_img[l].data(), net->wm_img[l].size(), hipMemcpyHostToDevice, s->st);
     }
     // State needs no clearing for correctness (a row of c is initialised when first touched);
     // it is zeroed once so that the workspace never exposes stale bytes.
@@ -708,6 +794,7 @@ const char *idf_layer_kernel(const idf_streams *s, int layer)
 {
     if (!s || layer < 0 || layer >= (int)s->net->g.size()) return nullptr;
     if (s->use_cascade1d) return kind_name(kKindCascade1d);
+    if (s->mfma[layer]) return kind_name(kKindConvMfma);
     return s->net->g[layer].kind == IDF_CONV ? kind_name(kKindConvGeneric) : kind_name(kKindPoolGeneric);
 }
 
