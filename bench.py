@@ -30,6 +30,8 @@ DTYPE = {"f32": "f32", "bf16": "bf16", "i8": "int8"}
 # kernel family -> (bound kind, peak key per precision)
 KERNEL_PEAK = {
     "conv_generic": {"f32": ("alu", "f32_valu"), "bf16": ("alu", "f32_valu"), "i8": ("alu", "i32_valu")},
+    "cascade1d": {"f32": ("alu", "f32_valu")},
+    "conv3x3_mfma": {"bf16": ("mfma", "bf16_mfma"), "i8": ("mfma", "i8_mfma")},
     "pool_generic": None, "copy_out": None,
 }
 
@@ -135,7 +137,13 @@ def main():
     ev0, mc0 = macs_total()
     st.profile_begin()
     step()
-    prof = st.profile_end()
+    by_layer = st.profile_end()
+    prof = {}
+    for p in by_layer:                       # "family@layer" -> family
+        f = prof.setdefault(p["name"].split("@")[0], dict(name=p["name"].split("@")[0], launches=0, total_ms=0.0,
+                                                          algorithmic_bytes=0.0))
+        f["launches"] += p["launches"]; f["total_ms"] += p["total_ms"]; f["algorithmic_bytes"] += p["algorithmic_bytes"]
+    prof = list(prof.values())
     ev1, mc1 = macs_total()
     macs_exec_layer = mc1 - mc0
     macs_exec = float(macs_exec_layer.sum())
@@ -174,6 +182,9 @@ def main():
         "gmacs_executed": macs_exec / (dt / steps) / 1e9,
         "executed_over_dense": macs_exec / macs_dense,
         "kernels": {p["name"]: {"launches": p["launches"], "total_ms": p["total_ms"]} for p in prof},
+        "kernels_by_layer": {p["name"]: {"launches": p["launches"], "avg_us": p["total_ms"] * 1e3 / p["launches"],
+                                         "alg_GBps": p["algorithmic_bytes"] / (p["total_ms"] * 1e-3) / 1e9}
+                             for p in by_layer},
         "roofline": roof,
     }
     if not args.no_cpu_baseline:

@@ -169,8 +169,9 @@ const char *idf_layer_kernel(const idf_streams *s, int layer);
  * measures itself).  Between idf_profile_begin and idf_profile_end every kernel the library
  * launches for this stream set is bracketed by a HIP event pair that the runtime stamps at the
  * kernel's own start and end.  idf_profile_end synchronises the stream and returns, per kernel
- * family, the number of launches, the summed execution time and the summed algorithmic bytes
- * (rows read and written, retained state read and written, weights once per launch).
+ * family and layer (name "family@layer"; families that span the whole net have no "@layer"), the
+ * number of launches, the summed execution time and the summed algorithmic bytes (network input
+ * read, retained state read and written, weights once per launch, output rows written).
  * out: host array of max_kinds entries; *n_kinds receives how many were filled. */
 typedef struct {
     char name[32];

@@ -207,9 +207,9 @@ class Streams:
         _check(load_library().idf_profile_begin(self._h))
 
     def profile_end(self):
-        arr = (KernelProfile * 16)()
+        arr = (KernelProfile * 64)()
         n = C.c_int()
-        _check(load_library().idf_profile_end(self._h, 16, arr, C.byref(n)))
+        _check(load_library().idf_profile_end(self._h, 64, arr, C.byref(n)))
         return [dict(name=arr[i].name.decode(), launches=int(arr[i].launches), total_ms=float(arr[i].total_ms),
                      algorithmic_bytes=float(arr[i].algorithmic_bytes)) for i in range(n.value)]
 

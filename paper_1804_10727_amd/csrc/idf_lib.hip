@@ -61,7 +61,7 @@ struct StreamHost {
 };
 
 struct ProfRec {
-    int kind;
+    int kind, layer;
     hipEvent_t a, b;
     double bytes;
 };
@@ -249,7 +249,7 @@ int dev_fail(hipError_t e, const char *what)
 }
 
 // Launch context of the next kernel: plain, or with a fresh event pair while profiling.
-LaunchCtx launch_ctx(idf_streams *s, int kind, double bytes)
+LaunchCtx launch_ctx(idf_streams *s, int kind, double bytes, int layer = -1)
 {
     LaunchCtx c;
     c.st = s->st;
@@ -264,7 +264,7 @@ LaunchCtx launch_ctx(idf_streams *s, int kind, double bytes)
         return c;
     }
     c.start = ev[0]; c.stop = ev[1];
-    s->prof.push_back(ProfRec{kind, ev[0], ev[1], bytes});
+    s->prof.push_back(ProfRec{kind, layer, ev[0], ev[1], bytes});
     return c;
 }
 
@@ -424,7 +424,7 @@ int enqueue_cascade(idf_streams *s, const StreamSel &sel, const void *dev_rows, 
                 c.in_by_position = by_pos; c.to_output = !pool && last_out; c.bias = a.bias;
                 double bytes = conv_step_bytes(net, c, sel.n);
                 if (pool) bytes += sel.n * (double)g.w_out * g.c_out * eb;      // the held row, written or read
-                hipError_t e = launch_conv3x3_mfma(net.precision, a, sel, launch_ctx(s, kKindConvMfma, bytes));
+                hipError_t e = launch_conv3x3_mfma(net.precision, a, sel, launch_ctx(s, kKindConvMfma, bytes, l));
                 if (e != hipSuccess) return dev_fail(e, "mfma conv launch");
             }
             in = edst; in_stride = edst_stride; in_row0 = e_lo; by_pos = 0;
@@ -454,7 +454,7 @@ int enqueue_cascade(idf_streams *s, const StreamSel &sel, const void *dev_rows, 
                 a.stats = stats; a.n_layers = n;
                 conv_generic_plan(a);
                 hipError_t e = launch_conv_generic(net.precision, a, sel,
-                                                   launch_ctx(s, kKindConvGeneric, conv_step_bytes(net, a, sel.n)));
+                                                   launch_ctx(s, kKindConvGeneric, conv_step_bytes(net, a, sel.n), l));
                 if (e != hipSuccess) return dev_fail(e, "conv launch");
                 yy += c;
             }
@@ -471,7 +471,7 @@ int enqueue_cascade(idf_streams *s, const StreamSel &sel, const void *dev_rows, 
             const double row_in = (double)g.w_in * g.c_out * eb, row_out = (double)g.w_out * g.c_out;
             const double bytes = sel.n * (cnt * row_in + (a.hold_new ? row_in : 0) + (y0 % 2 ? row_in : 0) +
                                           (double)(o_fin - o_lo) * row_out * (last ? 4 : eb));
-            hipError_t e = launch_pool_generic(net.precision, a, sel, launch_ctx(s, kKindPoolGeneric, bytes));
+            hipError_t e = launch_pool_generic(net.precision, a, sel, launch_ctx(s, kKindPoolGeneric, bytes, l));
             if (e != hipSuccess) return dev_fail(e, "pool launch");
         }
         in = dst; in_stride = dst_stride; in_row0 = o_lo; by_pos = 0;
@@ -770,20 +770,24 @@ int idf_profile_end(idf_streams *s, int max_kinds, idf_kernel_profile *out, int 
     s->prof_on = false;
     hipError_t e = hipStreamSynchronize(s->st);
     if (e != hipSuccess) return dev_fail(e, "profile_end");
-    double ms[kKindCount] = {0}, bytes[kKindCount] = {0};
-    uint64_t cnt[kKindCount] = {0};
+    struct Agg { double ms = 0, bytes = 0; uint64_t cnt = 0; };
+    std::map<std::pair<int, int>, Agg> agg;
     for (ProfRec &r : s->prof) {
         float t = 0.f;
-        if (hipEventElapsedTime(&t, r.a, r.b) == hipSuccess) { ms[r.kind] += t; bytes[r.kind] += r.bytes; cnt[r.kind]++; }
+        if (hipEventElapsedTime(&t, r.a, r.b) == hipSuccess) {
+            Agg &g = agg[{r.kind, r.layer}];
+            g.ms += t; g.bytes += r.bytes; g.cnt++;
+        }
         s->ev_pool.push_back(r.a); s->ev_pool.push_back(r.b);
     }
     s->prof.clear();
     int n = 0;
-    for (int k = 0; k < kKindCount && n < max_kinds; ++k) {
-        if (!cnt[k]) continue;
+    for (auto &kv : agg) {
+        if (n >= max_kinds) break;
         memset(&out[n], 0, sizeof(out[n]));
-        snprintf(out[n].name, sizeof(out[n].name), "%s", kind_name(k));
-        out[n].launches = cnt[k]; out[n].total_ms = ms[k]; out[n].algorithmic_bytes = bytes[k];
+        if (kv.first.second >= 0) snprintf(out[n].name, sizeof(out[n].name), "%s@%d", kind_name(kv.first.first), kv.first.second);
+        else snprintf(out[n].name, sizeof(out[n].name), "%s", kind_name(kv.first.first));
+        out[n].launches = kv.second.cnt; out[n].total_ms = kv.second.ms; out[n].algorithmic_bytes = kv.second.bytes;
         ++n;
     }
     *n_kinds = n;

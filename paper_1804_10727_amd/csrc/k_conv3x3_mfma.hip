@@ -141,22 +141,41 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
     const unsigned char *in_row = (const unsigned char *)a.in + (in_idx * a.in_stream_stride + a.in_row_off) * EB;
     for (int i = tid; i < chunks * kNzWords; i += NT) nz[i / kNzWords][i % kNzWords] = 0;
     __syncthreads();
+    const bool small_c = C_in < VL;                // first layers: 1..4 input channels
     {
         const bool count = co_chunk == 0 && a.stats;
         unsigned long long ev = 0, taps = 0;
-        const int cells = (MT + 2) * chunks;
-        for (int i = tid; i < cells; i += NT) {
-            const int p = i / chunks, c = i - p * chunks;
-            const int x = x0 - 1 + p;
-            i32x4 v = {0, 0, 0, 0};
-            if (x >= 0 && x < W) v = *reinterpret_cast<const i32x4 *>(in_row + ((int64_t)x * C_in + c * VL) * EB);
-            *reinterpret_cast<i32x4 *>(smem + p * xs_stride + c * 16) = v;
-            if (T::cell_nonzero(v)) {
-                atomicOr(&nz[c][p >> 5], 1u << (p & 31));
-                if (count && p >= 1 && p <= MT) {
-                    const int n = T::count_nonzero(v);
-                    ev += n;
-                    taps += n * (3 - (x == 0) - (x == W - 1));
+        if (!small_c) {
+            const int cells = (MT + 2) * chunks;
+            for (int i = tid; i < cells; i += NT) {
+                const int p = i / chunks, c = i - p * chunks;
+                const int x = x0 - 1 + p;
+                i32x4 v = {0, 0, 0, 0};
+                if (x >= 0 && x < W) v = *reinterpret_cast<const i32x4 *>(in_row + ((int64_t)x * C_in + c * VL) * EB);
+                *reinterpret_cast<i32x4 *>(smem + p * xs_stride + c * 16) = v;
+                if (T::cell_nonzero(v)) {
+                    atomicOr(&nz[c][p >> 5], 1u << (p & 31));
+                    if (count && p >= 1 && p <= MT) {
+                        const int n = T::count_nonzero(v);
+                        ev += n;
+                        taps += n * (3 - (x == 0) - (x == W - 1));
+                    }
+                }
+            }
+        } else {
+            // the stretch is kept as one flat vector: A[x_out][k] is element (x_out - x0) * C_in + k of it
+            const ev_t *in_e = reinterpret_cast<const ev_t *>(in_row);
+            ev_t *xs_e = reinterpret_cast<ev_t *>(smem);
+            const int elems = (MT + 2) * C_in;
+            for (int i = tid; i < elems; i += NT) {
+                const int p = i / C_in;
+                const int x = x0 - 1 + p;
+                ev_t v = 0;
+                if (x >= 0 && x < W) v = in_e[(int64_t)x * C_in + (i - p * C_in)];
+                xs_e[i] = v;
+                if (count && p >= 1 && p <= MT && T::ev_nonzero(v)) {
+                    ev += 1;
+                    taps += 3 - (x == 0) - (x == W - 1);
                 }
             }
         }
@@ -179,8 +198,8 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
     const int steps = (KT + KI - 1) / KI;
     unsigned long long live;
     {
-        bool occ = false;
-        if (lane < steps) {
+        bool occ = small_c && lane < steps;          // few channels: every step is visited
+        if (!small_c && lane < steps) {
 #pragma unroll
             for (int hlf = 0; hlf < 2; ++hlf) {
                 const int k0 = lane * KI + hlf * VL;
@@ -218,7 +237,15 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
             const int k0 = s * KI + hlf * VL;
             const int kx = k0 / C_in, ci = k0 - kx * C_in;
             aq[d] = i32x4{0, 0, 0, 0};
-            if (k0 < KT) aq[d] = *reinterpret_cast<const i32x4 *>(smem + (r + kx) * xs_stride + ci * EB);
+            if (small_c) {
+                const ev_t *xs_e = reinterpret_cast<const ev_t *>(smem) + r * C_in;
+                ev_t e[VL];
+#pragma unroll
+                for (int q = 0; q < VL; ++q) e[q] = k0 + q < KT ? xs_e[k0 + q] : (ev_t)0;
+                __builtin_memcpy(&aq[d], e, 16);
+            } else if (k0 < KT) {
+                aq[d] = *reinterpret_cast<const i32x4 *>(smem + (r + kx) * xs_stride + ci * EB);
+            }
             const unsigned char *wp = wbase + s * w_step;
             bq[d][0] = *reinterpret_cast<const i32x4 *>(wp);
             bq[d][1] = *reinterpret_cast<const i32x4 *>(wp + w_ky);
@@ -357,7 +384,7 @@ bool conv3x3_mfma_eligible(int prec, const Geom &g)
     const int vl = prec == IDF_PREC_BF16 ? 8 : 16;
     if (g.kind != IDF_CONV || g.k_h != 3 || g.k_w != 3 || g.s_h != 1 || g.s_w != 1 || g.p_h != 1 || g.p_w != 1) return false;
     if (g.h_in < 2 || g.w_in < 2) return false;
-    if (g.c_in % vl != 0 || g.c_out % 16 != 0) return false;
+    if ((g.c_in % vl != 0 && g.c_in > 4) || g.c_out % 16 != 0) return false;
     const int steps = (3 * g.c_in + 2 * vl - 1) / (2 * vl);
     if (steps > 64 || g.c_in / vl > 64) return false;
     return true;
