@@ -172,6 +172,7 @@ struct MfmaTap {
 
 struct MfmaStep {
     int w, c_in, c_out, c_out_pad;
+    unsigned c_in_rcp;                 // ceil(2^32 / c_in): k / c_in = umulhi(k, c_in_rcp) for the k in use
     int act, shr, clamp_hi;
     int layer, pool_layer, n_layers;   // pool_layer < 0: no fused pool
     int taps_y;                        // taps of this input row that land inside the output (for the counters)

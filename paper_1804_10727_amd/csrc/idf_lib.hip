@@ -379,6 +379,7 @@ int enqueue_cascade(idf_streams *s, const StreamSel &sel, const void *dev_rows, 
             for (int64_t y = y0; y < y0 + cnt; ++y) {
                 MfmaStep a{};
                 a.w = g.w_out; a.c_in = g.c_in; a.c_out = g.c_out; a.c_out_pad = (g.c_out + 63) / 64 * 64;
+                a.c_in_rcp = (unsigned)((0x100000000ull + g.c_in - 1) / g.c_in);
                 a.act = g.act; a.shr = g.shr; a.clamp_hi = g.clamp_hi;
                 a.layer = l; a.pool_layer = pool ? l + 1 : -1; a.n_layers = n;
                 a.tile = conv3x3_mfma_tile(g, sel.n);

@@ -115,50 +115,113 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
     const int chunks = C_in / VL;                  // 16-byte cells per position
     const int xs_stride = C_in * EB + 16;          // bytes per position in LDS (padded against bank conflicts)
 
-    // ---- retained rows: issue the loads now, use them in the epilogue ---------------------
+    // Order of the global loads: the hardware counts outstanding loads in issue order, so what
+    // is needed first is requested first -- the row stretch, then the retained state (used only
+    // in the epilogue), then the weights of the first K-steps -- and waiting for the stretch
+    // leaves everything younger in flight.
     const int row_lane = (lane >> 5) * 4;          // D layout: row = 8*i + (lane/32)*4 + j, col = lane%32
     const int xo_base = x0 + wm * 32 + row_lane;
     const int co = co0 + wn * 32 + (lane & 31);
     const bool co_ok = co < C_out;
+    // Addresses are clamped into the row instead of predicated per lane: the loads then sit in
+    // straight-line code; lanes outside the tile simply never store.
+    const int co_c = co_ok ? co : C_out - 1;
+    const bool small_c = C_in < VL;                // first layers: 1..4 input channels
+    const int64_t in_idx = a.in_by_position ? (int64_t)(sel.pos0 + si) : (int64_t)stream;
+    const unsigned char *in_row = (const unsigned char *)a.in + (in_idx * a.in_stream_stride + a.in_row_off) * EB;
+    for (int i = tid; i < chunks * kNzWords; i += NT) nz[i / kNzWords][i % kNzWords] = 0;
+
+    // ---- (1) input row stretch [x0-1, x0+MT+1): first batch of 16-byte cells ------------------
+    constexpr int kBatch = 9;                      // cells per lane per batch (one batch for C_in <= 256 at 64 positions)
+    const int cells = small_c ? 0 : (MT + 2) * chunks;
+    i32x4 tv[kBatch];
+    auto tile_issue = [&](int base) {
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b) {
+            int i = base + b * NT + tid;
+            i = i < cells ? i : cells - 1;
+            const int p = i / chunks, c = i - p * chunks;
+            int x = x0 - 1 + p;
+            x = x < 0 ? 0 : (x >= W ? W - 1 : x);
+            tv[b] = *reinterpret_cast<const i32x4 *>(in_row + ((int64_t)x * C_in + c * VL) * EB);
+        }
+    };
+    if (cells > 0) tile_issue(0);
+
+    // ---- (2) retained rows of c, the pool's held row, the bias --------------------------------
     st_t *ring = (st_t *)a.ring + (int64_t)stream * a.ring_stream_stride;
     st_t init[3][16];
 #pragma unroll
     for (int ky = 0; ky < 3; ++ky) {
-        const bool rd = a.t[ky].valid && !a.t[ky].fresh;
-        const st_t b0 = a.bias && co_ok ? ((const st_t *)a.bias)[co] : (st_t)0;
-        const st_t *rrow = ring + (int64_t)a.t[ky].ring_slot * W * C_out;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) init[ky][q] = 0;
+        if (a.t[ky].valid && !a.t[ky].fresh) {
+            const st_t *rrow = ring + (int64_t)a.t[ky].ring_slot * W * C_out;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int xo = xo_base + 8 * i + j;
+                    init[ky][i * 4 + j] = rrow[(int64_t)(xo < W ? xo : W - 1) * C_out + co_c];
+                }
+        }
+    }
+    const st_t bias_v = a.bias ? ((const st_t *)a.bias)[co_c] : (st_t)0;
+    ev_t *held = (ev_t *)a.held + (int64_t)stream * a.held_stream_stride;
+    uint32_t heldv[16];                            // one register each: nothing to pack, so nothing to wait for
+    {
+        const bool need = a.t[2].valid && a.t[2].emit == kEmitPoolHeld;   // only row y-1 can pair with the held row
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int xo = xo_base + 8 * i + j;
-                init[ky][i * 4 + j] = (rd && co_ok && xo < W) ? rrow[(int64_t)xo * C_out + co] : b0;
+                heldv[i * 4 + j] = 0;
+                if (need) heldv[i * 4 + j] = (uint32_t)held[(int64_t)(xo < W ? xo : W - 1) * C_out + co_c];
             }
     }
 
-    // ---- input row stretch [x0-1, x0+MT+1) -> LDS, with occupancy bits ----------------------
-    const int64_t in_idx = a.in_by_position ? (int64_t)(sel.pos0 + si) : (int64_t)stream;
-    const unsigned char *in_row = (const unsigned char *)a.in + (in_idx * a.in_stream_stride + a.in_row_off) * EB;
-    for (int i = tid; i < chunks * kNzWords; i += NT) nz[i / kNzWords][i % kNzWords] = 0;
-    __syncthreads();
-    const bool small_c = C_in < VL;                // first layers: 1..4 input channels
+    // ---- (3) weights of the first K-steps, before it is known which steps are live -----------
+    const int KT = 3 * C_in;
+    const int steps = (KT + KI - 1) / KI;
+    const int hlf = lane >> 5, r = wm * 32 + (lane & 31);
+    const unsigned char *wbase = (const unsigned char *)a.wfrag + ((int64_t)hlf * a.c_out_pad + co0 + wn * 32 + (lane & 31)) * 16;
+    const int64_t w_step = (int64_t)2 * a.c_out_pad * 16;           // bytes per K-step
+    const int64_t w_ky = (int64_t)steps * w_step;                    // bytes per ky
+    constexpr int kDepth = 6;                                        // K-steps in flight
+    i32x4 aq[kDepth], bq[kDepth][3];
+    auto fetch_b = [&](int d, int sn) {
+        const unsigned char *wp = wbase + sn * w_step;
+        bq[d][0] = *reinterpret_cast<const i32x4 *>(wp);
+        bq[d][1] = *reinterpret_cast<const i32x4 *>(wp + w_ky);
+        bq[d][2] = *reinterpret_cast<const i32x4 *>(wp + 2 * w_ky);
+    };
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) fetch_b(d, d < steps ? d : steps - 1);
+
+    // ---- stretch -> LDS, with occupancy bits and the counters ---------------------------------
+    __syncthreads();                               // occupancy bits are cleared
     {
         const bool count = co_chunk == 0 && a.stats;
         unsigned long long ev = 0, taps = 0;
         if (!small_c) {
-            const int cells = (MT + 2) * chunks;
-            for (int i = tid; i < cells; i += NT) {
-                const int p = i / chunks, c = i - p * chunks;
-                const int x = x0 - 1 + p;
-                i32x4 v = {0, 0, 0, 0};
-                if (x >= 0 && x < W) v = *reinterpret_cast<const i32x4 *>(in_row + ((int64_t)x * C_in + c * VL) * EB);
-                *reinterpret_cast<i32x4 *>(smem + p * xs_stride + c * 16) = v;
-                if (T::cell_nonzero(v)) {
-                    atomicOr(&nz[c][p >> 5], 1u << (p & 31));
-                    if (count && p >= 1 && p <= MT) {
-                        const int n = T::count_nonzero(v);
-                        ev += n;
-                        taps += n * (3 - (x == 0) - (x == W - 1));
+            for (int base = 0; base < cells; base += NT * kBatch) {
+                if (base > 0) tile_issue(base);
+#pragma unroll
+                for (int b = 0; b < kBatch; ++b) {
+                    const int i = base + b * NT + tid;
+                    if (i >= cells) continue;
+                    const int p = i / chunks, c = i - p * chunks;
+                    const int x = x0 - 1 + p;
+                    if (x < 0 || x >= W) tv[b] = i32x4{0, 0, 0, 0};
+                    *reinterpret_cast<i32x4 *>(smem + p * xs_stride + c * 16) = tv[b];
+                    if (T::cell_nonzero(tv[b])) {
+                        atomicOr(&nz[c][p >> 5], 1u << (p & 31));
+                        if (count && p >= 1 && p <= MT) {
+                            const int n = T::count_nonzero(tv[b]);
+                            ev += n;
+                            taps += n * (3 - (x == 0) - (x == W - 1));
+                        }
                     }
                 }
             }
@@ -194,15 +257,13 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
     }
 
     // ---- which K-steps have anything in them for this wave's 32 positions -------------------
-    const int KT = 3 * C_in;
-    const int steps = (KT + KI - 1) / KI;
     unsigned long long live;
     {
         bool occ = small_c && lane < steps;          // few channels: every step is visited
         if (!small_c && lane < steps) {
 #pragma unroll
-            for (int hlf = 0; hlf < 2; ++hlf) {
-                const int k0 = lane * KI + hlf * VL;
+            for (int h2 = 0; h2 < 2; ++h2) {
+                const int k0 = lane * KI + h2 * VL;
                 if (k0 < KT) {
                     const int kx = k0 / C_in, c = (k0 - kx * C_in) / VL;
                     const int start = wm * 32 + kx;               // first tile position of the window
@@ -221,54 +282,85 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
     for (int ky = 0; ky < 3; ++ky)
 #pragma unroll
         for (int q = 0; q < 16; ++q) acc[ky][q] = 0;
-    const int hlf = lane >> 5, r = wm * 32 + (lane & 31);
-    const unsigned char *wbase = (const unsigned char *)a.wfrag + ((int64_t)hlf * a.c_out_pad + co0 + wn * 32 + (lane & 31)) * 16;
-    const int64_t w_step = (int64_t)2 * a.c_out_pad * 16;           // bytes per K-step
-    const int64_t w_ky = (int64_t)steps * w_step;                    // bytes per ky
-    // Operands of the next live steps are fetched kDepth steps ahead of their use.
-    constexpr int kDepth = 4;
-    int sq[kDepth];
-    i32x4 aq[kDepth], bq[kDepth][3];
-    auto fetch = [&](int d) {
-        if (live) {
-            const int s = __builtin_ctzll(live);
+    if (small_c) {
+        // first layers: K = 3*C_in <= 12, a single step; the fragment is gathered element by element
+        const ev_t *xs_e = reinterpret_cast<const ev_t *>(smem) + r * C_in;
+        const int k0 = hlf * VL;
+        ev_t e[VL];
+#pragma unroll
+        for (int q = 0; q < VL; ++q) e[q] = k0 + q < KT ? xs_e[k0 + q] : (ev_t)0;
+        i32x4 av;
+        __builtin_memcpy(&av, e, 16);
+        acc[0] = T::mfma(av, bq[0][0], acc[0]);
+        acc[1] = T::mfma(av, bq[0][1], acc[1]);
+        acc[2] = T::mfma(av, bq[0][2], acc[2]);
+    } else {
+        // Software pipeline over the live steps, kDepth steps deep.  Every slot issues its loads
+        // unconditionally (past the end the last live step is simply fetched again), so the
+        // loop body is straight-line code and each slot waits for exactly its own operands.
+        const int n_live = __builtin_popcountll(live);
+        int s_last = 0;
+        auto next_step = [&]() {
+            const int f = __builtin_ffsll((long long)live);           // 0 when nothing is left
+            const int sn = f ? f - 1 : s_last;
+            s_last = sn;
             live &= live - 1;
-            sq[d] = s;
-            const int k0 = s * KI + hlf * VL;
-            const int kx = k0 / C_in, ci = k0 - kx * C_in;
-            aq[d] = i32x4{0, 0, 0, 0};
-            if (small_c) {
-                const ev_t *xs_e = reinterpret_cast<const ev_t *>(smem) + r * C_in;
-                ev_t e[VL];
+            return sn;
+        };
+        auto fetch_a = [&](int d, int sn) {
+            const int k0 = sn * KI + hlf * VL;
+            const int kx = (int)__umulhi((unsigned)k0, a.c_in_rcp);   // k0 / C_in
+            const int ci = k0 - kx * C_in;
+            const bool ok = k0 < KT;                                  // half a step of padding at the end of K
+            const i32x4 v = *reinterpret_cast<const i32x4 *>(smem + (r + (ok ? kx : 0)) * xs_stride + (ok ? ci : 0) * EB);
+            aq[d] = ok ? v : i32x4{0, 0, 0, 0};
+        };
+        if (n_live > 0) {
 #pragma unroll
-                for (int q = 0; q < VL; ++q) e[q] = k0 + q < KT ? xs_e[k0 + q] : (ev_t)0;
-                __builtin_memcpy(&aq[d], e, 16);
-            } else if (k0 < KT) {
-                aq[d] = *reinterpret_cast<const i32x4 *>(smem + (r + kx) * xs_stride + ci * EB);
+            for (int d = 0; d < kDepth; ++d) {
+                const int sn = next_step();
+                fetch_a(d, sn);
+                if (sn != (d < steps ? d : steps - 1)) fetch_b(d, sn);   // the guess was another step
             }
-            const unsigned char *wp = wbase + s * w_step;
-            bq[d][0] = *reinterpret_cast<const i32x4 *>(wp);
-            bq[d][1] = *reinterpret_cast<const i32x4 *>(wp + w_ky);
-            bq[d][2] = *reinterpret_cast<const i32x4 *>(wp + 2 * w_ky);
-        } else {
-            sq[d] = -1;
-        }
-    };
+            for (int it = 0; it < n_live; it += kDepth) {
 #pragma unroll
-    for (int d = 0; d < kDepth; ++d) fetch(d);
-    for (bool more = true; more;) {
-#pragma unroll
-        for (int d = 0; d < kDepth; ++d) {
-            if (sq[d] < 0) { more = false; break; }
-            acc[0] = T::mfma(aq[d], bq[d][0], acc[0]);
-            acc[1] = T::mfma(aq[d], bq[d][1], acc[1]);
-            acc[2] = T::mfma(aq[d], bq[d][2], acc[2]);
-            fetch(d);
+                for (int d = 0; d < kDepth; ++d) {
+                    if (it + d < n_live) {
+                        acc[0] = T::mfma(aq[d], bq[d][0], acc[0]);
+                        acc[1] = T::mfma(aq[d], bq[d][1], acc[1]);
+                        acc[2] = T::mfma(aq[d], bq[d][2], acc[2]);
+                    }
+                    const int sn = next_step();
+                    fetch_a(d, sn);
+                    fetch_b(d, sn);
+                }
+            }
         }
     }
 
     // ---- epilogue -----------------------------------------------------------------------------
-    ev_t *held = (ev_t *)a.held + (int64_t)stream * a.held_stream_stride;
+    // Rows of c go back to the ring straight from the accumulator layout (32 lanes x 4 bytes = one
+    // full 128-byte line per row of the tile).  Event-type rows (1 or 2 bytes per value) would be
+    // partial-line writes from that layout, so they are staged in LDS as [position][channel] and
+    // leave as 16-byte chunks that tile whole lines.
+    ev_t *stage = reinterpret_cast<ev_t *>(smem);
+    bool stage_free = false;                          // the stretch in LDS may still be read by slower waves
+    auto flush = [&](ev_t *grow, int row_w, int p0, int npos) {
+        // grow: the row [x][C_out] in global memory; positions p0 .. p0+npos-1 of it are staged
+        __syncthreads();
+        constexpr int kPer = 16 / EB;                 // channels per 16-byte chunk
+        constexpr int kCpp = NC / kPer;               // chunks per position
+        for (int i = tid; i < npos * kCpp; i += NT) {
+            const int p = i / kCpp, k = i - p * kCpp;
+            const int x = p0 + p, cch = co0 + k * kPer;
+            if (x < row_w && cch < C_out)
+                *reinterpret_cast<i32x4 *>(grow + (int64_t)x * C_out + cch) =
+                    *reinterpret_cast<const i32x4 *>(stage + p * NC + k * kPer);
+        }
+        __syncthreads();
+    };
+    const int col = wn * 32 + (lane & 31);            // channel within the chunk
+    const int prow = wm * 32 + row_lane;              // first of this lane's positions within the tile
     ev_t hprev[16];                                   // activations of the even row finalised by tap 2
 #pragma unroll
     for (int q = 0; q < 16; ++q) hprev[q] = 0;
@@ -278,8 +370,9 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
         const MfmaTap &t = a.t[ky];
         if (!t.valid) continue;
         st_t c[16];
+        const bool cont = !t.fresh;                   // continues a retained row; else starts from the bias
 #pragma unroll
-        for (int q = 0; q < 16; ++q) c[q] = init[ky][q] + acc[ky][q];
+        for (int q = 0; q < 16; ++q) c[q] = (cont ? init[ky][q] : bias_v) + acc[ky][q];
         if (t.emit == kEmitNone) {
             st_t *rrow = ring + (int64_t)t.ring_slot * W * C_out;
 #pragma unroll
@@ -291,67 +384,77 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
                 }
             continue;
         }
-        st_t h[16];
+        ev_t e[16];
 #pragma unroll
-        for (int q = 0; q < 16; ++q) h[q] = T::activate(c[q], a.act, a.shr, a.clamp_hi);
+        for (int q = 0; q < 16; ++q) e[q] = T::to_ev(T::activate(c[q], a.act, a.shr, a.clamp_hi));
         if (a.pool_layer >= 0 && a.stats) {          // what the fused pool receives counts as its events
             unsigned int n = 0;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    n += (co_ok && xo_base + 8 * i + j < W && T::ev_nonzero(T::to_ev(h[i * 4 + j]))) ? 1u : 0u;
+                    n += (co_ok && xo_base + 8 * i + j < W && T::ev_nonzero(e[i * 4 + j])) ? 1u : 0u;
             for (int off = 32; off > 0; off >>= 1) n += __shfl_down(n, off);
             if (lane == 0 && n)
                 atomicAdd(a.stats + ((int64_t)stream * a.n_layers + a.pool_layer) * 2, (unsigned long long)n);
         }
-        if (t.emit == kEmitDirect) {
+        if (t.emit == kEmitDirect && a.to_output) {
+            // last layer: 4-byte values, not rounded to the event type
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int xo = xo_base + 8 * i + j;
                     if (!(co_ok && xo < W)) continue;
-                    const int64_t off = (int64_t)stream * a.dst_stream_stride + (t.dst_slot * W + xo) * C_out + co;
-                    if (a.to_output) ((st_t *)a.dst)[off] = h[i * 4 + j];
-                    else ((ev_t *)a.dst)[off] = T::to_ev(h[i * 4 + j]);
+                    ((st_t *)a.dst)[(int64_t)stream * a.dst_stream_stride + (t.dst_slot * W + xo) * C_out + co] =
+                        T::activate(c[i * 4 + j], a.act, a.shr, a.clamp_hi);
                 }
-        } else if (t.emit == kEmitHold) {
+        } else if (t.emit == kEmitDirect || (t.emit == kEmitHold && t.store_held)) {
+            if (!stage_free) { __syncthreads(); stage_free = true; }
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int xo = xo_base + 8 * i + j;
-                    const ev_t e = T::to_ev(h[i * 4 + j]);
-                    hprev[i * 4 + j] = e;
-                    if (t.store_held && co_ok && xo < W) held[(int64_t)xo * C_out + co] = e;
-                }
-        } else {   // pool with the held row (kEmitPoolHeld) or with the row finalised a moment ago (kEmitPoolReg)
+                for (int j = 0; j < 4; ++j) stage[(prow + 8 * i + j) * NC + col] = e[i * 4 + j];
+            ev_t *grow = t.emit == kEmitHold
+                             ? held
+                             : (ev_t *)a.dst + (int64_t)stream * a.dst_stream_stride + t.dst_slot * W * C_out;
+            flush(grow, W, x0, MT);
+        }
+        if (t.emit == kEmitHold) {
+#pragma unroll
+            for (int q = 0; q < 16; ++q) hprev[q] = e[q];
+        } else if (t.emit == kEmitPoolHeld || t.emit == kEmitPoolReg) {
+            // 2x2 max: this row and the even row of the pair, positions 2j and 2j+1 (both in this lane)
             const int Wp = W / 2;
+            if (!stage_free && !a.to_output) { __syncthreads(); stage_free = true; }
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int jj = 0; jj < 2; ++jj) {
-                    const int xo = xo_base + 8 * i + 2 * jj;
-                    const int xp = xo >> 1;
-                    if (!(co_ok && xp < Wp)) continue;
-                    st_t m = T::ev_val(T::to_ev(h[i * 4 + 2 * jj]));
-                    const st_t m1 = T::ev_val(T::to_ev(h[i * 4 + 2 * jj + 1]));
+                    st_t m = T::ev_val(e[i * 4 + 2 * jj]);
+                    const st_t m1 = T::ev_val(e[i * 4 + 2 * jj + 1]);
                     m = m1 > m ? m1 : m;
                     st_t e0, e1;
                     if (t.emit == kEmitPoolHeld) {
-                        e0 = T::ev_val(held[(int64_t)xo * C_out + co]);
-                        e1 = T::ev_val(held[(int64_t)(xo + 1) * C_out + co]);
+                        e0 = T::ev_val((ev_t)heldv[i * 4 + 2 * jj]);
+                        e1 = T::ev_val((ev_t)heldv[i * 4 + 2 * jj + 1]);
                     } else {
                         e0 = T::ev_val(hprev[i * 4 + 2 * jj]);
                         e1 = T::ev_val(hprev[i * 4 + 2 * jj + 1]);
                     }
                     m = e0 > m ? e0 : m;
                     m = e1 > m ? e1 : m;
-                    const int64_t off = (int64_t)stream * a.dst_stream_stride + (t.dst_slot * Wp + xp) * C_out + co;
-                    if (a.to_output) ((st_t *)a.dst)[off] = m;
-                    else ((ev_t *)a.dst)[off] = T::to_ev(m);
+                    const int pl = ((prow + 8 * i) >> 1) + jj;        // pooled position within the tile
+                    if (a.to_output) {
+                        const int xp = (x0 >> 1) + pl;
+                        if (co_ok && xp < Wp)
+                            ((st_t *)a.dst)[(int64_t)stream * a.dst_stream_stride + (t.dst_slot * Wp + xp) * C_out + co] = m;
+                    } else {
+                        stage[pl * NC + col] = T::to_ev(m);
+                    }
                 }
+            if (!a.to_output)
+                flush((ev_t *)a.dst + (int64_t)stream * a.dst_stream_stride + t.dst_slot * Wp * C_out, Wp, x0 >> 1, MT / 2);
         }
     }
 }
@@ -361,7 +464,9 @@ hipError_t launch_one(const MfmaStep &a, const StreamSel &sel, const LaunchCtx &
 {
     constexpr int MT = 32 * WM, NC = 32 * WN;
     const int x_tiles = (a.w + MT - 1) / MT, co_chunks = (a.c_out + NC - 1) / NC;
-    const size_t lds = (size_t)(MT + 2) * (a.c_in * T::EB + 16);
+    size_t lds = (size_t)(MT + 2) * (a.c_in * T::EB + 16);
+    const size_t stage = (size_t)MT * NC * T::EB;       // the epilogue reuses the space to stage emitted rows
+    if (lds < stage) lds = stage;
     return launch(k_conv3x3_mfma<T, WM, WN>, dim3(x_tiles * co_chunks, 1, sel.n), dim3(64 * WM * WN), lds, lc, a, sel);
 }
 
