@@ -121,6 +121,7 @@ struct PoolStep {
 // Whole-net cascade for 1-D nets (one launch per push).
 constexpr int kCasThreads = 512;
 constexpr int kCasKMax = 9;        // kernel height at most
+constexpr int kCasTapsPad = 12;    // taps per (c_in, c_out) pair in the cascade's weight packing: three 16-byte loads
 constexpr int kCasRowsMax = 16;    // rows a layer receives per push at most
 constexpr int kCasMaxLayers = 8;
 
@@ -140,7 +141,7 @@ struct CascadeArgs {
     int n_layers;
     Geom g[kCasMaxLayers];
     CascadeLayer sched[kCasMaxLayers];
-    const void *w[kCasMaxLayers];        // [k_h][c_in][c_out]
+    const void *w[kCasMaxLayers];        // [c_in][c_out][kCasTapsPad]
     const void *bias[kCasMaxLayers];
     void *ring[kCasMaxLayers];           // [stream][slot = o mod k_h][c_out]
     int64_t ring_stride[kCasMaxLayers];

@@ -23,6 +23,17 @@ inline hipError_t launch(K kernel, dim3 grid, dim3 block, size_t lds, const Laun
     return hipGetLastError();
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits until every global
+// store and atomic of the wave has been acknowledged (a release fence over all address spaces),
+// a memory round trip that the kernels here do not need at their internal barriers: what the
+// waves of a workgroup exchange goes through LDS.
+__device__ __forceinline__ void lds_barrier()
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier\n\ts_waitcnt lgkmcnt(0)" ::: "memory");
+#endif
+}
+
 enum KernelKind { kKindConvGeneric = 0, kKindPoolGeneric, kKindCopyOut, kKindCascade1d, kKindConvMfma, kKindCount };
 inline const char *kind_name(int k)
 {

@@ -83,6 +83,7 @@ struct idf_streams {
     std::vector<int> transit_cap;                                    // rows per stream
     size_t out_off = 0, stats_off = 0;
     int64_t out_stride = 0;
+    std::vector<std::vector<float>> cas_w;      // cascade packing of the weights (kept until the upload has run)
     std::vector<StreamHost> h;
     std::vector<int> stamp;
     int stamp_gen = 0;
@@ -153,9 +154,9 @@ int make_layout(const idf_net &net, int B, int max_seg, int64_t out_cap, Layout 
     L.cascade1d = cascade1d_eligible(net.precision, net.g.data(), n, L.transit_cap.data(), max_seg);
     for (int l = 0; l < n; ++l) {
         if (net.g[l].kind != IDF_CONV) continue;
-        // the 1-D cascade reads weights zero-padded to kCasKMax taps (same layout, longer)
+        // the 1-D cascade reads its own packing: [c_in][c_out][kCasTapsPad] floats, taps zero-padded
         size_t wsz = net.w_img[l].size();
-        if (L.cascade1d) wsz = wsz / net.g[l].k_h * kCasKMax;
+        if (L.cascade1d) wsz = (size_t)net.g[l].c_in * net.g[l].c_out * kCasTapsPad * 4;
         L.w_off[l] = off; off = align_up(off + wsz);
         L.b_off[l] = off; off = align_up(off + net.b_img[l].size());
         L.wm_off[l] = off; off = align_up(off + net.wm_img[l].size());
@@ -612,7 +613,19 @@ int idf_open_streams(idf_net *net, int n_streams, int max_seg_rows, int64_t out_
     hipError_t e = hipMemsetAsync(s->ws, 0, L.sizes.weights_bytes, s->st);     // zero padding of the weights
     for (size_t l = 0; l < net->g.size() && e == hipSuccess; ++l) {
         if (net->g[l].kind != IDF_CONV) continue;
-        e = hipMemcpyAsync(s->ws + s->w_off[l], net->w_img[l].data(), net->w_img[l].size(), hipMemcpyHostToDevice, s->st);
+        if (L.cascade1d) {
+            const Geom &g = net->g[l];
+            const float *src = (const float *)net->w_img[l].data();      // [k_h][1][c_in][c_out]
+            s->cas_w.emplace_back((size_t)g.c_in * g.c_out * kCasTapsPad, 0.f);
+            std::vector<float> &img = s->cas_w.back();
+            for (int ky = 0; ky < g.k_h; ++ky)
+                for (int ci = 0; ci < g.c_in; ++ci)
+                    for (int co = 0; co < g.c_out; ++co)
+                        img[((size_t)ci * g.c_out + co) * kCasTapsPad + ky] = src[((size_t)ky * g.c_in + ci) * g.c_out + co];
+            e = hipMemcpyAsync(s->ws + s->w_off[l], img.data(), img.size() * 4, hipMemcpyHostToDevice, s->st);
+        } else {
+            e = hipMemcpyAsync(s->ws + s->w_off[l], net->w_img[l].data(), net->w_img[l].size(), hipMemcpyHostToDevice, s->st);
+        }
         if (e == hipSuccess && !net->b_img[l].empty())
             e = hipMemcpyAsync(s->ws + s->b_off[l], net->b_img[l].data(), net->b_img[l].size(), hipMemcpyHostToDevice, s->st);
         if (e == hipSuccess && !net->wm_img[l].empty())

@@ -200,7 +200,7 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
     for (int d = 0; d < kDepth; ++d) fetch_b(d, d < steps ? d : steps - 1);
 
     // ---- stretch -> LDS, with occupancy bits and the counters ---------------------------------
-    __syncthreads();                               // occupancy bits are cleared
+    lds_barrier();                               // occupancy bits are cleared
     {
         const bool count = co_chunk == 0 && a.stats;
         unsigned long long ev = 0, taps = 0;
@@ -246,7 +246,7 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
             for (int off = 32; off > 0; off >>= 1) { ev += __shfl_down(ev, off); taps += __shfl_down(taps, off); }
             if (lane == 0) { red[0][wave] = ev; red[1][wave] = taps; }
         }
-        __syncthreads();
+        lds_barrier();
         if (count && tid == 0) {
             unsigned long long e = 0, t = 0;
             for (int wv = 0; wv < WM * WN; ++wv) { e += red[0][wv]; t += red[1][wv]; }
@@ -347,7 +347,7 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
     bool stage_free = false;                          // the stretch in LDS may still be read by slower waves
     auto flush = [&](ev_t *grow, int row_w, int p0, int npos) {
         // grow: the row [x][C_out] in global memory; positions p0 .. p0+npos-1 of it are staged
-        __syncthreads();
+        lds_barrier();
         constexpr int kPer = 16 / EB;                 // channels per 16-byte chunk
         constexpr int kCpp = NC / kPer;               // chunks per position
         for (int i = tid; i < npos * kCpp; i += NT) {
@@ -357,7 +357,7 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
                 *reinterpret_cast<i32x4 *>(grow + (int64_t)x * C_out + cch) =
                     *reinterpret_cast<const i32x4 *>(stage + p * NC + k * kPer);
         }
-        __syncthreads();
+        lds_barrier();
     };
     const int col = wn * 32 + (lane & 31);            // channel within the chunk
     const int prow = wm * 32 + row_lane;              // first of this lane's positions within the tile
@@ -410,7 +410,7 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
                         T::activate(c[i * 4 + j], a.act, a.shr, a.clamp_hi);
                 }
         } else if (t.emit == kEmitDirect || (t.emit == kEmitHold && t.store_held)) {
-            if (!stage_free) { __syncthreads(); stage_free = true; }
+            if (!stage_free) { lds_barrier(); stage_free = true; }
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -426,7 +426,7 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
         } else if (t.emit == kEmitPoolHeld || t.emit == kEmitPoolReg) {
             // 2x2 max: this row and the even row of the pair, positions 2j and 2j+1 (both in this lane)
             const int Wp = W / 2;
-            if (!stage_free && !a.to_output) { __syncthreads(); stage_free = true; }
+            if (!stage_free && !a.to_output) { lds_barrier(); stage_free = true; }
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
