@@ -61,19 +61,8 @@ def cpu_baseline(wl, budget_s=20.0):
                       f"scalar event-by-event fp64/int64, one stream per thread, {dt:.1f} s"}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None)
-    ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (streams are independent: more GPUs "
-              "would each take a share of the streams, no figure for that is produced here)", file=sys.stderr)
-        sys.exit(2)
-
+def run_workload(config, steps_arg=None, warmup_arg=None):
+    """Times `steps` whole batches of one workload; returns (result dict, workload)."""
     import numpy as np
     import torch
     import workloads
@@ -81,14 +70,13 @@ def main():
     from paper_1804_10727_amd.binding import input_tensor, load_library
     import ctypes as C
 
-    assert torch.cuda.is_available(), "bench.py needs the GPU"
     dev = "cuda:0"
-    wl = workloads.make(args.config)
+    wl = workloads.make(config)
     B, H, W, C0, seg = wl["streams"], wl["in_h"], wl["in_w"], wl["in_c"], wl["seg_rows"]
     n_seg = (H + seg - 1) // seg
     assert H % seg == 0
-    steps = args.steps if args.steps is not None else {1: 5, 2: 10, 3: 50, 4: 10, 5: 5}[args.config]
-    warmup = args.warmup if args.warmup is not None else 2
+    steps = steps_arg if steps_arg is not None else {1: 5, 2: 10, 3: 50, 4: 10, 5: 5}[config]
+    warmup = warmup_arg if warmup_arg is not None else 2
 
     net = idf.net_from_workload(wl)
     st = idf.Streams(net, B, max_seg_rows=seg, device=dev)
@@ -176,7 +164,7 @@ def main():
         "metric": "input_pixels_per_s", "value": value, "unit": "pixels/s", "n_gpus": 1, "steps": steps,
         "warmup": warmup, "ms_per_step": ms_per_step, "host_enqueue_ms_per_step": t_enq / steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": DTYPE[wl["precision"]], "data": "synthetic",
-        "config": {"workload": WORKLOADS[args.config], "streams": B, "rows_per_sample": H, "row_width": W,
+        "config": {"workload": WORKLOADS[config], "streams": B, "rows_per_sample": H, "row_width": W,
                    "in_channels": C0, "rows_per_push": seg, "pushes_per_step": n_seg,
                    "layers": len(wl["layers"]), "state_bytes_per_stream": int(st.sizes.state_bytes_per_stream)},
         "gmacs_dense_equivalent": macs_dense / (dt / steps) / 1e9,
@@ -188,10 +176,41 @@ def main():
                              for p in by_layer},
         "roofline": roof,
     }
-    if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(wl)
     st.close()
     net.destroy()
+    return res, wl
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", dest="others", action="store_false",
+                    help="skip the short runs of the other workloads (reported under other_workloads)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (streams are independent: more GPUs "
+              "would each take a share of the streams, no figure for that is produced here)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    res, wl = run_workload(args.config, args.steps, args.warmup)
+    if args.others:
+        # the other multi-stream workloads, a few steps each, as context in the same line
+        res["other_workloads"] = {}
+        for c in (3, 4, 5):
+            if c == args.config:
+                continue
+            o, _ = run_workload(c, None, 1)
+            res["other_workloads"][o["config"]["workload"]] = {
+                k: o[k] for k in ("value", "unit", "ms_per_step", "steps", "dtype", "gmacs_dense_equivalent",
+                                  "gmacs_executed", "roofline")}
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(res))
 
 

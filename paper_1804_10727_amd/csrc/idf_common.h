@@ -121,33 +121,56 @@ struct PoolStep {
 // Whole-net cascade for 1-D nets (one launch per push).
 constexpr int kCasThreads = 512;
 constexpr int kCasKMax = 9;        // kernel height at most
-constexpr int kCasTapsPad = 12;    // taps per (c_in, c_out) pair in the cascade's weight packing: three 16-byte loads
 constexpr int kCasRowsMax = 16;    // rows a layer receives per push at most
 constexpr int kCasMaxLayers = 8;
+constexpr int kCasSlotsMax = kCasRowsMax + kCasKMax - 1;   // output rows a layer touches per push at most
+constexpr int kCasAhead = 4;       // input channels whose weights are in flight per lane
+
+// Lanes of the cascade's workgroup take the output channels (padded to a power of two) and
+// split the input channels round-robin over the kCasThreads / pad groups that result; every
+// lane runs the same number of steps, a multiple of kCasAhead, and the weight packing is
+// zero padded to the input channels those steps reach.
+IDF_HD int cascade1d_steps(int c_in, int c_out)
+{
+    int cp = 1;
+    while (cp < c_out) cp *= 2;
+    const int n_grp = kCasThreads / cp;
+    const int n_q = (c_in + n_grp - 1) / n_grp;
+    return (n_q + kCasAhead - 1) / kCasAhead * kCasAhead;
+}
+IDF_HD int cascade1d_cin_pad(int c_in, int c_out)
+{
+    int cp = 1;
+    while (cp < c_out) cp *= 2;
+    return kCasThreads / cp * cascade1d_steps(c_in, c_out);
+}
 
 // One layer's step in small integers.  Accumulator slot t stands for output row o_base + t.
 struct CascadeLayer {
     int cnt;                 // new input rows (0: the layer does not fire)
     int t_lo, t_fin, t_hi;   // slots [t_lo, t_hi) are live; those below t_fin become final
-    int slot0;               // ring slot of o_base (slot of t is (slot0 + t) mod k_h)
     int d0;                  // first input row of slot 0 minus the first new row
     int at_start;            // 1: the first new row is row 0 of the sample
     int rho;                 // (first new row + padding) mod stride
     int cp_log;              // log2 of c_out rounded up to a power of two
+    int c_in, c_out, k_h, s_h, act;
+    int steps;               // cascade1d_steps(c_in, c_out)
+    int ring_floats;         // k_h * c_out
+    int pad_;
+    const void *w;           // cascade packing, see cascade1d_weight_index
+    const void *bias;
+    void *ring;              // this launch's first stream is at ring + stream * ring_stride floats
+    int64_t ring_stride;
     unsigned char taps[kCasRowsMax];   // per new row: kernel taps landing inside the output
+    unsigned char slot[kCasSlotsMax];  // ring slot of accumulator slot t: (slot0 + t) mod k_h
 };
 
 struct CascadeArgs {
     int n_layers;
-    Geom g[kCasMaxLayers];
+    int n_rows;
     CascadeLayer sched[kCasMaxLayers];
-    const void *w[kCasMaxLayers];        // [c_in][c_out][kCasTapsPad]
-    const void *bias[kCasMaxLayers];
-    void *ring[kCasMaxLayers];           // [stream][slot = o mod k_h][c_out]
-    int64_t ring_stride[kCasMaxLayers];
     const void *in;                      // [position][n_rows][c0]
     int64_t in_stream_stride;
-    int n_rows;
     void *out;                           // output area [stream][out_cap][c_out]
     int64_t out_stride, out_cap, out_slot0;
     unsigned long long *stats;

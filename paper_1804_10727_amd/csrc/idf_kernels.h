@@ -50,6 +50,7 @@ hipError_t launch_copy_out(const CopyOut &a, const StreamSel &sel, int64_t first
 // Whole-net cascade for 1-D float32 nets: can it serve this net (rows_cap[l] = most rows layer
 // l emits per push)?
 bool cascade1d_eligible(int prec, const Geom *g, int n_layers, const int *rows_cap, int max_seg_rows);
+size_t cascade1d_weight_index(int c_in, int c_out, int ci, int co, int ky);
 int cascade1d_slot_off(int S, int rho);   // accumulator slot 0 relative to floor((y0 + p) / S)
 hipError_t launch_cascade1d(const CascadeArgs &a, const StreamSel &sel, const LaunchCtx &lc);
 

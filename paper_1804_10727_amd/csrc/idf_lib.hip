@@ -154,9 +154,9 @@ int make_layout(const idf_net &net, int B, int max_seg, int64_t out_cap, Layout 
     L.cascade1d = cascade1d_eligible(net.precision, net.g.data(), n, L.transit_cap.data(), max_seg);
     for (int l = 0; l < n; ++l) {
         if (net.g[l].kind != IDF_CONV) continue;
-        // the 1-D cascade reads its own packing: [c_in][c_out][kCasTapsPad] floats, taps zero-padded
+        // the 1-D cascade reads its own packing, taps zero-padded to kCasKMax
         size_t wsz = net.w_img[l].size();
-        if (L.cascade1d) wsz = (size_t)net.g[l].c_in * net.g[l].c_out * kCasTapsPad * 4;
+        if (L.cascade1d) wsz = (size_t)cascade1d_cin_pad(net.g[l].c_in, net.g[l].c_out) * net.g[l].c_out * kCasKMax * 4;
         L.w_off[l] = off; off = align_up(off + wsz);
         L.b_off[l] = off; off = align_up(off + net.b_img[l].size());
         L.wm_off[l] = off; off = align_up(off + net.wm_img[l].size());
@@ -298,28 +298,30 @@ int enqueue_cascade1d(idf_streams *s, const StreamSel &sel, const void *dev_rows
     int64_t y0 = r, cnt = n_rows;
     for (int l = 0; l < n; ++l) {
         const Geom &g = net.g[l];
-        a.g[l] = g;
-        a.w[l] = s->ws + s->w_off[l];
-        a.bias[l] = net.b_img[l].empty() ? nullptr : s->ws + s->b_off[l];
-        a.ring[l] = s->ws + s->ring_off[l];
-        a.ring_stride[l] = s->ring_stride[l];
+        CascadeLayer &L = a.sched[l];
+        L.c_in = g.c_in; L.c_out = g.c_out; L.k_h = g.k_h; L.s_h = g.s_h; L.act = g.act;
+        L.steps = cascade1d_steps(g.c_in, g.c_out);
+        L.ring_floats = g.k_h * g.c_out;
+        L.w = s->ws + s->w_off[l];
+        L.bias = net.b_img[l].empty() ? nullptr : s->ws + s->b_off[l];
+        L.ring = s->ws + s->ring_off[l];
+        L.ring_stride = s->ring_stride[l];
+        L.cp_log = 0;
+        while ((1 << L.cp_log) < g.c_out) ++L.cp_log;
         if (cnt > 0) {
             ConvStep c{};
             c.g = g; c.y0 = y0; c.cnt = (int)cnt; c.o_lo = rows_final(g, y0); c.o_fin = rows_final(g, y0 + cnt);
             c.o_hi = std::max(rows_touched(g, y0 + cnt), c.o_fin);
-            c.in_by_position = l == 0; c.to_output = l == n - 1; c.bias = a.bias[l];
+            c.in_by_position = l == 0; c.to_output = l == n - 1; c.bias = L.bias;
             bytes += conv_step_bytes(net, c, sel.n);
-            CascadeLayer &L = a.sched[l];
             const int64_t y0p = y0 + g.p_h;
             L.rho = (int)(y0p % g.s_h);
             const int64_t o_base = y0p / g.s_h + cascade1d_slot_off(g.s_h, L.rho);
             L.cnt = (int)cnt;
             L.t_lo = (int)(c.o_lo - o_base); L.t_fin = (int)(c.o_fin - o_base); L.t_hi = (int)(c.o_hi - o_base);
-            L.slot0 = (int)(((o_base % g.k_h) + g.k_h) % g.k_h);
+            for (int t = 0; t < kCasSlotsMax; ++t) L.slot[t] = (unsigned char)((((o_base + t) % g.k_h) + g.k_h) % g.k_h);
             L.d0 = (int)(o_base * g.s_h - g.p_h - y0);
             L.at_start = y0 == 0;
-            L.cp_log = 0;
-            while ((1 << L.cp_log) < g.c_out) ++L.cp_log;
             for (int j = 0; j < cnt && j < kCasRowsMax; ++j) {
                 int t = 0;
                 for (int ky = 0; ky < g.k_h; ++ky) {
@@ -616,12 +618,12 @@ int idf_open_streams(idf_net *net, int n_streams, int max_seg_rows, int64_t out_
         if (L.cascade1d) {
             const Geom &g = net->g[l];
             const float *src = (const float *)net->w_img[l].data();      // [k_h][1][c_in][c_out]
-            s->cas_w.emplace_back((size_t)g.c_in * g.c_out * kCasTapsPad, 0.f);
+            s->cas_w.emplace_back((size_t)cascade1d_cin_pad(g.c_in, g.c_out) * g.c_out * kCasKMax, 0.f);
             std::vector<float> &img = s->cas_w.back();
             for (int ky = 0; ky < g.k_h; ++ky)
                 for (int ci = 0; ci < g.c_in; ++ci)
                     for (int co = 0; co < g.c_out; ++co)
-                        img[((size_t)ci * g.c_out + co) * kCasTapsPad + ky] = src[((size_t)ky * g.c_in + ci) * g.c_out + co];
+                        img[cascade1d_weight_index(g.c_in, g.c_out, ci, co, ky)] = src[((size_t)ky * g.c_in + ci) * g.c_out + co];
             e = hipMemcpyAsync(s->ws + s->w_off[l], img.data(), img.size() * 4, hipMemcpyHostToDevice, s->st);
         } else {
             e = hipMemcpyAsync(s->ws + s->w_off[l], net->w_img[l].data(), net->w_img[l].size(), hipMemcpyHostToDevice, s->st);

@@ -6,31 +6,35 @@
 // every layer (Fig. 1) -- is brought into LDS when the kernel starts, lives there while the
 // segment runs through the layers, and is written back once at the end.  Per layer the
 // workgroup
-//   1. has the new input rows in LDS, stored per input channel ([channel][row]) so that one
-//      wide LDS read brings all new rows of a channel;
+//   1. has the new input rows in LDS, stored per input channel ([channel][row], rows past the
+//      segment zero) so that one wide LDS read brings all new rows of a channel, next to a bit
+//      per channel telling whether any of them holds an event;
 //   2. accumulates w * dh (event-delivery rule of Sec. 3) with output channels across lanes
 //      and the input channels dealt round-robin to groups of lanes.  Zero values are not
-//      events: a channel that is silent in every new row is skipped, and in short segments
-//      single zero rows are branched over as well.  Each lane keeps the partial sums of all
-//      touched output rows of its channel in registers; the register holding (input row j,
-//      tap ky) is fixed at compile time;
+//      events: a channel without an event in the segment is skipped.  Each lane keeps the
+//      partial sums of all touched output rows of its channel in registers; the register
+//      holding (input row j, tap ky) is fixed at compile time;
 //   3. adds the groups' partial sums in a fixed order to the retained c (or to the bias for
 //      rows touched for the first time), then either activates and emits the row to the next
-//      layer (LDS) -- counting the non-zero values it emits with a wave ballot, they are the
-//      next layer's events -- or stores it back into the LDS copy of the rolling buffer.
+//      layer (LDS) -- a wave ballot of the non-zero values it emits gives the next layer's
+//      events and channel bits -- or keeps it for the rolling buffer.
 //
-// The kernel is a chain of dependent layers on one compute unit, and what limits it is the
-// path from memory: every weight is needed exactly once per push and has to come through the
-// vector memory pipeline of that one compute unit.  Hence the weights are one continuous
-// stream of requests running four input channels ahead of their use, across layer boundaries
-// (the tail of layer l already requests the head of layer l+1); the argument block is copied
-// to LDS in one sweep; and nothing is stored to global memory before the last layer is done
-// (loads, stores and atomics of a wave share one in-order counter here, so a store in the middle
-// of the chain would make every later load wait for the store's acknowledgement).
+// The kernel is a chain of dependent layers on one compute unit with two waves per SIMD, and
+// what limits it is the number of instructions a wave has to issue (one per four cycles):
+// hence per channel a handful of instructions besides the multiply-adds themselves -- running
+// offsets instead of address arithmetic, no per-row masks, one bit test for silence -- and
+// variants for 4, 8 and 16 new rows.  Every weight is needed exactly once per push; the
+// weights are one continuous stream of requests running four input channels ahead of their
+// use, across layer boundaries (the tail of layer l already requests the head of layer l+1).
+// Nothing is stored to global memory before the last layer is done (loads, stores and atomics
+// of a wave share one in-order counter here, so a store in the middle of the chain would make
+// every later load wait for the store's acknowledgement).
 //
 // Serves float32 nets whose layers are all convolutions over a width-1 signal with at most 64
 // channels, kernel height <= 9, stride <= 2 and at most 16 rows per layer per push.  Weights
-// come packed [c_in][c_out][12 taps, zero padded]: three 16-byte loads per channel pair.
+// come in a packing of their own (cascade1d_weight_index): two 16-byte loads and one 4-byte
+// load per channel pair, each wave-wide load covering whole cache lines, input channels
+// padded with zeros so that every lane can run the same number of steps.
 #include "idf.h"
 #include "idf_kernels.h"
 
@@ -40,11 +44,11 @@ namespace {
 
 constexpr int kT = kCasThreads;
 constexpr int kKMax = kCasKMax;
-constexpr int kRowsMax = kCasRowsMax;
-constexpr int kTMax = kRowsMax + kKMax - 1;          // touched output rows at most
+constexpr int kTMax = kCasSlotsMax;                  // touched output rows at most
 constexpr int kCellsPerThread = (kTMax * 64 + kT - 1) / kT;
 constexpr int kXStride = 20;                         // floats per channel in LDS (16 rows + pad, 16-byte aligned)
-constexpr int kAhead = 4;                            // input channels whose weights are in flight
+constexpr int kAhead = kCasAhead;                    // input channels whose weights are in flight
+constexpr int kBatch = 4;                            // input channels whose rows are read from LDS together
 constexpr int kArgWords = (sizeof(CascadeArgs) + 3) / 4;
 constexpr int kRingPerLayer = kKMax * 64;            // floats of rolling buffer per layer at most
 
@@ -58,6 +62,7 @@ struct Lds {
     float red[kT * kTMax];                       // partial sums [group][slot][channel lane]
     float ring[kCasMaxLayers][kRingPerLayer];    // the stream's rolling buffers, [layer][slot][channel]
     float bias[kCasMaxLayers][64];
+    unsigned int chmask[2][2];                   // per x buffer: bit c set when channel c holds an event
     unsigned int events[kCasMaxLayers], taps[kCasMaxLayers];
     uint32_t args[kArgWords];                    // the kernel's argument block
 };
@@ -65,24 +70,27 @@ struct Lds {
 // Pointers read back from LDS have lost their address space; saying "global" again lets the
 // compiler use global (not flat) loads, whose completion order it can count on.
 typedef __attribute__((address_space(1))) float gfloat;
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(1))) v4f gfloat4;
 template <class P> __device__ __forceinline__ const gfloat *as_global(const P *p) { return (const gfloat *)p; }
+// The same for a pointer every lane holds alike: kept in scalar registers, so that a load is
+// "scalar base + per-lane offset" with no 64-bit arithmetic per lane.
+__device__ __forceinline__ const gfloat *uniform_global(const void *p)
+{
+    const uint64_t v = (uint64_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (const gfloat *)(((uint64_t)hi << 32) | lo);
+}
 
-struct Wq { float w[kAhead][kCasTapsPad]; };     // weights of kAhead input channels, all taps
+struct Wq { float w[kAhead][kKMax]; };           // weights of kAhead input channels, all taps
 
-// Where a lane finds its weights of one layer: w[ci][co][taps] with ci = grp, grp + n_grp, ...
+// Where a lane finds its weights of one layer: offsets (in floats) of its first input channel
+// and the step to its next one, for the two 4-tap groups and for the ninth tap.
 struct WSrc {
     const gfloat *w;
-    int c_in, c_out, grp, n_grp, co_c, n_qp;     // n_qp: channels per lane, rounded up to kAhead
+    uint32_t off4, off4b, off8, step4, step8;
+    int n_qp;                                    // input channels per lane, rounded up to kAhead
 };
-
-template <int NIN> __device__ __forceinline__ void load_rows(const float *p, float (&xv)[NIN])
-{
-#pragma unroll
-    for (int q = 0; q < NIN / 4; ++q) {
-        const float4 v = *reinterpret_cast<const float4 *>(p + 4 * q);
-        xv[4 * q] = v.x; xv[4 * q + 1] = v.y; xv[4 * q + 2] = v.z; xv[4 * q + 3] = v.w;
-    }
-}
 
 // Lane mapping of one layer: channel lane within the power-of-two pad of c_out, group of lanes.
 struct Lanes { int cp_log, cp, co, grp, n_grp; };
@@ -94,97 +102,124 @@ __device__ __forceinline__ Lanes lanes_of(int cp_log, int tid)
     return m;
 }
 
-__device__ __forceinline__ WSrc wsrc_of(const CascadeArgs &a, int l, int tid)
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }   // same in every lane: keep it scalar
+
+__device__ __forceinline__ WSrc wsrc_of(const CascadeLayer &sl, int tid)
 {
-    const Lanes m = lanes_of(a.sched[l].cp_log, tid);
+    const int cp_log = uni(sl.cp_log), c_out = uni(sl.c_out);
+    const Lanes m = lanes_of(cp_log, tid);
     WSrc s;
-    s.w = as_global((const float *)a.w[l]);
-    s.c_in = a.g[l].c_in; s.c_out = a.g[l].c_out;
-    s.grp = m.grp; s.n_grp = m.n_grp;
-    s.co_c = m.co < s.c_out ? m.co : s.c_out - 1;        // clamped: loads need no predicate
-    const int n_q = (s.c_in + m.n_grp - 1) / m.n_grp;
-    s.n_qp = (n_q + kAhead - 1) / kAhead * kAhead;
+    s.w = uniform_global(sl.w);
+    s.n_qp = uni(sl.steps);
+    const int co_c = m.co < c_out ? m.co : c_out - 1;        // clamped: loads need no predicate
+    s.off4 = (uint32_t)((m.grp * 2 * c_out + co_c) * 4);
+    s.off4b = s.off4 + (uint32_t)(c_out * 4);
+    s.off8 = (uint32_t)((m.n_grp * s.n_qp * 8 + m.grp) * c_out + co_c);
+    s.step4 = (uint32_t)(m.n_grp * 2 * c_out * 4);
+    s.step8 = (uint32_t)(m.n_grp * c_out);
     return s;
 }
 
-// Request the weights of this lane's q-th input channel of a layer (all taps).  Past the end the
-// last channel is fetched again: the loads stay unconditional.
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(1))) v4f gfloat4;
-__device__ __forceinline__ void fetch_w(float (&w)[kCasTapsPad], const WSrc &s, int q)
+// Request the weights of this lane's q-th input channel of a layer (all taps); q < n_qp, or
+// q < kAhead for the layer after: the packing is padded to that many channels.
+static_assert(kKMax == 9, "the weight packing is two 16-byte groups and one single tap");
+__device__ __forceinline__ void fetch_w(float (&w)[kKMax], const WSrc &s, int q)
 {
-    int ci = s.grp + q * s.n_grp;
-    ci = ci < s.c_in ? ci : s.c_in - 1;
-    const gfloat4 *p = (const gfloat4 *)(s.w + (ci * s.c_out + s.co_c) * kCasTapsPad);
+    const v4f a = *(const gfloat4 *)(s.w + (s.off4 + (uint32_t)q * s.step4));
+    const v4f b = *(const gfloat4 *)(s.w + (s.off4b + (uint32_t)q * s.step4));
+    w[8] = s.w[s.off8 + (uint32_t)q * s.step8];
+    w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w;
+    w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w;
+}
+
+template <int NIN> __device__ __forceinline__ void load_rows(const float *p, float (&xv)[NIN])
+{
 #pragma unroll
-    for (int u = 0; u < kCasTapsPad / 4; ++u) {
-        const v4f v = p[u];
-        w[4 * u] = v.x; w[4 * u + 1] = v.y; w[4 * u + 2] = v.z; w[4 * u + 3] = v.w;
+    for (int q = 0; q < NIN / 4; ++q) {
+        const float4 v = *reinterpret_cast<const float4 *>(p + 4 * q);
+        xv[4 * q] = v.x; xv[4 * q + 1] = v.y; xv[4 * q + 2] = v.z; xv[4 * q + 3] = v.w;
     }
 }
 
 // Step 2 for one layer.  wq holds the weights of this lane's first kAhead input channels; on
-// return it holds those of the next layer's first kAhead channels.
+// return it holds those of the next layer's first kAhead channels.  visit: this lane's view
+// of the channel bits, already shifted so that bit 0 belongs to its first channel (all zero
+// for lanes beyond c_out).
 template <int S, int NIN, int RHO>
-__device__ __forceinline__ void accumulate(const float *__restrict__ x, int cnt, int co, int cp, const WSrc &cur,
-                                           const WSrc &nxt, Wq &wq, float *__restrict__ red)
+__device__ __forceinline__ void accumulate(const float *__restrict__ x, const Lanes &m, const WSrc &cur, const WSrc &nxt,
+                                           Wq &wq, unsigned long long visit, float *__restrict__ red)
 {
     constexpr int OFF = slot_off<S, RHO>();
     constexpr int TS = slot_cnt<S, NIN, RHO>();
     float acc[TS];
 #pragma unroll
     for (int t = 0; t < TS; ++t) acc[t] = 0.f;
-    const int n_q = (cur.c_in + cur.n_grp - 1) / cur.n_grp;  // input channels per lane, at most
+    // moving on by n_grp channels: two shifts of at most 32 (a single shift by 64 or more is not defined)
+    const int sh1 = m.n_grp < 32 ? m.n_grp : 32, sh2 = m.n_grp - sh1 < 32 ? m.n_grp - sh1 : 32;
+    int ci = m.grp;
     for (int qc = 0; qc < cur.n_qp; qc += kAhead) {
-        float xv[kAhead][NIN];
 #pragma unroll
-        for (int p = 0; p < kAhead; ++p) {                    // all LDS reads of the batch first
-            const int ci = cur.grp + (qc + p) * cur.n_grp;
-            load_rows<NIN>(x + (ci < cur.c_in ? ci : cur.c_in - 1) * kXStride, xv[p]);
-        }
+        for (int h = 0; h < kAhead; h += kBatch) {
+            float xv[kBatch][NIN];
 #pragma unroll
-        for (int p = 0; p < kAhead; ++p) {
-            const int ci = cur.grp + (qc + p) * cur.n_grp;
-            bool any = false;
-#pragma unroll
-            for (int j = 0; j < NIN; ++j) {
-                if (j >= cnt) xv[p][j] = 0.f;                 // rows beyond the segment
-                any |= xv[p][j] != 0.f;
+            for (int p = 0; p < kBatch; ++p) {                // all LDS reads of the batch first
+                const int cc = ci + p * m.n_grp;
+                load_rows<NIN>(x + (cc < 63 ? cc : 63) * kXStride, xv[p]);
             }
-            if (qc + p < n_q && ci < cur.c_in && co < cur.c_out && any) {
 #pragma unroll
-                for (int j = 0; j < NIN; ++j) {
-                    if (NIN <= 4 && xv[p][j] == 0.f) continue;            // zero: no event
+            for (int p = 0; p < kBatch; ++p) {
+                if (visit & 1ull) {
 #pragma unroll
-                    for (int ky = 0; ky < kKMax; ++ky) {
-                        if ((RHO + j - ky) % S != 0) continue;            // tap does not land on an output row
-                        const int slot = (RHO + j - ky) / S - OFF;
-                        acc[slot] = fmaf(xv[p][j], wq.w[p][ky], acc[slot]);
+                    for (int j = 0; j < NIN; ++j) {
+#pragma unroll
+                        for (int ky = 0; ky < kKMax; ++ky) {
+                            if ((RHO + j - ky) % S != 0) continue;        // tap does not land on an output row
+                            const int slot = (RHO + j - ky) / S - OFF;
+                            acc[slot] = fmaf(xv[p][j], wq.w[h + p][ky], acc[slot]);
+                        }
                     }
                 }
+                visit = (visit >> sh1) >> sh2;
+                // the slot is free: request what it will hold next, kAhead channels on -- which
+                // at the end of this layer is the head of the next one
+                const int qn = qc + h + p + kAhead;
+                if (qn < cur.n_qp) fetch_w(wq.w[h + p], cur, qn);
+                else fetch_w(wq.w[h + p], nxt, qn - cur.n_qp);
             }
-            // the slot is free: request what it will hold next, kAhead channels on -- which at
-            // the end of this layer is the head of the next one
-            const int qn = qc + p + kAhead;
-            if (qn < cur.n_qp) fetch_w(wq.w[p], cur, qn);
-            else fetch_w(wq.w[p], nxt, qn - cur.n_qp);
+            ci += kBatch * m.n_grp;
         }
     }
-    if (co < cur.c_out) {
+    float *rp = red + ((m.grp * kTMax) << m.cp_log) + m.co;
 #pragma unroll
-        for (int t = 0; t < TS; ++t) red[(cur.grp * kTMax + t) * cp + co] = acc[t];
-    }
+    for (int t = 0; t < TS; ++t) rp[t << m.cp_log] = acc[t];
 }
 
 template <int S, int RHO>
-__device__ __forceinline__ void accumulate_rows(const float *x, int cnt, int co, int cp, const WSrc &cur,
-                                                const WSrc &nxt, Wq &wq, float *red)
+__device__ __forceinline__ void accumulate_rows(const float *x, int cnt, const Lanes &m, const WSrc &cur, const WSrc &nxt,
+                                                Wq &wq, unsigned long long visit, float *red)
 {
-    if (cnt <= 4) accumulate<S, 4, RHO>(x, cnt, co, cp, cur, nxt, wq, red);
-    else accumulate<S, 16, RHO>(x, cnt, co, cp, cur, nxt, wq, red);
+    if (cnt <= 4) accumulate<S, 4, RHO>(x, m, cur, nxt, wq, visit, red);
+    else if (cnt <= 8) accumulate<S, 8, RHO>(x, m, cur, nxt, wq, visit, red);
+    else accumulate<S, 16, RHO>(x, m, cur, nxt, wq, visit, red);
+}
+
+// OR of the cp-bit fields of a 64-bit ballot (cp a power of two): which channels had a hit.
+__device__ __forceinline__ unsigned long long fold_channels(unsigned long long b, int cp)
+{
+    for (int w = 32; w >= cp; w >>= 1) b |= b >> w;
+    return cp == 64 ? b : b & ((1ull << cp) - 1ull);
 }
 
 }  // namespace
+
+// Weight packing: taps 0..7 as [c_in][2][c_out][4] (a wave's 16-byte loads tile whole cache
+// lines), then tap 8 as [c_in][c_out]; c_in counted with its zero padding
+// (cascade1d_cin_pad), kernels shorter than 9 taps zero padded.
+size_t cascade1d_weight_index(int c_in, int c_out, int ci, int co, int ky)
+{
+    if (ky < 8) return (((size_t)ci * 2 + ky / 4) * c_out + co) * 4 + ky % 4;
+    return ((size_t)cascade1d_cin_pad(c_in, c_out) * 8 + ci) * c_out + co;
+}
 
 int cascade1d_slot_off(int S, int rho) { return ceil_div_c(rho - kKMax + 1, S); }
 
@@ -203,89 +238,119 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs a_u
             (const __attribute__((address_space(4))) uint32_t *)__builtin_amdgcn_kernarg_segment_ptr();
         for (int i = tid; i < kArgWords; i += kT) lds.args[i] = kp[i];
         if (tid < kCasMaxLayers) { lds.events[tid] = 0; lds.taps[tid] = 0; }
+        if (tid < 4) lds.chmask[tid >> 1][tid & 1] = 0;
+        for (int i = tid; i < 64 * kXStride / 4; i += kT)       // rows past the segment read as zero
+            reinterpret_cast<float4 *>(lds.x[0])[i] = float4{0.f, 0.f, 0.f, 0.f};
     }
     (void)a_unused;
     lds_barrier();
     const CascadeArgs &a = *reinterpret_cast<const CascadeArgs *>(lds.args);
-    const int n_layers = a.n_layers;
+    const int n_layers = uni(a.n_layers);
 
     // Everything the chain needs from memory except the later weights, requested at once: the
-    // first weights, the new input rows, the rolling buffers and biases of all layers.
+    // first weights, the new input rows, the rolling buffers and biases of all firing layers.
     Wq wq;
-    WSrc cur = wsrc_of(a, 0, tid);
+    WSrc cur = wsrc_of(a.sched[0], tid);
 #pragma unroll
     for (int p = 0; p < kAhead; ++p) fetch_w(wq.w[p], cur, p);
     {
-        const int c0 = a.g[0].c_in, n = a.n_rows * c0;
+        const int c0 = uni(a.sched[0].c_in), n = uni(a.n_rows) * c0;
         const gfloat *in = as_global((const float *)a.in) + (int64_t)(sel.pos0 + si) * a.in_stream_stride;
-        unsigned int ev = 0, taps = 0;                          // the network input's events (eventise step)
-        for (int i = tid; i < n; i += kT) {
-            const int j = i / c0, c = i - j * c0;
-            const float v = in[i];
-            lds.x[0][c * kXStride + j] = v;
-            if (v != 0.f) { ev += 1; taps += a.sched[0].taps[j]; }
+        const float xin = tid < n ? in[tid] : 0.f;               // at most 16 rows x 64 channels: two per lane
+        const float xin2 = tid + kT < n ? in[tid + kT] : 0.f;
+        float rv[kCasMaxLayers][2], bv[kCasMaxLayers];
+#pragma unroll
+        for (int l = 0; l < kCasMaxLayers; ++l) {
+            rv[l][0] = rv[l][1] = bv[l] = 0.f;
+            if (l < n_layers && uni(a.sched[l].cnt) > 0) {
+                const CascadeLayer &sl = a.sched[l];
+                const gfloat *ring = as_global((const float *)sl.ring) + (int64_t)stream * sl.ring_stride;
+                const int n_r = uni(sl.ring_floats);
+                if (tid < n_r) rv[l][0] = ring[tid];
+                if (tid + kT < n_r) rv[l][1] = ring[tid + kT];
+                const gfloat *bias = as_global((const float *)sl.bias);
+                if (bias && tid < uni(sl.c_out)) bv[l] = bias[tid];
+            }
         }
+        unsigned int ev = 0, taps = 0;                          // the network input's events (eventise step)
+        auto put = [&](int i, float v) {
+            if (i < n && v != 0.f) {
+                const int j = i / c0, c = i - j * c0;
+                lds.x[0][c * kXStride + j] = v;
+                atomicOr(&lds.chmask[0][c >> 5], 1u << (c & 31));
+                ev += 1; taps += a.sched[0].taps[j];
+            }
+        };
+        put(tid, xin);
+        put(tid + kT, xin2);
         if (a.stats && __ballot(ev != 0)) {
             for (int off = 32; off > 0; off >>= 1) { ev += __shfl_down(ev, off); taps += __shfl_down(taps, off); }
             if (lane == 0) { atomicAdd(&lds.events[0], ev); atomicAdd(&lds.taps[0], taps); }
         }
-        for (int l = 0; l < n_layers; ++l) {
-            const gfloat *ring = as_global((const float *)a.ring[l]) + (int64_t)stream * a.ring_stride[l];
-            const int n_r = a.g[l].k_h * a.g[l].c_out;
-            for (int i = tid; i < n_r; i += kT) lds.ring[l][i] = ring[i];
-            const gfloat *bias = as_global((const float *)a.bias[l]);
-            if (tid < a.g[l].c_out) lds.bias[l][tid] = bias ? bias[tid] : 0.f;
+#pragma unroll
+        for (int l = 0; l < kCasMaxLayers; ++l) {
+            if (l < n_layers && uni(a.sched[l].cnt) > 0) {
+                lds.ring[l][tid] = rv[l][0];
+                if (tid + kT < kRingPerLayer) lds.ring[l][tid + kT] = rv[l][1];
+                if (tid < 64) lds.bias[l][tid] = bv[l];
+            }
         }
     }
     lds_barrier();
 
     int cur_buf = 0;
     for (int l = 0; l < n_layers; ++l) {
-        // this layer's step, copied out of LDS once (the barriers below would force re-reads)
-        const CascadeLayer s = a.sched[l];
-        const int cnt = s.cnt;
+        // this layer's step: the scalars copied out of LDS once (the barriers below would force
+        // re-reads), the small tables read in place
+        const CascadeLayer &sl = a.sched[l];
+        const int cnt = uni(sl.cnt);
         if (cnt <= 0) break;
-        const int c_out = cur.c_out, K = a.g[l].k_h, S = a.g[l].s_h, act = a.g[l].act;
+        const int t_lo = uni(sl.t_lo), t_fin = uni(sl.t_fin), t_hi = uni(sl.t_hi), d0 = uni(sl.d0);
+        const int at_start = uni(sl.at_start), rho = uni(sl.rho), cp_log = uni(sl.cp_log);
+        const int c_out = uni(sl.c_out), S = uni(sl.s_h), act = uni(sl.act);
+        const unsigned char *slot_of = sl.slot;
         const float *x = lds.x[cur_buf];
-        const bool more = l + 1 < n_layers && a.sched[l + 1].cnt > 0;
-        const WSrc nxt = more ? wsrc_of(a, l + 1, tid) : cur;
+        float *xn = lds.x[cur_buf ^ 1];
+        const bool more = l + 1 < n_layers && uni(a.sched[l + 1].cnt) > 0;
+        const WSrc nxt = more ? wsrc_of(a.sched[l + 1], tid) : cur;
         // per emitted row: the taps it lands on in layer l+1 (read by one lane per wave, from LDS)
         const unsigned char *taps_next = a.sched[more ? l + 1 : l].taps;
+        const Lanes m = lanes_of(cp_log, tid);
 
-        // retained rows are read before anybody stores (a finished and a new row can share a slot)
-        const Lanes m = lanes_of(s.cp_log, tid);
-        float init[kCellsPerThread];
-#pragma unroll
-        for (int q = 0; q < kCellsPerThread; ++q) {
-            const int idx = tid + q * kT;
-            init[q] = 0.f;
-            const int c = idx & (m.cp - 1), t = idx >> m.cp_log;
-            if (t < s.t_lo || t >= s.t_hi || c >= c_out) continue;
-            const bool fresh = s.d0 + t * S >= 0 || s.at_start;   // first input row of the row is new
-            init[q] = fresh ? lds.bias[l][c] : lds.ring[l][((s.slot0 + t) % K) * c_out + c];
-        }
+        // this lane's view of the channel bits: bit q*n_grp of it belongs to its q-th channel
+        unsigned long long visit = ((unsigned long long)lds.chmask[cur_buf][1] << 32) | lds.chmask[cur_buf][0];
+        visit = (m.grp < 64 && m.co < c_out) ? visit >> m.grp : 0ull;
+        // the other buffer is free (its readers are past the previous layer's first barrier):
+        // clear it for the rows this layer emits
+        for (int i = tid; i < 64 * kXStride / 4; i += kT) reinterpret_cast<float4 *>(xn)[i] = float4{0.f, 0.f, 0.f, 0.f};
+        if (tid < 2) lds.chmask[cur_buf ^ 1][tid] = 0;
 
-        if (S == 1) accumulate_rows<1, 0>(x, cnt, m.co, m.cp, cur, nxt, wq, lds.red);
-        else if (s.rho == 0) accumulate_rows<2, 0>(x, cnt, m.co, m.cp, cur, nxt, wq, lds.red);
-        else accumulate_rows<2, 1>(x, cnt, m.co, m.cp, cur, nxt, wq, lds.red);
+        if (S == 1) accumulate_rows<1, 0>(x, cnt, m, cur, nxt, wq, visit, lds.red);
+        else if (rho == 0) accumulate_rows<2, 0>(x, cnt, m, cur, nxt, wq, visit, lds.red);
+        else accumulate_rows<2, 1>(x, cnt, m, cur, nxt, wq, visit, lds.red);
         lds_barrier();
 
         const bool last = l == n_layers - 1;
         gfloat *out = (gfloat *)a.out + (int64_t)stream * a.out_stride;
         const int64_t out_slot0 = a.out_slot0, out_cap = a.out_cap;
         const bool count = a.stats && more;
-        float *xn = lds.x[cur_buf ^ 1];
+        const int n_cells = (t_hi - t_lo) << cp_log;
         unsigned int ev = 0, taps = 0;
+        float keep[kCellsPerThread];                 // rows that stay in the rolling buffer
+        int keep_at[kCellsPerThread];
 #pragma unroll
         for (int q = 0; q < kCellsPerThread; ++q) {
             const int idx = tid + q * kT;
-            const int c = idx & (m.cp - 1), t = idx >> m.cp_log;
-            const bool live = t >= s.t_lo && t < s.t_hi && c < c_out;
+            const int c = idx & (m.cp - 1), t = t_lo + (idx >> cp_log);
+            const bool live = idx < n_cells && c < c_out;
             bool emitted_nz = false;
+            keep_at[q] = -1;
             if (live) {
-                float sum = init[q];
-                const float *rp = lds.red + (t << m.cp_log) + c;
-                const int g_stride = kTMax << m.cp_log;
+                const bool fresh = d0 + t * S >= 0 || at_start;   // first input row of the row is new
+                const int at = slot_of[t] * c_out + c;
+                float sum = fresh ? lds.bias[l][c] : lds.ring[l][at];
+                const float *rp = lds.red + (t << cp_log) + c;
+                const int g_stride = kTMax << cp_log;
                 for (int gi = 0; gi < m.n_grp; gi += 8) {     // n_grp is a multiple of 8; fixed order
                     float v[8];
 #pragma unroll
@@ -293,52 +358,72 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs a_u
 #pragma unroll
                     for (int u = 0; u < 8; ++u) sum += v[u];
                 }
-                if (t < s.t_fin) {
+                if (t < t_fin) {
                     const float h = act == IDF_ACT_NONE ? sum : fmaxf(sum, 0.f);
                     if (last) {
-                        int64_t slot = out_slot0 + (t - s.t_lo);
+                        int64_t slot = out_slot0 + (t - t_lo);
                         if (slot >= out_cap) slot -= out_cap;
                         out[slot * c_out + c] = h;
-                    } else {
-                        xn[c * kXStride + (t - s.t_lo)] = h;
-                        emitted_nz = h != 0.f;
+                    } else if (h != 0.f) {
+                        xn[c * kXStride + (t - t_lo)] = h;
+                        emitted_nz = true;
                     }
                 } else {
-                    lds.ring[l][((s.slot0 + t) % K) * c_out + c] = sum;
+                    keep[q] = sum; keep_at[q] = at;           // stored once every reader of the buffer is done
                 }
             }
             // The non-zero values just emitted are the next layer's events: ballot them.  A wave
             // covers 64 / cp consecutive rows, cp lanes each.
-            if (count) {
+            if (more) {
                 const unsigned long long nzb = __ballot(emitted_nz);
                 if (nzb && lane == 0) {
-                    const int t0 = (tid + q * kT) >> m.cp_log;            // row of lane 0
-                    const unsigned long long rowmask = m.cp == 64 ? ~0ull : ((1ull << m.cp) - 1ull);
-                    for (int rr = 0; rr < (64 >> m.cp_log); ++rr) {
-                        const int n = __popcll((nzb >> (rr << m.cp_log)) & rowmask);
-                        const int j = t0 + rr - s.t_lo;
-                        if (n && j >= 0 && j < kRowsMax) { ev += n; taps += n * taps_next[j]; }
+                    const unsigned long long chans = fold_channels(nzb, m.cp);
+                    if ((uint32_t)chans) atomicOr(&lds.chmask[cur_buf ^ 1][0], (uint32_t)chans);
+                    if ((uint32_t)(chans >> 32)) atomicOr(&lds.chmask[cur_buf ^ 1][1], (uint32_t)(chans >> 32));
+                    if (count) {
+                        const int j0 = (idx >> cp_log);                       // new row of lane 0
+                        const unsigned long long rowmask = m.cp == 64 ? ~0ull : ((1ull << m.cp) - 1ull);
+                        for (int rr = 0; rr < (64 >> cp_log); ++rr) {
+                            const int n = __popcll((nzb >> (rr << cp_log)) & rowmask);
+                            if (n) { ev += n; taps += n * taps_next[j0 + rr]; }
+                        }
                     }
                 }
             }
         }
         if (count && lane == 0 && ev) { atomicAdd(&lds.events[l + 1], ev); atomicAdd(&lds.taps[l + 1], taps); }
         lds_barrier();
+#pragma unroll
+        for (int q = 0; q < kCellsPerThread; ++q)
+            if (keep_at[q] >= 0) lds.ring[l][keep_at[q]] = keep[q];
         cur_buf ^= 1;
         cur = nxt;
     }
+    lds_barrier();
 
     // the rolling buffers go back to memory, the counters are added up
-    for (int l = 0; l < n_layers; ++l) {
-        if (a.sched[l].cnt <= 0) break;
-        gfloat *ring = (gfloat *)a.ring[l] + (int64_t)stream * a.ring_stride[l];
-        const int n_r = a.g[l].k_h * a.g[l].c_out;
-        for (int i = tid; i < n_r; i += kT) ring[i] = lds.ring[l][i];
+    {
+        float rv[kCasMaxLayers][2];
+#pragma unroll
+        for (int l = 0; l < kCasMaxLayers; ++l) {
+            rv[l][0] = lds.ring[l][tid];
+            rv[l][1] = tid + kT < kRingPerLayer ? lds.ring[l][tid + kT] : 0.f;
+        }
+#pragma unroll
+        for (int l = 0; l < kCasMaxLayers; ++l) {
+            if (l < n_layers && uni(a.sched[l].cnt) > 0) {
+                const CascadeLayer &sl = a.sched[l];
+                gfloat *ring = (gfloat *)sl.ring + (int64_t)stream * sl.ring_stride;
+                const int n_r = uni(sl.ring_floats);
+                if (tid < n_r) ring[tid] = rv[l][0];
+                if (tid + kT < n_r) ring[tid + kT] = rv[l][1];
+            }
+        }
     }
     if (a.stats && tid < n_layers && a.sched[tid].cnt > 0) {
         unsigned long long *dst = a.stats + ((int64_t)stream * n_layers + tid) * 2;
         if (lds.events[tid]) atomicAdd(dst, (unsigned long long)lds.events[tid]);
-        if (lds.taps[tid]) atomicAdd(dst + 1, (unsigned long long)lds.taps[tid] * a.g[tid].c_out);
+        if (lds.taps[tid]) atomicAdd(dst + 1, (unsigned long long)lds.taps[tid] * a.sched[tid].c_out);
     }
 }
 
