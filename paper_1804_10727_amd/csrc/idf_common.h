@@ -156,13 +156,14 @@ struct CascadeLayer {
     int c_in, c_out, k_h, s_h, act;
     int steps;               // cascade1d_steps(c_in, c_out)
     int ring_floats;         // k_h * c_out
-    int pad_;
+    int slot0;               // ring slot of accumulator slot 0 (slot of t is (slot0 + t) mod k_h)
     const void *w;           // cascade packing, see cascade1d_weight_index
     const void *bias;
     void *ring;              // this launch's first stream is at ring + stream * ring_stride floats
     int64_t ring_stride;
+    int rcp_k;               // ceil(65536 / k_h): (v * rcp_k) >> 16 == v / k_h for the small v that occur
+    int pad_;
     unsigned char taps[kCasRowsMax];   // per new row: kernel taps landing inside the output
-    unsigned char slot[kCasSlotsMax];  // ring slot of accumulator slot t: (slot0 + t) mod k_h
 };
 
 struct CascadeArgs {

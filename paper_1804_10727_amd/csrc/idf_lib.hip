@@ -302,6 +302,7 @@ int enqueue_cascade1d(idf_streams *s, const StreamSel &sel, const void *dev_rows
         L.c_in = g.c_in; L.c_out = g.c_out; L.k_h = g.k_h; L.s_h = g.s_h; L.act = g.act;
         L.steps = cascade1d_steps(g.c_in, g.c_out);
         L.ring_floats = g.k_h * g.c_out;
+        L.rcp_k = (65536 + g.k_h - 1) / g.k_h;
         L.w = s->ws + s->w_off[l];
         L.bias = net.b_img[l].empty() ? nullptr : s->ws + s->b_off[l];
         L.ring = s->ws + s->ring_off[l];
@@ -319,7 +320,7 @@ int enqueue_cascade1d(idf_streams *s, const StreamSel &sel, const void *dev_rows
             const int64_t o_base = y0p / g.s_h + cascade1d_slot_off(g.s_h, L.rho);
             L.cnt = (int)cnt;
             L.t_lo = (int)(c.o_lo - o_base); L.t_fin = (int)(c.o_fin - o_base); L.t_hi = (int)(c.o_hi - o_base);
-            for (int t = 0; t < kCasSlotsMax; ++t) L.slot[t] = (unsigned char)((((o_base + t) % g.k_h) + g.k_h) % g.k_h);
+            L.slot0 = (int)(((o_base % g.k_h) + g.k_h) % g.k_h);
             L.d0 = (int)(o_base * g.s_h - g.p_h - y0);
             L.at_start = y0 == 0;
             for (int j = 0; j < cnt && j < kCasRowsMax; ++j) {

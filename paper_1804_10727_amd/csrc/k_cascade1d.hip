@@ -4,8 +4,8 @@
 //
 // The stream's whole retained state -- the rolling buffer of K rows of pre-activations c of
 // every layer (Fig. 1) -- is brought into LDS when the kernel starts, lives there while the
-// segment runs through the layers, and is written back once at the end.  Per layer the
-// workgroup
+// segment runs through the layers; rows that stay unfinished go back to memory as they are
+// summed.  Per layer the workgroup
 //   1. has the new input rows in LDS, stored per input channel ([channel][row], rows past the
 //      segment zero) so that one wide LDS read brings all new rows of a channel, next to a bit
 //      per channel telling whether any of them holds an event;
@@ -26,9 +26,6 @@
 // variants for 4, 8 and 16 new rows.  Every weight is needed exactly once per push; the
 // weights are one continuous stream of requests running four input channels ahead of their
 // use, across layer boundaries (the tail of layer l already requests the head of layer l+1).
-// Nothing is stored to global memory before the last layer is done (loads, stores and atomics
-// of a wave share one in-order counter here, so a store in the middle of the chain would make
-// every later load wait for the store's acknowledgement).
 //
 // Serves float32 nets whose layers are all convolutions over a width-1 signal with at most 64
 // channels, kernel height <= 9, stride <= 2 and at most 16 rows per layer per push.  Weights
@@ -63,7 +60,7 @@ struct Lds {
     float ring[kCasMaxLayers][kRingPerLayer];    // the stream's rolling buffers, [layer][slot][channel]
     float bias[kCasMaxLayers][64];
     unsigned int chmask[2][2];                   // per x buffer: bit c set when channel c holds an event
-    unsigned int events[kCasMaxLayers], taps[kCasMaxLayers];
+    unsigned long long nzlog[kCasMaxLayers][kT / 64][kCellsPerThread];   // ballots of emitted non-zeros
     uint32_t args[kArgWords];                    // the kernel's argument block
 };
 
@@ -223,73 +220,98 @@ size_t cascade1d_weight_index(int c_in, int c_out, int ci, int co, int ky)
 
 int cascade1d_slot_off(int S, int rho) { return ceil_div_c(rho - kKMax + 1, S); }
 
-__global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs a_unused, const StreamSel sel)
+__global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka, const StreamSel sel)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     Lds &lds = *reinterpret_cast<Lds *>(lds_raw);
     const int tid = threadIdx.x, lane = tid & 63;
     const int si = blockIdx.x;
     const int stream = sel_stream(sel, si);
+    const int n_layers = ka.n_layers;
 
     // The argument block (first kernel argument, offset 0 of the kernel-argument segment) goes to
-    // LDS in one sweep: per-layer descriptors then cost an LDS read instead of a memory round trip.
+    // LDS in one sweep: inside the chain a layer's descriptor then costs an LDS read instead of a
+    // memory round trip.  The prologue itself reads the arguments as scalars, so that everything
+    // the chain needs from memory except the later weights is requested at once, next to that
+    // sweep: the first weights, the new input rows, the rolling buffers and biases of the firing
+    // layers.
+    constexpr int kArgPerLane = (kArgWords + kT - 1) / kT;
+    uint32_t argw[kArgPerLane];
     {
         const __attribute__((address_space(4))) uint32_t *kp =
             (const __attribute__((address_space(4))) uint32_t *)__builtin_amdgcn_kernarg_segment_ptr();
-        for (int i = tid; i < kArgWords; i += kT) lds.args[i] = kp[i];
-        if (tid < kCasMaxLayers) { lds.events[tid] = 0; lds.taps[tid] = 0; }
+#pragma unroll
+        for (int u = 0; u < kArgPerLane; ++u) {
+            const int i = tid + u * kT;
+            argw[u] = kp[i < kArgWords ? i : kArgWords - 1];
+        }
+    }
+    Wq wq;
+    WSrc cur = wsrc_of(ka.sched[0], tid);
+#pragma unroll
+    for (int p = 0; p < kAhead; ++p) fetch_w(wq.w[p], cur, p);
+    const int c0 = ka.sched[0].c_in, n_in = ka.n_rows * c0;      // at most 16 rows x 64 channels: two per lane
+    float xin[2];
+    {
+        const gfloat *in = as_global((const float *)ka.in) + (int64_t)(sel.pos0 + si) * ka.in_stream_stride;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int i = tid + u * kT;
+            xin[u] = in[i < n_in ? i : n_in - 1];
+        }
+    }
+    float rv[kCasMaxLayers][2], bv[kCasMaxLayers];
+#pragma unroll
+    for (int l = 0; l < kCasMaxLayers; ++l) {
+        rv[l][0] = rv[l][1] = bv[l] = 0.f;
+        if (l < n_layers && ka.sched[l].cnt > 0) {
+            const CascadeLayer &sl = ka.sched[l];
+            const gfloat *ring = as_global((const float *)sl.ring) + (int64_t)stream * sl.ring_stride;
+            const int n_r = sl.ring_floats;
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int i = tid + u * kT;
+                rv[l][u] = ring[i < n_r ? i : n_r - 1];
+            }
+            const gfloat *bias = as_global((const float *)sl.bias);
+            if (bias) bv[l] = bias[tid < sl.c_out ? tid : sl.c_out - 1];
+        }
+    }
+    {
         if (tid < 4) lds.chmask[tid >> 1][tid & 1] = 0;
         for (int i = tid; i < 64 * kXStride / 4; i += kT)       // rows past the segment read as zero
             reinterpret_cast<float4 *>(lds.x[0])[i] = float4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < kArgPerLane; ++u) {
+            const int i = tid + u * kT;
+            if (i < kArgWords) lds.args[i] = argw[u];
+        }
     }
-    (void)a_unused;
     lds_barrier();
     const CascadeArgs &a = *reinterpret_cast<const CascadeArgs *>(lds.args);
-    const int n_layers = uni(a.n_layers);
-
-    // Everything the chain needs from memory except the later weights, requested at once: the
-    // first weights, the new input rows, the rolling buffers and biases of all firing layers.
-    Wq wq;
-    WSrc cur = wsrc_of(a.sched[0], tid);
-#pragma unroll
-    for (int p = 0; p < kAhead; ++p) fetch_w(wq.w[p], cur, p);
     {
-        const int c0 = uni(a.sched[0].c_in), n = uni(a.n_rows) * c0;
-        const gfloat *in = as_global((const float *)a.in) + (int64_t)(sel.pos0 + si) * a.in_stream_stride;
-        const float xin = tid < n ? in[tid] : 0.f;               // at most 16 rows x 64 channels: two per lane
-        const float xin2 = tid + kT < n ? in[tid + kT] : 0.f;
-        float rv[kCasMaxLayers][2], bv[kCasMaxLayers];
-#pragma unroll
-        for (int l = 0; l < kCasMaxLayers; ++l) {
-            rv[l][0] = rv[l][1] = bv[l] = 0.f;
-            if (l < n_layers && uni(a.sched[l].cnt) > 0) {
-                const CascadeLayer &sl = a.sched[l];
-                const gfloat *ring = as_global((const float *)sl.ring) + (int64_t)stream * sl.ring_stride;
-                const int n_r = uni(sl.ring_floats);
-                if (tid < n_r) rv[l][0] = ring[tid];
-                if (tid + kT < n_r) rv[l][1] = ring[tid + kT];
-                const gfloat *bias = as_global((const float *)sl.bias);
-                if (bias && tid < uni(sl.c_out)) bv[l] = bias[tid];
-            }
-        }
         unsigned int ev = 0, taps = 0;                          // the network input's events (eventise step)
-        auto put = [&](int i, float v) {
-            if (i < n && v != 0.f) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int i = tid + u * kT;
+            if (i < n_in && xin[u] != 0.f) {
                 const int j = i / c0, c = i - j * c0;
-                lds.x[0][c * kXStride + j] = v;
+                lds.x[0][c * kXStride + j] = xin[u];
                 atomicOr(&lds.chmask[0][c >> 5], 1u << (c & 31));
                 ev += 1; taps += a.sched[0].taps[j];
             }
-        };
-        put(tid, xin);
-        put(tid + kT, xin2);
-        if (a.stats && __ballot(ev != 0)) {
+        }
+        if (ka.stats && __ballot(ev != 0)) {
             for (int off = 32; off > 0; off >>= 1) { ev += __shfl_down(ev, off); taps += __shfl_down(taps, off); }
-            if (lane == 0) { atomicAdd(&lds.events[0], ev); atomicAdd(&lds.taps[0], taps); }
+            if (lane == 0) {
+                unsigned long long *dst = ka.stats + (int64_t)stream * n_layers * 2;
+                atomicAdd(dst, (unsigned long long)ev);
+                atomicAdd(dst + 1, (unsigned long long)taps * ka.sched[0].c_out);
+            }
         }
 #pragma unroll
         for (int l = 0; l < kCasMaxLayers; ++l) {
-            if (l < n_layers && uni(a.sched[l].cnt) > 0) {
+            if (l < n_layers && ka.sched[l].cnt > 0) {
                 lds.ring[l][tid] = rv[l][0];
                 if (tid + kT < kRingPerLayer) lds.ring[l][tid + kT] = rv[l][1];
                 if (tid < 64) lds.bias[l][tid] = bv[l];
@@ -300,15 +322,15 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs a_u
 
     int cur_buf = 0;
     for (int l = 0; l < n_layers; ++l) {
-        // this layer's step: the scalars copied out of LDS once (the barriers below would force
-        // re-reads), the small tables read in place
+        // this layer's step: scalars copied out of LDS once (the barriers below would force re-reads)
         const CascadeLayer &sl = a.sched[l];
         const int cnt = uni(sl.cnt);
         if (cnt <= 0) break;
         const int t_lo = uni(sl.t_lo), t_fin = uni(sl.t_fin), t_hi = uni(sl.t_hi), d0 = uni(sl.d0);
         const int at_start = uni(sl.at_start), rho = uni(sl.rho), cp_log = uni(sl.cp_log);
         const int c_out = uni(sl.c_out), S = uni(sl.s_h), act = uni(sl.act);
-        const unsigned char *slot_of = sl.slot;
+        const int K = uni(sl.k_h), slot0 = uni(sl.slot0), rcp_k = uni(sl.rcp_k);
+        gfloat *ringg = (gfloat *)uniform_global(sl.ring) + (int64_t)stream * sl.ring_stride;
         const float *x = lds.x[cur_buf];
         float *xn = lds.x[cur_buf ^ 1];
         const bool more = l + 1 < n_layers && uni(a.sched[l + 1].cnt) > 0;
@@ -330,102 +352,122 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs a_u
         else accumulate_rows<2, 1>(x, cnt, m, cur, nxt, wq, visit, lds.red);
         lds_barrier();
 
+        // Step 3.  Every lane owns up to kCellsPerThread (row, channel) cells; all LDS reads of
+        // all its cells are issued before anything is summed.
         const bool last = l == n_layers - 1;
-        gfloat *out = (gfloat *)a.out + (int64_t)stream * a.out_stride;
-        const int64_t out_slot0 = a.out_slot0, out_cap = a.out_cap;
-        const bool count = a.stats && more;
-        const int n_cells = (t_hi - t_lo) << cp_log;
-        unsigned int ev = 0, taps = 0;
-        float keep[kCellsPerThread];                 // rows that stay in the rolling buffer
-        int keep_at[kCellsPerThread];
+        const int rows_per_pass = kT >> cp_log;
+        const int c = tid & (m.cp - 1), cc = c < c_out ? c : c_out - 1;
+        int t_of[kCellsPerThread], at[kCellsPerThread];
+        bool live[kCellsPerThread];
+        float sum[kCellsPerThread], ringv[kCellsPerThread];
+        const float bias_c = lds.bias[l][cc];
 #pragma unroll
         for (int q = 0; q < kCellsPerThread; ++q) {
-            const int idx = tid + q * kT;
-            const int c = idx & (m.cp - 1), t = t_lo + (idx >> cp_log);
-            const bool live = idx < n_cells && c < c_out;
-            bool emitted_nz = false;
-            keep_at[q] = -1;
-            if (live) {
-                const bool fresh = d0 + t * S >= 0 || at_start;   // first input row of the row is new
-                const int at = slot_of[t] * c_out + c;
-                float sum = fresh ? lds.bias[l][c] : lds.ring[l][at];
-                const float *rp = lds.red + (t << cp_log) + c;
-                const int g_stride = kTMax << cp_log;
-                for (int gi = 0; gi < m.n_grp; gi += 8) {     // n_grp is a multiple of 8; fixed order
-                    float v[8];
+            const int t = t_lo + (tid >> cp_log) + q * rows_per_pass;
+            live[q] = t < t_hi && c < c_out;
+            t_of[q] = t < t_hi ? t : (t_hi > t_lo ? t_hi - 1 : t_lo);   // clamped: reads need no predicate
+            const int v = slot0 + t_of[q];
+            at[q] = (v - ((v * rcp_k) >> 16) * K) * c_out + cc;   // ring slot (slot0 + t) mod K
+            ringv[q] = lds.ring[l][at[q]];
+        }
+        {
+            const int g_stride = kTMax << cp_log;
+            bool wave_has[kCellsPerThread];                   // some lane of this wave owns a live cell q
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) v[u] = rp[(gi + u) * g_stride];
+            for (int q = 0; q < kCellsPerThread; ++q) wave_has[q] = __ballot(live[q]) != 0ull;
+            float part[kCellsPerThread][8];
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) sum += v[u];
+            for (int q = 0; q < kCellsPerThread; ++q)
+                if (wave_has[q]) {
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) part[q][u] = lds.red[(t_of[q] << cp_log) + c + u * g_stride];
                 }
-                if (t < t_fin) {
-                    const float h = act == IDF_ACT_NONE ? sum : fmaxf(sum, 0.f);
+#pragma unroll
+            for (int q = 0; q < kCellsPerThread; ++q) {
+                const bool fresh = d0 + t_of[q] * S >= 0 || at_start;   // first input row of the row is new
+                sum[q] = fresh ? bias_c : ringv[q];
+                if (wave_has[q]) {
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) sum[q] += part[q][u];    // fixed order
+                }
+            }
+            for (int gi = 8; gi < m.n_grp; gi += 8) {         // n_grp is a multiple of 8
+#pragma unroll
+                for (int q = 0; q < kCellsPerThread; ++q)
+                    if (wave_has[q]) {
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) part[q][u] = lds.red[(t_of[q] << cp_log) + c + (gi + u) * g_stride];
+                    }
+#pragma unroll
+                for (int q = 0; q < kCellsPerThread; ++q)
+                    if (wave_has[q]) {
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) sum[q] += part[q][u];
+                    }
+            }
+        }
+        unsigned long long nzb[kCellsPerThread];
+#pragma unroll
+        for (int q = 0; q < kCellsPerThread; ++q) {
+            bool emitted_nz = false;
+            if (live[q]) {
+                if (t_of[q] < t_fin) {
+                    const float h = act == IDF_ACT_NONE ? sum[q] : fmaxf(sum[q], 0.f);
                     if (last) {
-                        int64_t slot = out_slot0 + (t - t_lo);
-                        if (slot >= out_cap) slot -= out_cap;
-                        out[slot * c_out + c] = h;
+                        int64_t slot = ka.out_slot0 + (t_of[q] - t_lo);
+                        if (slot >= ka.out_cap) slot -= ka.out_cap;
+                        ((gfloat *)ka.out)[(int64_t)stream * ka.out_stride + slot * c_out + c] = h;
                     } else if (h != 0.f) {
-                        xn[c * kXStride + (t - t_lo)] = h;
+                        xn[c * kXStride + (t_of[q] - t_lo)] = h;
                         emitted_nz = true;
                     }
                 } else {
-                    keep[q] = sum; keep_at[q] = at;           // stored once every reader of the buffer is done
+                    ringg[at[q]] = sum[q];                    // stays in the rolling buffer
                 }
             }
-            // The non-zero values just emitted are the next layer's events: ballot them.  A wave
-            // covers 64 / cp consecutive rows, cp lanes each.
-            if (more) {
-                const unsigned long long nzb = __ballot(emitted_nz);
-                if (nzb && lane == 0) {
-                    const unsigned long long chans = fold_channels(nzb, m.cp);
-                    if ((uint32_t)chans) atomicOr(&lds.chmask[cur_buf ^ 1][0], (uint32_t)chans);
-                    if ((uint32_t)(chans >> 32)) atomicOr(&lds.chmask[cur_buf ^ 1][1], (uint32_t)(chans >> 32));
-                    if (count) {
-                        const int j0 = (idx >> cp_log);                       // new row of lane 0
-                        const unsigned long long rowmask = m.cp == 64 ? ~0ull : ((1ull << m.cp) - 1ull);
-                        for (int rr = 0; rr < (64 >> cp_log); ++rr) {
-                            const int n = __popcll((nzb >> (rr << cp_log)) & rowmask);
-                            if (n) { ev += n; taps += n * taps_next[j0 + rr]; }
-                        }
-                    }
-                }
+            nzb[q] = more ? __ballot(emitted_nz) : 0ull;
+        }
+        // The non-zero values just emitted are the next layer's events: their channels get their
+        // bits now; the ballots are kept and counted after the chain.
+        if (more && lane == 0) {
+#pragma unroll
+            for (int q = 0; q < kCellsPerThread; ++q) lds.nzlog[l][tid >> 6][q] = nzb[q];
+            if (nzb[0] | nzb[1] | nzb[2]) {
+                const unsigned long long chans = fold_channels(nzb[0] | nzb[1] | nzb[2], m.cp);
+                if ((uint32_t)chans) atomicOr(&lds.chmask[cur_buf ^ 1][0], (uint32_t)chans);
+                if ((uint32_t)(chans >> 32)) atomicOr(&lds.chmask[cur_buf ^ 1][1], (uint32_t)(chans >> 32));
             }
         }
-        if (count && lane == 0 && ev) { atomicAdd(&lds.events[l + 1], ev); atomicAdd(&lds.taps[l + 1], taps); }
         lds_barrier();
-#pragma unroll
-        for (int q = 0; q < kCellsPerThread; ++q)
-            if (keep_at[q] >= 0) lds.ring[l][keep_at[q]] = keep[q];
         cur_buf ^= 1;
         cur = nxt;
     }
-    lds_barrier();
 
-    // the rolling buffers go back to memory, the counters are added up
-    {
-        float rv[kCasMaxLayers][2];
-#pragma unroll
-        for (int l = 0; l < kCasMaxLayers; ++l) {
-            rv[l][0] = lds.ring[l][tid];
-            rv[l][1] = tid + kT < kRingPerLayer ? lds.ring[l][tid + kT] : 0.f;
-        }
-#pragma unroll
-        for (int l = 0; l < kCasMaxLayers; ++l) {
-            if (l < n_layers && uni(a.sched[l].cnt) > 0) {
-                const CascadeLayer &sl = a.sched[l];
-                gfloat *ring = (gfloat *)sl.ring + (int64_t)stream * sl.ring_stride;
-                const int n_r = uni(sl.ring_floats);
-                if (tid < n_r) ring[tid] = rv[l][0];
-                if (tid + kT < n_r) ring[tid + kT] = rv[l][1];
+    // Events and executed taps of layers 1..: one lane per kept ballot (layer, wave, cell).  A
+    // wave's ballot covers 64 / cp consecutive new rows of the layer before, cp lanes each.
+    if (ka.stats && tid < (n_layers - 1) * (kT / 64) * kCellsPerThread) {
+        const int l = tid / ((kT / 64) * kCellsPerThread), r = tid - l * ((kT / 64) * kCellsPerThread);
+        const int wv = r / kCellsPerThread, q = r - wv * kCellsPerThread;
+        if (a.sched[l].cnt > 0 && a.sched[l + 1].cnt > 0) {
+            const unsigned long long nz = lds.nzlog[l][wv][q];
+            if (nz) {
+                const int cp_log = a.sched[l].cp_log, cp = 1 << cp_log;
+                const int j0 = ((wv * 64) >> cp_log) + q * (kT >> cp_log);
+                const unsigned long long rowmask = cp == 64 ? ~0ull : ((1ull << cp) - 1ull);
+                unsigned int ev = 0, taps = 0;
+                for (int rr = 0; rr < (64 >> cp_log); ++rr) {
+                    const int n = __popcll((nz >> (rr << cp_log)) & rowmask);
+                    if (n) { ev += n; taps += n * a.sched[l + 1].taps[j0 + rr]; }
+                }
+                unsigned long long *dst = ka.stats + ((int64_t)stream * n_layers + l + 1) * 2;
+                atomicAdd(dst, (unsigned long long)ev);
+                atomicAdd(dst + 1, (unsigned long long)taps * a.sched[l + 1].c_out);
             }
         }
     }
-    if (a.stats && tid < n_layers && a.sched[tid].cnt > 0) {
-        unsigned long long *dst = a.stats + ((int64_t)stream * n_layers + tid) * 2;
-        if (lds.events[tid]) atomicAdd(dst, (unsigned long long)lds.events[tid]);
-        if (lds.taps[tid]) atomicAdd(dst + 1, (unsigned long long)lds.taps[tid] * a.sched[tid].c_out);
-    }
 }
+
+static_assert(kCellsPerThread == 3, "the event ballots above are written for three cells per lane");
 
 bool cascade1d_eligible(int prec, const Geom *g, int n_layers, const int *rows_cap, int max_seg_rows)
 {
