@@ -81,12 +81,11 @@ __device__ __forceinline__ const gfloat *uniform_global(const void *p)
 
 struct Wq { float w[kAhead][kKMax]; };           // weights of kAhead input channels, all taps
 
-// Where a lane finds its weights of one layer: offsets (in floats) of its first input channel
-// and the step to its next one, for the two 4-tap groups and for the ninth tap.
-struct WSrc {
-    const gfloat *w;
-    uint32_t off4, off4b, off8, step4, step8;
-    int n_qp;                                    // input channels per lane, rounded up to kAhead
+// A lane's place in the weight stream of one layer: byte offsets of its next input channel in
+// the two 4-tap groups and in the ninth-tap plane, and the steps to the channel after.
+struct WCur {
+    const __attribute__((address_space(1))) char *w;
+    uint32_t o4, o4b, o8, step4, step8;
 };
 
 // Lane mapping of one layer: channel lane within the power-of-two pad of c_out, group of lanes.
@@ -101,32 +100,34 @@ __device__ __forceinline__ Lanes lanes_of(int cp_log, int tid)
 
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }   // same in every lane: keep it scalar
 
-__device__ __forceinline__ WSrc wsrc_of(const CascadeLayer &sl, int tid)
+// The cursor at the lane's first input channel of a layer.
+__device__ __forceinline__ WCur cursor_of(const CascadeLayer &sl, int tid)
 {
-    const int cp_log = uni(sl.cp_log), c_out = uni(sl.c_out);
+    const int cp_log = uni(sl.cp_log), c_out = uni(sl.c_out), n_qp = uni(sl.steps);
     const Lanes m = lanes_of(cp_log, tid);
-    WSrc s;
-    s.w = uniform_global(sl.w);
-    s.n_qp = uni(sl.steps);
+    WCur s;
+    s.w = (const __attribute__((address_space(1))) char *)uniform_global(sl.w);
     const int co_c = m.co < c_out ? m.co : c_out - 1;        // clamped: loads need no predicate
-    s.off4 = (uint32_t)((m.grp * 2 * c_out + co_c) * 4);
-    s.off4b = s.off4 + (uint32_t)(c_out * 4);
-    s.off8 = (uint32_t)((m.n_grp * s.n_qp * 8 + m.grp) * c_out + co_c);
-    s.step4 = (uint32_t)(m.n_grp * 2 * c_out * 4);
-    s.step8 = (uint32_t)(m.n_grp * c_out);
+    s.o4 = (uint32_t)((m.grp * 2 * c_out + co_c) * 16);
+    s.o4b = s.o4 + (uint32_t)(c_out * 16);
+    s.o8 = (uint32_t)(((m.n_grp * n_qp * 8 + m.grp) * c_out + co_c) * 4);
+    s.step4 = (uint32_t)(m.n_grp * 2 * c_out * 16);
+    s.step8 = (uint32_t)(m.n_grp * c_out * 4);
     return s;
 }
 
-// Request the weights of this lane's q-th input channel of a layer (all taps); q < n_qp, or
-// q < kAhead for the layer after: the packing is padded to that many channels.
+// Request the weights (all taps) of the input channel the cursor stands on, and move it on.  A
+// cursor may run over its layer's steps (a multiple of kAhead), and over the first kAhead
+// channels of any layer: the packing is padded to that.
 static_assert(kKMax == 9, "the weight packing is two 16-byte groups and one single tap");
-__device__ __forceinline__ void fetch_w(float (&w)[kKMax], const WSrc &s, int q)
+__device__ __forceinline__ void fetch_w(float (&w)[kKMax], WCur &s)
 {
-    const v4f a = *(const gfloat4 *)(s.w + (s.off4 + (uint32_t)q * s.step4));
-    const v4f b = *(const gfloat4 *)(s.w + (s.off4b + (uint32_t)q * s.step4));
-    w[8] = s.w[s.off8 + (uint32_t)q * s.step8];
+    const v4f a = *(const gfloat4 *)(s.w + s.o4);
+    const v4f b = *(const gfloat4 *)(s.w + s.o4b);
+    w[8] = *(const gfloat *)(s.w + s.o8);
     w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w;
     w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w;
+    s.o4 += s.step4; s.o4b += s.step4; s.o8 += s.step8;
 }
 
 template <int NIN> __device__ __forceinline__ void load_rows(const float *p, float (&xv)[NIN])
@@ -138,12 +139,13 @@ template <int NIN> __device__ __forceinline__ void load_rows(const float *p, flo
     }
 }
 
-// Step 2 for one layer.  wq holds the weights of this lane's first kAhead input channels; on
-// return it holds those of the next layer's first kAhead channels.  visit: this lane's view
+// Step 2 for one layer of n_qp steps.  wq holds the weights of this lane's first kAhead input
+// channels and wc stands on the channel after them; on return the same holds for the next
+// layer, whose cursor at its first channel is nxt0.  visit: this lane's view
 // of the channel bits, already shifted so that bit 0 belongs to its first channel (all zero
 // for lanes beyond c_out).
 template <int S, int NIN, int RHO>
-__device__ __forceinline__ void accumulate(const float *__restrict__ x, const Lanes &m, const WSrc &cur, const WSrc &nxt,
+__device__ __forceinline__ void accumulate(const float *__restrict__ x, const Lanes &m, int n_qp, WCur &wc, const WCur &nxt0,
                                            Wq &wq, unsigned long long visit, float *__restrict__ red)
 {
     constexpr int OFF = slot_off<S, RHO>();
@@ -154,7 +156,8 @@ __device__ __forceinline__ void accumulate(const float *__restrict__ x, const La
     // moving on by n_grp channels: two shifts of at most 32 (a single shift by 64 or more is not defined)
     const int sh1 = m.n_grp < 32 ? m.n_grp : 32, sh2 = m.n_grp - sh1 < 32 ? m.n_grp - sh1 : 32;
     int ci = m.grp;
-    for (int qc = 0; qc < cur.n_qp; qc += kAhead) {
+    for (int qc = 0; qc < n_qp; qc += kAhead) {
+        if (qc + kAhead >= n_qp) wc = nxt0;                       // the tail of this layer requests the head of the next
 #pragma unroll
         for (int h = 0; h < kAhead; h += kBatch) {
             float xv[kBatch][NIN];
@@ -177,11 +180,7 @@ __device__ __forceinline__ void accumulate(const float *__restrict__ x, const La
                     }
                 }
                 visit = (visit >> sh1) >> sh2;
-                // the slot is free: request what it will hold next, kAhead channels on -- which
-                // at the end of this layer is the head of the next one
-                const int qn = qc + h + p + kAhead;
-                if (qn < cur.n_qp) fetch_w(wq.w[h + p], cur, qn);
-                else fetch_w(wq.w[h + p], nxt, qn - cur.n_qp);
+                fetch_w(wq.w[h + p], wc);     // the slot is free: request what it will hold next, kAhead channels on
             }
             ci += kBatch * m.n_grp;
         }
@@ -192,12 +191,12 @@ __device__ __forceinline__ void accumulate(const float *__restrict__ x, const La
 }
 
 template <int S, int RHO>
-__device__ __forceinline__ void accumulate_rows(const float *x, int cnt, const Lanes &m, const WSrc &cur, const WSrc &nxt,
+__device__ __forceinline__ void accumulate_rows(const float *x, int cnt, const Lanes &m, int n_qp, WCur &wc, const WCur &nxt0,
                                                 Wq &wq, unsigned long long visit, float *red)
 {
-    if (cnt <= 4) accumulate<S, 4, RHO>(x, m, cur, nxt, wq, visit, red);
-    else if (cnt <= 8) accumulate<S, 8, RHO>(x, m, cur, nxt, wq, visit, red);
-    else accumulate<S, 16, RHO>(x, m, cur, nxt, wq, visit, red);
+    if (cnt <= 4) accumulate<S, 4, RHO>(x, m, n_qp, wc, nxt0, wq, visit, red);
+    else if (cnt <= 8) accumulate<S, 8, RHO>(x, m, n_qp, wc, nxt0, wq, visit, red);
+    else accumulate<S, 16, RHO>(x, m, n_qp, wc, nxt0, wq, visit, red);
 }
 
 // OR of the cp-bit fields of a 64-bit ballot (cp a power of two): which channels had a hit.
@@ -247,9 +246,9 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
         }
     }
     Wq wq;
-    WSrc cur = wsrc_of(ka.sched[0], tid);
+    WCur wc = cursor_of(ka.sched[0], tid);
 #pragma unroll
-    for (int p = 0; p < kAhead; ++p) fetch_w(wq.w[p], cur, p);
+    for (int p = 0; p < kAhead; ++p) fetch_w(wq.w[p], wc);
     const int c0 = ka.sched[0].c_in, n_in = ka.n_rows * c0;      // at most 16 rows x 64 channels: two per lane
     float xin[2];
     {
@@ -334,7 +333,8 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
         const float *x = lds.x[cur_buf];
         float *xn = lds.x[cur_buf ^ 1];
         const bool more = l + 1 < n_layers && uni(a.sched[l + 1].cnt) > 0;
-        const WSrc nxt = more ? wsrc_of(a.sched[l + 1], tid) : cur;
+        const WCur nxt0 = cursor_of(a.sched[more ? l + 1 : l], tid);
+        const int n_qp = uni(sl.steps);
         // per emitted row: the taps it lands on in layer l+1 (read by one lane per wave, from LDS)
         const unsigned char *taps_next = a.sched[more ? l + 1 : l].taps;
         const Lanes m = lanes_of(cp_log, tid);
@@ -347,9 +347,9 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
         for (int i = tid; i < 64 * kXStride / 4; i += kT) reinterpret_cast<float4 *>(xn)[i] = float4{0.f, 0.f, 0.f, 0.f};
         if (tid < 2) lds.chmask[cur_buf ^ 1][tid] = 0;
 
-        if (S == 1) accumulate_rows<1, 0>(x, cnt, m, cur, nxt, wq, visit, lds.red);
-        else if (rho == 0) accumulate_rows<2, 0>(x, cnt, m, cur, nxt, wq, visit, lds.red);
-        else accumulate_rows<2, 1>(x, cnt, m, cur, nxt, wq, visit, lds.red);
+        if (S == 1) accumulate_rows<1, 0>(x, cnt, m, n_qp, wc, nxt0, wq, visit, lds.red);
+        else if (rho == 0) accumulate_rows<2, 0>(x, cnt, m, n_qp, wc, nxt0, wq, visit, lds.red);
+        else accumulate_rows<2, 1>(x, cnt, m, n_qp, wc, nxt0, wq, visit, lds.red);
         lds_barrier();
 
         // Step 3.  Every lane owns up to kCellsPerThread (row, channel) cells; all LDS reads of
@@ -440,7 +440,6 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
         }
         lds_barrier();
         cur_buf ^= 1;
-        cur = nxt;
     }
 
     // Events and executed taps of layers 1..: one lane per kept ballot (layer, wave, cell).  A
