@@ -327,7 +327,7 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
         if (cnt <= 0) break;
         const int t_lo = uni(sl.t_lo), t_fin = uni(sl.t_fin), t_hi = uni(sl.t_hi), d0 = uni(sl.d0);
         const int at_start = uni(sl.at_start), rho = uni(sl.rho), cp_log = uni(sl.cp_log);
-        const int c_out = uni(sl.c_out), S = uni(sl.s_h), act = uni(sl.act);
+        const int c_out = uni(sl.c_out), c_in = uni(sl.c_in), S = uni(sl.s_h), act = uni(sl.act);
         const int K = uni(sl.k_h), slot0 = uni(sl.slot0), rcp_k = uni(sl.rcp_k);
         gfloat *ringg = (gfloat *)uniform_global(sl.ring) + (int64_t)stream * sl.ring_stride;
         const float *x = lds.x[cur_buf];
@@ -335,6 +335,8 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
         const bool more = l + 1 < n_layers && uni(a.sched[l + 1].cnt) > 0;
         const WCur nxt0 = cursor_of(a.sched[more ? l + 1 : l], tid);
         const int n_qp = uni(sl.steps);
+        // groups of lanes beyond the input channels hold no partial sums (they write zeros): not read
+        const int n_red = (kT >> cp_log) < ((c_in + 7) & ~7) ? (kT >> cp_log) : ((c_in + 7) & ~7);
         // per emitted row: the taps it lands on in layer l+1 (read by one lane per wave, from LDS)
         const unsigned char *taps_next = a.sched[more ? l + 1 : l].taps;
         const Lanes m = lanes_of(cp_log, tid);
@@ -391,7 +393,7 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
                     for (int u = 0; u < 8; ++u) sum[q] += part[q][u];    // fixed order
                 }
             }
-            for (int gi = 8; gi < m.n_grp; gi += 8) {         // n_grp is a multiple of 8
+            for (int gi = 8; gi < n_red; gi += 8) {           // n_grp is a multiple of 8
 #pragma unroll
                 for (int q = 0; q < kCellsPerThread; ++q)
                     if (wave_has[q]) {
