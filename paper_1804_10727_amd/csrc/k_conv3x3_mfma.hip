@@ -104,6 +104,18 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
     __shared__ uint32_t nz[64][kNzWords];          // per channel chunk: positions with a non-zero cell
     __shared__ unsigned long long red[2][WM * WN];
 
+    // Every argument the kernel uses is asked for here, in one batch of scalar loads with one
+    // wait: left to first use, the loads end up behind conditions and cost one memory round
+    // trip each, one after the other.
+    asm volatile("" ::"s"(a.w), "s"(a.c_in), "s"(a.c_out), "s"(a.c_out_pad), "s"(a.c_in_rcp), "s"(a.act), "s"(a.shr),
+                 "s"(a.clamp_hi), "s"(a.layer), "s"(a.pool_layer), "s"(a.n_layers), "s"(a.taps_y), "s"(a.in_by_position),
+                 "s"(a.to_output), "s"(a.in), "s"(a.in_stream_stride), "s"(a.in_row_off), "s"(a.ring),
+                 "s"(a.ring_stream_stride), "s"(a.held), "s"(a.held_stream_stride), "s"(a.dst), "s"(a.dst_stream_stride),
+                 "s"(a.wfrag), "s"(a.bias), "s"(a.stats));
+    asm volatile("" ::"s"(a.t[0].valid), "s"(a.t[0].fresh), "s"(a.t[0].emit), "s"(a.t[0].store_held), "s"(a.t[0].ring_slot),
+                 "s"(a.t[0].dst_slot), "s"(a.t[1].valid), "s"(a.t[1].fresh), "s"(a.t[1].emit), "s"(a.t[1].store_held),
+                 "s"(a.t[1].ring_slot), "s"(a.t[1].dst_slot), "s"(a.t[2].valid), "s"(a.t[2].fresh), "s"(a.t[2].emit),
+                 "s"(a.t[2].store_held), "s"(a.t[2].ring_slot), "s"(a.t[2].dst_slot), "s"(sel.n), "s"(sel.base), "s"(sel.pos0));
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WM, wn = wave / WM;
     const int si = blockIdx.z;
