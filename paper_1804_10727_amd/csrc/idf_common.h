@@ -198,6 +198,7 @@ struct MfmaTap {
 struct MfmaStep {
     int w, c_in, c_out, c_out_pad;
     unsigned c_in_rcp;                 // ceil(2^32 / c_in): k / c_in = umulhi(k, c_in_rcp) for the k in use
+    unsigned chunks_rcp;               // the same for the 16-byte cells per position (0: fewer channels than a cell)
     int act, shr, clamp_hi;
     int layer, pool_layer, n_layers;   // pool_layer < 0: no fused pool
     int taps_y;                        // taps of this input row that land inside the output (for the counters)

@@ -384,6 +384,10 @@ int enqueue_cascade(idf_streams *s, const StreamSel &sel, const void *dev_rows, 
                 MfmaStep a{};
                 a.w = g.w_out; a.c_in = g.c_in; a.c_out = g.c_out; a.c_out_pad = (g.c_out + 63) / 64 * 64;
                 a.c_in_rcp = (unsigned)((0x100000000ull + g.c_in - 1) / g.c_in);
+                {
+                    const int chunks = g.c_in / (net.precision == IDF_PREC_BF16 ? 8 : 16);
+                    a.chunks_rcp = chunks > 1 ? (unsigned)((0x100000000ull + chunks - 1) / chunks) : 0u;
+                }
                 a.act = g.act; a.shr = g.shr; a.clamp_hi = g.clamp_hi;
                 a.layer = l; a.pool_layer = pool ? l + 1 : -1; a.n_layers = n;
                 a.tile = conv3x3_mfma_tile(g, sel.n);

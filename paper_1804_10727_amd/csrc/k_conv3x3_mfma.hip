@@ -107,7 +107,7 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
     // Every argument the kernel uses is asked for here, in one batch of scalar loads with one
     // wait: left to first use, the loads end up behind conditions and cost one memory round
     // trip each, one after the other.
-    asm volatile("" ::"s"(a.w), "s"(a.c_in), "s"(a.c_out), "s"(a.c_out_pad), "s"(a.c_in_rcp), "s"(a.act), "s"(a.shr),
+    asm volatile("" ::"s"(a.w), "s"(a.c_in), "s"(a.c_out), "s"(a.c_out_pad), "s"(a.c_in_rcp), "s"(a.chunks_rcp), "s"(a.act), "s"(a.shr),
                  "s"(a.clamp_hi), "s"(a.layer), "s"(a.pool_layer), "s"(a.n_layers), "s"(a.taps_y), "s"(a.in_by_position),
                  "s"(a.to_output), "s"(a.in), "s"(a.in_stream_stride), "s"(a.in_row_off), "s"(a.ring),
                  "s"(a.ring_stream_stride), "s"(a.held), "s"(a.held_stream_stride), "s"(a.dst), "s"(a.dst_stream_stride),
@@ -152,7 +152,7 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
         for (int b = 0; b < kBatch; ++b) {
             int i = base + b * NT + tid;
             i = i < cells ? i : cells - 1;
-            const int p = i / chunks, c = i - p * chunks;
+            const int p = a.chunks_rcp ? (int)__umulhi((unsigned)i, a.chunks_rcp) : i, c = i - p * chunks;   // i / chunks
             int x = x0 - 1 + p;
             x = x < 0 ? 0 : (x >= W ? W - 1 : x);
             tv[b] = *reinterpret_cast<const i32x4 *>(in_row + ((int64_t)x * C_in + c * VL) * EB);
@@ -161,6 +161,20 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
     if (cells > 0) tile_issue(0);
 
     // ---- (2) retained rows of c, the pool's held row, the bias --------------------------------
+    // This lane's 16 cells of a row [W][C_out]: element offsets (clamped into the row, so loads
+    // need no predicate) and which of them exist.  A wave whose cells all exist -- every wave
+    // when W is a multiple of 32 and C_out a multiple of the chunk -- stores without predicates.
+    int roff[16];
+    unsigned int vmask = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int xo = xo_base + 8 * i + j;
+            roff[i * 4 + j] = (xo < W ? xo : W - 1) * C_out + co_c;
+            vmask |= (co_ok && xo < W) ? 1u << (i * 4 + j) : 0u;
+        }
+    const bool wave_full = __ballot(vmask != 0xffffu) == 0ull;
     st_t *ring = (st_t *)a.ring + (int64_t)stream * a.ring_stream_stride;
     st_t init[3][16];
 #pragma unroll
@@ -170,12 +184,7 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
         if (a.t[ky].valid && !a.t[ky].fresh) {
             const st_t *rrow = ring + (int64_t)a.t[ky].ring_slot * W * C_out;
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int xo = xo_base + 8 * i + j;
-                    init[ky][i * 4 + j] = rrow[(int64_t)(xo < W ? xo : W - 1) * C_out + co_c];
-                }
+            for (int q = 0; q < 16; ++q) init[ky][q] = rrow[roff[q]];
         }
     }
     const st_t bias_v = a.bias ? ((const st_t *)a.bias)[co_c] : (st_t)0;
@@ -184,13 +193,10 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
     {
         const bool need = a.t[2].valid && a.t[2].emit == kEmitPoolHeld;   // only row y-1 can pair with the held row
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int xo = xo_base + 8 * i + j;
-                heldv[i * 4 + j] = 0;
-                if (need) heldv[i * 4 + j] = (uint32_t)held[(int64_t)(xo < W ? xo : W - 1) * C_out + co_c];
-            }
+        for (int q = 0; q < 16; ++q) {
+            heldv[q] = 0;
+            if (need) heldv[q] = (uint32_t)held[roff[q]];
+        }
     }
 
     // ---- (3) weights of the first K-steps, before it is known which steps are live -----------
@@ -223,7 +229,7 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
                 for (int b = 0; b < kBatch; ++b) {
                     const int i = base + b * NT + tid;
                     if (i >= cells) continue;
-                    const int p = i / chunks, c = i - p * chunks;
+                    const int p = a.chunks_rcp ? (int)__umulhi((unsigned)i, a.chunks_rcp) : i, c = i - p * chunks;
                     const int x = x0 - 1 + p;
                     if (x < 0 || x >= W) tv[b] = i32x4{0, 0, 0, 0};
                     *reinterpret_cast<i32x4 *>(smem + p * xs_stride + c * 16) = tv[b];
@@ -387,13 +393,14 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
         for (int q = 0; q < 16; ++q) c[q] = (cont ? init[ky][q] : bias_v) + acc[ky][q];
         if (t.emit == kEmitNone) {
             st_t *rrow = ring + (int64_t)t.ring_slot * W * C_out;
+            if (wave_full) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+                for (int q = 0; q < 16; ++q) rrow[roff[q]] = c[q];
+            } else {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int xo = xo_base + 8 * i + j;
-                    if (co_ok && xo < W) rrow[(int64_t)xo * C_out + co] = c[i * 4 + j];
-                }
+                for (int q = 0; q < 16; ++q)
+                    if (vmask >> q & 1u) rrow[roff[q]] = c[q];
+            }
             continue;
         }
         ev_t e[16];
@@ -402,25 +409,17 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
         if (a.pool_layer >= 0 && a.stats) {          // what the fused pool receives counts as its events
             unsigned int n = 0;
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    n += (co_ok && xo_base + 8 * i + j < W && T::ev_nonzero(e[i * 4 + j])) ? 1u : 0u;
+            for (int q = 0; q < 16; ++q) n += ((vmask >> q & 1u) && T::ev_nonzero(e[q])) ? 1u : 0u;
             for (int off = 32; off > 0; off >>= 1) n += __shfl_down(n, off);
             if (lane == 0 && n)
                 atomicAdd(a.stats + ((int64_t)stream * a.n_layers + a.pool_layer) * 2, (unsigned long long)n);
         }
         if (t.emit == kEmitDirect && a.to_output) {
             // last layer: 4-byte values, not rounded to the event type
+            st_t *orow = (st_t *)a.dst + (int64_t)stream * a.dst_stream_stride + t.dst_slot * W * C_out;
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int xo = xo_base + 8 * i + j;
-                    if (!(co_ok && xo < W)) continue;
-                    ((st_t *)a.dst)[(int64_t)stream * a.dst_stream_stride + (t.dst_slot * W + xo) * C_out + co] =
-                        T::activate(c[i * 4 + j], a.act, a.shr, a.clamp_hi);
-                }
+            for (int q = 0; q < 16; ++q)
+                if (wave_full || (vmask >> q & 1u)) orow[roff[q]] = T::activate(c[q], a.act, a.shr, a.clamp_hi);
         } else if (t.emit == kEmitDirect || (t.emit == kEmitHold && t.store_held)) {
             if (!stage_free) { lds_barrier(); stage_free = true; }
 #pragma unroll
