@@ -166,12 +166,21 @@ struct CascadeLayer {
     unsigned char taps[kCasRowsMax];   // per new row: kernel taps landing inside the output
 };
 
+// The layers can be dealt to up to kCasMaxStages groups of workgroups (blockIdx.y) that run side
+// by side in one launch, stage s working on the segment pushed s launches earlier: its first
+// layer reads what stage s-1 wrote in the launch before (double-buffered by launch parity).
+constexpr int kCasMaxStages = 4;
+
 struct CascadeArgs {
     int n_layers;
-    int n_rows;
-    CascadeLayer sched[kCasMaxLayers];
-    const void *in;                      // [position][n_rows][c0]
+    int n_stages;
+    int stage_lo[kCasMaxStages + 1];     // stage s runs layers [stage_lo[s], stage_lo[s+1])
+    int transit_wr;                      // parity of the hand-over buffers written by this launch
+    CascadeLayer sched[kCasMaxLayers];   // sched[l] describes the segment layer l's stage works on
+    const void *in;                      // stage 0: [position][rows][c0]
     int64_t in_stream_stride;
+    void *transit;                       // hand-over rows [boundary][parity][stream][row][channel]
+    int64_t transit_stream_stride, transit_buf_stride;   // floats
     void *out;                           // output area [stream][out_cap][c_out]
     int64_t out_stride, out_cap, out_slot0;
     unsigned long long *stats;

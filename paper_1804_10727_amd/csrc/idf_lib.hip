@@ -84,6 +84,14 @@ struct idf_streams {
     size_t out_off = 0, stats_off = 0;
     int64_t out_stride = 0;
     std::vector<std::vector<float>> cas_w;      // cascade packing of the weights (kept until the upload has run)
+    // 1-D cascade, layers dealt to stages that run side by side, stage k on the segment pushed k
+    // launches earlier: the segments still on their way, newest first
+    struct CasPush { bool valid = false; CascadeLayer sched[kCasMaxLayers]; int64_t out_slot0 = 0; };
+    int cas_stages = 1;
+    int cas_lo[kCasMaxStages + 1] = {0, 0, 0, 0, 0};
+    CasPush cas_hist[kCasMaxStages - 1];
+    int cas_parity = 0;
+    size_t cas_transit_off = 0;
     std::vector<StreamHost> h;
     std::vector<int> stamp;
     int stamp_gen = 0;
@@ -132,6 +140,7 @@ struct Layout {
     size_t out_off = 0, stats_off = 0, total = 0;
     int64_t out_stride = 0;
     bool cascade1d = false;          // the whole-net 1-D kernel serves this stream set
+    size_t cas_transit_off = 0;      // hand-over rows between the cascade's stages
     idf_sizes sizes{};
 };
 
@@ -192,6 +201,10 @@ int make_layout(const idf_net &net, int B, int max_seg, int64_t out_cap, Layout 
     L.out_stride = out_cap * net.out_w * net.out_c;
     L.out_off = off; off = align_up(off + (size_t)L.out_stride * 4 * B);
     L.stats_off = off; off = align_up(off + (size_t)B * n * 2 * sizeof(unsigned long long));
+    if (L.cascade1d) {
+        L.cas_transit_off = off;
+        off = align_up(off + (size_t)(kCasMaxStages - 1) * 2 * B * kCasRowsMax * 64 * 4);
+    }
     L.total = off;
     L.sizes.workspace_bytes = off;
     L.sizes.state_bytes_per_stream = state_per_stream;
@@ -286,19 +299,61 @@ double conv_step_bytes(const idf_net &net, const ConvStep &a, int n_streams)
     return per_stream * n_streams + weights;
 }
 
-// Enqueue everything one group of streams (all at row r, n new rows) needs.
-int enqueue_cascade1d(idf_streams *s, const StreamSel &sel, const void *dev_rows, int n_rows, int64_t r,
-                      int64_t out_slot0)
+// Deals the cascade's layers to stages.  A stage costs a fixed part and a part per layer that
+// grows with the layer's steps; the split with the cheapest slowest stage wins, as long as every
+// workgroup of a launch (streams x stages) gets a compute unit of its own.
+void plan_cascade_stages(idf_streams *s)
 {
     const idf_net &net = *s->net;
     const int n = (int)net.g.size();
-    CascadeArgs a{};
-    a.n_layers = n;
-    double bytes = 0;
+    int cus = 0, dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+        cus = 0;
+    int max_stages = std::min({kCasMaxStages, n, std::max(1, cus / std::max(1, s->B))});
+    if (const char *e = getenv("IDF_CASCADE_STAGES")) max_stages = std::max(1, std::min(max_stages, atoi(e)));
+    std::vector<double> cost(n);
+    for (int l = 0; l < n; ++l) cost[l] = 2.5 + 0.2 * cascade1d_steps(net.g[l].c_in, net.g[l].c_out);
+    const double fixed = 4.0;
+    double best = 1e30;
+    int best_lo[kCasMaxStages + 1] = {0, n, n, n, n}, best_n = 1;
+    // up to three cut points: try them all
+    for (int a = 1; a <= n; ++a)
+        for (int b = a; b <= n; ++b)
+            for (int c = b; c <= n; ++c) {
+                const int lo[5] = {0, a, b, c, n};
+                int stages = 0;
+                double worst = 0;
+                bool ok = true;
+                for (int k = 0; k < 4; ++k) {
+                    if (lo[k] == lo[k + 1]) { if (lo[k] != n) ok = false; continue; }
+                    ++stages;
+                    double t = fixed;
+                    for (int l = lo[k]; l < lo[k + 1]; ++l) t += cost[l];
+                    worst = std::max(worst, t);
+                }
+                if (!ok || stages > max_stages) continue;
+                worst += 0.3 * stages;                      // on a tie, fewer stages
+                if (worst < best) {
+                    best = worst; best_n = stages;
+                    int k2 = 0;
+                    for (int k = 0; k < 4; ++k) if (lo[k] != lo[k + 1]) best_lo[k2++] = lo[k];
+                    for (; k2 <= kCasMaxStages; ++k2) best_lo[k2] = n;
+                }
+            }
+    s->cas_stages = best_n;
+    for (int k = 0; k <= kCasMaxStages; ++k) s->cas_lo[k] = best_lo[k];
+}
+
+// The step of every layer for a segment of n_rows rows arriving at row r.
+int cascade_schedule(idf_streams *s, int n_rows, int64_t r, int n_streams, idf_streams::CasPush &p, double &bytes)
+{
+    const idf_net &net = *s->net;
+    const int n = (int)net.g.size();
     int64_t y0 = r, cnt = n_rows;
     for (int l = 0; l < n; ++l) {
         const Geom &g = net.g[l];
-        CascadeLayer &L = a.sched[l];
+        CascadeLayer &L = p.sched[l];
+        L = CascadeLayer{};
         L.c_in = g.c_in; L.c_out = g.c_out; L.k_h = g.k_h; L.s_h = g.s_h; L.act = g.act;
         L.steps = cascade1d_steps(g.c_in, g.c_out);
         L.ring_floats = g.k_h * g.c_out;
@@ -314,7 +369,7 @@ int enqueue_cascade1d(idf_streams *s, const StreamSel &sel, const void *dev_rows
             c.g = g; c.y0 = y0; c.cnt = (int)cnt; c.o_lo = rows_final(g, y0); c.o_fin = rows_final(g, y0 + cnt);
             c.o_hi = std::max(rows_touched(g, y0 + cnt), c.o_fin);
             c.in_by_position = l == 0; c.to_output = l == n - 1; c.bias = L.bias;
-            bytes += conv_step_bytes(net, c, sel.n);
+            bytes += conv_step_bytes(net, c, n_streams);
             const int64_t y0p = y0 + g.p_h;
             L.rho = (int)(y0p % g.s_h);
             const int64_t o_base = y0p / g.s_h + cascade1d_slot_off(g.s_h, L.rho);
@@ -333,16 +388,84 @@ int enqueue_cascade1d(idf_streams *s, const StreamSel &sel, const void *dev_rows
                 }
                 L.taps[j] = (unsigned char)t;
             }
-            if (cnt > kCasRowsMax || L.t_lo < 0 || L.t_hi > kCasRowsMax + kCasKMax - 1)
+            if (cnt > kCasRowsMax || L.t_lo < 0 || L.t_hi > kCasSlotsMax)
                 return fail(IDF_ESTATE, "internal: cascade schedule of layer %d out of range", l);
             y0 = c.o_lo; cnt = c.o_fin - c.o_lo;
         }
     }
-    a.in = dev_rows; a.in_stream_stride = (int64_t)n_rows * net.in_c; a.n_rows = n_rows;
-    a.out = s->ws + s->out_off; a.out_stride = s->out_stride; a.out_cap = s->out_cap; a.out_slot0 = out_slot0;
+    return IDF_OK;
+}
+
+// One launch: stage 0 takes the new segment (none: the stages only move on), stage k the segment
+// pushed k launches earlier.  staged == false: all layers in one stage, nothing may be on its way.
+int cascade_launch(idf_streams *s, const StreamSel &sel, const void *dev_rows, int n_rows,
+                   const idf_streams::CasPush *fresh, bool staged, double bytes)
+{
+    const int n = (int)s->net->g.size();
+    CascadeArgs a{};
+    a.n_layers = n;
+    a.n_stages = staged ? s->cas_stages : 1;
+    for (int k = 0; k <= kCasMaxStages; ++k) a.stage_lo[k] = staged ? s->cas_lo[k] : (k == 0 ? 0 : n);
+    a.transit_wr = s->cas_parity;
+    const idf_streams::CasPush *last_stage = fresh;       // whose output rows this launch completes
+    for (int k = 0; k < a.n_stages; ++k) {
+        const idf_streams::CasPush *src = k == 0 ? fresh : (s->cas_hist[k - 1].valid ? &s->cas_hist[k - 1] : nullptr);
+        for (int l = a.stage_lo[k]; l < a.stage_lo[k + 1]; ++l) {
+            if (src) a.sched[l] = src->sched[l];
+            else a.sched[l] = CascadeLayer{};               // cnt 0: the stage has nothing to do
+        }
+        if (k == a.n_stages - 1) last_stage = src;
+    }
+    a.in = dev_rows; a.in_stream_stride = (int64_t)n_rows * s->net->in_c;
+    a.transit = s->ws + s->cas_transit_off;
+    a.transit_stream_stride = (int64_t)kCasRowsMax * 64;
+    a.transit_buf_stride = a.transit_stream_stride * s->B;
+    a.out = s->ws + s->out_off; a.out_stride = s->out_stride; a.out_cap = s->out_cap;
+    a.out_slot0 = last_stage ? last_stage->out_slot0 : 0;
     a.stats = (unsigned long long *)(s->ws + s->stats_off);
     hipError_t e = launch_cascade1d(a, sel, launch_ctx(s, kKindCascade1d, bytes));
-    return e == hipSuccess ? IDF_OK : dev_fail(e, "cascade launch");
+    if (e != hipSuccess) return dev_fail(e, "cascade launch");
+    if (staged) {
+        for (int k = kCasMaxStages - 2; k > 0; --k) s->cas_hist[k] = s->cas_hist[k - 1];
+        if (fresh) s->cas_hist[0] = *fresh; else s->cas_hist[0].valid = false;
+        for (int k = s->cas_stages - 1; k < kCasMaxStages - 1; ++k) s->cas_hist[k].valid = false;   // left the last stage
+        s->cas_parity ^= 1;
+    }
+    return IDF_OK;
+}
+
+// Runs the segments still on their way through the remaining stages.
+int cascade_drain(idf_streams *s)
+{
+    if (!s->use_cascade1d) return IDF_OK;
+    StreamSel all{};
+    all.n = s->B; all.base = 0; all.pos0 = 0;
+    for (;;) {
+        bool pending = false;
+        for (int k = 0; k < kCasMaxStages - 1; ++k) pending |= s->cas_hist[k].valid;
+        if (!pending) return IDF_OK;
+        int rc = cascade_launch(s, all, nullptr, 0, nullptr, true, 0.0);
+        if (rc != IDF_OK) return rc;
+    }
+}
+
+// Enqueue everything one group of streams (all at row r, n new rows) needs.
+int enqueue_cascade1d(idf_streams *s, const StreamSel &sel, const void *dev_rows, int n_rows, int64_t r,
+                      int64_t out_slot0)
+{
+    idf_streams::CasPush p;
+    double bytes = 0;
+    int rc = cascade_schedule(s, n_rows, r, sel.n, p, bytes);
+    if (rc != IDF_OK) return rc;
+    p.valid = true; p.out_slot0 = out_slot0;
+    // Stages hold segments of all streams together: a push of all streams in step joins them, any
+    // other first lets them finish and then runs through all layers at once.
+    const bool in_step = s->cas_stages > 1 && sel.base == 0 && sel.pos0 == 0 && sel.n == s->B;
+    if (!in_step) {
+        rc = cascade_drain(s);
+        if (rc != IDF_OK) return rc;
+    }
+    return cascade_launch(s, sel, dev_rows, n_rows, &p, in_step, bytes);
 }
 
 int enqueue_cascade(idf_streams *s, const StreamSel &sel, const void *dev_rows, int n_rows, int64_t r,
@@ -607,6 +730,8 @@ int idf_open_streams(idf_net *net, int n_streams, int max_seg_rows, int64_t out_
     s->transit_stride = L.transit_stride; s->transit_cap = L.transit_cap;
     s->out_off = L.out_off; s->stats_off = L.stats_off; s->out_stride = L.out_stride; s->sizes = L.sizes;
     s->use_cascade1d = L.cascade1d;
+    s->cas_transit_off = L.cas_transit_off;
+    if (L.cascade1d) plan_cascade_stages(s);
     s->mfma.assign(net->g.size(), 0);
     if (!getenv("IDF_NO_MFMA")) {
         for (size_t l = 0; l < net->g.size(); ++l) {
@@ -651,6 +776,7 @@ int idf_open_streams(idf_net *net, int n_streams, int max_seg_rows, int64_t out_
 int idf_close_streams(idf_streams *s)
 {
     if (!s) return IDF_OK;
+    (void)cascade_drain(s);
     hipError_t e = hipStreamSynchronize(s->st);
     for (ProfRec &r : s->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     for (hipEvent_t ev : s->ev_pool) (void)hipEventDestroy(ev);
@@ -704,6 +830,8 @@ int idf_read_outputs(idf_streams *s, const int32_t *stream_ids, int n_ids, void 
     int rc = check_ids(s, stream_ids, n_ids);
     if (rc != IDF_OK) return rc;
     if (max_rows < 1) return fail(IDF_EINVAL, "max_rows must be >= 1");
+    rc = cascade_drain(s);                 // rows still between stages belong to what was pushed
+    if (rc != IDF_OK) return rc;
     const idf_net &net = *s->net;
     std::map<std::pair<int64_t, int>, std::vector<std::pair<int, int>>> groups;
     for (int i = 0; i < n_ids; ++i) {
@@ -737,6 +865,8 @@ int idf_reset_streams(idf_streams *s, const int32_t *stream_ids, int n_ids)
     if (!s) return fail(IDF_EINVAL, "null argument");
     int rc = check_ids(s, stream_ids, n_ids);
     if (rc != IDF_OK) return rc;
+    rc = cascade_drain(s);
+    if (rc != IDF_OK) return rc;
     const size_t per = s->net->g.size() * 2 * sizeof(unsigned long long);
     for (int i = 0; i < n_ids; ++i) {
         const int id = stream_ids ? stream_ids[i] : i;
@@ -753,6 +883,7 @@ int idf_get_stats(idf_streams *s, int stream_id, uint64_t *events_in, uint64_t *
     if (stream_id < 0 || stream_id >= s->B) return fail(IDF_EINVAL, "stream id %d outside [0, %d)", stream_id, s->B);
     const int n = (int)s->net->g.size();
     std::vector<unsigned long long> buf((size_t)n * 2);
+    if (int rc = cascade_drain(s)) return rc;
     hipError_t e = hipStreamSynchronize(s->st);
     if (e == hipSuccess)
         e = hipMemcpy(buf.data(), s->ws + s->stats_off + (size_t)stream_id * n * 2 * sizeof(unsigned long long),
@@ -788,6 +919,7 @@ int idf_profile_end(idf_streams *s, int max_kinds, idf_kernel_profile *out, int 
 {
     if (!s || !out || !n_kinds || max_kinds < 1) return fail(IDF_EINVAL, "null argument");
     if (!s->prof_on) return fail(IDF_ESTATE, "profiling is not on");
+    if (int rc = cascade_drain(s)) return rc;
     s->prof_on = false;
     hipError_t e = hipStreamSynchronize(s->st);
     if (e != hipSuccess) return dev_fail(e, "profile_end");

@@ -227,6 +227,8 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
     const int si = blockIdx.x;
     const int stream = sel_stream(sel, si);
     const int n_layers = ka.n_layers;
+    const int stage = blockIdx.y, lb = ka.stage_lo[stage], le = ka.stage_lo[stage + 1];
+    if (ka.sched[lb].cnt <= 0) return;                           // nothing has reached this stage
 
     // The argument block (first kernel argument, offset 0 of the kernel-argument segment) goes to
     // LDS in one sweep: inside the chain a layer's descriptor then costs an LDS read instead of a
@@ -246,13 +248,17 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
         }
     }
     Wq wq;
-    WCur wc = cursor_of(ka.sched[0], tid);
+    WCur wc = cursor_of(ka.sched[lb], tid);
 #pragma unroll
     for (int p = 0; p < kAhead; ++p) fetch_w(wq.w[p], wc);
-    const int c0 = ka.sched[0].c_in, n_in = ka.n_rows * c0;      // at most 16 rows x 64 channels: two per lane
+    const int c0 = ka.sched[lb].c_in, n_in = ka.sched[lb].cnt * c0;   // at most 16 rows x 64 channels: two per lane
     float xin[2];
     {
-        const gfloat *in = as_global((const float *)ka.in) + (int64_t)(sel.pos0 + si) * ka.in_stream_stride;
+        // the new segment, or the rows the stage before handed over in the previous launch
+        const gfloat *in = stage == 0
+            ? as_global((const float *)ka.in) + (int64_t)(sel.pos0 + si) * ka.in_stream_stride
+            : as_global((const float *)ka.transit) + ((stage - 1) * 2 + (ka.transit_wr ^ 1)) * ka.transit_buf_stride +
+                  (int64_t)stream * ka.transit_stream_stride;
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int i = tid + u * kT;
@@ -263,7 +269,7 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
 #pragma unroll
     for (int l = 0; l < kCasMaxLayers; ++l) {
         rv[l][0] = rv[l][1] = bv[l] = 0.f;
-        if (l < n_layers && ka.sched[l].cnt > 0) {
+        if (l >= lb && l < le && ka.sched[l].cnt > 0) {
             const CascadeLayer &sl = ka.sched[l];
             const gfloat *ring = as_global((const float *)sl.ring) + (int64_t)stream * sl.ring_stride;
             const int n_r = sl.ring_floats;
@@ -297,20 +303,20 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
                 const int j = i / c0, c = i - j * c0;
                 lds.x[0][c * kXStride + j] = xin[u];
                 atomicOr(&lds.chmask[0][c >> 5], 1u << (c & 31));
-                ev += 1; taps += a.sched[0].taps[j];
+                ev += 1; taps += a.sched[lb].taps[j];
             }
         }
         if (ka.stats && __ballot(ev != 0)) {
             for (int off = 32; off > 0; off >>= 1) { ev += __shfl_down(ev, off); taps += __shfl_down(taps, off); }
             if (lane == 0) {
-                unsigned long long *dst = ka.stats + (int64_t)stream * n_layers * 2;
+                unsigned long long *dst = ka.stats + ((int64_t)stream * n_layers + lb) * 2;
                 atomicAdd(dst, (unsigned long long)ev);
-                atomicAdd(dst + 1, (unsigned long long)taps * ka.sched[0].c_out);
+                atomicAdd(dst + 1, (unsigned long long)taps * ka.sched[lb].c_out);
             }
         }
 #pragma unroll
         for (int l = 0; l < kCasMaxLayers; ++l) {
-            if (l < n_layers && ka.sched[l].cnt > 0) {
+            if (l >= lb && l < le && ka.sched[l].cnt > 0) {
                 lds.ring[l][tid] = rv[l][0];
                 if (tid + kT < kRingPerLayer) lds.ring[l][tid + kT] = rv[l][1];
                 if (tid < 64) lds.bias[l][tid] = bv[l];
@@ -320,7 +326,7 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
     lds_barrier();
 
     int cur_buf = 0;
-    for (int l = 0; l < n_layers; ++l) {
+    for (int l = lb; l < le; ++l) {
         // this layer's step: scalars copied out of LDS once (the barriers below would force re-reads)
         const CascadeLayer &sl = a.sched[l];
         const int cnt = uni(sl.cnt);
@@ -332,7 +338,7 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
         gfloat *ringg = (gfloat *)uniform_global(sl.ring) + (int64_t)stream * sl.ring_stride;
         const float *x = lds.x[cur_buf];
         float *xn = lds.x[cur_buf ^ 1];
-        const bool more = l + 1 < n_layers && uni(a.sched[l + 1].cnt) > 0;
+        const bool more = l + 1 < le && uni(a.sched[l + 1].cnt) > 0;
         const WCur nxt0 = cursor_of(a.sched[more ? l + 1 : l], tid);
         const int n_qp = uni(sl.steps);
         // groups of lanes beyond the input channels hold no partial sums (they write zeros): not read
@@ -356,7 +362,9 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
 
         // Step 3.  Every lane owns up to kCellsPerThread (row, channel) cells; all LDS reads of
         // all its cells are issued before anything is summed.
-        const bool last = l == n_layers - 1;
+        const bool last = l == n_layers - 1, hand_over = l == le - 1 && !last;
+        gfloat *tr = (gfloat *)ka.transit + (stage * 2 + ka.transit_wr) * ka.transit_buf_stride +
+                     (int64_t)stream * ka.transit_stream_stride;
         const int rows_per_pass = kT >> cp_log;
         const int c = tid & (m.cp - 1), cc = c < c_out ? c : c_out - 1;
         int t_of[kCellsPerThread], at[kCellsPerThread];
@@ -419,6 +427,8 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
                         int64_t slot = ka.out_slot0 + (t_of[q] - t_lo);
                         if (slot >= ka.out_cap) slot -= ka.out_cap;
                         ((gfloat *)ka.out)[(int64_t)stream * ka.out_stride + slot * c_out + c] = h;
+                    } else if (hand_over) {
+                        tr[(t_of[q] - t_lo) * c_out + c] = h;  // the next stage takes it up in the next launch
                     } else if (h != 0.f) {
                         xn[c * kXStride + (t_of[q] - t_lo)] = h;
                         emitted_nz = true;
@@ -446,8 +456,8 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
 
     // Events and executed taps of layers 1..: one lane per kept ballot (layer, wave, cell).  A
     // wave's ballot covers 64 / cp consecutive new rows of the layer before, cp lanes each.
-    if (ka.stats && tid < (n_layers - 1) * (kT / 64) * kCellsPerThread) {
-        const int l = tid / ((kT / 64) * kCellsPerThread), r = tid - l * ((kT / 64) * kCellsPerThread);
+    if (ka.stats && tid < (le - 1 - lb) * (kT / 64) * kCellsPerThread) {
+        const int l = lb + tid / ((kT / 64) * kCellsPerThread), r = tid - (l - lb) * ((kT / 64) * kCellsPerThread);
         const int wv = r / kCellsPerThread, q = r - wv * kCellsPerThread;
         if (a.sched[l].cnt > 0 && a.sched[l + 1].cnt > 0) {
             const unsigned long long nz = lds.nzlog[l][wv][q];
@@ -488,7 +498,7 @@ hipError_t launch_cascade1d(const CascadeArgs &a, const StreamSel &sel, const La
     static hipError_t prepared = hipFuncSetAttribute(reinterpret_cast<const void *>(k_cascade1d),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Lds));
     if (prepared != hipSuccess) return prepared;
-    return launch(k_cascade1d, dim3(sel.n), dim3(kCasThreads), sizeof(Lds), lc, a, sel);
+    return launch(k_cascade1d, dim3(sel.n, a.n_stages), dim3(kCasThreads), sizeof(Lds), lc, a, sel);
 }
 
 }  // namespace idf
