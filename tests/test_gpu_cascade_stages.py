@@ -1,0 +1,111 @@
+"""GPU parity for the 1-D cascade when its layers are dealt to stages that run side by side,
+each one push behind the stage before: what a caller can observe (rows readable after a
+read, counters, state after pushes of only some streams) must not depend on that."""
+import os
+
+import numpy as np
+import pytest
+
+import workloads as wl_mod
+from helpers import TOL, check_stream, oracle_dense, oracle_stream, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(wl, seg, reads_at, stages=None, ids_plan=None):
+    """Push the whole sample seg rows at a time, reading after the pushes listed in reads_at."""
+    import torch
+    import paper_1804_10727_amd as idf
+    from paper_1804_10727_amd.binding import input_tensor
+    old = os.environ.get("IDF_CASCADE_STAGES")
+    if stages is not None:
+        os.environ["IDF_CASCADE_STAGES"] = str(stages)
+    try:
+        net = idf.net_from_workload(wl)
+        st = idf.Streams(net, wl["streams"], max_seg_rows=seg)
+    finally:
+        if stages is not None:
+            if old is None:
+                del os.environ["IDF_CASCADE_STAGES"]
+            else:
+                os.environ["IDF_CASCADE_STAGES"] = old
+    assert all(k == "cascade1d" for k in st.layer_kernels())
+    x = input_tensor(wl)
+    B, H = wl["streams"], wl["in_h"]
+    got = [[] for _ in range(B)]
+
+    def read():
+        out, first, cnt = st.read_outputs(int(st.sizes.out_h))
+        torch.cuda.synchronize()
+        o = out.cpu().numpy()
+        for b in range(B):
+            if cnt[b]:
+                assert first[b] == sum(len(c) for c in got[b])
+                got[b].append(o[b, :cnt[b]].copy())
+    for i, r in enumerate(range(0, H, seg)):
+        st.push_segment(x[:, r:r + seg].contiguous())
+        if i in reads_at:
+            read()
+    read()
+    stats = [st.get_stats(b) for b in range(B)]
+    st.close(); net.destroy()
+    return [np.concatenate(g) for g in got], stats
+
+
+def test_reads_between_pushes_see_every_completed_row():
+    wl = wl_mod.make(2, streams=5, length=640, channels=(8, 16, 16, 32, 32, 64))
+    n_push = 640 // 16
+    outs, stats = _run(wl, 16, reads_at={0, 1, 2, 7, 8, 20, n_push - 2})
+    for b in range(5):
+        check_stream(wl, outs[b], b)
+        _, e_st = oracle_stream(wl, b)
+        assert stats[b]["events_in"][0] == e_st["events_in"][0]
+        assert np.allclose(stats[b]["events_in"].astype(float), e_st["events_in"].astype(float), rtol=5e-3)
+
+
+@pytest.mark.parametrize("seg", [1, 5, 16])
+def test_staged_and_unstaged_agree_bit_for_bit(seg):
+    wl = wl_mod.make(2, streams=3, length=400, channels=(8, 8, 16, 16, 32, 64))
+    a, sa = _run(wl, seg, reads_at={3})
+    b, sb = _run(wl, seg, reads_at={3}, stages=1)
+    c, sc = _run(wl, seg, reads_at=set(), stages=2)
+    for i in range(3):
+        assert np.array_equal(a[i], b[i]) and np.array_equal(a[i], c[i])
+        assert sa[i]["events_in"].tolist() == sb[i]["events_in"].tolist() == sc[i]["events_in"].tolist()
+        assert sa[i]["macs"].tolist() == sb[i]["macs"].tolist()
+
+
+def test_pushes_of_some_streams_between_pushes_of_all():
+    import torch
+    import paper_1804_10727_amd as idf
+    from paper_1804_10727_amd.binding import input_tensor
+    wl = wl_mod.make(2, streams=4, length=320, channels=(8, 8, 8, 16, 16, 16))
+    net = idf.net_from_workload(wl)
+    st = idf.Streams(net, 4, max_seg_rows=16)
+    x = input_tensor(wl)
+    # all in step, then streams 2 and 0 run ahead (segments of all streams are still between
+    # stages at that point), the others catch up, all in step again
+    for r in range(0, 96, 16):
+        st.push_segment(x[:, r:r + 16].contiguous())
+    ahead = np.array([2, 0], dtype=np.int32)
+    for r in range(96, 160, 16):
+        st.push_segment(x[[2, 0], r:r + 16].contiguous(), stream_ids=ahead)
+    behind = np.array([1, 3], dtype=np.int32)
+    for r in range(96, 160, 8):
+        st.push_segment(x[[1, 3], r:r + 8].contiguous(), stream_ids=behind)
+    for r in range(160, 320, 16):
+        st.push_segment(x[:, r:r + 16].contiguous())
+    out, first, cnt = st.read_outputs(int(st.sizes.out_h))
+    torch.cuda.synchronize()
+    o = out.cpu().numpy()
+    for b in range(4):
+        d = oracle_dense(wl, b)
+        assert cnt[b] == d.shape[0]
+        assert rel_err(o[b, :cnt[b]], d) <= TOL["f32"]
+    st.close(); net.destroy()
+
+
+def test_single_stream_one_sample_per_push_with_bias():
+    wl = wl_mod.make(1, length=300)
+    outs, _ = _run(wl, 1, reads_at={0, 1, 2, 3, 10, 11})
+    check_stream(wl, outs[0], 0)
