@@ -129,6 +129,11 @@ int idf_close_streams(idf_streams *s);
  *   1 <= n_rows <= max_seg_rows.
  * Zero values are not events: they cause no arithmetic (Sec. 1).  Completed rows of the last
  * layer are appended to the stream's output area.
+ * For 1-D nets the deeper layers of a segment may be enqueued only with the next pushes (layers
+ * run in stages side by side, each stage on the segment one push older); idf_read_outputs,
+ * idf_get_stats, idf_reset_streams, idf_close_streams and idf_profile_end first enqueue whatever
+ * is still on its way, so what they return is always the result of every pushed row having gone
+ * through every layer it can influence.  The last segment's dev_rows is read by the push itself.
  * IDF_EINVAL: bad id, duplicate id, n_rows out of range.  IDF_ESTATE: the rows would run past row
  * in_h-1 of the current sample, or the completed output rows would not fit the output area
  * (read first). */
