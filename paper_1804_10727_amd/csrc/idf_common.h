@@ -225,6 +225,14 @@ struct MfmaStep {
     unsigned long long *stats;
 };
 
+// Steps of several layers for one launch of the matrix-core kernel.
+constexpr int kMfmaBatchMax = 8;
+struct MfmaBatch {
+    int n;
+    int wg_lo[kMfmaBatchMax + 1];      // filled by the launcher: first workgroup of each step
+    MfmaStep st[kMfmaBatchMax];
+};
+
 struct CopyOut {
     const void *src;             // output area [stream][out_cap][row_elems]
     int64_t src_stream_stride;

@@ -60,6 +60,7 @@ int conv3x3_mfma_tile(const Geom &g, int n_streams);
 // Packs weights [k_h][k_w][c_in][c_out] into fragment order; returns the size (out may be null).
 size_t conv3x3_mfma_pack(int prec, const Geom &g, const void *w_khkwcico, void *out);
 hipError_t launch_conv3x3_mfma(int prec, const MfmaStep &a, const StreamSel &sel, const LaunchCtx &lc);
+hipError_t launch_conv3x3_mfma_batch(int prec, const MfmaBatch &b, const StreamSel &sel, const LaunchCtx &lc);
 
 // Largest number of touched output rows one generic conv step can take for a layer with
 // c_out output channels (the host splits longer steps).

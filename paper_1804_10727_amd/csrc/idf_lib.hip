@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <deque>
 #include <map>
 #include <new>
 #include <string>
@@ -92,6 +93,15 @@ struct idf_streams {
     CasPush cas_hist[kCasMaxStages - 1];
     int cas_parity = 0;
     size_t cas_transit_off = 0;
+    // 2-D nets served by the matrix-core kernel throughout: one launch per arriving row holds a
+    // step of every conv layer, each on a row that was complete before the launch.  Per conv
+    // layer ("unit") the rows waiting for it, and where in the ring of hand-over rows they lie.
+    struct StgRow { int64_t y; int slot; };
+    bool stg2d = false;
+    std::vector<int> stg_unit;                  // conv layer of unit k
+    std::vector<std::deque<StgRow>> stg_fifo;
+    std::vector<int64_t> stg_seq;               // rows emitted by unit k so far
+    int64_t stg_out_next = 0;                   // output slot of the next completed row
     std::vector<StreamHost> h;
     std::vector<int> stamp;
     int stamp_gen = 0;
@@ -144,6 +154,24 @@ struct Layout {
     idf_sizes sizes{};
 };
 
+constexpr int kStgSlots = 8;         // hand-over rows kept per layer and stream when layers are staged
+
+// Every conv layer can run on the matrix-core kernel and every pool is fused behind one.
+bool net_all_mfma(const idf_net &net)
+{
+    const int n = (int)net.g.size();
+    int units = 0;
+    for (int l = 0; l < n; ++l) {
+        if (net.g[l].kind == IDF_CONV) {
+            if (net.wm_img[l].empty()) return false;
+            ++units;
+        } else if (l == 0 || net.g[l - 1].kind != IDF_CONV || net.g[l].k_w != 2) {
+            return false;
+        }
+    }
+    return units >= 1 && units <= kMfmaBatchMax;
+}
+
 int make_layout(const idf_net &net, int B, int max_seg, int64_t out_cap, Layout &L)
 {
     const int n = (int)net.g.size();
@@ -161,6 +189,7 @@ int make_layout(const idf_net &net, int B, int max_seg, int64_t out_cap, Layout 
         }
     }
     L.cascade1d = cascade1d_eligible(net.precision, net.g.data(), n, L.transit_cap.data(), max_seg);
+    const bool all_mfma = net_all_mfma(net);
     for (int l = 0; l < n; ++l) {
         if (net.g[l].kind != IDF_CONV) continue;
         // the 1-D cascade reads its own packing, taps zero-padded to kCasKMax
@@ -186,7 +215,9 @@ int make_layout(const idf_net &net, int B, int max_seg, int64_t out_cap, Layout 
         }
         cap = L.transit_cap[l];
         if (l < n - 1) {
-            L.transit_stride[l] = (int64_t)cap * g.w_out * g.c_out;
+            // room for the hand-over ring when the layers are staged across pushes
+            const int rows = all_mfma ? std::max(cap, kStgSlots) : cap;
+            L.transit_stride[l] = (int64_t)rows * g.w_out * g.c_out;
             L.transit_off[l] = off; off = align_up(off + (size_t)L.transit_stride[l] * eb * B);
             transit_per_stream += (size_t)L.transit_stride[l] * eb;
         }
@@ -468,10 +499,169 @@ int enqueue_cascade1d(idf_streams *s, const StreamSel &sel, const void *dev_rows
     return cascade_launch(s, sel, dev_rows, n_rows, &p, in_step, bytes);
 }
 
+// The matrix-core step of conv layer l (with the pool fused behind it, if any) for input row y:
+// everything but where the input row lies and where emitted rows go.  rows_out[ky] = index, in
+// the layer whose rows leave the step, of the row tap ky emits, or -1.
+void make_mfma_step(idf_streams *s, int l, int64_t y, int n_streams, MfmaStep &a, int64_t rows_out[3], double &bytes)
+{
+    const idf_net &net = *s->net;
+    const int n = (int)net.g.size();
+    const int eb = ev_bytes(net.precision);
+    const Geom &g = net.g[l];
+    const bool pool = l + 1 < n && s->mfma[l + 1] == 2;
+    const int lp = pool ? l + 1 : l;
+    const bool last_out = lp == n - 1;
+    const Geom &gp = net.g[lp];
+    a = MfmaStep{};
+    a.w = g.w_out; a.c_in = g.c_in; a.c_out = g.c_out; a.c_out_pad = (g.c_out + 63) / 64 * 64;
+    a.c_in_rcp = (unsigned)((0x100000000ull + g.c_in - 1) / g.c_in);
+    {
+        const int chunks = g.c_in / (net.precision == IDF_PREC_BF16 ? 8 : 16);
+        a.chunks_rcp = chunks > 1 ? (unsigned)((0x100000000ull + chunks - 1) / chunks) : 0u;
+    }
+    a.act = g.act; a.shr = g.shr; a.clamp_hi = g.clamp_hi;
+    a.layer = l; a.pool_layer = pool ? l + 1 : -1; a.n_layers = n;
+    a.tile = conv3x3_mfma_tile(g, n_streams);
+    const int64_t fin_after = rows_final(g, y + 1);
+    int taps_y = 0;
+    for (int ky = 0; ky < 3; ++ky) {
+        MfmaTap &t = a.t[ky];
+        rows_out[ky] = -1;
+        const int64_t o = y + 1 - ky;
+        t.valid = o >= 0 && o < g.h_out;
+        if (!t.valid) continue;
+        ++taps_y;
+        t.fresh = std::max<int64_t>(0, o - 1) >= y;
+        t.ring_slot = (int)(o % 3);
+        const bool fin = o < fin_after;
+        if (!fin) { t.emit = kEmitNone; continue; }
+        int64_t row = o;                                // row index in the leaving layer
+        if (!pool) t.emit = kEmitDirect;
+        else if (o % 2 == 0) {
+            t.emit = kEmitHold;
+            t.store_held = (o / 2 < gp.h_out) && !(o + 1 < fin_after);
+            continue;
+        } else {
+            t.emit = (o - 1 >= rows_final(g, y)) ? kEmitPoolReg : kEmitPoolHeld;
+            row = o / 2;
+            if (row >= gp.h_out) { t.emit = kEmitHold; t.store_held = 0; continue; }
+        }
+        rows_out[ky] = row;
+    }
+    a.taps_y = taps_y;
+    a.ring = s->ws + s->ring_off[l]; a.ring_stream_stride = s->ring_stride[l];
+    a.held = pool ? s->ws + s->held_off[l + 1] : nullptr;
+    a.held_stream_stride = pool ? s->held_stride[l + 1] : 0;
+    a.dst = last_out ? (void *)(s->ws + s->out_off) : (void *)(s->ws + s->transit_off[lp]);
+    a.dst_stream_stride = last_out ? s->out_stride : s->transit_stride[lp];
+    a.to_output = last_out;
+    a.wfrag = s->ws + s->wm_off[l];
+    a.bias = net.b_img[l].empty() ? nullptr : s->ws + s->b_off[l];
+    a.stats = (unsigned long long *)(s->ws + s->stats_off);
+    ConvStep c{};
+    c.g = g; c.y0 = y; c.cnt = 1; c.o_lo = rows_final(g, y); c.o_fin = fin_after;
+    c.o_hi = std::max(rows_touched(g, y + 1), c.o_fin);
+    c.in_by_position = l == 0; c.to_output = !pool && last_out; c.bias = a.bias;
+    bytes = conv_step_bytes(net, c, n_streams);
+    if (pool) bytes += n_streams * (double)g.w_out * g.c_out * eb;      // the held row, written or read
+}
+
+// One launch for all streams: every conv layer that has a row waiting takes one step, layer 0 on
+// row j of the pushed segment (j < 0: no new row, the layers only move on).  What a step emits
+// waits for the next layer's step in a later launch.
+int stg_tick(idf_streams *s, const void *dev_rows, int n_rows, int j, int64_t r)
+{
+    const idf_net &net = *s->net;
+    const int nu = (int)s->stg_unit.size();
+    StreamSel all{};
+    all.n = s->B; all.base = 0; all.pos0 = 0;
+    MfmaBatch b{};
+    double bytes_total = 0;
+    for (int k = nu - 1; k >= 0; --k) {         // deeper first: they take only rows that were there before
+        const int l = s->stg_unit[k];
+        const Geom &g = net.g[l];
+        int64_t y;
+        int slot = 0;
+        if (k == 0) {
+            if (j < 0) continue;
+            y = r + j;
+        } else {
+            if (s->stg_fifo[k].empty()) continue;
+            y = s->stg_fifo[k].front().y; slot = s->stg_fifo[k].front().slot;
+            s->stg_fifo[k].pop_front();
+        }
+        MfmaStep a;
+        int64_t rows_out[3];
+        double bytes = 0;
+        make_mfma_step(s, l, y, s->B, a, rows_out, bytes);
+        if (k == 0) {
+            a.in = dev_rows; a.in_stream_stride = (int64_t)n_rows * net.in_w * net.in_c; a.in_by_position = 1;
+            a.in_row_off = (int64_t)j * g.w_in * g.c_in;
+        } else {
+            const int lp = l - 1;                 // the layer whose rows this one reads: conv or fused pool before it
+            a.in = s->ws + s->transit_off[lp]; a.in_stream_stride = s->transit_stride[lp]; a.in_by_position = 0;
+            a.in_row_off = (int64_t)slot * g.w_in * g.c_in;
+        }
+        for (int ky = 2; ky >= 0; --ky) {         // increasing row index
+            if (rows_out[ky] < 0) continue;
+            if (k == nu - 1) {
+                a.t[ky].dst_slot = s->stg_out_next;
+                s->stg_out_next = (s->stg_out_next + 1) % s->out_cap;
+            } else {
+                const int wslot = (int)(s->stg_seq[k]++ % kStgSlots);
+                a.t[ky].dst_slot = wslot;
+                s->stg_fifo[k + 1].push_back({rows_out[ky], wslot});
+            }
+        }
+        b.st[b.n++] = a;
+        bytes_total += bytes;
+    }
+    if (b.n == 0) return IDF_OK;
+    hipError_t e = launch_conv3x3_mfma_batch(net.precision, b, all, launch_ctx(s, kKindConvMfma, bytes_total, -1));
+    return e == hipSuccess ? IDF_OK : dev_fail(e, "staged mfma conv launch");
+}
+
+bool stg_pending(const idf_streams *s, size_t more_than)
+{
+    for (const auto &f : s->stg_fifo) if (f.size() > more_than) return true;
+    return false;
+}
+
+int stg_drain(idf_streams *s)
+{
+    while (s->stg2d && stg_pending(s, 0)) {
+        int rc = stg_tick(s, nullptr, 0, -1, 0);
+        if (rc != IDF_OK) return rc;
+    }
+    return IDF_OK;
+}
+
+// Everything still between stages or layers is enqueued: afterwards the work in the stream is
+// that of every pushed row having gone through every layer it can influence.
+int pipeline_drain(idf_streams *s)
+{
+    int rc = cascade_drain(s);
+    return rc != IDF_OK ? rc : stg_drain(s);
+}
+
 int enqueue_cascade(idf_streams *s, const StreamSel &sel, const void *dev_rows, int n_rows, int64_t r,
                     int64_t out_slot0)
 {
     if (s->use_cascade1d) return enqueue_cascade1d(s, sel, dev_rows, n_rows, r, out_slot0);
+    if (s->stg2d) {
+        if (sel.base == 0 && sel.pos0 == 0 && sel.n == s->B) {
+            if (!stg_pending(s, 0)) s->stg_out_next = out_slot0;
+            for (int j = 0; j < n_rows; ++j) {
+                int rc = stg_tick(s, dev_rows, n_rows, j, r);
+                // the hand-over rings hold kStgSlots rows: never let more than three wait
+                while (rc == IDF_OK && stg_pending(s, 3)) rc = stg_tick(s, nullptr, 0, -1, 0);
+                if (rc != IDF_OK) return rc;
+            }
+            return IDF_OK;
+        }
+        int rc = stg_drain(s);                     // some streams only: finish what is on its way, then layer by layer
+        if (rc != IDF_OK) return rc;
+    }
     const idf_net &net = *s->net;
     const int n = (int)net.g.size();
     const int eb = ev_bytes(net.precision);
@@ -504,58 +694,17 @@ int enqueue_cascade(idf_streams *s, const StreamSel &sel, const void *dev_rows, 
                 return fail(IDF_ESTATE, "internal: layer %d would emit %lld rows, room for %d", lp,
                             (long long)(e_fin - e_lo), s->transit_cap[lp]);
             for (int64_t y = y0; y < y0 + cnt; ++y) {
-                MfmaStep a{};
-                a.w = g.w_out; a.c_in = g.c_in; a.c_out = g.c_out; a.c_out_pad = (g.c_out + 63) / 64 * 64;
-                a.c_in_rcp = (unsigned)((0x100000000ull + g.c_in - 1) / g.c_in);
-                {
-                    const int chunks = g.c_in / (net.precision == IDF_PREC_BF16 ? 8 : 16);
-                    a.chunks_rcp = chunks > 1 ? (unsigned)((0x100000000ull + chunks - 1) / chunks) : 0u;
-                }
-                a.act = g.act; a.shr = g.shr; a.clamp_hi = g.clamp_hi;
-                a.layer = l; a.pool_layer = pool ? l + 1 : -1; a.n_layers = n;
-                a.tile = conv3x3_mfma_tile(g, sel.n);
-                const int64_t fin_after = rows_final(g, y + 1);
-                int taps_y = 0;
+                MfmaStep a;
+                int64_t rows_out[3];
+                double bytes = 0;
+                make_mfma_step(s, l, y, sel.n, a, rows_out, bytes);
                 for (int ky = 0; ky < 3; ++ky) {
-                    MfmaTap &t = a.t[ky];
-                    const int64_t o = y + 1 - ky;
-                    t.valid = o >= 0 && o < g.h_out;
-                    if (!t.valid) continue;
-                    ++taps_y;
-                    t.fresh = std::max<int64_t>(0, o - 1) >= y;
-                    t.ring_slot = (int)(o % 3);
-                    const bool fin = o < fin_after;
-                    if (!fin) { t.emit = kEmitNone; continue; }
-                    int64_t row = o;                                // row index in the leaving layer
-                    if (!pool) t.emit = kEmitDirect;
-                    else if (o % 2 == 0) {
-                        t.emit = kEmitHold;
-                        t.store_held = (o / 2 < gp.h_out) && !(o + 1 < fin_after);
-                        continue;
-                    } else {
-                        t.emit = (o - 1 >= rows_final(g, y)) ? kEmitPoolReg : kEmitPoolHeld;
-                        row = o / 2;
-                        if (row >= gp.h_out) { t.emit = kEmitHold; t.store_held = 0; continue; }
-                    }
-                    t.dst_slot = row - e_lo;
-                    if (last_out) t.dst_slot = (out_slot0 + t.dst_slot) % s->out_cap;
+                    if (rows_out[ky] < 0) continue;
+                    a.t[ky].dst_slot = rows_out[ky] - e_lo;
+                    if (last_out) a.t[ky].dst_slot = (out_slot0 + a.t[ky].dst_slot) % s->out_cap;
                 }
-                a.taps_y = taps_y;
                 a.in = in; a.in_stream_stride = in_stride; a.in_by_position = by_pos;
                 a.in_row_off = (y - in_row0) * (int64_t)g.w_in * g.c_in;
-                a.ring = s->ws + s->ring_off[l]; a.ring_stream_stride = s->ring_stride[l];
-                a.held = pool ? s->ws + s->held_off[l + 1] : nullptr;
-                a.held_stream_stride = pool ? s->held_stride[l + 1] : 0;
-                a.dst = edst; a.dst_stream_stride = edst_stride; a.to_output = last_out;
-                a.wfrag = s->ws + s->wm_off[l];
-                a.bias = net.b_img[l].empty() ? nullptr : s->ws + s->b_off[l];
-                a.stats = stats;
-                ConvStep c{};
-                c.g = g; c.y0 = y; c.cnt = 1; c.o_lo = rows_final(g, y); c.o_fin = fin_after;
-                c.o_hi = std::max(rows_touched(g, y + 1), c.o_fin);
-                c.in_by_position = by_pos; c.to_output = !pool && last_out; c.bias = a.bias;
-                double bytes = conv_step_bytes(net, c, sel.n);
-                if (pool) bytes += sel.n * (double)g.w_out * g.c_out * eb;      // the held row, written or read
                 hipError_t e = launch_conv3x3_mfma(net.precision, a, sel, launch_ctx(s, kKindConvMfma, bytes, l));
                 if (e != hipSuccess) return dev_fail(e, "mfma conv launch");
             }
@@ -740,6 +889,13 @@ int idf_open_streams(idf_net *net, int n_streams, int max_seg_rows, int64_t out_
             if (l + 1 < net->g.size() && net->g[l + 1].kind == IDF_MAXPOOL && net->g[l + 1].k_w == 2) s->mfma[l + 1] = 2;
         }
     }
+    s->stg2d = !getenv("IDF_NO_MFMA") && !getenv("IDF_NO_ROW_STAGES") && net_all_mfma(*net);
+    if (s->stg2d) {
+        for (size_t l = 0; l < net->g.size(); ++l)
+            if (net->g[l].kind == IDF_CONV) s->stg_unit.push_back((int)l);
+        s->stg_fifo.assign(s->stg_unit.size(), {});
+        s->stg_seq.assign(s->stg_unit.size(), 0);
+    }
     s->h.assign(n_streams, StreamHost{});
     s->stamp.assign(n_streams, 0);
     hipError_t e = hipMemsetAsync(s->ws, 0, L.sizes.weights_bytes, s->st);     // zero padding of the weights
@@ -776,7 +932,7 @@ int idf_open_streams(idf_net *net, int n_streams, int max_seg_rows, int64_t out_
 int idf_close_streams(idf_streams *s)
 {
     if (!s) return IDF_OK;
-    (void)cascade_drain(s);
+    (void)pipeline_drain(s);
     hipError_t e = hipStreamSynchronize(s->st);
     for (ProfRec &r : s->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     for (hipEvent_t ev : s->ev_pool) (void)hipEventDestroy(ev);
@@ -830,7 +986,7 @@ int idf_read_outputs(idf_streams *s, const int32_t *stream_ids, int n_ids, void 
     int rc = check_ids(s, stream_ids, n_ids);
     if (rc != IDF_OK) return rc;
     if (max_rows < 1) return fail(IDF_EINVAL, "max_rows must be >= 1");
-    rc = cascade_drain(s);                 // rows still between stages belong to what was pushed
+    rc = pipeline_drain(s);                // rows still between stages belong to what was pushed
     if (rc != IDF_OK) return rc;
     const idf_net &net = *s->net;
     std::map<std::pair<int64_t, int>, std::vector<std::pair<int, int>>> groups;
@@ -865,7 +1021,7 @@ int idf_reset_streams(idf_streams *s, const int32_t *stream_ids, int n_ids)
     if (!s) return fail(IDF_EINVAL, "null argument");
     int rc = check_ids(s, stream_ids, n_ids);
     if (rc != IDF_OK) return rc;
-    rc = cascade_drain(s);
+    rc = pipeline_drain(s);
     if (rc != IDF_OK) return rc;
     const size_t per = s->net->g.size() * 2 * sizeof(unsigned long long);
     for (int i = 0; i < n_ids; ++i) {
@@ -883,7 +1039,7 @@ int idf_get_stats(idf_streams *s, int stream_id, uint64_t *events_in, uint64_t *
     if (stream_id < 0 || stream_id >= s->B) return fail(IDF_EINVAL, "stream id %d outside [0, %d)", stream_id, s->B);
     const int n = (int)s->net->g.size();
     std::vector<unsigned long long> buf((size_t)n * 2);
-    if (int rc = cascade_drain(s)) return rc;
+    if (int rc = pipeline_drain(s)) return rc;
     hipError_t e = hipStreamSynchronize(s->st);
     if (e == hipSuccess)
         e = hipMemcpy(buf.data(), s->ws + s->stats_off + (size_t)stream_id * n * 2 * sizeof(unsigned long long),
@@ -919,7 +1075,7 @@ int idf_profile_end(idf_streams *s, int max_kinds, idf_kernel_profile *out, int 
 {
     if (!s || !out || !n_kinds || max_kinds < 1) return fail(IDF_EINVAL, "null argument");
     if (!s->prof_on) return fail(IDF_ESTATE, "profiling is not on");
-    if (int rc = cascade_drain(s)) return rc;
+    if (int rc = pipeline_drain(s)) return rc;
     s->prof_on = false;
     hipError_t e = hipStreamSynchronize(s->st);
     if (e != hipSuccess) return dev_fail(e, "profile_end");

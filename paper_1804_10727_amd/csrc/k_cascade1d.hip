@@ -343,8 +343,6 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
         const int n_qp = uni(sl.steps);
         // groups of lanes beyond the input channels hold no partial sums (they write zeros): not read
         const int n_red = (kT >> cp_log) < ((c_in + 7) & ~7) ? (kT >> cp_log) : ((c_in + 7) & ~7);
-        // per emitted row: the taps it lands on in layer l+1 (read by one lane per wave, from LDS)
-        const unsigned char *taps_next = a.sched[more ? l + 1 : l].taps;
         const Lanes m = lanes_of(cp_log, tid);
 
         // this lane's view of the channel bits: bit q*n_grp of it belongs to its q-th channel

@@ -21,6 +21,7 @@
 //     the rolling buffer; row y+1 is started from the bias.
 #include "idf.h"
 #include "idf_kernels.h"
+#include <algorithm>
 
 namespace idf {
 
@@ -95,7 +96,7 @@ constexpr int kMaxPos = 128 + 2;                 // positions of the widest tile
 constexpr int kNzWords = (kMaxPos + 31) / 32 + 1;
 
 template <class T, int WM, int WN>
-__global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a, const StreamSel sel)
+__device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &sel, const int bx)
 {
     using acc_t = typename T::acc_t; using st_t = typename T::st_t; using ev_t = typename T::ev_t;
     constexpr int VL = T::VL, EB = T::EB, KI = 2 * VL;
@@ -121,7 +122,7 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
     const int si = blockIdx.z;
     const int stream = sel_stream(sel, si);
     const int n_co_chunks = (a.c_out + NC - 1) / NC;
-    const int x_tile = blockIdx.x / n_co_chunks, co_chunk = blockIdx.x - x_tile * n_co_chunks;
+    const int x_tile = bx / n_co_chunks, co_chunk = bx - x_tile * n_co_chunks;
     const int x0 = x_tile * MT, co0 = co_chunk * NC;
     const int W = a.w, C_in = a.c_in, C_out = a.c_out;
     const int chunks = C_in / VL;                  // 16-byte cells per position
@@ -471,6 +472,40 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
 }
 
 template <class T, int WM, int WN>
+__global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a, const StreamSel sel)
+{
+    conv3x3_row<T, WM, WN>(a, sel, blockIdx.x);
+}
+
+// Several layers' steps in one launch (each on a row that was complete before the launch): the
+// workgroups of step k are blockIdx.x in [wg_lo[k], wg_lo[k+1]).
+template <class T>
+__global__ void __launch_bounds__(256) k_conv3x3_mfma_batch(const MfmaBatch b, const StreamSel sel)
+{
+    int k = 0;
+    while (k + 1 < b.n && (int)blockIdx.x >= b.wg_lo[k + 1]) ++k;
+    conv3x3_row<T, 2, 2>(b.st[k], sel, (int)blockIdx.x - b.wg_lo[k]);
+}
+
+template <class T>
+hipError_t launch_batch(const MfmaBatch &b0, const StreamSel &sel, const LaunchCtx &lc)
+{
+    MfmaBatch b = b0;
+    size_t lds = 0;
+    int wg = 0;
+    for (int k = 0; k < b.n; ++k) {
+        const MfmaStep &a = b.st[k];
+        b.wg_lo[k] = wg;
+        wg += ((a.w + 63) / 64) * ((a.c_out + 63) / 64);
+        lds = std::max(lds, (size_t)(64 + 2) * (a.c_in * T::EB + 16));
+        lds = std::max(lds, (size_t)64 * 64 * T::EB);
+    }
+    b.wg_lo[b.n] = wg;
+    if (b.n < 1 || wg < 1) return hipErrorInvalidValue;
+    return launch(k_conv3x3_mfma_batch<T>, dim3(wg, 1, sel.n), dim3(256), lds, lc, b, sel);
+}
+
+template <class T, int WM, int WN>
 hipError_t launch_one(const MfmaStep &a, const StreamSel &sel, const LaunchCtx &lc)
 {
     constexpr int MT = 32 * WM, NC = 32 * WN;
@@ -537,6 +572,13 @@ size_t conv3x3_mfma_pack(int prec, const Geom &g, const void *w_khkwcico, void *
             }
         }
     return bytes;
+}
+
+hipError_t launch_conv3x3_mfma_batch(int prec, const MfmaBatch &b, const StreamSel &sel, const LaunchCtx &lc)
+{
+    if (prec == IDF_PREC_BF16) return launch_batch<TraitsBf16>(b, sel, lc);
+    if (prec == IDF_PREC_I8) return launch_batch<TraitsI8>(b, sel, lc);
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_conv3x3_mfma(int prec, const MfmaStep &a, const StreamSel &sel, const LaunchCtx &lc)
