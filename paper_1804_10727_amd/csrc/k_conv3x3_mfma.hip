@@ -472,7 +472,7 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
 }
 
 template <class T, int WM, int WN>
-__global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a, const StreamSel sel)
+__global__ void __launch_bounds__(64 * WM * WN, 512 / (64 * WM * WN)) k_conv3x3_mfma(const MfmaStep a, const StreamSel sel)
 {
     conv3x3_row<T, WM, WN>(a, sel, blockIdx.x);
 }
@@ -480,7 +480,7 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
 // Several layers' steps in one launch (each on a row that was complete before the launch): the
 // workgroups of step k are blockIdx.x in [wg_lo[k], wg_lo[k+1]).
 template <class T>
-__global__ void __launch_bounds__(256) k_conv3x3_mfma_batch(const MfmaBatch b, const StreamSel sel)
+__global__ void __launch_bounds__(256, 2) k_conv3x3_mfma_batch(const MfmaBatch b, const StreamSel sel)
 {
     int k = 0;
     while (k + 1 < b.n && (int)blockIdx.x >= b.wg_lo[k + 1]) ++k;
