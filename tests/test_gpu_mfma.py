@@ -105,3 +105,87 @@ def test_streams_out_of_step_on_the_matrix_core_path():
     for b in range(5):
         check_stream(wl, o[b], b)
     st.close(); net.destroy()
+
+
+def _piecewise(wl, seg, reads_after, env=None):
+    """Whole sample seg rows per push, reading after the pushes listed; returns rows per stream."""
+    import os
+    import torch
+    import paper_1804_10727_amd as idf
+    from paper_1804_10727_amd.binding import input_tensor
+    saved = {k: os.environ.get(k) for k in (env or {})}
+    os.environ.update(env or {})
+    try:
+        net = idf.net_from_workload(wl)
+        st = idf.Streams(net, wl["streams"], max_seg_rows=seg)
+    finally:
+        for k, v in saved.items():
+            if v is None:
+                del os.environ[k]
+            else:
+                os.environ[k] = v
+    x = input_tensor(wl)
+    B, H = wl["streams"], wl["in_h"]
+    got = [[] for _ in range(B)]
+
+    def read(max_rows):
+        out, first, cnt = st.read_outputs(max_rows)
+        torch.cuda.synchronize()
+        o = out.cpu().numpy()
+        for b in range(B):
+            if cnt[b]:
+                assert first[b] == sum(len(c) for c in got[b])
+                got[b].append(o[b, :cnt[b]].copy())
+    for i, r in enumerate(range(0, H, seg)):
+        st.push_segment(x[:, r:r + seg].contiguous())
+        if i in reads_after:
+            read(3)
+    for _ in range(int(st.sizes.out_h) // 3 + 2):
+        read(3)
+    stats = [st.get_stats(b) for b in range(B)]
+    st.close(); net.destroy()
+    return [np.concatenate(g) for g in got], stats
+
+
+@pytest.mark.parametrize("seg", [1, 3])
+def test_rows_between_layers_never_show(seg):
+    """Layers run one launch behind each other across pushes; reads in between, the end of the
+    sample (two rows complete at once in every layer) and the counters must not show it."""
+    wl = i8_net(26, 44, 3, seed=11)
+    n_push = (26 + seg - 1) // seg
+    a, sa = _piecewise(wl, seg, reads_after={0, 1, 2, 5, n_push - 2, n_push - 1})
+    b, sb = _piecewise(wl, seg, reads_after={4}, env={"IDF_NO_ROW_STAGES": "1"})
+    for i in range(3):
+        check_stream(wl, a[i], i)
+        assert np.array_equal(a[i], b[i])
+        assert sa[i]["events_in"].tolist() == sb[i]["events_in"].tolist()
+        assert sa[i]["macs"].tolist() == sb[i]["macs"].tolist()
+    wl = bf16_net(20, 40, 2, seed=12, with_bias=True)
+    a, _ = _piecewise(wl, seg, reads_after={0, 3, 4})
+    b, _ = _piecewise(wl, seg, reads_after=set(), env={"IDF_NO_ROW_STAGES": "1"})
+    for i in range(2):
+        check_stream(wl, a[i], i)
+        assert np.array_equal(a[i], b[i])
+
+
+def test_two_samples_through_the_staged_layers():
+    import torch
+    import paper_1804_10727_amd as idf
+    from paper_1804_10727_amd.binding import input_tensor
+    wl = i8_net(18, 36, 4, seed=13)
+    net = idf.net_from_workload(wl)
+    st = idf.Streams(net, 2, max_seg_rows=2)
+    x = input_tensor(wl)
+    # the second sample starts while rows of the first are still between layers
+    for r in range(0, 18, 2):
+        st.push_segment(x[0:2, r:r + 2].contiguous())
+    out1, _, c1 = st.read_outputs(int(st.sizes.out_h))
+    for r in range(0, 18, 2):
+        st.push_segment(x[2:4, r:r + 2].contiguous())
+    out2, _, c2 = st.read_outputs(int(st.sizes.out_h))
+    torch.cuda.synchronize()
+    assert (c1 == st.sizes.out_h).all() and (c2 == st.sizes.out_h).all()
+    for i in range(2):
+        check_stream(wl, out1[i].cpu().numpy(), i)
+        check_stream(wl, out2[i].cpu().numpy(), 2 + i)
+    st.close(); net.destroy()
