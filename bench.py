@@ -31,7 +31,7 @@ DTYPE = {"f32": "f32", "bf16": "bf16", "i8": "int8"}
 KERNEL_PEAK = {
     "conv_generic": {"f32": ("alu", "f32_valu"), "bf16": ("alu", "f32_valu"), "i8": ("alu", "i32_valu")},
     "cascade1d": {"f32": ("alu", "f32_valu")},
-    "conv3x3_mfma": {"bf16": ("mfma", "bf16_mfma"), "i8": ("mfma", "i8_mfma")},
+    "conv3x3_mfma": {"f32": ("mfma", "f32_mfma"), "bf16": ("mfma", "bf16_mfma"), "i8": ("mfma", "i8_mfma")},
     "pool_generic": None, "copy_out": None,
 }
 

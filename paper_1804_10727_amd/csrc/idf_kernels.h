@@ -55,6 +55,7 @@ int cascade1d_slot_off(int S, int rho);   // accumulator slot 0 relative to floo
 hipError_t launch_cascade1d(const CascadeArgs &a, const StreamSel &sel, const LaunchCtx &lc);
 
 // Matrix-core kernel for 3x3 / stride 1 / same-padded conv layers (bf16 and int8 nets).
+int conv3x3_mfma_vl(int prec);
 bool conv3x3_mfma_eligible(int prec, const Geom &g);
 int conv3x3_mfma_tile(const Geom &g, int n_streams);
 // Packs weights [k_h][k_w][c_in][c_out] into fragment order; returns the size (out may be null).

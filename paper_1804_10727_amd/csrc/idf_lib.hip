@@ -516,7 +516,7 @@ void make_mfma_step(idf_streams *s, int l, int64_t y, int n_streams, MfmaStep &a
     a.w = g.w_out; a.c_in = g.c_in; a.c_out = g.c_out; a.c_out_pad = (g.c_out + 63) / 64 * 64;
     a.c_in_rcp = (unsigned)((0x100000000ull + g.c_in - 1) / g.c_in);
     {
-        const int chunks = g.c_in / (net.precision == IDF_PREC_BF16 ? 8 : 16);
+        const int chunks = g.c_in / conv3x3_mfma_vl(net.precision);
         a.chunks_rcp = chunks > 1 ? (unsigned)((0x100000000ull + chunks - 1) / chunks) : 0u;
     }
     a.act = g.act; a.shr = g.shr; a.clamp_hi = g.clamp_hi;

@@ -1,5 +1,5 @@
 // Matrix-core event propagation for one arriving row of a 3x3, stride 1, same-padded conv layer
-// (bfloat16 events and weights -> float32 state, or int8 -> int32).
+// (bfloat16 events and weights -> float32 state, int8 -> int32, or float32 throughout).
 //
 // For one input row y the update of Sec. 3 (c += w * dh for every event dh of the row) is,
 // for each of the three output rows o = y+1-ky the row can influence, a contraction
@@ -60,6 +60,8 @@ struct TraitsBf16 {
     }
     static __device__ __forceinline__ st_t ev_val(ev_t v) { return __uint_as_float((uint32_t)v << 16); }
     static __device__ __forceinline__ bool ev_nonzero(ev_t v) { return (v & 0x7fffu) != 0; }
+    static __device__ __forceinline__ uint32_t bits(ev_t v) { return v; }
+    static __device__ __forceinline__ ev_t from_bits(uint32_t u) { return (ev_t)u; }
 };
 
 struct TraitsI8 {
@@ -90,6 +92,41 @@ struct TraitsI8 {
     static __device__ __forceinline__ ev_t to_ev(st_t h) { return (ev_t)h; }
     static __device__ __forceinline__ st_t ev_val(ev_t v) { return v; }
     static __device__ __forceinline__ bool ev_nonzero(ev_t v) { return v != 0; }
+    static __device__ __forceinline__ uint32_t bits(ev_t v) { return (uint32_t)(uint8_t)v; }
+    static __device__ __forceinline__ ev_t from_bits(uint32_t u) { return (ev_t)(uint8_t)u; }
+};
+
+// float32 events, weights and state: the 16-byte fragment of a lane holds four k, served by four
+// 32x32x2 matrix instructions (instruction i pairs element i of the two half-waves' fragments;
+// which two k share an instruction does not matter to the sum).
+struct TraitsF32 {
+    static constexpr int VL = 4;
+    static constexpr int EB = 4;
+    using acc_t = f32x16; using st_t = float; using ev_t = float;
+    static __device__ __forceinline__ acc_t mfma(const i32x4 &a, const i32x4 &b, acc_t c)
+    {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            c = __builtin_amdgcn_mfma_f32_32x32x2f32(__int_as_float(a[i]), __int_as_float(b[i]), c, 0, 0, 0);
+        return c;
+    }
+    static __device__ __forceinline__ bool cell_nonzero(const i32x4 &v)
+    {   // zero is +0 or -0
+        return ((v.x | v.y | v.z | v.w) & 0x7fffffff) != 0;
+    }
+    static __device__ __forceinline__ int count_nonzero(const i32x4 &v)
+    {
+        int n = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) n += (v[i] & 0x7fffffff) != 0;
+        return n;
+    }
+    static __device__ __forceinline__ st_t activate(st_t c, int act, int, int) { return act == IDF_ACT_NONE ? c : fmaxf(c, 0.f); }
+    static __device__ __forceinline__ ev_t to_ev(st_t h) { return h; }
+    static __device__ __forceinline__ st_t ev_val(ev_t v) { return v; }
+    static __device__ __forceinline__ bool ev_nonzero(ev_t v) { return v != 0.f; }
+    static __device__ __forceinline__ uint32_t bits(ev_t v) { return __float_as_uint(v); }
+    static __device__ __forceinline__ ev_t from_bits(uint32_t u) { return __uint_as_float(u); }
 };
 
 constexpr int kMaxPos = 128 + 2;                 // positions of the widest tile plus halo
@@ -196,7 +233,7 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
             heldv[q] = 0;
-            if (need) heldv[q] = (uint32_t)held[roff[q]];
+            if (need) heldv[q] = T::bits(held[roff[q]]);
         }
     }
 
@@ -302,17 +339,22 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
 #pragma unroll
         for (int q = 0; q < 16; ++q) acc[ky][q] = 0;
     if (small_c) {
-        // first layers: K = 3*C_in <= 12, a single step; the fragment is gathered element by element
+        // first layers: K = 3*C_in <= 12, one or two steps (all prefetched); the fragment is gathered
+        // element by element
         const ev_t *xs_e = reinterpret_cast<const ev_t *>(smem) + r * C_in;
-        const int k0 = hlf * VL;
-        ev_t e[VL];
 #pragma unroll
-        for (int q = 0; q < VL; ++q) e[q] = k0 + q < KT ? xs_e[k0 + q] : (ev_t)0;
-        i32x4 av;
-        __builtin_memcpy(&av, e, 16);
-        acc[0] = T::mfma(av, bq[0][0], acc[0]);
-        acc[1] = T::mfma(av, bq[0][1], acc[1]);
-        acc[2] = T::mfma(av, bq[0][2], acc[2]);
+        for (int sn = 0; sn < (12 + KI - 1) / KI; ++sn) {
+            if (sn >= steps) break;
+            const int k0 = sn * KI + hlf * VL;
+            ev_t e[VL];
+#pragma unroll
+            for (int q = 0; q < VL; ++q) e[q] = k0 + q < KT ? xs_e[k0 + q] : (ev_t)0;
+            i32x4 av;
+            __builtin_memcpy(&av, e, 16);
+            acc[0] = T::mfma(av, bq[sn][0], acc[0]);
+            acc[1] = T::mfma(av, bq[sn][1], acc[1]);
+            acc[2] = T::mfma(av, bq[sn][2], acc[2]);
+        }
     } else {
         // Software pipeline over the live steps, kDepth steps deep.  Every slot issues its loads
         // unconditionally (past the end the last live step is simply fetched again), so the
@@ -448,8 +490,8 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
                     m = m1 > m ? m1 : m;
                     st_t e0, e1;
                     if (t.emit == kEmitPoolHeld) {
-                        e0 = T::ev_val((ev_t)heldv[i * 4 + 2 * jj]);
-                        e1 = T::ev_val((ev_t)heldv[i * 4 + 2 * jj + 1]);
+                        e0 = T::ev_val(T::from_bits(heldv[i * 4 + 2 * jj]));
+                        e1 = T::ev_val(T::from_bits(heldv[i * 4 + 2 * jj + 1]));
                     } else {
                         e0 = T::ev_val(hprev[i * 4 + 2 * jj]);
                         e1 = T::ev_val(hprev[i * 4 + 2 * jj + 1]);
@@ -529,10 +571,13 @@ template <class T> hipError_t launch_prec(const MfmaStep &a, const StreamSel &se
 
 }  // namespace
 
+// Elements of the event type per 16-byte fragment.
+int conv3x3_mfma_vl(int prec) { return prec == IDF_PREC_F32 ? 4 : prec == IDF_PREC_BF16 ? 8 : 16; }
+
 bool conv3x3_mfma_eligible(int prec, const Geom &g)
 {
-    if (prec != IDF_PREC_BF16 && prec != IDF_PREC_I8) return false;
-    const int vl = prec == IDF_PREC_BF16 ? 8 : 16;
+    if (prec != IDF_PREC_BF16 && prec != IDF_PREC_I8 && prec != IDF_PREC_F32) return false;
+    const int vl = conv3x3_mfma_vl(prec);
     if (g.kind != IDF_CONV || g.k_h != 3 || g.k_w != 3 || g.s_h != 1 || g.s_w != 1 || g.p_h != 1 || g.p_w != 1) return false;
     if (g.h_in < 2 || g.w_in < 2) return false;
     if ((g.c_in % vl != 0 && g.c_in > 4) || g.c_out % 16 != 0) return false;
@@ -554,7 +599,7 @@ int conv3x3_mfma_tile(const Geom &g, int n_streams)
 // zero padded to whole K-steps and to a multiple of 64 output channels.
 size_t conv3x3_mfma_pack(int prec, const Geom &g, const void *w_khkwcico, void *out)
 {
-    const int vl = prec == IDF_PREC_BF16 ? 8 : 16, eb = prec == IDF_PREC_BF16 ? 2 : 1;
+    const int vl = conv3x3_mfma_vl(prec), eb = 16 / vl;
     const int KT = 3 * g.c_in, steps = (KT + 2 * vl - 1) / (2 * vl), kc = 2 * steps;
     const int cop = (g.c_out + 63) / 64 * 64;
     const size_t bytes = (size_t)3 * kc * cop * 16;
@@ -576,6 +621,7 @@ size_t conv3x3_mfma_pack(int prec, const Geom &g, const void *w_khkwcico, void *
 
 hipError_t launch_conv3x3_mfma_batch(int prec, const MfmaBatch &b, const StreamSel &sel, const LaunchCtx &lc)
 {
+    if (prec == IDF_PREC_F32) return launch_batch<TraitsF32>(b, sel, lc);
     if (prec == IDF_PREC_BF16) return launch_batch<TraitsBf16>(b, sel, lc);
     if (prec == IDF_PREC_I8) return launch_batch<TraitsI8>(b, sel, lc);
     return hipErrorInvalidValue;
@@ -583,6 +629,7 @@ hipError_t launch_conv3x3_mfma_batch(int prec, const MfmaBatch &b, const StreamS
 
 hipError_t launch_conv3x3_mfma(int prec, const MfmaStep &a, const StreamSel &sel, const LaunchCtx &lc)
 {
+    if (prec == IDF_PREC_F32) return launch_prec<TraitsF32>(a, sel, lc);
     if (prec == IDF_PREC_BF16) return launch_prec<TraitsBf16>(a, sel, lc);
     if (prec == IDF_PREC_I8) return launch_prec<TraitsI8>(a, sel, lc);
     return hipErrorInvalidValue;
