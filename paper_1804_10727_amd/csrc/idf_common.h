@@ -193,7 +193,7 @@ enum { kEmitNone = 0,      // row not final: back to the rolling buffer
        kEmitHold,          // final, even row of a pool pair: becomes the pool's held row
        kEmitPoolHeld,      // final, odd row of a pool pair: max with the held row, emit pooled row
        kEmitPoolReg };     // final, odd row whose even partner became final in the same launch
-enum { kMfmaTile64x64 = 0, kMfmaTile128x32, kMfmaTile32x64, kMfmaTile32x32 };
+enum { kMfmaTile64x64 = 0, kMfmaTile128x32, kMfmaTile32x64, kMfmaTile32x32, kMfmaTile64x32 };
 
 struct MfmaTap {
     int valid;             // output row exists
@@ -229,6 +229,7 @@ struct MfmaStep {
 constexpr int kMfmaBatchMax = 8;
 struct MfmaBatch {
     int n;
+    int tile;                          // kMfmaTile* (not 128x32), the same for every step
     int wg_lo[kMfmaBatchMax + 1];      // filled by the launcher: first workgroup of each step
     MfmaStep st[kMfmaBatchMax];
 };

@@ -102,6 +102,7 @@ struct idf_streams {
     std::vector<std::deque<StgRow>> stg_fifo;
     std::vector<int64_t> stg_seq;               // rows emitted by unit k so far
     int64_t stg_out_next = 0;                   // output slot of the next completed row
+    int stg_tile = kMfmaTile64x64;              // tile shape of the staged launches
     std::vector<StreamHost> h;
     std::vector<int> stamp;
     int stamp_gen = 0;
@@ -576,6 +577,7 @@ int stg_tick(idf_streams *s, const void *dev_rows, int n_rows, int j, int64_t r)
     StreamSel all{};
     all.n = s->B; all.base = 0; all.pos0 = 0;
     MfmaBatch b{};
+    b.tile = s->stg_tile;
     double bytes_total = 0;
     for (int k = nu - 1; k >= 0; --k) {         // deeper first: they take only rows that were there before
         const int l = s->stg_unit[k];
@@ -894,6 +896,12 @@ int idf_open_streams(idf_net *net, int n_streams, int max_seg_rows, int64_t out_
         for (size_t l = 0; l < net->g.size(); ++l)
             if (net->g[l].kind == IDF_CONV) s->stg_unit.push_back((int)l);
         s->stg_fifo.assign(s->stg_unit.size(), {});
+        // one tile shape for all layers of a launch: 32 positions when no row is wider, 32
+        // channels when some layer has no more
+        int w_max = 0, c_min = 1 << 30;
+        for (int l : s->stg_unit) { w_max = std::max(w_max, net->g[l].w_out); c_min = std::min(c_min, net->g[l].c_out); }
+        s->stg_tile = w_max > 32 ? (c_min > 32 ? kMfmaTile64x64 : kMfmaTile64x32)
+                                 : (c_min > 32 ? kMfmaTile32x64 : kMfmaTile32x32);
         s->stg_seq.assign(s->stg_unit.size(), 0);
     }
     s->h.assign(n_streams, StreamHost{});

@@ -33,6 +33,7 @@ typedef __attribute__((ext_vector_type(16))) int i32x16;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 
 struct TraitsBf16 {
+    static constexpr int kDepth = 6;         // K-steps whose operands are in flight
     static constexpr int VL = 8;             // elements per 16-byte lane fragment
     static constexpr int EB = 2;             // bytes per element
     using acc_t = f32x16; using st_t = float; using ev_t = uint16_t;
@@ -65,6 +66,7 @@ struct TraitsBf16 {
 };
 
 struct TraitsI8 {
+    static constexpr int kDepth = 6;
     static constexpr int VL = 16;
     static constexpr int EB = 1;
     using acc_t = i32x16; using st_t = int32_t; using ev_t = int8_t;
@@ -100,6 +102,7 @@ struct TraitsI8 {
 // 32x32x2 matrix instructions (instruction i pairs element i of the two half-waves' fragments;
 // which two k share an instruction does not matter to the sum).
 struct TraitsF32 {
+    static constexpr int kDepth = 3;         // a step is twelve long matrix instructions here: little to hide
     static constexpr int VL = 4;
     static constexpr int EB = 4;
     using acc_t = f32x16; using st_t = float; using ev_t = float;
@@ -244,7 +247,7 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
     const unsigned char *wbase = (const unsigned char *)a.wfrag + ((int64_t)hlf * a.c_out_pad + co0 + wn * 32 + (lane & 31)) * 16;
     const int64_t w_step = (int64_t)2 * a.c_out_pad * 16;           // bytes per K-step
     const int64_t w_ky = (int64_t)steps * w_step;                    // bytes per ky
-    constexpr int kDepth = 6;                                        // K-steps in flight
+    constexpr int kDepth = T::kDepth;                                // K-steps in flight
     i32x4 aq[kDepth], bq[kDepth][3];
     auto fetch_b = [&](int d, int sn) {
         const unsigned char *wp = wbase + sn * w_step;
@@ -514,37 +517,50 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
 }
 
 template <class T, int WM, int WN>
-__global__ void __launch_bounds__(64 * WM * WN, 512 / (64 * WM * WN)) k_conv3x3_mfma(const MfmaStep a, const StreamSel sel)
+__global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a, const StreamSel sel)
 {
     conv3x3_row<T, WM, WN>(a, sel, blockIdx.x);
 }
 
 // Several layers' steps in one launch (each on a row that was complete before the launch): the
-// workgroups of step k are blockIdx.x in [wg_lo[k], wg_lo[k+1]).
-template <class T>
-__global__ void __launch_bounds__(256, 2) k_conv3x3_mfma_batch(const MfmaBatch b, const StreamSel sel)
+// workgroups of step k are blockIdx.x in [wg_lo[k], wg_lo[k+1]).  One tile shape for all steps.
+template <class T, int WM, int WN>
+__global__ void __launch_bounds__(64 * WM * WN, 2) k_conv3x3_mfma_batch(const MfmaBatch b, const StreamSel sel)
 {
     int k = 0;
     while (k + 1 < b.n && (int)blockIdx.x >= b.wg_lo[k + 1]) ++k;
-    conv3x3_row<T, 2, 2>(b.st[k], sel, (int)blockIdx.x - b.wg_lo[k]);
+    conv3x3_row<T, WM, WN>(b.st[k], sel, (int)blockIdx.x - b.wg_lo[k]);
 }
 
-template <class T>
-hipError_t launch_batch(const MfmaBatch &b0, const StreamSel &sel, const LaunchCtx &lc)
+template <class T, int WM, int WN>
+hipError_t launch_batch_shape(const MfmaBatch &b0, const StreamSel &sel, const LaunchCtx &lc)
 {
+    constexpr int MT = 32 * WM, NC = 32 * WN;
     MfmaBatch b = b0;
     size_t lds = 0;
     int wg = 0;
     for (int k = 0; k < b.n; ++k) {
         const MfmaStep &a = b.st[k];
         b.wg_lo[k] = wg;
-        wg += ((a.w + 63) / 64) * ((a.c_out + 63) / 64);
-        lds = std::max(lds, (size_t)(64 + 2) * (a.c_in * T::EB + 16));
-        lds = std::max(lds, (size_t)64 * 64 * T::EB);
+        wg += ((a.w + MT - 1) / MT) * ((a.c_out + NC - 1) / NC);
+        lds = std::max(lds, (size_t)(MT + 2) * (a.c_in * T::EB + 16));
+        lds = std::max(lds, (size_t)MT * NC * T::EB);
     }
     b.wg_lo[b.n] = wg;
     if (b.n < 1 || wg < 1) return hipErrorInvalidValue;
-    return launch(k_conv3x3_mfma_batch<T>, dim3(wg, 1, sel.n), dim3(256), lds, lc, b, sel);
+    return launch(k_conv3x3_mfma_batch<T, WM, WN>, dim3(wg, 1, sel.n), dim3(64 * WM * WN), lds, lc, b, sel);
+}
+
+template <class T>
+hipError_t launch_batch(const MfmaBatch &b, const StreamSel &sel, const LaunchCtx &lc)
+{
+    switch (b.tile) {
+    case kMfmaTile64x64: return launch_batch_shape<T, 2, 2>(b, sel, lc);
+    case kMfmaTile64x32: return launch_batch_shape<T, 2, 1>(b, sel, lc);
+    case kMfmaTile32x64: return launch_batch_shape<T, 1, 2>(b, sel, lc);
+    case kMfmaTile32x32: return launch_batch_shape<T, 1, 1>(b, sel, lc);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 template <class T, int WM, int WN>
