@@ -224,3 +224,19 @@ def test_unbounded_1d_stream_with_small_output_ring():
         assert n == d.shape[0]
         assert rel_err(g, d) <= TOL["f32"]
     st.close(); net.destroy()
+
+
+@pytest.mark.parametrize("cfg", [3, 4, 5])
+def test_generic_kernels_when_the_matrix_core_path_is_off(cfg, monkeypatch):
+    """The any-shape kernels serve what the fast kernels do not; with the matrix-core path
+    switched off they must carry the 2-D configurations on their own."""
+    monkeypatch.setenv("IDF_NO_MFMA", "1")
+    kw = {3: dict(streams=3, size=12, channels=(8, 8, 16, 16)),
+          4: dict(streams=2, size=24, channels=(4, 4, 8, 8, 16, 16, 16, 16)),
+          5: dict(streams=2, size=16, channels=(8, 8, 16, 16, 16, 16, 16))}[cfg]
+    wl = wl_mod.make(cfg, **kw)
+    out, st, net = gpu_run(wl, return_streams=True)
+    assert all(k in ("conv_generic", "pool_generic") for k in st.layer_kernels())
+    for b in range(wl["streams"]):
+        check_stream(wl, out[b], b)
+    st.close(); net.destroy()
