@@ -166,6 +166,17 @@ int idf_get_stats(idf_streams *s, int stream_id, uint64_t *events_in, uint64_t *
 /* Rows of the current sample a stream has been given so far (host bookkeeping, no device work). */
 int idf_rows_pushed(const idf_streams *s, int stream_id, int64_t *rows);
 
+/* Averaging output units (Fig. 1: the output neuron that averages the last layer; Sec. 4: output
+ * units whose value converges as rows come in): one accumulator per channel of the last layer,
+ * fed by the rows the last layer completes; the value is the running mean over the positions of
+ * the rows completed so far in the current sample (a bounded net starts anew with the first row
+ * of the next sample).  Accumulation is in float64 (exact for int32 outputs).
+ * idf_enable_head: before the first push after open (IDF_ESTATE otherwise).
+ * idf_read_head: mean (host) [n_ids][out_c], rows (host) [n_ids] = rows averaged.  Synchronises
+ * the stream.  IDF_ESTATE if the head was not enabled. */
+int idf_enable_head(idf_streams *s);
+int idf_read_head(idf_streams *s, const int32_t *stream_ids, int n_ids, double *mean, int64_t *rows);
+
 /* Which kernel family serves layer i of an open stream set: a short static name such as
  * "generic", for reports.  NULL on a bad index. */
 const char *idf_layer_kernel(const idf_streams *s, int layer);

@@ -16,7 +16,8 @@ ACT = {"none": 0, "relu": 1, "relu_shr_clamp": 2}
 
 EXPORTS = ["idf_create_net", "idf_destroy_net", "idf_query_sizes", "idf_open_streams", "idf_close_streams",
            "idf_push_segment", "idf_read_outputs", "idf_reset_streams", "idf_get_stats", "idf_rows_pushed",
-           "idf_layer_kernel", "idf_last_error", "idf_profile_begin", "idf_profile_end"]
+           "idf_layer_kernel", "idf_last_error", "idf_profile_begin", "idf_profile_end", "idf_enable_head",
+           "idf_read_head"]
 
 
 class IdfError(RuntimeError):
@@ -82,6 +83,8 @@ def load_library():
     L.idf_reset_streams.argtypes = [C.c_void_p, C.c_void_p, C.c_int]
     L.idf_get_stats.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
     L.idf_rows_pushed.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_int64)]
+    L.idf_enable_head.argtypes = [C.c_void_p]
+    L.idf_read_head.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
     L.idf_profile_begin.argtypes = [C.c_void_p]
     L.idf_profile_end.argtypes = [C.c_void_p, C.c_int, C.POINTER(KernelProfile), C.POINTER(C.c_int)]
     _LIB = L
@@ -202,6 +205,18 @@ class Streams:
         r = C.c_int64()
         _check(load_library().idf_rows_pushed(self._h, stream_id, C.byref(r)))
         return r.value
+
+    def enable_head(self):
+        _check(load_library().idf_enable_head(self._h))
+
+    def read_head(self, stream_ids=None):
+        """(rows averaged [n], mean [n][out_c]) of the averaging output units."""
+        keep, ptr = _ids(stream_ids)
+        n = self.n_streams if stream_ids is None else len(keep)
+        mean = np.zeros((n, int(self.sizes.out_c)), dtype=np.float64)
+        rows = np.zeros(n, dtype=np.int64)
+        _check(load_library().idf_read_head(self._h, ptr, n, mean.ctypes.data, rows.ctypes.data))
+        return rows, mean
 
     def profile_begin(self):
         _check(load_library().idf_profile_begin(self._h))

@@ -244,4 +244,17 @@ struct CopyOut {
     int elem_bytes;
 };
 
+// Averaging output units: rows [first_slot, first_slot + n_rows) of the output ring are added to
+// the per-channel sums of each selected stream.
+struct HeadAcc {
+    const void *src;             // output area [stream][out_cap][w][c], 4-byte elements
+    int64_t src_stream_stride;
+    int64_t out_cap;
+    int w, c;
+    int is_int;                  // elements are int32 (else float32)
+    int zero_first;              // the sums start anew with these rows
+    double count;                // positions averaged once these rows are in
+    double *sums, *mean;         // [stream][c] each
+};
+
 }  // namespace idf

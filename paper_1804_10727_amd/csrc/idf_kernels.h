@@ -34,16 +34,17 @@ __device__ __forceinline__ void lds_barrier()
 #endif
 }
 
-enum KernelKind { kKindConvGeneric = 0, kKindPoolGeneric, kKindCopyOut, kKindCascade1d, kKindConvMfma, kKindCount };
+enum KernelKind { kKindConvGeneric = 0, kKindPoolGeneric, kKindCopyOut, kKindCascade1d, kKindConvMfma, kKindHead, kKindCount };
 inline const char *kind_name(int k)
 {
-    static const char *names[kKindCount] = {"conv_generic", "pool_generic", "copy_out", "cascade1d", "conv3x3_mfma"};
+    static const char *names[kKindCount] = {"conv_generic", "pool_generic", "copy_out", "cascade1d", "conv3x3_mfma", "head_accumulate"};
     return k >= 0 && k < kKindCount ? names[k] : "?";
 }
 
 // Generic kernels: any layer shape, any precision (prec = IDF_PREC_*).
 hipError_t launch_conv_generic(int prec, const ConvStep &a, const StreamSel &sel, const LaunchCtx &lc);
 hipError_t launch_pool_generic(int prec, const PoolStep &a, const StreamSel &sel, const LaunchCtx &lc);
+hipError_t launch_head_accumulate(const HeadAcc &a, const StreamSel &sel, int64_t first_slot, int n_rows, const LaunchCtx &lc);
 hipError_t launch_copy_out(const CopyOut &a, const StreamSel &sel, int64_t first_slot, int n_rows,
                            const LaunchCtx &lc);
 

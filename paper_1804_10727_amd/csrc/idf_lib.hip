@@ -12,6 +12,7 @@
 #include <map>
 #include <new>
 #include <string>
+#include <tuple>
 #include <vector>
 
 #include "idf.h"
@@ -59,6 +60,8 @@ struct StreamHost {
     int64_t r = 0;            // rows of the current sample received
     int64_t out_written = 0;  // output rows completed since open/reset
     int64_t out_read = 0;     // output rows handed over
+    int64_t head_done = 0;    // output rows the averaging units have taken in
+    int64_t head_base = 0;    // first of the rows they average (start of the current sample)
 };
 
 struct ProfRec {
@@ -82,7 +85,8 @@ struct idf_streams {
     std::vector<int> mfma;           // per layer: 1 = matrix-core conv kernel, 2 = pool fused into the conv before it
     std::vector<int64_t> ring_stride, held_stride, transit_stride;   // elements per stream
     std::vector<int> transit_cap;                                    // rows per stream
-    size_t out_off = 0, stats_off = 0;
+    size_t out_off = 0, stats_off = 0, head_off = 0;
+    bool head_on = false;
     int64_t out_stride = 0;
     std::vector<std::vector<float>> cas_w;      // cascade packing of the weights (kept until the upload has run)
     // 1-D cascade, layers dealt to stages that run side by side, stage k on the segment pushed k
@@ -148,7 +152,7 @@ struct Layout {
     std::vector<size_t> w_off, b_off, wm_off, ring_off, held_off, transit_off;
     std::vector<int64_t> ring_stride, held_stride, transit_stride;
     std::vector<int> transit_cap;
-    size_t out_off = 0, stats_off = 0, total = 0;
+    size_t out_off = 0, stats_off = 0, head_off = 0, total = 0;
     int64_t out_stride = 0;
     bool cascade1d = false;          // the whole-net 1-D kernel serves this stream set
     size_t cas_transit_off = 0;      // hand-over rows between the cascade's stages
@@ -233,6 +237,7 @@ int make_layout(const idf_net &net, int B, int max_seg, int64_t out_cap, Layout 
     L.out_stride = out_cap * net.out_w * net.out_c;
     L.out_off = off; off = align_up(off + (size_t)L.out_stride * 4 * B);
     L.stats_off = off; off = align_up(off + (size_t)B * n * 2 * sizeof(unsigned long long));
+    L.head_off = off; off = align_up(off + (size_t)B * net.out_c * 2 * sizeof(double));   // sums, means
     if (L.cascade1d) {
         L.cas_transit_off = off;
         off = align_up(off + (size_t)(kCasMaxStages - 1) * 2 * B * kCasRowsMax * 64 * 4);
@@ -763,6 +768,48 @@ int enqueue_cascade(idf_streams *s, const StreamSel &sel, const void *dev_rows, 
     return IDF_OK;
 }
 
+// The averaging units take in the output rows completed since they last did.  Must run before
+// read_outputs gives those rows' slots free.
+int head_catch_up(idf_streams *s, const int32_t *stream_ids, int n_ids)
+{
+    if (!s->head_on) return IDF_OK;
+    const idf_net &net = *s->net;
+    struct Key { int64_t slot; int64_t n; int zero; int64_t count;
+                 bool operator<(const Key &o) const { return std::tie(slot, n, zero, count) < std::tie(o.slot, o.n, o.zero, o.count); } };
+    std::map<Key, std::vector<std::pair<int, int>>> groups;
+    for (int i = 0; i < n_ids; ++i) {
+        const int id = stream_ids ? stream_ids[i] : i;
+        StreamHost &h = s->h[id];
+        const int64_t b = h.out_written;
+        int64_t a = h.head_done;
+        if (b <= a) continue;
+        int zero = 0;
+        if (net.out_h > 0) {
+            const int64_t sb = (b - 1) / net.out_h * net.out_h;      // first row of the newest sample with a row
+            if (sb > h.head_base) { zero = 1; a = std::max(a, sb); h.head_base = sb; }
+        }
+        if (b - a > s->out_cap) return fail(IDF_ESTATE, "internal: rows for the averaging units no longer in the output area");
+        groups[Key{a % s->out_cap, b - a, zero, (b - h.head_base) * (int64_t)net.out_w}].push_back({i, id});
+        h.head_done = b;
+    }
+    HeadAcc a{};
+    a.src = s->ws + s->out_off; a.src_stream_stride = s->out_stride; a.out_cap = s->out_cap;
+    a.w = net.out_w; a.c = net.out_c; a.is_int = net.precision == IDF_PREC_I8;
+    a.sums = (double *)(s->ws + s->head_off); a.mean = a.sums + (size_t)s->B * net.out_c;
+    for (auto &kv : groups) {
+        a.zero_first = kv.first.zero; a.count = (double)kv.first.count;
+        const int64_t slot = kv.first.slot;
+        const int n = (int)kv.first.n;
+        int rc = for_each_selection(kv.second, [&](const StreamSel &sel) {
+            hipError_t e = launch_head_accumulate(a, sel, slot, n,
+                                                  launch_ctx(s, kKindHead, 4.0 * n * net.out_w * net.out_c * sel.n));
+            return e == hipSuccess ? IDF_OK : dev_fail(e, "head launch");
+        });
+        if (rc != IDF_OK) return rc;
+    }
+    return IDF_OK;
+}
+
 }  // namespace
 
 // -----------------------------------------------------------------------------------------
@@ -881,6 +928,7 @@ int idf_open_streams(idf_net *net, int n_streams, int max_seg_rows, int64_t out_
     s->transit_stride = L.transit_stride; s->transit_cap = L.transit_cap;
     s->out_off = L.out_off; s->stats_off = L.stats_off; s->out_stride = L.out_stride; s->sizes = L.sizes;
     s->use_cascade1d = L.cascade1d;
+    s->head_off = L.head_off;
     s->cas_transit_off = L.cas_transit_off;
     if (L.cascade1d) plan_cascade_stages(s);
     s->mfma.assign(net->g.size(), 0);
@@ -996,6 +1044,8 @@ int idf_read_outputs(idf_streams *s, const int32_t *stream_ids, int n_ids, void 
     if (max_rows < 1) return fail(IDF_EINVAL, "max_rows must be >= 1");
     rc = pipeline_drain(s);                // rows still between stages belong to what was pushed
     if (rc != IDF_OK) return rc;
+    rc = head_catch_up(s, stream_ids, n_ids);
+    if (rc != IDF_OK) return rc;
     const idf_net &net = *s->net;
     std::map<std::pair<int64_t, int>, std::vector<std::pair<int, int>>> groups;
     for (int i = 0; i < n_ids; ++i) {
@@ -1035,6 +1085,9 @@ int idf_reset_streams(idf_streams *s, const int32_t *stream_ids, int n_ids)
     for (int i = 0; i < n_ids; ++i) {
         const int id = stream_ids ? stream_ids[i] : i;
         hipError_t e = hipMemsetAsync(s->ws + s->stats_off + per * id, 0, per, s->st);
+        if (e == hipSuccess)
+            e = hipMemsetAsync(s->ws + s->head_off + (size_t)id * s->net->out_c * sizeof(double), 0,
+                               (size_t)s->net->out_c * sizeof(double), s->st);
         if (e != hipSuccess) return dev_fail(e, "reset_streams");
         s->h[id] = StreamHost{};
     }
@@ -1068,6 +1121,40 @@ int idf_rows_pushed(const idf_streams *s, int stream_id, int64_t *rows)
     if (!s || !rows) return fail(IDF_EINVAL, "null argument");
     if (stream_id < 0 || stream_id >= s->B) return fail(IDF_EINVAL, "stream id %d outside [0, %d)", stream_id, s->B);
     *rows = s->h[stream_id].r;
+    return IDF_OK;
+}
+
+int idf_enable_head(idf_streams *s)
+{
+    if (!s) return fail(IDF_EINVAL, "null argument");
+    for (const StreamHost &h : s->h)
+        if (h.r != 0 || h.out_written != 0) return fail(IDF_ESTATE, "the averaging units must be enabled before the first push");
+    s->head_on = true;
+    return IDF_OK;
+}
+
+int idf_read_head(idf_streams *s, const int32_t *stream_ids, int n_ids, double *mean, int64_t *rows)
+{
+    if (!s || !mean || !rows) return fail(IDF_EINVAL, "null argument");
+    if (!s->head_on) return fail(IDF_ESTATE, "the averaging units are not enabled");
+    int rc = check_ids(s, stream_ids, n_ids);
+    if (rc != IDF_OK) return rc;
+    rc = pipeline_drain(s);
+    if (rc != IDF_OK) return rc;
+    rc = head_catch_up(s, stream_ids, n_ids);
+    if (rc != IDF_OK) return rc;
+    const int c = s->net->out_c;
+    std::vector<double> all((size_t)s->B * c);
+    hipError_t e = hipStreamSynchronize(s->st);
+    if (e == hipSuccess)
+        e = hipMemcpy(all.data(), s->ws + s->head_off + (size_t)s->B * c * sizeof(double), all.size() * sizeof(double),
+                      hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return dev_fail(e, "read_head");
+    for (int i = 0; i < n_ids; ++i) {
+        const int id = stream_ids ? stream_ids[i] : i;
+        rows[i] = s->h[id].head_done - s->h[id].head_base;
+        for (int k = 0; k < c; ++k) mean[(size_t)i * c + k] = rows[i] > 0 ? all[(size_t)id * c + k] : 0.0;
+    }
     return IDF_OK;
 }
 

@@ -353,4 +353,47 @@ hipError_t launch_copy_out(const CopyOut &a, const StreamSel &sel, int64_t first
                   first_slot, n_rows);
 }
 
+// ---------------------------------------------------------------------------------------
+// Averaging output units (Fig. 1): per stream and channel, the sum over all positions of the
+// rows the last layer has completed, and the running mean.  One workgroup per (stream, block of
+// 64 channels); four groups of lanes take every fourth position and are added in a fixed order.
+// ---------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_head_accumulate(const HeadAcc a, const StreamSel sel, int64_t first_slot,
+                                                         int n_rows)
+{
+    __shared__ double part[4][64];
+    const int stream = sel_stream(sel, blockIdx.z);
+    const int cl = threadIdx.x & 63, grp = threadIdx.x >> 6;
+    const int ch = blockIdx.x * 64 + cl;
+    const uint32_t *src = (const uint32_t *)a.src + (int64_t)stream * a.src_stream_stride;
+    double acc = 0.0;
+    if (ch < a.c) {
+        for (int r = 0; r < n_rows; ++r) {
+            int64_t slot = first_slot + r;
+            if (slot >= a.out_cap) slot -= a.out_cap;
+            const uint32_t *row = src + slot * (int64_t)a.w * a.c;
+            for (int x = grp; x < a.w; x += 4) {
+                const uint32_t u = row[(int64_t)x * a.c + ch];
+                acc += a.is_int ? (double)(int32_t)u : (double)__uint_as_float(u);
+            }
+        }
+    }
+    part[grp][cl] = acc;
+    __syncthreads();
+    if (grp == 0 && ch < a.c) {
+        const int64_t at = (int64_t)stream * a.c + ch;
+        double sum = a.zero_first ? 0.0 : a.sums[at];
+        sum += ((part[0][cl] + part[1][cl]) + part[2][cl]) + part[3][cl];
+        a.sums[at] = sum;
+        a.mean[at] = a.count > 0.0 ? sum / a.count : 0.0;
+    }
+}
+
+hipError_t launch_head_accumulate(const HeadAcc &a, const StreamSel &sel, int64_t first_slot, int n_rows,
+                                  const LaunchCtx &lc)
+{
+    return launch(k_head_accumulate, dim3((unsigned)((a.c + 63) / 64), 1, sel.n), dim3(256), 0, lc, a, sel, first_slot,
+                  n_rows);
+}
+
 }  // namespace idf

@@ -1,0 +1,98 @@
+"""GPU parity for the averaging output units (Fig. 1; Sec. 4: output units whose value settles as
+rows come in): running per-channel mean of the last layer's completed rows, against the oracle's
+head fed the same rows, at several points of the presentation."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl_mod
+from helpers import TOL
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle_stream(wl, b):
+    return oracle.Stream(wl["layers"], wl["in_h"], wl["in_w"], wl["in_c"], wl["weights"], wl["biases"],
+                         integer=wl["precision"] == "i8",
+                         emit_round="bf16" if wl["precision"] == "bf16" else None, avg_head=True)
+
+
+def _check(wl, seg, read_at, exact):
+    import paper_1804_10727_amd as idf
+    from paper_1804_10727_amd.binding import input_tensor
+    B, H = wl["streams"], wl["in_h"]
+    net = idf.net_from_workload(wl)
+    st = idf.Streams(net, B, max_seg_rows=seg)
+    st.enable_head()
+    ref = [_oracle_stream(wl, b) for b in range(B)]
+    x = input_tensor(wl)
+    seen_nonzero = False
+    for i, r in enumerate(range(0, H, seg)):
+        st.push_segment(x[:, r:r + seg].contiguous())
+        for b in range(B):
+            ref[b].push(wl["x"][b, r:r + seg])
+        if i in read_at or r + seg >= H:
+            rows, mean = st.read_head()
+            for b in range(B):
+                o_rows, o_mean = ref[b].head()
+                assert rows[b] == o_rows
+                scale = max(float(np.max(np.abs(o_mean))), 1e-30)
+                err = float(np.max(np.abs(mean[b] - o_mean))) / scale
+                assert err <= (1e-12 if exact else (2e-2 if wl["precision"] == "bf16" else TOL["f32"])), (i, b, err)
+                seen_nonzero |= o_rows > 0 and scale > 1e-20
+        if i == 1:      # reading outputs in between must not disturb the units
+            st.read_outputs(4)
+    assert seen_nonzero
+    st.close(); net.destroy()
+
+
+def test_fig1_net_one_sample_per_push():
+    # the two-layer K=3 net of Fig. 1 with its averaging output neuron, one sample at a time
+    from workloads import conv
+    rng = np.random.default_rng(5)
+    layers = [conv(1, 1, 3, 1), conv(1, 1, 3, 1)]
+    ws = [(np.abs(rng.normal(size=(1, 1, 3, 1))) + 0.1).astype(np.float32) for _ in layers]
+    x = (rng.random((1, 60, 1, 1)) + 0.25).astype(np.float32)
+    wl = dict(name="fig1", precision="f32", in_h=60, in_w=1, in_c=1, layers=layers, weights=ws,
+              biases=[None, None], x=x, seg_rows=1, streams=1)
+    _check(wl, 1, read_at={0, 3, 4, 5, 6, 20}, exact=False)
+
+
+def test_1d_streams_in_segments():
+    wl = wl_mod.make(2, streams=3, length=480, channels=(8, 8, 16, 16, 32, 32))
+    _check(wl, 16, read_at={0, 2, 3, 9, 17}, exact=False)
+
+
+def test_2d_int_exact_and_float():
+    wl = wl_mod.make(4, streams=2, size=24, channels=(4, 4, 8, 8, 16, 16, 16, 16))
+    _check(wl, 1, read_at={5, 12, 20, 23}, exact=True)
+    wl = wl_mod.make(3, streams=3, size=16, channels=(8, 8, 16, 16))
+    _check(wl, 2, read_at={1, 3, 6}, exact=False)
+
+
+def test_head_restarts_with_the_next_sample_and_needs_enabling():
+    import paper_1804_10727_amd as idf
+    from paper_1804_10727_amd.binding import input_tensor
+    wl = wl_mod.make(3, streams=4, size=12, channels=(8, 8, 8, 8))
+    net = idf.net_from_workload(wl)
+    st = idf.Streams(net, 2)
+    with pytest.raises(idf.IdfError):
+        st.read_head()
+    st.enable_head()
+    x = input_tensor(wl)
+    for sample in range(2):
+        for r in range(12):
+            st.push_segment(x[2 * sample:2 * sample + 2, r:r + 1].contiguous())
+            if sample == 1 and r == 6:
+                st.read_outputs(64)          # the first sample's rows leave the output area
+        rows, mean = st.read_head()
+        for i in range(2):
+            ref = _oracle_stream(wl, 2 * sample + i)
+            ref.push(wl["x"][2 * sample + i])
+            o_rows, o_mean = ref.head()
+            assert rows[i] == o_rows == st.sizes.out_h
+            assert np.max(np.abs(mean[i] - o_mean)) <= TOL["f32"] * np.max(np.abs(o_mean))
+    st.push_segment(x[0:2, 0:1].contiguous())
+    with pytest.raises(idf.IdfError):
+        st.enable_head()
+    st.close(); net.destroy()
