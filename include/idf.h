@@ -174,6 +174,22 @@ int idf_rows_pushed(const idf_streams *s, int stream_id, int64_t *rows);
  * idf_enable_head: before the first push after open (IDF_ESTATE otherwise).
  * idf_read_head: mean (host) [n_ids][out_c], rows (host) [n_ids] = rows averaged.  Synchronises
  * the stream.  IDF_ESTATE if the head was not enabled. */
+/* The retained state of one stream -- the "hidden state" of the recurrent view of Sec. 5: rolling
+ * buffers of c of every conv layer, held rows of the pools, the counters of idf_get_stats, the
+ * averaging units, and where the stream stands -- copied to / from a caller-owned device buffer
+ * of idf_snapshot_bytes() bytes.  A snapshot can be restored into any stream of the same set of
+ * open streams: that stream continues exactly where the snapshot was taken; what it held before
+ * is gone.  Both need the stream's completed output rows to have been read (IDF_ESTATE otherwise);
+ * both are enqueued on the stream like a push. */
+typedef struct {
+    int64_t rows_pushed;      /* rows of the current sample received */
+    int64_t out_rows;         /* output rows completed (and read) since open / reset */
+    int64_t head_rows;        /* rows the averaging units hold */
+} idf_stream_pos;
+int idf_snapshot_bytes(const idf_streams *s, size_t *bytes);
+int idf_snapshot(idf_streams *s, int stream_id, void *dev_buf, idf_stream_pos *pos);
+int idf_restore(idf_streams *s, int stream_id, const void *dev_buf, const idf_stream_pos *pos);
+
 int idf_enable_head(idf_streams *s);
 int idf_read_head(idf_streams *s, const int32_t *stream_ids, int n_ids, double *mean, int64_t *rows);
 

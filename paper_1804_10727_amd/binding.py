@@ -17,7 +17,7 @@ ACT = {"none": 0, "relu": 1, "relu_shr_clamp": 2}
 EXPORTS = ["idf_create_net", "idf_destroy_net", "idf_query_sizes", "idf_open_streams", "idf_close_streams",
            "idf_push_segment", "idf_read_outputs", "idf_reset_streams", "idf_get_stats", "idf_rows_pushed",
            "idf_layer_kernel", "idf_last_error", "idf_profile_begin", "idf_profile_end", "idf_enable_head",
-           "idf_read_head"]
+           "idf_read_head", "idf_snapshot_bytes", "idf_snapshot", "idf_restore"]
 
 
 class IdfError(RuntimeError):
@@ -84,6 +84,9 @@ def load_library():
     L.idf_get_stats.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
     L.idf_rows_pushed.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_int64)]
     L.idf_enable_head.argtypes = [C.c_void_p]
+    L.idf_snapshot_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
+    L.idf_snapshot.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+    L.idf_restore.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
     L.idf_read_head.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
     L.idf_profile_begin.argtypes = [C.c_void_p]
     L.idf_profile_end.argtypes = [C.c_void_p, C.c_int, C.POINTER(KernelProfile), C.POINTER(C.c_int)]
@@ -205,6 +208,21 @@ class Streams:
         r = C.c_int64()
         _check(load_library().idf_rows_pushed(self._h, stream_id, C.byref(r)))
         return r.value
+
+    def snapshot(self, stream_id):
+        """(device buffer, position) holding the stream's retained state."""
+        import torch
+        L = load_library()
+        nb = C.c_size_t()
+        _check(L.idf_snapshot_bytes(self._h, C.byref(nb)))
+        buf = torch.empty(max(1, nb.value), dtype=torch.uint8, device=self.device)
+        pos = (C.c_int64 * 3)()
+        _check(L.idf_snapshot(self._h, stream_id, C.c_void_p(buf.data_ptr()), pos))
+        return buf, tuple(pos)
+
+    def restore(self, stream_id, buf, pos):
+        arr = (C.c_int64 * 3)(*pos)
+        _check(load_library().idf_restore(self._h, stream_id, C.c_void_p(buf.data_ptr()), arr))
 
     def enable_head(self):
         _check(load_library().idf_enable_head(self._h))

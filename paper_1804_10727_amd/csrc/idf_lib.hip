@@ -768,6 +768,19 @@ int enqueue_cascade(idf_streams *s, const StreamSel &sel, const void *dev_rows, 
     return IDF_OK;
 }
 
+// One stream's pieces of the workspace, in the order they are laid out in a snapshot.
+template <class F> void for_each_state_piece(const idf_streams *s, int id, F &&f)
+{
+    const idf_net &net = *s->net;
+    const int n = (int)net.g.size();
+    const int eb = ev_bytes(net.precision);
+    for (int l = 0; l < n; ++l) {
+        if (net.g[l].kind == IDF_CONV) f(s->ring_off[l] + (size_t)id * s->ring_stride[l] * 4, (size_t)s->ring_stride[l] * 4);
+        else f(s->held_off[l] + (size_t)id * s->held_stride[l] * eb, (size_t)s->held_stride[l] * eb);
+    }
+    f(s->stats_off + (size_t)id * n * 2 * sizeof(unsigned long long), (size_t)n * 2 * sizeof(unsigned long long));
+    f(s->head_off + (size_t)id * net.out_c * sizeof(double), (size_t)net.out_c * sizeof(double));
+}
 // The averaging units take in the output rows completed since they last did.  Must run before
 // read_outputs gives those rows' slots free.
 int head_catch_up(idf_streams *s, const int32_t *stream_ids, int n_ids)
@@ -1121,6 +1134,63 @@ int idf_rows_pushed(const idf_streams *s, int stream_id, int64_t *rows)
     if (!s || !rows) return fail(IDF_EINVAL, "null argument");
     if (stream_id < 0 || stream_id >= s->B) return fail(IDF_EINVAL, "stream id %d outside [0, %d)", stream_id, s->B);
     *rows = s->h[stream_id].r;
+    return IDF_OK;
+}
+
+int idf_snapshot_bytes(const idf_streams *s, size_t *bytes)
+{
+    if (!s || !bytes) return fail(IDF_EINVAL, "null argument");
+    size_t total = 0;
+    for_each_state_piece(s, 0, [&](size_t, size_t n) { total += align_up(n, 16); });
+    *bytes = total;
+    return IDF_OK;
+}
+
+int idf_snapshot(idf_streams *s, int stream_id, void *dev_buf, idf_stream_pos *pos)
+{
+    if (!s || !dev_buf || !pos) return fail(IDF_EINVAL, "null argument");
+    if (stream_id < 0 || stream_id >= s->B) return fail(IDF_EINVAL, "stream id %d outside [0, %d)", stream_id, s->B);
+    int rc = pipeline_drain(s);
+    if (rc != IDF_OK) return rc;
+    const int32_t id32 = stream_id;
+    rc = head_catch_up(s, &id32, 1);
+    if (rc != IDF_OK) return rc;
+    const StreamHost &h = s->h[stream_id];
+    if (h.out_written != h.out_read) return fail(IDF_ESTATE, "stream %d: %lld completed output rows not read yet", stream_id,
+                                                 (long long)(h.out_written - h.out_read));
+    size_t at = 0;
+    hipError_t e = hipSuccess;
+    for_each_state_piece(s, stream_id, [&](size_t off, size_t n) {
+        if (e == hipSuccess && n) e = hipMemcpyAsync((char *)dev_buf + at, s->ws + off, n, hipMemcpyDeviceToDevice, s->st);
+        at += align_up(n, 16);
+    });
+    if (e != hipSuccess) return dev_fail(e, "snapshot");
+    pos->rows_pushed = h.r; pos->out_rows = h.out_written; pos->head_rows = h.head_done - h.head_base;
+    return IDF_OK;
+}
+
+int idf_restore(idf_streams *s, int stream_id, const void *dev_buf, const idf_stream_pos *pos)
+{
+    if (!s || !dev_buf || !pos) return fail(IDF_EINVAL, "null argument");
+    if (stream_id < 0 || stream_id >= s->B) return fail(IDF_EINVAL, "stream id %d outside [0, %d)", stream_id, s->B);
+    const idf_net &net = *s->net;
+    if (pos->rows_pushed < 0 || (net.in_h > 0 && pos->rows_pushed >= net.in_h) || pos->out_rows < 0 ||
+        pos->head_rows < 0 || pos->head_rows > pos->out_rows)
+        return fail(IDF_EINVAL, "inconsistent stream position");
+    int rc = pipeline_drain(s);
+    if (rc != IDF_OK) return rc;
+    StreamHost &h = s->h[stream_id];
+    if (h.out_written != h.out_read) return fail(IDF_ESTATE, "stream %d: %lld completed output rows not read yet", stream_id,
+                                                 (long long)(h.out_written - h.out_read));
+    size_t at = 0;
+    hipError_t e = hipSuccess;
+    for_each_state_piece(s, stream_id, [&](size_t off, size_t n) {
+        if (e == hipSuccess && n) e = hipMemcpyAsync(s->ws + off, (const char *)dev_buf + at, n, hipMemcpyDeviceToDevice, s->st);
+        at += align_up(n, 16);
+    });
+    if (e != hipSuccess) return dev_fail(e, "restore");
+    h.r = pos->rows_pushed; h.out_written = h.out_read = pos->out_rows;
+    h.head_done = pos->out_rows; h.head_base = pos->out_rows - pos->head_rows;
     return IDF_OK;
 }
 
