@@ -36,6 +36,75 @@ KERNEL_PEAK = {
 }
 
 
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
+KERNEL_SYMBOL = {"cascade1d": "k_cascade1d", "conv3x3_mfma": "k_conv3x3_mfma", "conv_generic": "k_conv_generic"}
+
+
+def sources_digest():
+    """Digest of the kernel and host sources: counter readings are only quoted for the code they were taken on."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_1804_10727_amd", "csrc", "*")) + [os.path.join(ROOT, "include", "idf.h")]):
+        h.update(open(f, "rb").read())
+    return h.hexdigest()
+
+
+def stored_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed counter runs, or None (none taken, or
+    the sources have changed since)."""
+    try:
+        rec = json.load(open(TRAFFIC_FILE)).get(workload)
+    except (OSError, ValueError):
+        return None
+    if not rec or rec.get("kernel") != kernel or rec.get("sources_sha256") != sources_digest():
+        return None
+    return rec["fetch_bytes_per_launch"] + rec["write_bytes_per_launch"]
+
+
+def traffic_from_counters(config, fetch_dir, write_dir):
+    """Turns two `rocprofv3 --pmc` runs of this bench (FETCH_SIZE, then WRITE_SIZE; KiB per
+    dispatch) into HBM bytes per launch of the dominant kernel.  Each counter is scaled by what
+    it reads for the plain copy kernel of read_outputs, whose size is known."""
+    import csv
+    import glob
+    import workloads
+    wl = workloads.make(config)
+    shape = workloads.output_shape(wl)
+    copy_kib = wl["streams"] * float(shape[0] * shape[1] * shape[2]) * 4 / 1024.0       # read = written
+
+    def averages(d, counter):
+        tot, cnt = {}, {}
+        for f in glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True):
+            for row in csv.DictReader(open(f)):
+                if row["Counter_Name"] != counter:
+                    continue
+                k = row["Kernel_Name"]
+                tot[k] = tot.get(k, 0.0) + float(row["Counter_Value"]); cnt[k] = cnt.get(k, 0) + 1
+        return {k: (tot[k] / cnt[k], cnt[k]) for k in tot}
+
+    out = {}
+    for counter, d in (("FETCH_SIZE", fetch_dir), ("WRITE_SIZE", write_dir)):
+        av = averages(d, counter)
+        copy = [v for k, v in av.items() if "k_copy_out" in k]
+        assert copy, f"no k_copy_out dispatch in {d}"
+        factor = copy_kib / copy[0][0]
+        dom = {k: v for k, v in av.items() if any(sym in k for sym in KERNEL_SYMBOL.values())}
+        name = max(dom, key=lambda k: dom[k][0] * dom[k][1])
+        out[counter] = (factor, dom[name][0] * factor * 1024.0, name, dom[name][1])
+    family = [f for f, sym in KERNEL_SYMBOL.items() if sym in out["FETCH_SIZE"][2]][0]
+    rec = {"kernel": family, "fetch_factor": out["FETCH_SIZE"][0], "write_factor": out["WRITE_SIZE"][0],
+           "fetch_bytes_per_launch": out["FETCH_SIZE"][1], "write_bytes_per_launch": out["WRITE_SIZE"][1],
+           "dispatches": out["FETCH_SIZE"][3], "sources_sha256": sources_digest()}
+    try:
+        allrec = json.load(open(TRAFFIC_FILE))
+    except (OSError, ValueError):
+        allrec = {}
+    allrec[WORKLOADS[config]] = rec
+    json.dump(allrec, open(TRAFFIC_FILE, "w"), indent=1, sort_keys=True)
+    print(json.dumps({WORKLOADS[config]: rec}, indent=1))
+
+
 def cpu_baseline(wl, budget_s=20.0):
     """The CPU oracle's event-by-event streaming scheme, as it stands, on this machine's cores."""
     import oracle
@@ -154,7 +223,7 @@ def run_workload(config, steps_arg=None, warmup_arg=None):
     else:
         roof = {"bound": "hbm", "achieved": bytes_per_launch / avg_s / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    roof["traffic"] = stored_traffic(WORKLOADS[config], dom["name"])
     roof.update({"kernel": dom["name"], "avg_launch_us": avg_s * 1e6, "launches_per_step": dom["launches"],
                  "algorithmic_bytes_per_launch": bytes_per_launch, "executed_flops_per_launch": flops_per_launch,
                  "kernel_time_share": dom["total_ms"] / sum(p["total_ms"] for p in prof),
@@ -190,7 +259,13 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", dest="others", action="store_false",
                     help="skip the short runs of the other workloads (reported under other_workloads)")
+    ap.add_argument("--traffic-from", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"),
+                    help="no GPU run: read two rocprofv3 --pmc outputs of this bench (FETCH_SIZE, WRITE_SIZE) "
+                         "and store the dominant kernel's HBM bytes per launch in profiles/traffic.json")
     args = ap.parse_args()
+    if args.traffic_from:
+        traffic_from_counters(args.config, *args.traffic_from)
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (streams are independent: more GPUs "
               "would each take a share of the streams, no figure for that is produced here)", file=sys.stderr)
