@@ -224,10 +224,24 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     Lds &lds = *reinterpret_cast<Lds *>(lds_raw);
     const int tid = threadIdx.x, lane = tid & 63;
-    const int si = blockIdx.x;
+    // Workgroups go to the eight XCDs in turn by their linear number.  The stages are dealt to the
+    // XCDs (with four stages, two XCDs each): a stage's weights are then fetched into the L2 of
+    // its XCDs only, not into all eight.
+    int si, stage;
+    {
+        const int id = blockIdx.x, n_st = ka.n_stages;
+        if ((8 % n_st) == 0 && ((sel.n * n_st) & 7) == 0) {
+            const int per = 8 / n_st, xcd = id & 7;
+            stage = xcd / per;
+            si = (id >> 3) * per + (xcd - stage * per);
+        } else {
+            stage = id / sel.n;
+            si = id - stage * sel.n;
+        }
+    }
     const int stream = sel_stream(sel, si);
     const int n_layers = ka.n_layers;
-    const int stage = blockIdx.y, lb = ka.stage_lo[stage], le = ka.stage_lo[stage + 1];
+    const int lb = ka.stage_lo[stage], le = ka.stage_lo[stage + 1];
     if (ka.sched[lb].cnt <= 0) return;                           // nothing has reached this stage
 
     // The argument block (first kernel argument, offset 0 of the kernel-argument segment) goes to
@@ -496,7 +510,7 @@ hipError_t launch_cascade1d(const CascadeArgs &a, const StreamSel &sel, const La
     static hipError_t prepared = hipFuncSetAttribute(reinterpret_cast<const void *>(k_cascade1d),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Lds));
     if (prepared != hipSuccess) return prepared;
-    return launch(k_cascade1d, dim3(sel.n, a.n_stages), dim3(kCasThreads), sizeof(Lds), lc, a, sel);
+    return launch(k_cascade1d, dim3(sel.n * a.n_stages), dim3(kCasThreads), sizeof(Lds), lc, a, sel);
 }
 
 }  // namespace idf

@@ -136,7 +136,7 @@ constexpr int kMaxPos = 128 + 2;                 // positions of the widest tile
 constexpr int kNzWords = (kMaxPos + 31) / 32 + 1;
 
 template <class T, int WM, int WN>
-__device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &sel, const int bx)
+__device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &sel, const int bx, const int si)
 {
     using acc_t = typename T::acc_t; using st_t = typename T::st_t; using ev_t = typename T::ev_t;
     constexpr int VL = T::VL, EB = T::EB, KI = 2 * VL;
@@ -159,7 +159,6 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
                  "s"(a.t[2].store_held), "s"(a.t[2].ring_slot), "s"(a.t[2].dst_slot), "s"(sel.n), "s"(sel.base), "s"(sel.pos0));
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WM, wn = wave / WM;
-    const int si = blockIdx.z;
     const int stream = sel_stream(sel, si);
     const int n_co_chunks = (a.c_out + NC - 1) / NC;
     const int x_tile = bx / n_co_chunks, co_chunk = bx - x_tile * n_co_chunks;
@@ -519,17 +518,23 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
 template <class T, int WM, int WN>
 __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a, const StreamSel sel)
 {
-    conv3x3_row<T, WM, WN>(a, sel, blockIdx.x);
+    conv3x3_row<T, WM, WN>(a, sel, blockIdx.x, blockIdx.z);
 }
 
 // Several layers' steps in one launch (each on a row that was complete before the launch): the
-// workgroups of step k are blockIdx.x in [wg_lo[k], wg_lo[k+1]).  One tile shape for all steps.
+// workgroups of step k are tiles [wg_lo[k], wg_lo[k+1]) for every stream.  One tile shape for all steps.
+// The work is laid out stream by stream, and within a stream step by step with the deepest (longest)
+// steps first; consecutive workgroups go to the eight XCDs in turn, which spreads every step evenly.
+// (Giving each XCD one contiguous eighth of a step-major order, so that a layer's weights meet in one
+// L2, was measured slower: the steps differ too much in length.)
 template <class T, int WM, int WN>
 __global__ void __launch_bounds__(64 * WM * WN, 2) k_conv3x3_mfma_batch(const MfmaBatch b, const StreamSel sel)
 {
-    int k = 0;
-    while (k + 1 < b.n && (int)blockIdx.x >= b.wg_lo[k + 1]) ++k;
-    conv3x3_row<T, WM, WN>(b.st[k], sel, (int)blockIdx.x - b.wg_lo[k]);
+    const int tile = blockIdx.x, si = blockIdx.z;
+    int k = 0;                                   // all bounds in one batch of scalar loads, no dependent chain
+#pragma unroll
+    for (int j = 1; j < kMfmaBatchMax; ++j) k += (j < b.n && tile >= b.wg_lo[j]) ? 1 : 0;
+    conv3x3_row<T, WM, WN>(b.st[k], sel, tile - b.wg_lo[k], si);
 }
 
 template <class T, int WM, int WN>
