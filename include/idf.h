@@ -140,6 +140,17 @@ int idf_close_streams(idf_streams *s);
 int idf_push_segment(idf_streams *s, const int32_t *stream_ids, int n_ids, const void *dev_rows,
                      int n_rows);
 
+/* Present the next n_px pixels of the current row (Sec. 3: segments can be arbitrarily small, down
+ * to single components): columns x0 .. x0+n_px-1, in order -- x0 must be the stream's next column.
+ *   dev_pixels (device): [n_ids][n_px][in_c] in the input type.
+ * The pixels are taken into the first layer's rolling buffer at once; rows can only become final,
+ * and the deeper layers fire, with the segment that makes the row whole (x0 + n_px == in_w), which
+ * then does everything a pushed row does.  A row begun this way must be finished this way.
+ * IDF_EUNSUPPORTED unless the first layer is a 3x3 / stride 1 / same-padded convolution (the one the
+ * matrix-core kernel serves); IDF_ESTATE: x0 is not the next column. */
+int idf_push_pixels(idf_streams *s, const int32_t *stream_ids, int n_ids, const void *dev_pixels, int x0,
+                    int n_px);
+
 /* Hand over the output rows completed since the previous read.
  *   dev_out (device): [n_ids][max_rows][out_w][out_c] float32 (F32, BF16) or int32 (I8); for
  *                     stream i rows 0 .. n_rows[i]-1 are written.

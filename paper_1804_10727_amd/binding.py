@@ -17,7 +17,7 @@ ACT = {"none": 0, "relu": 1, "relu_shr_clamp": 2}
 EXPORTS = ["idf_create_net", "idf_destroy_net", "idf_query_sizes", "idf_open_streams", "idf_close_streams",
            "idf_push_segment", "idf_read_outputs", "idf_reset_streams", "idf_get_stats", "idf_rows_pushed",
            "idf_layer_kernel", "idf_last_error", "idf_profile_begin", "idf_profile_end", "idf_enable_head",
-           "idf_read_head", "idf_snapshot_bytes", "idf_snapshot", "idf_restore"]
+           "idf_read_head", "idf_push_pixels", "idf_snapshot_bytes", "idf_snapshot", "idf_restore"]
 
 
 class IdfError(RuntimeError):
@@ -84,6 +84,7 @@ def load_library():
     L.idf_get_stats.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
     L.idf_rows_pushed.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_int64)]
     L.idf_enable_head.argtypes = [C.c_void_p]
+    L.idf_push_pixels.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int]
     L.idf_snapshot_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
     L.idf_snapshot.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
     L.idf_restore.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
@@ -179,6 +180,13 @@ class Streams:
         n_rows = rows.shape[1] if n_rows is None else n_rows
         assert rows.is_contiguous() and rows.is_cuda
         _check(load_library().idf_push_segment(self._h, ptr, n_ids, C.c_void_p(rows.data_ptr()), n_rows))
+
+    def push_pixels(self, pixels, x0, stream_ids=None):
+        """pixels: device tensor [n_ids][n_px][in_c] -- the next columns of the current row."""
+        keep, ptr = _ids(stream_ids)
+        assert pixels.is_contiguous()
+        _check(load_library().idf_push_pixels(self._h, ptr, pixels.shape[0], C.c_void_p(pixels.data_ptr()), int(x0),
+                                              int(pixels.shape[1])))
 
     def read_outputs(self, max_rows, stream_ids=None, n_ids=None, out=None):
         import torch

@@ -211,6 +211,8 @@ struct MfmaStep {
     int act, shr, clamp_hi;
     int layer, pool_layer, n_layers;   // pool_layer < 0: no fused pool
     int taps_y;                        // taps of this input row that land inside the output (for the counters)
+    int x_lo, x_hi;                    // columns of the input row that are given (a pixel segment); the rest reads as zero
+    int skip_clear_tiles;              // tiles no given column reaches have nothing to do (no row starts or ends)
     int tile;                          // kMfmaTile*
     MfmaTap t[3];
     const void *in;                    // input rows

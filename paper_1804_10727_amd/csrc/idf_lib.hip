@@ -62,6 +62,7 @@ struct StreamHost {
     int64_t out_read = 0;     // output rows handed over
     int64_t head_done = 0;    // output rows the averaging units have taken in
     int64_t head_base = 0;    // first of the rows they average (start of the current sample)
+    int x_next = 0;           // columns of the current row received (pixel segments)
 };
 
 struct ProfRec {
@@ -107,6 +108,8 @@ struct idf_streams {
     std::vector<int64_t> stg_seq;               // rows emitted by unit k so far
     int64_t stg_out_next = 0;                   // output slot of the next completed row
     int stg_tile = kMfmaTile64x64;              // tile shape of the staged launches
+    // a pixel segment being pushed: columns [x_lo, x_hi) of the current row of layer 0 (else the whole row)
+    struct Part { bool on = false; int x_lo = 0, x_hi = 0; bool first = true, last = true; } part;
     std::vector<StreamHost> h;
     std::vector<int> stamp;
     int stamp_gen = 0;
@@ -528,6 +531,10 @@ void make_mfma_step(idf_streams *s, int l, int64_t y, int n_streams, MfmaStep &a
     a.act = g.act; a.shr = g.shr; a.clamp_hi = g.clamp_hi;
     a.layer = l; a.pool_layer = pool ? l + 1 : -1; a.n_layers = n;
     a.tile = conv3x3_mfma_tile(g, n_streams);
+    const bool part = l == 0 && s->part.on;
+    a.x_lo = part ? s->part.x_lo : 0; a.x_hi = part ? s->part.x_hi : g.w_in;
+    const bool first_part = !part || s->part.first, last_part = !part || s->part.last;
+    a.skip_clear_tiles = !first_part && !last_part;
     const int64_t fin_after = rows_final(g, y + 1);
     int taps_y = 0;
     for (int ky = 0; ky < 3; ++ky) {
@@ -537,9 +544,9 @@ void make_mfma_step(idf_streams *s, int l, int64_t y, int n_streams, MfmaStep &a
         t.valid = o >= 0 && o < g.h_out;
         if (!t.valid) continue;
         ++taps_y;
-        t.fresh = std::max<int64_t>(0, o - 1) >= y;
+        t.fresh = first_part && std::max<int64_t>(0, o - 1) >= y;     // later segments of the row continue it
         t.ring_slot = (int)(o % 3);
-        const bool fin = o < fin_after;
+        const bool fin = last_part && o < fin_after;                  // nothing is final before the row is whole
         if (!fin) { t.emit = kEmitNone; continue; }
         int64_t row = o;                                // row index in the leaving layer
         if (!pool) t.emit = kEmitDirect;
@@ -604,6 +611,7 @@ int stg_tick(idf_streams *s, const void *dev_rows, int n_rows, int j, int64_t r)
         if (k == 0) {
             a.in = dev_rows; a.in_stream_stride = (int64_t)n_rows * net.in_w * net.in_c; a.in_by_position = 1;
             a.in_row_off = (int64_t)j * g.w_in * g.c_in;
+            if (s->part.on) { a.in_stream_stride = (int64_t)(s->part.x_hi - s->part.x_lo) * net.in_c; a.in_row_off = -(int64_t)s->part.x_lo * net.in_c; }
         } else {
             const int lp = l - 1;                 // the layer whose rows this one reads: conv or fused pool before it
             a.in = s->ws + s->transit_off[lp]; a.in_stream_stride = s->transit_stride[lp]; a.in_by_position = 0;
@@ -712,6 +720,7 @@ int enqueue_cascade(idf_streams *s, const StreamSel &sel, const void *dev_rows, 
                 }
                 a.in = in; a.in_stream_stride = in_stride; a.in_by_position = by_pos;
                 a.in_row_off = (y - in_row0) * (int64_t)g.w_in * g.c_in;
+                if (l == 0 && s->part.on) { a.in_stream_stride = (int64_t)(s->part.x_hi - s->part.x_lo) * net.in_c; a.in_row_off = -(int64_t)s->part.x_lo * net.in_c; }
                 hipError_t e = launch_conv3x3_mfma(net.precision, a, sel, launch_ctx(s, kKindConvMfma, bytes, l));
                 if (e != hipSuccess) return dev_fail(e, "mfma conv launch");
             }
@@ -1022,6 +1031,8 @@ int idf_push_segment(idf_streams *s, const int32_t *stream_ids, int n_ids, const
     for (int i = 0; i < n_ids; ++i) {
         const int id = stream_ids ? stream_ids[i] : i;
         const StreamHost &h = s->h[id];
+        if (h.x_next != 0 && !s->part.on)
+            return fail(IDF_ESTATE, "stream %d: %d columns of a row were pushed as pixels, the row must be finished that way", id, h.x_next);
         if (net.in_h > 0 && h.r + n_rows > net.in_h)
             return fail(IDF_ESTATE, "stream %d: rows %lld..%lld run past the sample of %d rows", id,
                         (long long)h.r, (long long)(h.r + n_rows - 1), net.in_h);
@@ -1043,8 +1054,58 @@ int idf_push_segment(idf_streams *s, const int32_t *stream_ids, int n_ids, const
         StreamHost &h = s->h[id];
         h.out_written += output_rows_of_push(net, h.r, n_rows);
         h.r += n_rows;
+        h.x_next = 0;
         if (net.in_h > 0 && h.r == net.in_h) h.r = 0;      // next sample
     }
+    return IDF_OK;
+}
+
+int idf_push_pixels(idf_streams *s, const int32_t *stream_ids, int n_ids, const void *dev_pixels, int x0, int n_px)
+{
+    if (!s || !dev_pixels) return fail(IDF_EINVAL, "null argument");
+    const idf_net &net = *s->net;
+    if (n_px < 1 || x0 < 0 || x0 + n_px > net.in_w) return fail(IDF_EINVAL, "columns %d..%d outside the row of %d", x0, x0 + n_px - 1, net.in_w);
+    if (x0 == 0 && n_px == net.in_w) return idf_push_segment(s, stream_ids, n_ids, dev_pixels, 1);
+    if (s->mfma.empty() || s->mfma[0] != 1)
+        return fail(IDF_EUNSUPPORTED, "pixel segments need a first layer served by the matrix-core kernel (3x3, stride 1, same padding)");
+    int rc = check_ids(s, stream_ids, n_ids);
+    if (rc != IDF_OK) return rc;
+    for (int i = 0; i < n_ids; ++i) {
+        const int id = stream_ids ? stream_ids[i] : i;
+        if (s->h[id].x_next != x0)
+            return fail(IDF_ESTATE, "stream %d: next column is %d, not %d", id, s->h[id].x_next, x0);
+    }
+    s->part.on = true; s->part.x_lo = x0; s->part.x_hi = x0 + n_px; s->part.first = x0 == 0; s->part.last = x0 + n_px == net.in_w;
+    if (s->part.last) {
+        // the row is whole: everything a pushed row does, with layer 0 taking only these columns
+        rc = idf_push_segment(s, stream_ids, n_ids, dev_pixels, 1);
+        s->part = idf_streams::Part{};
+        return rc;
+    }
+    // layer 0 takes the columns into its rolling buffer; nothing can be final yet
+    std::map<int64_t, std::vector<std::pair<int, int>>> groups;
+    for (int i = 0; i < n_ids; ++i) {
+        const int id = stream_ids ? stream_ids[i] : i;
+        if (net.in_h > 0 && s->h[id].r >= net.in_h) { s->part = idf_streams::Part{}; return fail(IDF_ESTATE, "stream %d: sample complete", id); }
+        groups[s->h[id].r].push_back({i, id});
+    }
+    for (auto &kv : groups) {
+        const int64_t r = kv.first;
+        rc = for_each_selection(kv.second, [&](const StreamSel &sel) {
+            MfmaStep a;
+            int64_t rows_out[3];
+            double bytes = 0;
+            make_mfma_step(s, 0, r, sel.n, a, rows_out, bytes);
+            a.in = dev_pixels; a.in_stream_stride = (int64_t)n_px * net.in_c; a.in_by_position = 1;
+            a.in_row_off = -(int64_t)x0 * net.in_c;
+            hipError_t e = launch_conv3x3_mfma(net.precision, a, sel, launch_ctx(s, kKindConvMfma, bytes, 0));
+            return e == hipSuccess ? IDF_OK : dev_fail(e, "pixel segment launch");
+        });
+        if (rc != IDF_OK) break;
+    }
+    s->part = idf_streams::Part{};
+    if (rc != IDF_OK) return rc;
+    for (int i = 0; i < n_ids; ++i) s->h[stream_ids ? stream_ids[i] : i].x_next = x0 + n_px;
     return IDF_OK;
 }
 

@@ -149,7 +149,7 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
     // wait: left to first use, the loads end up behind conditions and cost one memory round
     // trip each, one after the other.
     asm volatile("" ::"s"(a.w), "s"(a.c_in), "s"(a.c_out), "s"(a.c_out_pad), "s"(a.c_in_rcp), "s"(a.chunks_rcp), "s"(a.act), "s"(a.shr),
-                 "s"(a.clamp_hi), "s"(a.layer), "s"(a.pool_layer), "s"(a.n_layers), "s"(a.taps_y), "s"(a.in_by_position),
+                 "s"(a.clamp_hi), "s"(a.x_lo), "s"(a.x_hi), "s"(a.skip_clear_tiles), "s"(a.layer), "s"(a.pool_layer), "s"(a.n_layers), "s"(a.taps_y), "s"(a.in_by_position),
                  "s"(a.to_output), "s"(a.in), "s"(a.in_stream_stride), "s"(a.in_row_off), "s"(a.ring),
                  "s"(a.ring_stream_stride), "s"(a.held), "s"(a.held_stream_stride), "s"(a.dst), "s"(a.dst_stream_stride),
                  "s"(a.wfrag), "s"(a.bias), "s"(a.stats));
@@ -163,6 +163,8 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
     const int n_co_chunks = (a.c_out + NC - 1) / NC;
     const int x_tile = bx / n_co_chunks, co_chunk = bx - x_tile * n_co_chunks;
     const int x0 = x_tile * MT, co0 = co_chunk * NC;
+    // a pixel segment in the middle of a row: tiles it cannot reach are left alone
+    if (a.skip_clear_tiles && (x0 + MT < a.x_lo || x0 > a.x_hi)) return;
     const int W = a.w, C_in = a.c_in, C_out = a.c_out;
     const int chunks = C_in / VL;                  // 16-byte cells per position
     const int xs_stride = C_in * EB + 16;          // bytes per position in LDS (padded against bank conflicts)
@@ -194,7 +196,7 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
             i = i < cells ? i : cells - 1;
             const int p = a.chunks_rcp ? (int)__umulhi((unsigned)i, a.chunks_rcp) : i, c = i - p * chunks;   // i / chunks
             int x = x0 - 1 + p;
-            x = x < 0 ? 0 : (x >= W ? W - 1 : x);
+            x = x < a.x_lo ? a.x_lo : (x >= a.x_hi ? a.x_hi - 1 : x);
             tv[b] = *reinterpret_cast<const i32x4 *>(in_row + ((int64_t)x * C_in + c * VL) * EB);
         }
     };
@@ -271,7 +273,7 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
                     if (i >= cells) continue;
                     const int p = a.chunks_rcp ? (int)__umulhi((unsigned)i, a.chunks_rcp) : i, c = i - p * chunks;
                     const int x = x0 - 1 + p;
-                    if (x < 0 || x >= W) tv[b] = i32x4{0, 0, 0, 0};
+                    if (x < a.x_lo || x >= a.x_hi) tv[b] = i32x4{0, 0, 0, 0};
                     *reinterpret_cast<i32x4 *>(smem + p * xs_stride + c * 16) = tv[b];
                     if (T::cell_nonzero(tv[b])) {
                         atomicOr(&nz[c][p >> 5], 1u << (p & 31));
@@ -292,7 +294,7 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
                 const int p = i / C_in;
                 const int x = x0 - 1 + p;
                 ev_t v = 0;
-                if (x >= 0 && x < W) v = in_e[(int64_t)x * C_in + (i - p * C_in)];
+                if (x >= a.x_lo && x < a.x_hi) v = in_e[(int64_t)x * C_in + (i - p * C_in)];
                 xs_e[i] = v;
                 if (count && p >= 1 && p <= MT && T::ev_nonzero(v)) {
                     ev += 1;
