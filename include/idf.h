@@ -177,6 +177,20 @@ int idf_get_stats(idf_streams *s, int stream_id, uint64_t *events_in, uint64_t *
 /* Rows of the current sample a stream has been given so far (host bookkeeping, no device work). */
 int idf_rows_pushed(const idf_streams *s, int stream_id, int64_t *rows);
 
+/* Eager emission -- Sec. 3 taken literally: every neuron announces a change of f(c) at once, as an
+ * event that the next layer takes in at once, so that after every pushed segment the announced
+ * activations of every layer are those of the conventional network on the input seen so far (the
+ * rest taken as zero; Sec. 4, Fig. 3).  Whole maps of state and announced values are kept per
+ * stream, in a second caller-owned device workspace of idf_query_eager_bytes() bytes; bounded
+ * samples, float32 or int8 nets (IDF_EUNSUPPORTED otherwise).  After idf_enable_eager (before the
+ * first push) idf_push_segment delivers eagerly, idf_read_outputs is refused (IDF_ESTATE) and
+ *   idf_read_announced(level, ...) copies the announced map [n_ids][H][W][C] of 4-byte values of
+ *   level 0 (the input) .. n_layers (the last layer) to dev_out, in stream order.
+ * idf_get_stats then counts, per layer, the non-zero changes delivered to it. */
+int idf_query_eager_bytes(const idf_net *net, int n_streams, size_t *bytes);
+int idf_enable_eager(idf_streams *s, void *dev_workspace, size_t workspace_bytes);
+int idf_read_announced(idf_streams *s, int level, const int32_t *stream_ids, int n_ids, void *dev_out);
+
 /* Averaging output units (Fig. 1: the output neuron that averages the last layer; Sec. 4: output
  * units whose value converges as rows come in): one accumulator per channel of the last layer,
  * fed by the rows the last layer completes; the value is the running mean over the positions of

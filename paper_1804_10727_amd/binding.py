@@ -17,7 +17,7 @@ ACT = {"none": 0, "relu": 1, "relu_shr_clamp": 2}
 EXPORTS = ["idf_create_net", "idf_destroy_net", "idf_query_sizes", "idf_open_streams", "idf_close_streams",
            "idf_push_segment", "idf_read_outputs", "idf_reset_streams", "idf_get_stats", "idf_rows_pushed",
            "idf_layer_kernel", "idf_last_error", "idf_profile_begin", "idf_profile_end", "idf_enable_head",
-           "idf_read_head", "idf_push_pixels", "idf_snapshot_bytes", "idf_snapshot", "idf_restore"]
+           "idf_read_head", "idf_push_pixels", "idf_query_eager_bytes", "idf_enable_eager", "idf_read_announced", "idf_snapshot_bytes", "idf_snapshot", "idf_restore"]
 
 
 class IdfError(RuntimeError):
@@ -84,6 +84,9 @@ def load_library():
     L.idf_get_stats.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
     L.idf_rows_pushed.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_int64)]
     L.idf_enable_head.argtypes = [C.c_void_p]
+    L.idf_query_eager_bytes.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_size_t)]
+    L.idf_enable_eager.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
+    L.idf_read_announced.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p]
     L.idf_push_pixels.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int]
     L.idf_snapshot_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
     L.idf_snapshot.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
@@ -231,6 +234,25 @@ class Streams:
     def restore(self, stream_id, buf, pos):
         arr = (C.c_int64 * 3)(*pos)
         _check(load_library().idf_restore(self._h, stream_id, C.c_void_p(buf.data_ptr()), arr))
+
+    def enable_eager(self):
+        """Eager emission: allocates the second workspace and switches the streams over."""
+        import torch
+        L = load_library()
+        nb = C.c_size_t()
+        _check(L.idf_query_eager_bytes(self.net._h, self.n_streams, C.byref(nb)))
+        self._eager_ws = torch.empty(max(1, nb.value), dtype=torch.uint8, device=self.device)
+        _check(L.idf_enable_eager(self._h, C.c_void_p(self._eager_ws.data_ptr()), nb.value))
+
+    def read_announced(self, level, shape, stream_ids=None):
+        """Announced map of a level (0 = input), [n][H][W][C]; shape = (H, W, C) of that level."""
+        import torch
+        keep, ptr = _ids(stream_ids)
+        n = self.n_streams if stream_ids is None else len(keep)
+        out = torch.empty((n,) + tuple(shape), dtype=torch.int32 if self.net.precision == "i8" else torch.float32,
+                          device=self.device)
+        _check(load_library().idf_read_announced(self._h, level, ptr, n, C.c_void_p(out.data_ptr())))
+        return out
 
     def enable_head(self):
         _check(load_library().idf_enable_head(self._h))

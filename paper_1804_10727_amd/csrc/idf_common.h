@@ -246,6 +246,25 @@ struct CopyOut {
     int elem_bytes;
 };
 
+// One layer's step in eager emission: output rows [o_lo, o_hi) take in the delta rows
+// [i_lo, i_hi) of the layer before.  Per stream every layer keeps whole maps [H][W][C] of 4-byte
+// values: state c, announced value, and the deltas it emitted for the segment in flight.
+struct EagerStep {
+    Geom g;                      // unused for the input step
+    int layer, n_layers;
+    int o_lo, o_hi, i_lo, i_hi;
+    int w_out, c_out;            // input step: shape of an input row
+    int init_bias;               // the state starts from the bias (first pass of a sample)
+    const void *in;              // input step: pushed rows [position][rows][w][c], event type
+    int64_t in_stream_stride;
+    const void *dlt_in, *ann_in; // maps of the layer before
+    int64_t in_map_stride;       // elements per stream of those
+    void *c, *ann, *dlt_out;     // this layer's maps
+    int64_t map_stride;
+    const void *w, *bias;
+    unsigned long long *stats;
+};
+
 // Averaging output units: rows [first_slot, first_slot + n_rows) of the output ring are added to
 // the per-channel sums of each selected stream.
 struct HeadAcc {

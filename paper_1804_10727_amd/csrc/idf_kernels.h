@@ -34,10 +34,10 @@ __device__ __forceinline__ void lds_barrier()
 #endif
 }
 
-enum KernelKind { kKindConvGeneric = 0, kKindPoolGeneric, kKindCopyOut, kKindCascade1d, kKindConvMfma, kKindHead, kKindCount };
+enum KernelKind { kKindConvGeneric = 0, kKindPoolGeneric, kKindCopyOut, kKindCascade1d, kKindConvMfma, kKindHead, kKindEager, kKindCount };
 inline const char *kind_name(int k)
 {
-    static const char *names[kKindCount] = {"conv_generic", "pool_generic", "copy_out", "cascade1d", "conv3x3_mfma", "head_accumulate"};
+    static const char *names[kKindCount] = {"conv_generic", "pool_generic", "copy_out", "cascade1d", "conv3x3_mfma", "head_accumulate", "eager"};
     return k >= 0 && k < kKindCount ? names[k] : "?";
 }
 
@@ -45,6 +45,8 @@ inline const char *kind_name(int k)
 hipError_t launch_conv_generic(int prec, const ConvStep &a, const StreamSel &sel, const LaunchCtx &lc);
 hipError_t launch_pool_generic(int prec, const PoolStep &a, const StreamSel &sel, const LaunchCtx &lc);
 hipError_t launch_head_accumulate(const HeadAcc &a, const StreamSel &sel, int64_t first_slot, int n_rows, const LaunchCtx &lc);
+// what: 0 = pushed rows become the announced input, 1 = conv layer, 2 = pool layer
+hipError_t launch_eager(int prec, int what, const EagerStep &a, const StreamSel &sel, const LaunchCtx &lc);
 hipError_t launch_copy_out(const CopyOut &a, const StreamSel &sel, int64_t first_slot, int n_rows,
                            const LaunchCtx &lc);
 

@@ -108,6 +108,13 @@ struct idf_streams {
     std::vector<int64_t> stg_seq;               // rows emitted by unit k so far
     int64_t stg_out_next = 0;                   // output slot of the next completed row
     int stg_tile = kMfmaTile64x64;              // tile shape of the staged launches
+    // eager emission: whole maps per stream and level (0 = input) in a workspace of its own
+    struct Eager {
+        bool on = false;
+        char *ws = nullptr;
+        std::vector<int64_t> elems;               // per level: H*W*C of one stream
+        std::vector<size_t> ann_off, c_off, dlt_off;   // per level (c: conv layers only)
+    } eager;
     // a pixel segment being pushed: columns [x_lo, x_hi) of the current row of layer 0 (else the whole row)
     struct Part { bool on = false; int x_lo = 0, x_hi = 0; bool first = true, last = true; } part;
     std::vector<StreamHost> h;
@@ -790,6 +797,119 @@ template <class F> void for_each_state_piece(const idf_streams *s, int id, F &&f
     f(s->stats_off + (size_t)id * n * 2 * sizeof(unsigned long long), (size_t)n * 2 * sizeof(unsigned long long));
     f(s->head_off + (size_t)id * net.out_c * sizeof(double), (size_t)net.out_c * sizeof(double));
 }
+// Layout of the eager-emission workspace for B streams; returns its size.
+size_t eager_layout(const idf_net &net, int B, idf_streams::Eager *e)
+{
+    const int n = (int)net.g.size();
+    std::vector<int64_t> elems(n + 1);
+    elems[0] = (int64_t)net.in_h * net.in_w * net.in_c;
+    for (int l = 0; l < n; ++l) elems[l + 1] = (int64_t)net.g[l].h_out * net.g[l].w_out * net.g[l].c_out;
+    size_t off = 0;
+    std::vector<size_t> ann(n + 1), c(n + 1, 0), dlt(n + 1);
+    for (int lv = 0; lv <= n; ++lv) {
+        ann[lv] = off; off = align_up(off + (size_t)elems[lv] * 4 * B);
+        dlt[lv] = off; off = align_up(off + (size_t)elems[lv] * 4 * B);
+        if (lv > 0 && net.g[lv - 1].kind == IDF_CONV) { c[lv] = off; off = align_up(off + (size_t)elems[lv] * 4 * B); }
+    }
+    if (e) { e->elems = elems; e->ann_off = ann; e->c_off = c; e->dlt_off = dlt; }
+    return off;
+}
+
+// One pass of eager emission for a selection of streams: the input rows [a, b) (pushed rows, or
+// none when only the biases announce themselves) and, layer by layer, the band of rows they reach.
+int eager_pass(idf_streams *s, const StreamSel &sel, const void *dev_rows, int n_rows, int64_t a, int64_t b, bool init_bias)
+{
+    const idf_net &net = *s->net;
+    const int n = (int)net.g.size();
+    idf_streams::Eager &E = s->eager;
+    unsigned long long *stats = (unsigned long long *)(s->ws + s->stats_off);
+    if (dev_rows) {
+        EagerStep st{};
+        st.layer = 0; st.n_layers = n; st.o_lo = (int)a; st.o_hi = (int)b; st.w_out = net.in_w; st.c_out = net.in_c;
+        st.in = dev_rows; st.in_stream_stride = (int64_t)n_rows * net.in_w * net.in_c;
+        st.ann = E.ws + E.ann_off[0]; st.dlt_out = E.ws + E.dlt_off[0]; st.map_stride = E.elems[0];
+        st.stats = stats;
+        hipError_t e = launch_eager(net.precision, 0, st, sel,
+                                    launch_ctx(s, kKindEager, (double)(b - a) * net.in_w * net.in_c * sel.n * 9.0, 0));
+        if (e != hipSuccess) return dev_fail(e, "eager input launch");
+    }
+    for (int l = 0; l < n && b > a; ++l) {
+        const Geom &g = net.g[l];
+        EagerStep st{};
+        st.g = g; st.layer = l; st.n_layers = n; st.i_lo = (int)a; st.i_hi = (int)b; st.init_bias = init_bias;
+        int64_t oa, ob;
+        if (g.kind == IDF_CONV) {
+            // output rows whose footprint meets [a, b)
+            const int64_t t = a + g.p_h - g.k_h + 1;
+            oa = t <= 0 ? 0 : (t + g.s_h - 1) / g.s_h;
+            ob = std::min<int64_t>(g.h_out, (b - 1 + g.p_h) / g.s_h + 1);
+        } else {
+            oa = a / 2; ob = std::min<int64_t>(g.h_out, (b - 1) / 2 + 1);
+        }
+        if (init_bias) { oa = 0; ob = g.h_out; }               // every neuron states its bias
+        st.o_lo = (int)oa; st.o_hi = (int)ob;
+        st.dlt_in = E.ws + E.dlt_off[l]; st.ann_in = E.ws + E.ann_off[l]; st.in_map_stride = E.elems[l];
+        st.c = g.kind == IDF_CONV ? E.ws + E.c_off[l + 1] : nullptr;
+        st.ann = E.ws + E.ann_off[l + 1]; st.dlt_out = E.ws + E.dlt_off[l + 1]; st.map_stride = E.elems[l + 1];
+        st.w = g.kind == IDF_CONV ? s->ws + s->w_off[l] : nullptr;
+        st.bias = (g.kind == IDF_CONV && !net.b_img[l].empty()) ? s->ws + s->b_off[l] : nullptr;
+        st.stats = stats;
+        const double cells = (double)std::max<int64_t>(0, ob - oa) * g.w_out * g.c_out * sel.n;
+        hipError_t e = launch_eager(net.precision, g.kind == IDF_CONV ? 1 : 2, st, sel,
+                                    launch_ctx(s, kKindEager, cells * 16.0, l));
+        if (e != hipSuccess) return dev_fail(e, "eager layer launch");
+        a = oa; b = ob;
+    }
+    return IDF_OK;
+}
+
+int eager_push(idf_streams *s, const int32_t *stream_ids, int n_ids, const void *dev_rows, int n_rows)
+{
+    const idf_net &net = *s->net;
+    const int n = (int)net.g.size();
+    idf_streams::Eager &E = s->eager;
+    std::map<int64_t, std::vector<std::pair<int, int>>> groups;
+    for (int i = 0; i < n_ids; ++i) {
+        const int id = stream_ids ? stream_ids[i] : i;
+        const StreamHost &h = s->h[id];
+        if (h.r + n_rows > net.in_h)
+            return fail(IDF_ESTATE, "stream %d: rows %lld..%lld run past the sample of %d rows", id, (long long)h.r,
+                        (long long)(h.r + n_rows - 1), net.in_h);
+        groups[h.r].push_back({i, id});
+    }
+    bool any_bias = false;
+    for (int l = 0; l < n; ++l) any_bias |= !net.b_img[l].empty();
+    for (auto &kv : groups) {
+        const int64_t r = kv.first;
+        if (r == 0) {
+            // a sample begins: all state zero (Sec. 3), then the biases announce themselves
+            for (auto &m : kv.second)
+                for (int lv = 0; lv <= n; ++lv) {
+                    const size_t bytes = (size_t)E.elems[lv] * 4, at = (size_t)m.second * bytes;
+                    hipError_t e = hipMemsetAsync(E.ws + E.ann_off[lv] + at, 0, bytes, s->st);
+                    if (e == hipSuccess) e = hipMemsetAsync(E.ws + E.dlt_off[lv] + at, 0, bytes, s->st);
+                    if (e == hipSuccess && lv > 0 && net.g[lv - 1].kind == IDF_CONV)
+                        e = hipMemsetAsync(E.ws + E.c_off[lv] + at, 0, bytes, s->st);
+                    if (e != hipSuccess) return dev_fail(e, "eager reset");
+                }
+        }
+        int rc = for_each_selection(kv.second, [&](const StreamSel &sel) {
+            if (r == 0 && any_bias) {
+                int rc2 = eager_pass(s, sel, nullptr, 0, 0, net.in_h, true);
+                if (rc2 != IDF_OK) return rc2;
+            }
+            return eager_pass(s, sel, dev_rows, n_rows, r, r + n_rows, false);
+        });
+        if (rc != IDF_OK) return rc;
+    }
+    for (int i = 0; i < n_ids; ++i) {
+        StreamHost &h = s->h[stream_ids ? stream_ids[i] : i];
+        h.r += n_rows;
+        if (h.r == net.in_h) h.r = 0;
+    }
+    return IDF_OK;
+}
+
 // The averaging units take in the output rows completed since they last did.  Must run before
 // read_outputs gives those rows' slots free.
 int head_catch_up(idf_streams *s, const int32_t *stream_ids, int n_ids)
@@ -1025,6 +1145,7 @@ int idf_push_segment(idf_streams *s, const int32_t *stream_ids, int n_ids, const
     int rc = check_ids(s, stream_ids, n_ids);
     if (rc != IDF_OK) return rc;
     if (n_rows < 1 || n_rows > s->max_seg) return fail(IDF_EINVAL, "n_rows %d outside [1, %d]", n_rows, s->max_seg);
+    if (s->eager.on) return eager_push(s, stream_ids, n_ids, dev_rows, n_rows);
     const idf_net &net = *s->net;
     // validate everything before anything is enqueued
     std::map<std::pair<int64_t, int64_t>, std::vector<std::pair<int, int>>> groups;
@@ -1116,6 +1237,7 @@ int idf_read_outputs(idf_streams *s, const int32_t *stream_ids, int n_ids, void 
     int rc = check_ids(s, stream_ids, n_ids);
     if (rc != IDF_OK) return rc;
     if (max_rows < 1) return fail(IDF_EINVAL, "max_rows must be >= 1");
+    if (s->eager.on) return fail(IDF_ESTATE, "eager emission: the output is read with idf_read_announced");
     rc = pipeline_drain(s);                // rows still between stages belong to what was pushed
     if (rc != IDF_OK) return rc;
     rc = head_catch_up(s, stream_ids, n_ids);
@@ -1252,6 +1374,48 @@ int idf_restore(idf_streams *s, int stream_id, const void *dev_buf, const idf_st
     if (e != hipSuccess) return dev_fail(e, "restore");
     h.r = pos->rows_pushed; h.out_written = h.out_read = pos->out_rows;
     h.head_done = pos->out_rows; h.head_base = pos->out_rows - pos->head_rows;
+    return IDF_OK;
+}
+
+int idf_query_eager_bytes(const idf_net *net, int n_streams, size_t *bytes)
+{
+    if (!net || !bytes || n_streams < 1) return fail(IDF_EINVAL, "bad argument");
+    if (net->in_h <= 0) return fail(IDF_EUNSUPPORTED, "eager emission keeps whole maps: the sample height must be known");
+    if (net->precision == IDF_PREC_BF16) return fail(IDF_EUNSUPPORTED, "eager emission is built for float32 and int8 nets");
+    *bytes = eager_layout(*net, n_streams, nullptr);
+    return IDF_OK;
+}
+
+int idf_enable_eager(idf_streams *s, void *dev_workspace, size_t workspace_bytes)
+{
+    if (!s || !dev_workspace) return fail(IDF_EINVAL, "null argument");
+    size_t need = 0;
+    int rc = idf_query_eager_bytes(s->net, s->B, &need);
+    if (rc != IDF_OK) return rc;
+    if (workspace_bytes < need) return fail(IDF_EINVAL, "eager workspace of %zu bytes, %zu needed", workspace_bytes, need);
+    for (const StreamHost &h : s->h)
+        if (h.r != 0 || h.out_written != 0) return fail(IDF_ESTATE, "eager emission must be enabled before the first push");
+    eager_layout(*s->net, s->B, &s->eager);
+    s->eager.ws = (char *)dev_workspace;
+    s->eager.on = true;
+    return IDF_OK;
+}
+
+int idf_read_announced(idf_streams *s, int level, const int32_t *stream_ids, int n_ids, void *dev_out)
+{
+    if (!s || !dev_out) return fail(IDF_EINVAL, "null argument");
+    if (!s->eager.on) return fail(IDF_ESTATE, "eager emission is not enabled");
+    const int n = (int)s->net->g.size();
+    if (level < 0 || level > n) return fail(IDF_EINVAL, "level %d outside [0, %d]", level, n);
+    int rc = check_ids(s, stream_ids, n_ids);
+    if (rc != IDF_OK) return rc;
+    const size_t bytes = (size_t)s->eager.elems[level] * 4;
+    for (int i = 0; i < n_ids; ++i) {
+        const int id = stream_ids ? stream_ids[i] : i;
+        hipError_t e = hipMemcpyAsync((char *)dev_out + (size_t)i * bytes, s->eager.ws + s->eager.ann_off[level] + (size_t)id * bytes,
+                                      bytes, hipMemcpyDeviceToDevice, s->st);
+        if (e != hipSuccess) return dev_fail(e, "read_announced");
+    }
     return IDF_OK;
 }
 

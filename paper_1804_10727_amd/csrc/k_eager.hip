@@ -1,0 +1,161 @@
+// Eager emission (Sec. 3, the stateful neuron and the event definition taken literally): every
+// neuron keeps its state c and the value it last announced; whenever f(c) differs from that
+// value the difference goes out as an event at once, is added, weighted, into the state of the
+// neurons it connects to, and those may announce changes in turn.  Nothing waits for a row to be
+// complete, so after any pushed segment the announced activations of every layer are those of the
+// conventional network applied to the input seen so far, the rest taken as zero (Sec. 4, Fig. 3:
+// the output is updated with every row presented).
+//
+// On the GPU the events of one segment are delivered layer by layer as a band of delta rows:
+// each cell of the band a layer can reach gathers w * delta over its footprint inside the band
+// of the layer before (zero deltas are skipped), announces f(c) minus what it announced last, and
+// writes that difference into its own delta band.  A max-pool is a stateful node that
+// re-evaluates its window of announced values.  Whole feature maps of c and of the announced
+// values are kept per stream (a ring of cone rows would do; this mode is about the output being
+// valid after every segment, not about the footprint).  All values are 4 bytes: float32, or
+// int32 for the quantised nets.
+#include "idf.h"
+#include "idf_kernels.h"
+
+namespace idf {
+
+namespace {
+
+template <bool INT> struct Val;
+template <> struct Val<false> {
+    using t = float; using w_t = float;
+    static __device__ __forceinline__ t act(const Geom &g, t c) { return g.act == IDF_ACT_NONE ? c : fmaxf(c, 0.f); }
+    static __device__ __forceinline__ t mac(t acc, t d, w_t w) { return fmaf(d, w, acc); }
+};
+template <> struct Val<true> {
+    using t = int32_t; using w_t = int8_t;
+    static __device__ __forceinline__ t act(const Geom &g, t c)
+    {
+        if (g.act == IDF_ACT_NONE) return c;
+        t r = c > 0 ? c : 0;
+        if (g.act == IDF_ACT_RELU_SHR_CLAMP) { r >>= g.shr; r = r > g.clamp_hi ? g.clamp_hi : r; }
+        return r;
+    }
+    static __device__ __forceinline__ t mac(t acc, t d, w_t w) { return acc + d * (t)w; }
+};
+
+// Non-zero differences announced by this workgroup: the events delivered to the next layer.
+__device__ __forceinline__ void count_events(bool nz, unsigned long long *dst)
+{
+    const unsigned long long b = __ballot(nz);
+    if (dst && b && (threadIdx.x & 63) == 0) atomicAdd(dst, (unsigned long long)__popcll(b));
+}
+
+// The pushed rows become the announced input; what changed goes out as the input's events.
+template <bool INT, class IN>
+__global__ void __launch_bounds__(256) k_eager_input(const EagerStep a, const StreamSel sel)
+{
+    using V = Val<INT>;
+    const int stream = sel_stream(sel, blockIdx.z);
+    const int64_t row_elems = (int64_t)a.w_out * a.c_out, n = (int64_t)(a.o_hi - a.o_lo) * row_elems;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    bool nz = false;
+    if (i < n) {
+        const IN *in = (const IN *)a.in + (int64_t)(sel.pos0 + blockIdx.z) * a.in_stream_stride;
+        typename V::t *ann = (typename V::t *)a.ann + (int64_t)stream * a.map_stride + a.o_lo * row_elems;
+        typename V::t *dlt = (typename V::t *)a.dlt_out + (int64_t)stream * a.map_stride + a.o_lo * row_elems;
+        const typename V::t v = (typename V::t)in[i], d = v - ann[i];
+        ann[i] = v; dlt[i] = d;
+        nz = d != 0;
+    }
+    count_events(nz, a.stats ? a.stats + ((int64_t)stream * a.n_layers + a.layer) * 2 : nullptr);
+}
+
+// Conv layer: cells of output rows [o_lo, o_hi) take in the delta rows [i_lo, i_hi) of the layer before.
+template <bool INT>
+__global__ void __launch_bounds__(256) k_eager_conv(const EagerStep a, const StreamSel sel)
+{
+    using V = Val<INT>;
+    using val_t = typename V::t;
+    const Geom &g = a.g;
+    const int stream = sel_stream(sel, blockIdx.z);
+    const int64_t n = (int64_t)(a.o_hi - a.o_lo) * g.w_out * g.c_out;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    bool nz = false;
+    if (i < n) {
+        const int co = (int)(i % g.c_out);
+        const int64_t pos = i / g.c_out;
+        const int x = (int)(pos % g.w_out), o = a.o_lo + (int)(pos / g.w_out);
+        const val_t *din = (const val_t *)a.dlt_in + (int64_t)stream * a.in_map_stride;
+        const typename V::w_t *w = (const typename V::w_t *)a.w;
+        const int64_t cell = (int64_t)stream * a.map_stride + ((int64_t)o * g.w_out + x) * g.c_out + co;
+        val_t c = a.init_bias ? (a.bias ? ((const val_t *)a.bias)[co] : (val_t)0) : ((val_t *)a.c)[cell];
+        for (int ky = 0; ky < g.k_h; ++ky) {
+            const int iy = o * g.s_h - g.p_h + ky;
+            if (iy < a.i_lo || iy >= a.i_hi) continue;           // only the rows that carry this segment's events
+            for (int kx = 0; kx < g.k_w; ++kx) {
+                const int ix = x * g.s_w - g.p_w + kx;
+                if (ix < 0 || ix >= g.w_in) continue;
+                const val_t *dp = din + ((int64_t)iy * g.w_in + ix) * g.c_in;
+                const typename V::w_t *wp = w + ((int64_t)(ky * g.k_w + kx) * g.c_in) * g.c_out + co;
+                for (int ci = 0; ci < g.c_in; ++ci) {
+                    const val_t d = dp[ci];
+                    if (d != 0) c = V::mac(c, d, wp[(int64_t)ci * g.c_out]);   // zero: no event
+                }
+            }
+        }
+        ((val_t *)a.c)[cell] = c;
+        const val_t h = V::act(g, c), d = h - ((val_t *)a.ann)[cell];
+        ((val_t *)a.ann)[cell] = h;
+        ((val_t *)a.dlt_out)[cell] = d;
+        nz = d != 0;
+    }
+    count_events(nz, a.stats && a.layer + 1 < a.n_layers ? a.stats + ((int64_t)stream * a.n_layers + a.layer + 1) * 2 : nullptr);
+}
+
+// 2x2 max-pool as a stateful node: re-evaluates its window of announced values.
+template <bool INT>
+__global__ void __launch_bounds__(256) k_eager_pool(const EagerStep a, const StreamSel sel)
+{
+    using val_t = typename Val<INT>::t;
+    const Geom &g = a.g;
+    const int stream = sel_stream(sel, blockIdx.z);
+    const int64_t n = (int64_t)(a.o_hi - a.o_lo) * g.w_out * g.c_out;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    bool nz = false;
+    if (i < n) {
+        const int ch = (int)(i % g.c_out);
+        const int64_t pos = i / g.c_out;
+        const int x = (int)(pos % g.w_out), o = a.o_lo + (int)(pos / g.w_out);
+        const val_t *ain = (const val_t *)a.ann_in + (int64_t)stream * a.in_map_stride;
+        val_t m = ain[((int64_t)(2 * o) * g.w_in + x * g.s_w) * g.c_out + ch];
+        for (int dy = 0; dy < 2; ++dy)
+            for (int dx = 0; dx < g.k_w; ++dx) {
+                const val_t v = ain[((int64_t)(2 * o + dy) * g.w_in + x * g.s_w + dx) * g.c_out + ch];
+                m = v > m ? v : m;
+            }
+        const int64_t cell = (int64_t)stream * a.map_stride + ((int64_t)o * g.w_out + x) * g.c_out + ch;
+        const val_t d = m - ((val_t *)a.ann)[cell];
+        ((val_t *)a.ann)[cell] = m;
+        ((val_t *)a.dlt_out)[cell] = d;
+        nz = d != 0;
+    }
+    count_events(nz, a.stats && a.layer + 1 < a.n_layers ? a.stats + ((int64_t)stream * a.n_layers + a.layer + 1) * 2 : nullptr);
+}
+
+}  // namespace
+
+hipError_t launch_eager(int prec, int what, const EagerStep &a, const StreamSel &sel, const LaunchCtx &lc)
+{
+    const int64_t n = (int64_t)(a.o_hi - a.o_lo) * (what == 0 ? (int64_t)a.w_out * a.c_out : (int64_t)a.g.w_out * a.g.c_out);
+    if (n <= 0) return hipSuccess;
+    const dim3 grid((unsigned)((n + 255) / 256), 1, sel.n), block(256);
+    const bool is_int = prec == IDF_PREC_I8;
+    if (what == 0) {
+        if (is_int) return launch(k_eager_input<true, int8_t>, grid, block, 0, lc, a, sel);
+        return launch(k_eager_input<false, float>, grid, block, 0, lc, a, sel);
+    }
+    if (what == 1) {
+        if (is_int) return launch(k_eager_conv<true>, grid, block, 0, lc, a, sel);
+        return launch(k_eager_conv<false>, grid, block, 0, lc, a, sel);
+    }
+    if (is_int) return launch(k_eager_pool<true>, grid, block, 0, lc, a, sel);
+    return launch(k_eager_pool<false>, grid, block, 0, lc, a, sel);
+}
+
+}  // namespace idf
