@@ -32,7 +32,7 @@ KERNEL_PEAK = {
     "conv_generic": {"f32": ("alu", "f32_valu"), "bf16": ("alu", "f32_valu"), "i8": ("alu", "i32_valu")},
     "cascade1d": {"f32": ("alu", "f32_valu")},
     "conv3x3_mfma": {"f32": ("mfma", "f32_mfma"), "bf16": ("mfma", "bf16_mfma"), "i8": ("mfma", "i8_mfma")},
-    "pool_generic": None, "copy_out": None,
+    "pool_generic": None, "copy_out": None, "eager": None, "head_accumulate": None,
 }
 
 
@@ -130,7 +130,7 @@ def cpu_baseline(wl, budget_s=20.0):
                       f"scalar event-by-event fp64/int64, one stream per thread, {dt:.1f} s"}
 
 
-def run_workload(config, steps_arg=None, warmup_arg=None):
+def run_workload(config, steps_arg=None, warmup_arg=None, eager=False):
     """Times `steps` whole batches of one workload; returns (result dict, workload)."""
     import numpy as np
     import torch
@@ -149,6 +149,8 @@ def run_workload(config, steps_arg=None, warmup_arg=None):
 
     net = idf.net_from_workload(wl)
     st = idf.Streams(net, B, max_seg_rows=seg, device=dev)
+    if eager:
+        st.enable_eager()
     x = input_tensor(wl, dev)
     # segment-major copy in HBM: xs[i] is the contiguous block [B][seg][W][C] of push i
     xs = x.view(B, n_seg, seg, W, C0).permute(1, 0, 2, 3, 4).contiguous()
@@ -168,7 +170,10 @@ def run_workload(config, steps_arg=None, warmup_arg=None):
             rc = push(h, None, B, p, seg)
             if rc:
                 raise RuntimeError(L.idf_last_error().decode())
-        rc = read(h, None, B, out_ptr, out_h, first.ctypes.data, cnt.ctypes.data)
+        if eager:       # the announced map of the last layer, valid after every segment, read once per batch
+            rc = L.idf_read_announced(h, len(wl["layers"]), None, B, out_ptr)
+        else:
+            rc = read(h, None, B, out_ptr, out_h, first.ctypes.data, cnt.ctypes.data)
         if rc:
             raise RuntimeError(L.idf_last_error().decode())
 
@@ -233,7 +238,7 @@ def run_workload(config, steps_arg=None, warmup_arg=None):
         "metric": "input_pixels_per_s", "value": value, "unit": "pixels/s", "n_gpus": 1, "steps": steps,
         "warmup": warmup, "ms_per_step": ms_per_step, "host_enqueue_ms_per_step": t_enq / steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": DTYPE[wl["precision"]], "data": "synthetic",
-        "config": {"workload": WORKLOADS[config], "streams": B, "rows_per_sample": H, "row_width": W,
+        "config": {"workload": WORKLOADS[config] + ("_eager_emission" if eager else ""), "streams": B, "rows_per_sample": H, "row_width": W,
                    "in_channels": C0, "rows_per_push": seg, "pushes_per_step": n_seg,
                    "layers": len(wl["layers"]), "state_bytes_per_stream": int(st.sizes.state_bytes_per_stream)},
         "gmacs_dense_equivalent": macs_dense / (dt / steps) / 1e9,
@@ -256,6 +261,7 @@ def main():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2)")
+    ap.add_argument("--eager", action="store_true", help="eager emission (configs 3 and 4): output valid after every push")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", dest="others", action="store_false",
                     help="skip the short runs of the other workloads (reported under other_workloads)")
@@ -273,7 +279,10 @@ def main():
 
     import torch
     assert torch.cuda.is_available(), "bench.py needs the GPU"
-    res, wl = run_workload(args.config, args.steps, args.warmup)
+    res, wl = run_workload(args.config, args.steps, args.warmup, eager=args.eager)
+    if args.eager:
+        print(json.dumps(res))
+        return
     if args.others:
         # the other multi-stream workloads, a few steps each, as context in the same line
         res["other_workloads"] = {}

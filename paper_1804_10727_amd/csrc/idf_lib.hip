@@ -883,15 +883,22 @@ int eager_push(idf_streams *s, const int32_t *stream_ids, int n_ids, const void 
         const int64_t r = kv.first;
         if (r == 0) {
             // a sample begins: all state zero (Sec. 3), then the biases announce themselves
-            for (auto &m : kv.second)
-                for (int lv = 0; lv <= n; ++lv) {
-                    const size_t bytes = (size_t)E.elems[lv] * 4, at = (size_t)m.second * bytes;
-                    hipError_t e = hipMemsetAsync(E.ws + E.ann_off[lv] + at, 0, bytes, s->st);
-                    if (e == hipSuccess) e = hipMemsetAsync(E.ws + E.dlt_off[lv] + at, 0, bytes, s->st);
-                    if (e == hipSuccess && lv > 0 && net.g[lv - 1].kind == IDF_CONV)
-                        e = hipMemsetAsync(E.ws + E.c_off[lv] + at, 0, bytes, s->st);
-                    if (e != hipSuccess) return dev_fail(e, "eager reset");
+            int rc0 = for_each_selection(kv.second, [&](const StreamSel &sel) {
+                // streams lie side by side in every map: one fill per map and run of streams
+                for (int k = 0; k < (sel.base >= 0 ? 1 : sel.n); ++k) {
+                    const int first = sel.base >= 0 ? sel.base : sel.ids[k], cnt = sel.base >= 0 ? sel.n : 1;
+                    for (int lv = 0; lv <= n; ++lv) {
+                        const size_t per = (size_t)E.elems[lv] * 4, at = (size_t)first * per, bytes = per * cnt;
+                        hipError_t e = hipMemsetAsync(E.ws + E.ann_off[lv] + at, 0, bytes, s->st);
+                        if (e == hipSuccess) e = hipMemsetAsync(E.ws + E.dlt_off[lv] + at, 0, bytes, s->st);
+                        if (e == hipSuccess && lv > 0 && net.g[lv - 1].kind == IDF_CONV)
+                            e = hipMemsetAsync(E.ws + E.c_off[lv] + at, 0, bytes, s->st);
+                        if (e != hipSuccess) return dev_fail(e, "eager reset");
+                    }
                 }
+                return (int)IDF_OK;
+            });
+            if (rc0 != IDF_OK) return rc0;
         }
         int rc = for_each_selection(kv.second, [&](const StreamSel &sel) {
             if (r == 0 && any_bias) {
@@ -1186,6 +1193,7 @@ int idf_push_pixels(idf_streams *s, const int32_t *stream_ids, int n_ids, const 
     if (!s || !dev_pixels) return fail(IDF_EINVAL, "null argument");
     const idf_net &net = *s->net;
     if (n_px < 1 || x0 < 0 || x0 + n_px > net.in_w) return fail(IDF_EINVAL, "columns %d..%d outside the row of %d", x0, x0 + n_px - 1, net.in_w);
+    if (s->eager.on) return fail(IDF_EUNSUPPORTED, "pixel segments are not built for eager emission");
     if (x0 == 0 && n_px == net.in_w) return idf_push_segment(s, stream_ids, n_ids, dev_pixels, 1);
     if (s->mfma.empty() || s->mfma[0] != 1)
         return fail(IDF_EUNSUPPORTED, "pixel segments need a first layer served by the matrix-core kernel (3x3, stride 1, same padding)");
@@ -1333,6 +1341,8 @@ int idf_snapshot(idf_streams *s, int stream_id, void *dev_buf, idf_stream_pos *p
 {
     if (!s || !dev_buf || !pos) return fail(IDF_EINVAL, "null argument");
     if (stream_id < 0 || stream_id >= s->B) return fail(IDF_EINVAL, "stream id %d outside [0, %d)", stream_id, s->B);
+    if (s->eager.on) return fail(IDF_EUNSUPPORTED, "snapshots do not cover the maps of eager emission");
+    if (s->h[stream_id].x_next != 0) return fail(IDF_ESTATE, "stream %d: a row is half presented", stream_id);
     int rc = pipeline_drain(s);
     if (rc != IDF_OK) return rc;
     const int32_t id32 = stream_id;
@@ -1360,6 +1370,7 @@ int idf_restore(idf_streams *s, int stream_id, const void *dev_buf, const idf_st
     if (pos->rows_pushed < 0 || (net.in_h > 0 && pos->rows_pushed >= net.in_h) || pos->out_rows < 0 ||
         pos->head_rows < 0 || pos->head_rows > pos->out_rows)
         return fail(IDF_EINVAL, "inconsistent stream position");
+    if (s->eager.on) return fail(IDF_EUNSUPPORTED, "snapshots do not cover the maps of eager emission");
     int rc = pipeline_drain(s);
     if (rc != IDF_OK) return rc;
     StreamHost &h = s->h[stream_id];
@@ -1372,7 +1383,7 @@ int idf_restore(idf_streams *s, int stream_id, const void *dev_buf, const idf_st
         at += align_up(n, 16);
     });
     if (e != hipSuccess) return dev_fail(e, "restore");
-    h.r = pos->rows_pushed; h.out_written = h.out_read = pos->out_rows;
+    h.r = pos->rows_pushed; h.out_written = h.out_read = pos->out_rows; h.x_next = 0;
     h.head_done = pos->out_rows; h.head_base = pos->out_rows - pos->head_rows;
     return IDF_OK;
 }
@@ -1393,8 +1404,9 @@ int idf_enable_eager(idf_streams *s, void *dev_workspace, size_t workspace_bytes
     int rc = idf_query_eager_bytes(s->net, s->B, &need);
     if (rc != IDF_OK) return rc;
     if (workspace_bytes < need) return fail(IDF_EINVAL, "eager workspace of %zu bytes, %zu needed", workspace_bytes, need);
+    if (s->head_on) return fail(IDF_EUNSUPPORTED, "the averaging units read completed rows, eager emission has none");
     for (const StreamHost &h : s->h)
-        if (h.r != 0 || h.out_written != 0) return fail(IDF_ESTATE, "eager emission must be enabled before the first push");
+        if (h.r != 0 || h.out_written != 0 || h.x_next != 0) return fail(IDF_ESTATE, "eager emission must be enabled before the first push");
     eager_layout(*s->net, s->B, &s->eager);
     s->eager.ws = (char *)dev_workspace;
     s->eager.on = true;
@@ -1422,6 +1434,7 @@ int idf_read_announced(idf_streams *s, int level, const int32_t *stream_ids, int
 int idf_enable_head(idf_streams *s)
 {
     if (!s) return fail(IDF_EINVAL, "null argument");
+    if (s->eager.on) return fail(IDF_EUNSUPPORTED, "the averaging units read completed rows, eager emission has none");
     for (const StreamHost &h : s->h)
         if (h.r != 0 || h.out_written != 0) return fail(IDF_ESTATE, "the averaging units must be enabled before the first push");
     s->head_on = true;

@@ -106,3 +106,21 @@ def test_query_sizes_errors():
         un.query_sizes(1, 4, 0)          # unbounded needs an explicit output capacity
     assert un.query_sizes(1, 4, 64).out_h == 0
     un.destroy()
+
+
+def test_eager_workspace_size_and_refusals():
+    import ctypes as C
+    L = idf.load_library()
+    wl = wl_mod.make(3, streams=2, size=8, channels=(4, 4, 4, 4))
+    net = idf.net_from_workload(wl)
+    nb = C.c_size_t()
+    assert L.idf_query_eager_bytes(net._h, 2, C.byref(nb)) == 0
+    # announced value and delta per level (input + 5 layers), state for the 4 conv layers, 4 bytes each
+    maps = [8 * 8 * 3, 8 * 8 * 4, 8 * 8 * 4, 4 * 4 * 4, 4 * 4 * 4, 4 * 4 * 4]
+    least = 2 * 4 * (2 * sum(maps) + maps[1] + maps[2] + maps[4] + maps[5])
+    assert least <= nb.value <= least + 20 * 256
+    net.destroy()
+    wl1 = wl_mod.make(2, streams=1, length=200, channels=(4, 4, 4, 4, 4, 4))
+    net1 = idf.Net("f32", 0, 1, 1, wl1["layers"], wl1["weights"])       # unbounded: no whole maps
+    assert L.idf_query_eager_bytes(net1._h, 1, C.byref(nb)) == binding.IDF_EUNSUPPORTED
+    net1.destroy()
