@@ -218,6 +218,20 @@ int idf_restore(idf_streams *s, int stream_id, const void *dev_buf, const idf_st
 int idf_enable_head(idf_streams *s);
 int idf_read_head(idf_streams *s, const int32_t *stream_ids, int n_ids, double *mean, int64_t *rows);
 
+/* Fully connected output units over the last layer's map (Sec. 4: the class units whose values
+ * settle as rows come in, Fig. 3 / Fig. 4): unit k holds bias[k] plus the sum, over the rows the
+ * last layer has completed in the current sample, of weights[k][row][x][c] times the activation
+ * -- every non-zero activation is an event delivered to every unit (Sec. 3).  float64 sums.
+ *   weights (host) [n_units][out_h][out_w][out_c] float32, bias (host) [n_units] or NULL: copied.
+ *   dev_buf (device): idf_query_head_units_bytes() bytes, owned by the caller, kept by the streams.
+ * Enabling also enables the averaging units and has the same precondition (before the first push);
+ * bounded samples only (IDF_EUNSUPPORTED otherwise).
+ * idf_read_head_units: values (host) [n_ids][n_units], rows (host) [n_ids]; synchronises. */
+int idf_query_head_units_bytes(const idf_net *net, int n_streams, int n_units, size_t *bytes);
+int idf_enable_head_units(idf_streams *s, int n_units, const float *weights, const float *bias, void *dev_buf,
+                          size_t bytes);
+int idf_read_head_units(idf_streams *s, const int32_t *stream_ids, int n_ids, double *values, int64_t *rows);
+
 /* Which kernel family serves layer i of an open stream set: a short static name such as
  * "generic", for reports.  NULL on a bad index. */
 const char *idf_layer_kernel(const idf_streams *s, int layer);

@@ -210,3 +210,13 @@ def stream_run(wl_layers, x, weights, biases=None, *, seg_rows=1, integer=False,
     dt = np.int64 if integer else np.float64
     out = np.concatenate(chunks, axis=0) if chunks else np.empty((0, s.out_w, s.out_c), dtype=dt)
     return out, st
+
+
+def head_units(out_rows, weights, bias=None):
+    """Fully connected output units over the last layer's map (Sec. 4: the class units whose values
+    settle as rows are presented): bias plus the weighted sum of the rows completed so far.
+    out_rows [n][W][C] = the first n rows of the last layer's output; weights [K][H][W][C]."""
+    o = np.asarray(out_rows, dtype=np.float64)
+    w = np.asarray(weights, dtype=np.float64)[:, :o.shape[0]]
+    v = np.tensordot(w, o, axes=([1, 2, 3], [0, 1, 2]))
+    return v if bias is None else v + np.asarray(bias, dtype=np.float64)

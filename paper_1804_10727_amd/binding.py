@@ -17,7 +17,7 @@ ACT = {"none": 0, "relu": 1, "relu_shr_clamp": 2}
 EXPORTS = ["idf_create_net", "idf_destroy_net", "idf_query_sizes", "idf_open_streams", "idf_close_streams",
            "idf_push_segment", "idf_read_outputs", "idf_reset_streams", "idf_get_stats", "idf_rows_pushed",
            "idf_layer_kernel", "idf_last_error", "idf_profile_begin", "idf_profile_end", "idf_enable_head",
-           "idf_read_head", "idf_push_pixels", "idf_query_eager_bytes", "idf_enable_eager", "idf_read_announced", "idf_snapshot_bytes", "idf_snapshot", "idf_restore"]
+           "idf_read_head", "idf_query_head_units_bytes", "idf_enable_head_units", "idf_read_head_units", "idf_push_pixels", "idf_query_eager_bytes", "idf_enable_eager", "idf_read_announced", "idf_snapshot_bytes", "idf_snapshot", "idf_restore"]
 
 
 class IdfError(RuntimeError):
@@ -84,6 +84,9 @@ def load_library():
     L.idf_get_stats.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
     L.idf_rows_pushed.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_int64)]
     L.idf_enable_head.argtypes = [C.c_void_p]
+    L.idf_query_head_units_bytes.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_size_t)]
+    L.idf_enable_head_units.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]
+    L.idf_read_head_units.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
     L.idf_query_eager_bytes.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_size_t)]
     L.idf_enable_eager.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
     L.idf_read_announced.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p]
@@ -253,6 +256,27 @@ class Streams:
                           device=self.device)
         _check(load_library().idf_read_announced(self._h, level, ptr, n, C.c_void_p(out.data_ptr())))
         return out
+
+    def enable_head_units(self, weights, bias=None):
+        """weights [n_units][out_h][out_w][out_c] (float32), bias [n_units] or None."""
+        import torch
+        L = load_library()
+        w = np.ascontiguousarray(weights, dtype=np.float32)
+        b = None if bias is None else np.ascontiguousarray(bias, dtype=np.float32)
+        nb = C.c_size_t()
+        _check(L.idf_query_head_units_bytes(self.net._h, self.n_streams, w.shape[0], C.byref(nb)))
+        self._units_ws = torch.empty(max(1, nb.value), dtype=torch.uint8, device=self.device)
+        self._n_units = int(w.shape[0])
+        _check(L.idf_enable_head_units(self._h, w.shape[0], w.ctypes.data, None if b is None else b.ctypes.data,
+                                       C.c_void_p(self._units_ws.data_ptr()), nb.value))
+
+    def read_head_units(self, stream_ids=None):
+        keep, ptr = _ids(stream_ids)
+        n = self.n_streams if stream_ids is None else len(keep)
+        vals = np.zeros((n, self._n_units), dtype=np.float64)
+        rows = np.zeros(n, dtype=np.int64)
+        _check(load_library().idf_read_head_units(self._h, ptr, n, vals.ctypes.data, rows.ctypes.data))
+        return rows, vals
 
     def enable_head(self):
         _check(load_library().idf_enable_head(self._h))

@@ -278,4 +278,20 @@ struct HeadAcc {
     double *sums, *mean;         // [stream][c] each
 };
 
+// Fully connected output units over the last layer's map: rows [first_slot, first_slot + n_rows)
+// of the output ring, which are rows row0 .. of the sample, are added, weighted, to every unit.
+struct HeadUnits {
+    const void *src;             // output area [stream][out_cap][w][c], 4-byte elements
+    int64_t src_stream_stride;
+    int64_t out_cap;
+    int w, c, n_units;
+    int is_int;
+    int zero_first;              // the units start anew (from their bias) with these rows
+    int64_t row0;
+    int64_t map_elems;           // out_h * w * c: weights of one unit
+    const float *weights;        // [unit][out_h][w][c]
+    const float *bias;           // [unit] or null
+    double *values;              // [stream][unit]
+};
+
 }  // namespace idf

@@ -44,6 +44,7 @@ inline const char *kind_name(int k)
 // Generic kernels: any layer shape, any precision (prec = IDF_PREC_*).
 hipError_t launch_conv_generic(int prec, const ConvStep &a, const StreamSel &sel, const LaunchCtx &lc);
 hipError_t launch_pool_generic(int prec, const PoolStep &a, const StreamSel &sel, const LaunchCtx &lc);
+hipError_t launch_head_units(const HeadUnits &a, const StreamSel &sel, int64_t first_slot, int n_rows, const LaunchCtx &lc);
 hipError_t launch_head_accumulate(const HeadAcc &a, const StreamSel &sel, int64_t first_slot, int n_rows, const LaunchCtx &lc);
 // what: 0 = pushed rows become the announced input, 1 = conv layer, 2 = pool layer
 hipError_t launch_eager(int prec, int what, const EagerStep &a, const StreamSel &sel, const LaunchCtx &lc);

@@ -88,6 +88,9 @@ struct idf_streams {
     std::vector<int> transit_cap;                                    // rows per stream
     size_t out_off = 0, stats_off = 0, head_off = 0;
     bool head_on = false;
+    int head_units = 0;              // fully connected output units (0: only the averaging units)
+    char *head_units_ws = nullptr;   // caller's buffer: weights [unit][map], bias [unit], values [stream][unit]
+    bool head_units_bias = false;
     int64_t out_stride = 0;
     std::vector<std::vector<float>> cas_w;      // cascade packing of the weights (kept until the upload has run)
     // 1-D cascade, layers dealt to stages that run side by side, stage k on the segment pushed k
@@ -923,8 +926,8 @@ int head_catch_up(idf_streams *s, const int32_t *stream_ids, int n_ids)
 {
     if (!s->head_on) return IDF_OK;
     const idf_net &net = *s->net;
-    struct Key { int64_t slot; int64_t n; int zero; int64_t count;
-                 bool operator<(const Key &o) const { return std::tie(slot, n, zero, count) < std::tie(o.slot, o.n, o.zero, o.count); } };
+    struct Key { int64_t slot; int64_t n; int zero; int64_t count; int64_t row0;
+                 bool operator<(const Key &o) const { return std::tie(slot, n, zero, count, row0) < std::tie(o.slot, o.n, o.zero, o.count, o.row0); } };
     std::map<Key, std::vector<std::pair<int, int>>> groups;
     for (int i = 0; i < n_ids; ++i) {
         const int id = stream_ids ? stream_ids[i] : i;
@@ -938,7 +941,8 @@ int head_catch_up(idf_streams *s, const int32_t *stream_ids, int n_ids)
             if (sb > h.head_base) { zero = 1; a = std::max(a, sb); h.head_base = sb; }
         }
         if (b - a > s->out_cap) return fail(IDF_ESTATE, "internal: rows for the averaging units no longer in the output area");
-        groups[Key{a % s->out_cap, b - a, zero, (b - h.head_base) * (int64_t)net.out_w}].push_back({i, id});
+        if (s->head_units && a == h.head_base) zero = 1;      // first rows of a sample: the units start from their bias
+        groups[Key{a % s->out_cap, b - a, zero, (b - h.head_base) * (int64_t)net.out_w, a - h.head_base}].push_back({i, id});
         h.head_done = b;
     }
     HeadAcc a{};
@@ -952,6 +956,16 @@ int head_catch_up(idf_streams *s, const int32_t *stream_ids, int n_ids)
         int rc = for_each_selection(kv.second, [&](const StreamSel &sel) {
             hipError_t e = launch_head_accumulate(a, sel, slot, n,
                                                   launch_ctx(s, kKindHead, 4.0 * n * net.out_w * net.out_c * sel.n));
+            if (e == hipSuccess && s->head_units) {
+                HeadUnits u{};
+                u.src = a.src; u.src_stream_stride = a.src_stream_stride; u.out_cap = a.out_cap; u.w = a.w; u.c = a.c;
+                u.n_units = s->head_units; u.is_int = a.is_int; u.zero_first = kv.first.zero; u.row0 = kv.first.row0;
+                u.map_elems = (int64_t)net.out_h * net.out_w * net.out_c;
+                u.weights = (const float *)s->head_units_ws;
+                u.bias = s->head_units_bias ? u.weights + (size_t)s->head_units * u.map_elems : nullptr;
+                u.values = (double *)(s->head_units_ws + align_up(((size_t)s->head_units * u.map_elems + s->head_units) * 4));
+                e = launch_head_units(u, sel, slot, n, launch_ctx(s, kKindHead, 8.0 * n * net.out_w * net.out_c * sel.n * s->head_units));
+            }
             return e == hipSuccess ? IDF_OK : dev_fail(e, "head launch");
         });
         if (rc != IDF_OK) return rc;
@@ -1342,6 +1356,7 @@ int idf_snapshot(idf_streams *s, int stream_id, void *dev_buf, idf_stream_pos *p
     if (!s || !dev_buf || !pos) return fail(IDF_EINVAL, "null argument");
     if (stream_id < 0 || stream_id >= s->B) return fail(IDF_EINVAL, "stream id %d outside [0, %d)", stream_id, s->B);
     if (s->eager.on) return fail(IDF_EUNSUPPORTED, "snapshots do not cover the maps of eager emission");
+    if (s->head_units) return fail(IDF_EUNSUPPORTED, "snapshots do not cover the fully connected output units");
     if (s->h[stream_id].x_next != 0) return fail(IDF_ESTATE, "stream %d: a row is half presented", stream_id);
     int rc = pipeline_drain(s);
     if (rc != IDF_OK) return rc;
@@ -1371,6 +1386,7 @@ int idf_restore(idf_streams *s, int stream_id, const void *dev_buf, const idf_st
         pos->head_rows < 0 || pos->head_rows > pos->out_rows)
         return fail(IDF_EINVAL, "inconsistent stream position");
     if (s->eager.on) return fail(IDF_EUNSUPPORTED, "snapshots do not cover the maps of eager emission");
+    if (s->head_units) return fail(IDF_EUNSUPPORTED, "snapshots do not cover the fully connected output units");
     int rc = pipeline_drain(s);
     if (rc != IDF_OK) return rc;
     StreamHost &h = s->h[stream_id];
@@ -1438,6 +1454,64 @@ int idf_enable_head(idf_streams *s)
     for (const StreamHost &h : s->h)
         if (h.r != 0 || h.out_written != 0) return fail(IDF_ESTATE, "the averaging units must be enabled before the first push");
     s->head_on = true;
+    return IDF_OK;
+}
+
+int idf_query_head_units_bytes(const idf_net *net, int n_streams, int n_units, size_t *bytes)
+{
+    if (!net || !bytes || n_streams < 1 || n_units < 1) return fail(IDF_EINVAL, "bad argument");
+    if (net->out_h <= 0) return fail(IDF_EUNSUPPORTED, "output units have one weight per position: the sample height must be known");
+    const size_t map = (size_t)net->out_h * net->out_w * net->out_c;
+    *bytes = align_up(((size_t)n_units * map + n_units) * 4) + align_up((size_t)n_streams * n_units * sizeof(double));
+    return IDF_OK;
+}
+
+int idf_enable_head_units(idf_streams *s, int n_units, const float *weights, const float *bias, void *dev_buf, size_t bytes)
+{
+    if (!s || !weights || !dev_buf) return fail(IDF_EINVAL, "null argument");
+    size_t need = 0;
+    int rc = idf_query_head_units_bytes(s->net, s->B, n_units, &need);
+    if (rc != IDF_OK) return rc;
+    if (bytes < need) return fail(IDF_EINVAL, "buffer of %zu bytes for the output units, %zu needed", bytes, need);
+    rc = idf_enable_head(s);                       // the units ride on the averaging units' bookkeeping
+    if (rc != IDF_OK) return rc;
+    const size_t map = (size_t)s->net->out_h * s->net->out_w * s->net->out_c;
+    hipError_t e = hipMemsetAsync(dev_buf, 0, need, s->st);
+    if (e == hipSuccess) e = hipMemcpyAsync(dev_buf, weights, (size_t)n_units * map * 4, hipMemcpyHostToDevice, s->st);
+    if (e == hipSuccess && bias)
+        e = hipMemcpyAsync((char *)dev_buf + (size_t)n_units * map * 4, bias, (size_t)n_units * 4, hipMemcpyHostToDevice, s->st);
+    if (e == hipSuccess) e = hipStreamSynchronize(s->st);          // the host arrays may go after the call
+    if (e != hipSuccess) return dev_fail(e, "enable_head_units");
+    s->head_units = n_units; s->head_units_ws = (char *)dev_buf; s->head_units_bias = bias != nullptr;
+    return IDF_OK;
+}
+
+int idf_read_head_units(idf_streams *s, const int32_t *stream_ids, int n_ids, double *values, int64_t *rows)
+{
+    if (!s || !values || !rows) return fail(IDF_EINVAL, "null argument");
+    if (!s->head_units) return fail(IDF_ESTATE, "no output units enabled");
+    int rc = check_ids(s, stream_ids, n_ids);
+    if (rc != IDF_OK) return rc;
+    rc = pipeline_drain(s);
+    if (rc != IDF_OK) return rc;
+    rc = head_catch_up(s, stream_ids, n_ids);
+    if (rc != IDF_OK) return rc;
+    const int k = s->head_units;
+    const size_t map = (size_t)s->net->out_h * s->net->out_w * s->net->out_c;
+    std::vector<double> all((size_t)s->B * k);
+    std::vector<float> b(k, 0.f);
+    hipError_t e = hipStreamSynchronize(s->st);
+    if (e == hipSuccess)
+        e = hipMemcpy(all.data(), s->head_units_ws + align_up(((size_t)k * map + k) * 4), all.size() * sizeof(double), hipMemcpyDeviceToHost);
+    if (e == hipSuccess && s->head_units_bias)
+        e = hipMemcpy(b.data(), s->head_units_ws + (size_t)k * map * 4, (size_t)k * 4, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return dev_fail(e, "read_head_units");
+    for (int i = 0; i < n_ids; ++i) {
+        const int id = stream_ids ? stream_ids[i] : i;
+        rows[i] = s->h[id].head_done - s->h[id].head_base;
+        // a unit that has received no row yet still states its bias (a constant input, Sec. 3)
+        for (int u = 0; u < k; ++u) values[(size_t)i * k + u] = rows[i] > 0 ? all[(size_t)id * k + u] : (double)b[u];
+    }
     return IDF_OK;
 }
 

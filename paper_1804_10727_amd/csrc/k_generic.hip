@@ -396,4 +396,47 @@ hipError_t launch_head_accumulate(const HeadAcc &a, const StreamSel &sel, int64_
                   n_rows);
 }
 
+// ---------------------------------------------------------------------------------------
+// Fully connected output units (Sec. 4: the output units whose values settle as rows come in): every
+// value of a completed row is an event that adds weight * value to each unit (Sec. 3, the same
+// event-delivery rule one layer up; zero values are skipped).  One workgroup per (stream, unit);
+// lanes stride over the rows' elements, partial sums are added in a fixed order.
+// ---------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_head_units(const HeadUnits a, const StreamSel sel, int64_t first_slot, int n_rows)
+{
+    __shared__ double part[256];
+    const int stream = sel_stream(sel, blockIdx.z), unit = blockIdx.x;
+    const uint32_t *src = (const uint32_t *)a.src + (int64_t)stream * a.src_stream_stride;
+    const float *w = a.weights + (int64_t)unit * a.map_elems;
+    const int64_t row_elems = (int64_t)a.w * a.c;
+    double acc = 0.0;
+    for (int r = 0; r < n_rows; ++r) {
+        int64_t slot = first_slot + r;
+        if (slot >= a.out_cap) slot -= a.out_cap;
+        const uint32_t *row = src + slot * row_elems;
+        const float *wr = w + (a.row0 + r) * row_elems;
+        for (int64_t e = threadIdx.x; e < row_elems; e += 256) {
+            const uint32_t u = row[e];
+            const double v = a.is_int ? (double)(int32_t)u : (double)__uint_as_float(u);
+            if (v != 0.0) acc += v * (double)wr[e];
+        }
+    }
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) part[threadIdx.x] += part[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const int64_t at = (int64_t)stream * a.n_units + unit;
+        const double start = a.zero_first ? (a.bias ? (double)a.bias[unit] : 0.0) : a.values[at];
+        a.values[at] = start + part[0];
+    }
+}
+
+hipError_t launch_head_units(const HeadUnits &a, const StreamSel &sel, int64_t first_slot, int n_rows, const LaunchCtx &lc)
+{
+    return launch(k_head_units, dim3((unsigned)a.n_units, 1, sel.n), dim3(256), 0, lc, a, sel, first_slot, n_rows);
+}
+
 }  // namespace idf

@@ -96,3 +96,45 @@ def test_head_restarts_with_the_next_sample_and_needs_enabling():
     with pytest.raises(idf.IdfError):
         st.enable_head()
     st.close(); net.destroy()
+
+
+@pytest.mark.parametrize("cfg,kw,seg", [
+    (3, dict(streams=3, size=16, channels=(16, 16, 32, 32)), 1),
+    (4, dict(streams=2, size=48, channels=(16, 16, 16, 16, 16, 16, 16, 16)), 2),
+])
+def test_fully_connected_output_units_settle_row_by_row(cfg, kw, seg):
+    """Ten class units over the last layer's map: after every few rows their values are the bias
+    plus the weighted sum of the rows completed so far; after the last row, the conventional
+    network's fully connected layer (Sec. 4, Fig. 3 / Fig. 4)."""
+    import paper_1804_10727_amd as idf
+    from paper_1804_10727_amd.binding import input_tensor
+    from helpers import oracle_dense
+    wl = wl_mod.make(cfg, **kw)
+    B, H = wl["streams"], wl["in_h"]
+    rng = np.random.default_rng(9)
+    net = idf.net_from_workload(wl)
+    st = idf.Streams(net, B, max_seg_rows=seg)
+    oh, ow, oc = int(st.sizes.out_h), int(st.sizes.out_w), int(st.sizes.out_c)
+    w = rng.normal(0, 1.0 / np.sqrt(oh * ow * oc), size=(10, oh, ow, oc)).astype(np.float32)
+    b = rng.normal(0, 0.1, size=(10,)).astype(np.float32)
+    st.enable_head_units(w, b)
+    dense = [oracle_dense(wl, s).astype(np.float64) for s in range(B)]
+    x = input_tensor(wl)
+    rows0, v0 = st.read_head_units()
+    assert (rows0 == 0).all() and np.allclose(v0, b[None, :].astype(np.float64))
+    seen = set()
+    for i, r in enumerate(range(0, H, seg)):
+        st.push_segment(x[:, r:r + seg].contiguous())
+        if True:
+            rows, vals = st.read_head_units()
+            for s in range(B):
+                want = oracle.head_units(dense[s][:rows[s]], w, b)
+                assert np.max(np.abs(vals[s] - want)) <= 1e-5 * max(1.0, np.max(np.abs(want))), (i, s)
+                seen.add(int(rows[s]))
+    assert oh in seen and len(seen) >= 3
+    for s in range(B):      # after the last row: the conventional network's dense layer on the whole map
+        full = np.tensordot(w.astype(np.float64), dense[s], axes=([1, 2, 3], [0, 1, 2])) + b
+        assert np.argmax(vals[s]) == np.argmax(full)
+    with pytest.raises(idf.IdfError):
+        st.snapshot(0)
+    st.close(); net.destroy()
