@@ -14,11 +14,11 @@
 //     those: a stretch of the row without events costs no weight fetch and no matrix
 //     instruction (zero values are not events, Sec. 1).
 //   * Weights come straight from global memory in the fragment layout (packed once on the host).
-//   * The retained rows of c (rows y-1 and y of the rolling buffer) are fetched at the start and
-//     are in flight during the contraction.  Epilogue: the row that is now final (y-1; also y
+//   * The retained rows of c (rows y-1 and y of the rolling buffer) are fetched at the start,
+//     straight into the accumulators; row y+1 starts there from the bias.  Epilogue: the row that is now final (y-1; also y
 //     when y is the last row of the sample) is activated, rounded to the event type and emitted
 //     -- through a fused 2x2 max-pool when one follows -- and forgotten; the others go back to
-//     the rolling buffer; row y+1 is started from the bias.
+//     the rolling buffer.
 #include "idf.h"
 #include "idf_kernels.h"
 #include <algorithm>
@@ -217,19 +217,22 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
             vmask |= (co_ok && xo < W) ? 1u << (i * 4 + j) : 0u;
         }
     const bool wave_full = __ballot(vmask != 0xffffu) == 0ull;
+    const st_t bias_v = a.bias ? ((const st_t *)a.bias)[co_c] : (st_t)0;
     st_t *ring = (st_t *)a.ring + (int64_t)stream * a.ring_stream_stride;
-    st_t init[3][16];
+    // They are loaded straight into the accumulators (a row touched for the first time starts
+    // from the bias there): the contraction then adds on top and the epilogue has nothing to add.
+    acc_t acc[3];
 #pragma unroll
     for (int ky = 0; ky < 3; ++ky) {
+        const st_t start = a.t[ky].valid ? bias_v : (st_t)0;
 #pragma unroll
-        for (int q = 0; q < 16; ++q) init[ky][q] = 0;
+        for (int q = 0; q < 16; ++q) acc[ky][q] = start;
         if (a.t[ky].valid && !a.t[ky].fresh) {
             const st_t *rrow = ring + (int64_t)a.t[ky].ring_slot * W * C_out;
 #pragma unroll
-            for (int q = 0; q < 16; ++q) init[ky][q] = rrow[roff[q]];
+            for (int q = 0; q < 16; ++q) acc[ky][q] = rrow[roff[q]];
         }
     }
-    const st_t bias_v = a.bias ? ((const st_t *)a.bias)[co_c] : (st_t)0;
     ev_t *held = (ev_t *)a.held + (int64_t)stream * a.held_stream_stride;
     uint32_t heldv[16];                            // one register each: nothing to pack, so nothing to wait for
     {
@@ -337,11 +340,6 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
     }
 
     // ---- contraction over the live K-steps ----------------------------------------------------
-    acc_t acc[3];
-#pragma unroll
-    for (int ky = 0; ky < 3; ++ky)
-#pragma unroll
-        for (int q = 0; q < 16; ++q) acc[ky][q] = 0;
     if (small_c) {
         // first layers: K = 3*C_in <= 12, one or two steps (all prefetched); the fragment is gathered
         // element by element
@@ -435,9 +433,8 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
         const MfmaTap &t = a.t[ky];
         if (!t.valid) continue;
         st_t c[16];
-        const bool cont = !t.fresh;                   // continues a retained row; else starts from the bias
 #pragma unroll
-        for (int q = 0; q < 16; ++q) c[q] = (cont ? init[ky][q] : bias_v) + acc[ky][q];
+        for (int q = 0; q < 16; ++q) c[q] = acc[ky][q];
         if (t.emit == kEmitNone) {
             st_t *rrow = ring + (int64_t)t.ring_slot * W * C_out;
             if (wave_full) {
