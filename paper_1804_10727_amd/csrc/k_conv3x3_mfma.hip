@@ -132,6 +132,12 @@ struct TraitsF32 {
     static __device__ __forceinline__ ev_t from_bits(uint32_t u) { return __uint_as_float(u); }
 };
 
+// A 4-byte cell at a byte offset from a base every lane shares.
+template <class P> __device__ __forceinline__ P *at4(P *base, uint32_t byte_off)
+{
+    return (P *)((const char *)base + byte_off);      // plain pointer arithmetic: the address space stays known
+}
+
 constexpr int kMaxPos = 128 + 2;                 // positions of the widest tile plus halo
 constexpr int kNzWords = (kMaxPos + 31) / 32 + 1;
 
@@ -206,14 +212,16 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
     // This lane's 16 cells of a row [W][C_out]: element offsets (clamped into the row, so loads
     // need no predicate) and which of them exist.  A wave whose cells all exist -- every wave
     // when W is a multiple of 32 and C_out a multiple of the chunk -- stores without predicates.
-    int roff[16];
+    // (kept as 32-bit byte offsets of 4-byte cells: with the row's base in scalar registers an
+    // access is then "scalar base + lane offset", no 64-bit arithmetic per cell)
+    uint32_t roff[16];
     unsigned int vmask = 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int xo = xo_base + 8 * i + j;
-            roff[i * 4 + j] = (xo < W ? xo : W - 1) * C_out + co_c;
+            roff[i * 4 + j] = (uint32_t)(((xo < W ? xo : W - 1) * C_out + co_c) * 4);
             vmask |= (co_ok && xo < W) ? 1u << (i * 4 + j) : 0u;
         }
     const bool wave_full = __ballot(vmask != 0xffffu) == 0ull;
@@ -230,7 +238,7 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
         if (a.t[ky].valid && !a.t[ky].fresh) {
             const st_t *rrow = ring + (int64_t)a.t[ky].ring_slot * W * C_out;
 #pragma unroll
-            for (int q = 0; q < 16; ++q) acc[ky][q] = rrow[roff[q]];
+            for (int q = 0; q < 16; ++q) acc[ky][q] = *at4(rrow, roff[q]);
         }
     }
     ev_t *held = (ev_t *)a.held + (int64_t)stream * a.held_stream_stride;
@@ -240,7 +248,7 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
             heldv[q] = 0;
-            if (need) heldv[q] = T::bits(held[roff[q]]);
+            if (need) heldv[q] = T::bits(*at4(held, roff[q] / (4 / EB)));
         }
     }
 
@@ -439,11 +447,11 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
             st_t *rrow = ring + (int64_t)t.ring_slot * W * C_out;
             if (wave_full) {
 #pragma unroll
-                for (int q = 0; q < 16; ++q) rrow[roff[q]] = c[q];
+                for (int q = 0; q < 16; ++q) *at4(rrow, roff[q]) = c[q];
             } else {
 #pragma unroll
                 for (int q = 0; q < 16; ++q)
-                    if (vmask >> q & 1u) rrow[roff[q]] = c[q];
+                    if (vmask >> q & 1u) *at4(rrow, roff[q]) = c[q];
             }
             continue;
         }
@@ -463,7 +471,7 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
             st_t *orow = (st_t *)a.dst + (int64_t)stream * a.dst_stream_stride + t.dst_slot * W * C_out;
 #pragma unroll
             for (int q = 0; q < 16; ++q)
-                if (wave_full || (vmask >> q & 1u)) orow[roff[q]] = T::activate(c[q], a.act, a.shr, a.clamp_hi);
+                if (wave_full || (vmask >> q & 1u)) *at4(orow, roff[q]) = T::activate(c[q], a.act, a.shr, a.clamp_hi);
         } else if (t.emit == kEmitDirect || (t.emit == kEmitHold && t.store_held)) {
             if (!stage_free) { lds_barrier(); stage_free = true; }
 #pragma unroll
