@@ -203,7 +203,7 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
             const int p = a.chunks_rcp ? (int)__umulhi((unsigned)i, a.chunks_rcp) : i, c = i - p * chunks;   // i / chunks
             int x = x0 - 1 + p;
             x = x < a.x_lo ? a.x_lo : (x >= a.x_hi ? a.x_hi - 1 : x);
-            tv[b] = *reinterpret_cast<const i32x4 *>(in_row + ((int64_t)x * C_in + c * VL) * EB);
+            tv[b] = *at4(reinterpret_cast<const i32x4 *>(in_row), (uint32_t)((x * C_in + c * VL) * EB));
         }
     };
     if (cells > 0) tile_issue(0);
@@ -256,16 +256,20 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
     const int KT = 3 * C_in;
     const int steps = (KT + KI - 1) / KI;
     const int hlf = lane >> 5, r = wm * 32 + (lane & 31);
-    const unsigned char *wbase = (const unsigned char *)a.wfrag + ((int64_t)hlf * a.c_out_pad + co0 + wn * 32 + (lane & 31)) * 16;
-    const int64_t w_step = (int64_t)2 * a.c_out_pad * 16;           // bytes per K-step
-    const int64_t w_ky = (int64_t)steps * w_step;                    // bytes per ky
+    // weights: the three ky planes as scalar bases, this lane's fragment as a 32-bit byte offset
+    const uint32_t w_lane = (uint32_t)((hlf * a.c_out_pad + co0 + wn * 32 + (lane & 31)) * 16);
+    const uint32_t w_step = (uint32_t)(2 * a.c_out_pad * 16);       // bytes per K-step
+    const i32x4 *w_plane[3];
+#pragma unroll
+    for (int ky = 0; ky < 3; ++ky)
+        w_plane[ky] = reinterpret_cast<const i32x4 *>((const unsigned char *)a.wfrag + (int64_t)ky * steps * w_step);
     constexpr int kDepth = T::kDepth;                                // K-steps in flight
     i32x4 aq[kDepth], bq[kDepth][3];
     auto fetch_b = [&](int d, int sn) {
-        const unsigned char *wp = wbase + sn * w_step;
-        bq[d][0] = *reinterpret_cast<const i32x4 *>(wp);
-        bq[d][1] = *reinterpret_cast<const i32x4 *>(wp + w_ky);
-        bq[d][2] = *reinterpret_cast<const i32x4 *>(wp + 2 * w_ky);
+        const uint32_t off = w_lane + (uint32_t)sn * w_step;
+        bq[d][0] = *at4(w_plane[0], off);
+        bq[d][1] = *at4(w_plane[1], off);
+        bq[d][2] = *at4(w_plane[2], off);
     };
 #pragma unroll
     for (int d = 0; d < kDepth; ++d) fetch_b(d, d < steps ? d : steps - 1);
