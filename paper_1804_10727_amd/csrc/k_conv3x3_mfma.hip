@@ -309,7 +309,7 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
                 const int p = i / C_in;
                 const int x = x0 - 1 + p;
                 ev_t v = 0;
-                if (x >= a.x_lo && x < a.x_hi) v = in_e[(int64_t)x * C_in + (i - p * C_in)];
+                if (x >= a.x_lo && x < a.x_hi) v = *at4(in_e, (uint32_t)((x * C_in + (i - p * C_in)) * EB));
                 xs_e[i] = v;
                 if (count && p >= 1 && p <= MT && T::ev_nonzero(v)) {
                     ev += 1;
@@ -429,7 +429,7 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
             const int p = i / kCpp, k = i - p * kCpp;
             const int x = p0 + p, cch = co0 + k * kPer;
             if (x < row_w && cch < C_out)
-                *reinterpret_cast<i32x4 *>(grow + (int64_t)x * C_out + cch) =
+                *at4(reinterpret_cast<i32x4 *>(grow), (uint32_t)((x * C_out + cch) * EB)) =
                     *reinterpret_cast<const i32x4 *>(stage + p * NC + k * kPer);
         }
         lds_barrier();
