@@ -46,10 +46,10 @@ struct TraitsBf16 {
         return ((v.x | v.y | v.z | v.w) & 0x7fff7fff) != 0;
     }
     static __device__ __forceinline__ int count_nonzero(const i32x4 &v)
-    {
+    {   // adding 0x7fff to the 15 magnitude bits of a half carries into its top bit unless they are all zero
         int n = 0;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { n += (v[i] & 0x7fff) != 0; n += (v[i] & 0x7fff0000) != 0; }
+        for (int i = 0; i < 4; ++i) n += __builtin_popcount((((uint32_t)v[i] & 0x7fff7fffu) + 0x7fff7fffu) & 0x80008000u);
         return n;
     }
     static __device__ __forceinline__ st_t activate(st_t c, int act, int, int) { return act == IDF_ACT_NONE ? c : fmaxf(c, 0.f); }
@@ -77,11 +77,12 @@ struct TraitsI8 {
     static __device__ __forceinline__ bool cell_nonzero(const i32x4 &v) { return (v.x | v.y | v.z | v.w) != 0; }
     static __device__ __forceinline__ int count_nonzero(const i32x4 &v)
     {
-        int n = 0;
+        int n = 0;          // per byte: the low seven bits carry into the top bit, or the top bit is set already
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int b = 0; b < 4; ++b) n += ((v[i] >> (8 * b)) & 0xff) != 0;
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t u = (uint32_t)v[i];
+            n += __builtin_popcount((((u & 0x7f7f7f7fu) + 0x7f7f7f7fu) | u) & 0x80808080u);
+        }
         return n;
     }
     static __device__ __forceinline__ st_t activate(st_t c, int act, int shr, int hi)
@@ -278,7 +279,7 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
     lds_barrier();                               // occupancy bits are cleared
     {
         const bool count = co_chunk == 0 && a.stats;
-        unsigned long long ev = 0, taps = 0;
+        unsigned int ev = 0, taps = 0;               // per lane: a few cells
         if (!small_c) {
             for (int base = 0; base < cells; base += NT * kBatch) {
                 if (base > 0) tile_issue(base);
