@@ -55,9 +55,7 @@ struct TraitsBf16 {
     static __device__ __forceinline__ st_t activate(st_t c, int act, int, int) { return act == IDF_ACT_NONE ? c : fmaxf(c, 0.f); }
     static __device__ __forceinline__ ev_t to_ev(st_t h)
     {
-        uint32_t u = __float_as_uint(h);
-        u += 0x7fffu + ((u >> 16) & 1u);           // round to nearest, ties to even
-        return (ev_t)(u >> 16);
+        return __builtin_bit_cast(ev_t, (__bf16)h);     // round to nearest, ties to even (one conversion instruction here)
     }
     static __device__ __forceinline__ st_t ev_val(ev_t v) { return __uint_as_float((uint32_t)v << 16); }
     static __device__ __forceinline__ bool ev_nonzero(ev_t v) { return (v & 0x7fffu) != 0; }
