@@ -33,7 +33,8 @@ typedef __attribute__((ext_vector_type(16))) int i32x16;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 
 struct TraitsBf16 {
-    static constexpr int kDepth = 6;         // K-steps whose operands are in flight
+    static constexpr int kOcc = 3;           // waves per SIMD the batch kernel is compiled for (168 registers)
+    static constexpr int kDepth = 3;         // K-steps whose operands are in flight: three waves hide more than six steps did for two
     static constexpr int VL = 8;             // elements per 16-byte lane fragment
     static constexpr int EB = 2;             // bytes per element
     using acc_t = f32x16; using st_t = float; using ev_t = uint16_t;
@@ -64,6 +65,7 @@ struct TraitsBf16 {
 };
 
 struct TraitsI8 {
+    static constexpr int kOcc = 2;           // at three the prologue spills and the kernel is slower
     static constexpr int kDepth = 6;
     static constexpr int VL = 16;
     static constexpr int EB = 1;
@@ -101,6 +103,7 @@ struct TraitsI8 {
 // 32x32x2 matrix instructions (instruction i pairs element i of the two half-waves' fragments;
 // which two k share an instruction does not matter to the sum).
 struct TraitsF32 {
+    static constexpr int kOcc = 2;
     static constexpr int kDepth = 3;         // a step is twelve long matrix instructions here: little to hide
     static constexpr int VL = 4;
     static constexpr int EB = 4;
@@ -175,9 +178,11 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
     const int xs_stride = C_in * EB + 16;          // bytes per position in LDS (padded against bank conflicts)
 
     // Order of the global loads: the hardware counts outstanding loads in issue order, so what
-    // is needed first is requested first -- the row stretch, then the retained state (used only
-    // in the epilogue), then the weights of the first K-steps -- and waiting for the stretch
-    // leaves everything younger in flight.
+    // is needed first is requested first -- the row stretch, then the retained state -- and
+    // waiting for the stretch leaves the state in flight.  The first weights are asked for only
+    // once the stretch has left its registers, and the pool's held row only in the epilogue:
+    // with fewer values alive at once, more waves fit a SIMD, which hides more than the earlier
+    // requests did.
     const int row_lane = (lane >> 5) * 4;          // D layout: row = 8*i + (lane/32)*4 + j, col = lane%32
     const int xo_base = x0 + wm * 32 + row_lane;
     const int co = co0 + wn * 32 + (lane & 31);
@@ -207,7 +212,7 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
     };
     if (cells > 0) tile_issue(0);
 
-    // ---- (2) retained rows of c, the pool's held row, the bias --------------------------------
+    // ---- (2) retained rows of c, the bias ------------------------------------------------------
     // This lane's 16 cells of a row [W][C_out]: element offsets (clamped into the row, so loads
     // need no predicate) and which of them exist.  A wave whose cells all exist -- every wave
     // when W is a multiple of 32 and C_out a multiple of the chunk -- stores without predicates.
@@ -241,17 +246,8 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
         }
     }
     ev_t *held = (ev_t *)a.held + (int64_t)stream * a.held_stream_stride;
-    uint32_t heldv[16];                            // one register each: nothing to pack, so nothing to wait for
-    {
-        const bool need = a.t[2].valid && a.t[2].emit == kEmitPoolHeld;   // only row y-1 can pair with the held row
-#pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            heldv[q] = 0;
-            if (need) heldv[q] = T::bits(*at4(held, roff[q] / (4 / EB)));
-        }
-    }
 
-    // ---- (3) weights of the first K-steps, before it is known which steps are live -----------
+    // ---- (3) weight fragments: addressing -------------------------------------------------------
     const int KT = 3 * C_in;
     const int steps = (KT + KI - 1) / KI;
     const int hlf = lane >> 5, r = wm * 32 + (lane & 31);
@@ -270,8 +266,6 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
         bq[d][1] = *at4(w_plane[1], off);
         bq[d][2] = *at4(w_plane[2], off);
     };
-#pragma unroll
-    for (int d = 0; d < kDepth; ++d) fetch_b(d, d < steps ? d : steps - 1);
 
     // ---- stretch -> LDS, with occupancy bits and the counters ---------------------------------
     lds_barrier();                               // occupancy bits are cleared
@@ -329,6 +323,10 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
             if (t) atomicAdd(dst + 1, t * (unsigned long long)(a.taps_y * C_out));
         }
     }
+
+    // weights of the first K-steps, before it is known which steps are live
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) fetch_b(d, d < steps ? d : steps - 1);
 
     // ---- which K-steps have anything in them for this wave's 32 positions -------------------
     unsigned long long live;
@@ -438,6 +436,15 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
     ev_t hprev[16];                                   // activations of the even row finalised by tap 2
 #pragma unroll
     for (int q = 0; q < 16; ++q) hprev[q] = 0;
+    uint32_t heldv[16];                               // the pool's held row: one register each, nothing to pack
+    {
+        const bool need = a.t[2].valid && a.t[2].emit == kEmitPoolHeld;   // only row y-1 can pair with the held row
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            heldv[q] = 0;
+            if (need) heldv[q] = T::bits(*at4(held, roff[q] / (4 / EB)));
+        }
+    }
 #pragma unroll
     for (int kk = 0; kk < 3; ++kk) {
         const int ky = 2 - kk;                        // row y-1 first
@@ -538,7 +545,7 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
 // (Giving each XCD one contiguous eighth of a step-major order, so that a layer's weights meet in one
 // L2, was measured slower: the steps differ too much in length.)
 template <class T, int WM, int WN>
-__global__ void __launch_bounds__(64 * WM * WN, 2) k_conv3x3_mfma_batch(const MfmaBatch b, const StreamSel sel)
+__global__ void __launch_bounds__(64 * WM * WN, T::kOcc) k_conv3x3_mfma_batch(const MfmaBatch b, const StreamSel sel)
 {
     const int tile = blockIdx.x, si = blockIdx.z;
     int k = 0;                                   // all bounds in one batch of scalar loads, no dependent chain
