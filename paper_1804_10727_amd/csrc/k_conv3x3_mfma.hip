@@ -65,7 +65,7 @@ struct TraitsBf16 {
 };
 
 struct TraitsI8 {
-    static constexpr int kOcc = 2;           // at three the prologue spills and the kernel is slower
+    static constexpr int kOcc = 2;           // three gain nothing where a launch is one short round of workgroups
     static constexpr int kDepth = 6;
     static constexpr int VL = 16;
     static constexpr int EB = 1;
@@ -220,14 +220,18 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
     // access is then "scalar base + lane offset", no 64-bit arithmetic per cell)
     uint32_t roff[16];
     unsigned int vmask = 0;
+    auto cell_offsets = [&](int xo_first) {
+        vmask = 0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int xo = xo_base + 8 * i + j;
-            roff[i * 4 + j] = (uint32_t)(((xo < W ? xo : W - 1) * C_out + co_c) * 4);
-            vmask |= (co_ok && xo < W) ? 1u << (i * 4 + j) : 0u;
-        }
+            for (int j = 0; j < 4; ++j) {
+                const int xo = xo_first + 8 * i + j;
+                roff[i * 4 + j] = (uint32_t)(((xo < W ? xo : W - 1) * C_out + co_c) * 4);
+                vmask |= (co_ok && xo < W) ? 1u << (i * 4 + j) : 0u;
+            }
+    };
+    cell_offsets(xo_base);
     const bool wave_full = __ballot(vmask != 0xffffu) == 0ull;
     const st_t bias_v = a.bias ? ((const st_t *)a.bias)[co_c] : (st_t)0;
     st_t *ring = (st_t *)a.ring + (int64_t)stream * a.ring_stream_stride;
@@ -415,6 +419,14 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
     // full 128-byte line per row of the tile).  Event-type rows (1 or 2 bytes per value) would be
     // partial-line writes from that layout, so they are staged in LDS as [position][channel] and
     // leave as 16-byte chunks that tile whole lines.
+    if (T::kOcc > 2) {
+        // The offsets are worked out again rather than kept: sixteen registers held across the
+        // contraction would be spilled to memory by every lane at three waves per SIMD.  (The
+        // empty statement hides from the compiler that it has seen this value before.)
+        int xo_again = xo_base;
+        asm volatile("" : "+v"(xo_again));
+        cell_offsets(xo_again);
+    }
     ev_t *stage = reinterpret_cast<ev_t *>(smem);
     bool stage_free = false;                          // the stretch in LDS may still be read by slower waves
     auto flush = [&](ev_t *grow, int row_w, int p0, int npos) {
