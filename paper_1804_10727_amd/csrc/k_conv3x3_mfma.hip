@@ -66,7 +66,7 @@ struct TraitsBf16 {
 
 struct TraitsI8 {
     static constexpr int kOcc = 2;           // three gain nothing where a launch is one short round of workgroups
-    static constexpr int kDepth = 6;
+    static constexpr int kDepth = 3;           // measured against 4 and 6 on the event workload
     static constexpr int VL = 16;
     static constexpr int EB = 1;
     using acc_t = i32x16; using st_t = int32_t; using ev_t = int8_t;
@@ -547,19 +547,22 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
 template <class T, int WM, int WN>
 __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a, const StreamSel sel)
 {
-    conv3x3_row<T, WM, WN>(a, sel, blockIdx.x, blockIdx.z);
+    conv3x3_row<T, WM, WN>(a, sel, blockIdx.z, blockIdx.x);      // tile by tile, the streams of a tile side by side
 }
 
 // Several layers' steps in one launch (each on a row that was complete before the launch): the
 // workgroups of step k are tiles [wg_lo[k], wg_lo[k+1]) for every stream.  One tile shape for all steps.
-// The work is laid out stream by stream, and within a stream step by step with the deepest (longest)
-// steps first; consecutive workgroups go to the eight XCDs in turn, which spreads every step evenly.
-// (Giving each XCD one contiguous eighth of a step-major order, so that a layer's weights meet in one
-// L2, was measured slower: the steps differ too much in length.)
+// The work is laid out tile by tile with the deepest (longest) steps first, and within a tile stream by
+// stream.  Consecutive workgroups go to the eight XCDs in turn: with a multiple of eight streams a
+// stream always meets the same XCD, so its row stretch is fetched into one L2 for all its channel
+// chunks, a weight fragment is fetched once per XCD and used by that XCD's streams close in time, and
+// every step is spread evenly.  (Stream by stream with the tiles inside was measured 8 % slower on the
+// VGG-style workload; one contiguous eighth of the order per XCD slower still: the steps differ too
+// much in length.)
 template <class T, int WM, int WN>
 __global__ void __launch_bounds__(64 * WM * WN, T::kOcc) k_conv3x3_mfma_batch(const MfmaBatch b, const StreamSel sel)
 {
-    const int tile = blockIdx.x, si = blockIdx.z;
+    const int tile = blockIdx.z, si = blockIdx.x;
     int k = 0;                                   // all bounds in one batch of scalar loads, no dependent chain
 #pragma unroll
     for (int j = 1; j < kMfmaBatchMax; ++j) k += (j < b.n && tile >= b.wg_lo[j]) ? 1 : 0;
@@ -581,8 +584,8 @@ hipError_t launch_batch_shape(const MfmaBatch &b0, const StreamSel &sel, const L
         lds = std::max(lds, (size_t)MT * NC * T::EB);
     }
     b.wg_lo[b.n] = wg;
-    if (b.n < 1 || wg < 1) return hipErrorInvalidValue;
-    return launch(k_conv3x3_mfma_batch<T, WM, WN>, dim3(wg, 1, sel.n), dim3(64 * WM * WN), lds, lc, b, sel);
+    if (b.n < 1 || wg < 1 || wg > 65535) return hipErrorInvalidValue;      // tiles are the grid's z extent
+    return launch(k_conv3x3_mfma_batch<T, WM, WN>, dim3(sel.n, 1, wg), dim3(64 * WM * WN), lds, lc, b, sel);
 }
 
 template <class T>
@@ -605,7 +608,8 @@ hipError_t launch_one(const MfmaStep &a, const StreamSel &sel, const LaunchCtx &
     size_t lds = (size_t)(MT + 2) * (a.c_in * T::EB + 16);
     const size_t stage = (size_t)MT * NC * T::EB;       // the epilogue reuses the space to stage emitted rows
     if (lds < stage) lds = stage;
-    return launch(k_conv3x3_mfma<T, WM, WN>, dim3(x_tiles * co_chunks, 1, sel.n), dim3(64 * WM * WN), lds, lc, a, sel);
+    if (x_tiles * co_chunks > 65535) return hipErrorInvalidValue;      // tiles are the grid's z extent
+    return launch(k_conv3x3_mfma<T, WM, WN>, dim3(sel.n, 1, x_tiles * co_chunks), dim3(64 * WM * WN), lds, lc, a, sel);
 }
 
 template <class T> hipError_t launch_prec(const MfmaStep &a, const StreamSel &sel, const LaunchCtx &lc)
