@@ -232,7 +232,6 @@ constexpr int kMfmaBatchMax = 8;
 struct MfmaBatch {
     int n;
     int tile;                          // kMfmaTile* (not 128x32), the same for every step
-    int wg_lo[kMfmaBatchMax + 1];      // filled by the launcher: first workgroup of each step
     MfmaStep st[kMfmaBatchMax];
 };
 

@@ -171,6 +171,7 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
     const int n_co_chunks = (a.c_out + NC - 1) / NC;
     const int x_tile = bx / n_co_chunks, co_chunk = bx - x_tile * n_co_chunks;
     const int x0 = x_tile * MT, co0 = co_chunk * NC;
+    if (x0 >= a.w) return;                         // a launch of several steps is as deep as its largest
     // a pixel segment in the middle of a row: tiles it cannot reach are left alone
     if (a.skip_clear_tiles && (x0 + MT < a.x_lo || x0 > a.x_hi)) return;
     const int W = a.w, C_in = a.c_in, C_out = a.c_out;
@@ -202,6 +203,7 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
     auto tile_issue = [&](int base) {
 #pragma unroll
         for (int b = 0; b < kBatch; ++b) {
+            if (base + b * NT >= cells) break;         // the same for every lane: narrow layers ask for less
             int i = base + b * NT + tid;
             i = i < cells ? i : cells - 1;
             const int p = a.chunks_rcp ? (int)__umulhi((unsigned)i, a.chunks_rcp) : i, c = i - p * chunks;   // i / chunks
@@ -550,42 +552,38 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
     conv3x3_row<T, WM, WN>(a, sel, blockIdx.z, blockIdx.x);      // tile by tile, the streams of a tile side by side
 }
 
-// Several layers' steps in one launch (each on a row that was complete before the launch): the
-// workgroups of step k are tiles [wg_lo[k], wg_lo[k+1]) for every stream.  One tile shape for all steps.
-// The work is laid out tile by tile with the deepest (longest) steps first, and within a tile stream by
-// stream.  Consecutive workgroups go to the eight XCDs in turn: with a multiple of eight streams a
-// stream always meets the same XCD, so its row stretch is fetched into one L2 for all its channel
-// chunks, a weight fragment is fetched once per XCD and used by that XCD's streams close in time, and
-// every step is spread evenly.  (Stream by stream with the tiles inside was measured 8 % slower on the
-// VGG-style workload; one contiguous eighth of the order per XCD slower still: the steps differ too
-// much in length.)
+// Several layers' steps in one launch (each on a row that was complete before the launch).  The grid
+// is (stream, tile, step): a workgroup knows its step from its own index, so its arguments arrive in
+// one round of scalar loads (a table of first tiles per step cost a second, dependent round: about
+// half a microsecond before the first row request of every workgroup).  Steps with fewer tiles than
+// the launch's largest leave a few workgroups that return at once.  One tile shape for all steps.
+// In dispatch order the streams of a tile lie side by side, then the tiles of a step, then the steps
+// with the deepest (longest) first.  Consecutive workgroups go to the eight XCDs in turn: with a
+// multiple of eight streams a stream always meets the same XCD, so its row stretch is fetched into one
+// L2 for all its channel chunks, a weight fragment is fetched once per XCD and used by that XCD's
+// streams close in time, and every step is spread evenly.  (Stream by stream with the tiles inside was
+// measured 8 % slower on the VGG-style workload; one contiguous eighth of the order per XCD slower
+// still: the steps differ too much in length.)
 template <class T, int WM, int WN>
 __global__ void __launch_bounds__(64 * WM * WN, T::kOcc) k_conv3x3_mfma_batch(const MfmaBatch b, const StreamSel sel)
 {
-    const int tile = blockIdx.z, si = blockIdx.x;
-    int k = 0;                                   // all bounds in one batch of scalar loads, no dependent chain
-#pragma unroll
-    for (int j = 1; j < kMfmaBatchMax; ++j) k += (j < b.n && tile >= b.wg_lo[j]) ? 1 : 0;
-    conv3x3_row<T, WM, WN>(b.st[k], sel, tile - b.wg_lo[k], si);
+    conv3x3_row<T, WM, WN>(b.st[blockIdx.z], sel, blockIdx.y, blockIdx.x);
 }
 
 template <class T, int WM, int WN>
-hipError_t launch_batch_shape(const MfmaBatch &b0, const StreamSel &sel, const LaunchCtx &lc)
+hipError_t launch_batch_shape(const MfmaBatch &b, const StreamSel &sel, const LaunchCtx &lc)
 {
     constexpr int MT = 32 * WM, NC = 32 * WN;
-    MfmaBatch b = b0;
     size_t lds = 0;
-    int wg = 0;
+    int tiles_max = 0;
     for (int k = 0; k < b.n; ++k) {
         const MfmaStep &a = b.st[k];
-        b.wg_lo[k] = wg;
-        wg += ((a.w + MT - 1) / MT) * ((a.c_out + NC - 1) / NC);
+        tiles_max = std::max(tiles_max, ((a.w + MT - 1) / MT) * ((a.c_out + NC - 1) / NC));
         lds = std::max(lds, (size_t)(MT + 2) * (a.c_in * T::EB + 16));
         lds = std::max(lds, (size_t)MT * NC * T::EB);
     }
-    b.wg_lo[b.n] = wg;
-    if (b.n < 1 || wg < 1 || wg > 65535) return hipErrorInvalidValue;      // tiles are the grid's z extent
-    return launch(k_conv3x3_mfma_batch<T, WM, WN>, dim3(sel.n, 1, wg), dim3(64 * WM * WN), lds, lc, b, sel);
+    if (b.n < 1 || tiles_max < 1 || tiles_max > 65535) return hipErrorInvalidValue;      // tiles are the grid's y extent
+    return launch(k_conv3x3_mfma_batch<T, WM, WN>, dim3(sel.n, tiles_max, b.n), dim3(64 * WM * WN), lds, lc, b, sel);
 }
 
 template <class T>
