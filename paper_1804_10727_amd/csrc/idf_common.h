@@ -177,6 +177,9 @@ struct CascadeArgs {
     int stage_lo[kCasMaxStages + 1];     // stage s runs layers [stage_lo[s], stage_lo[s+1])
     int transit_wr;                      // parity of the hand-over buffers written by this launch
     CascadeLayer sched[kCasMaxLayers];   // sched[l] describes the segment layer l's stage works on
+    CascadeLayer first[kCasMaxStages];   // filled by the launcher: first[s] = sched[stage_lo[s]], so that a
+                                         // workgroup finds it from its stage alone, in its first round of loads
+    int per;                             // filled by the launcher: streams side by side in blockIdx.x
     const void *in;                      // stage 0: [position][rows][c0]
     int64_t in_stream_stride;
     void *transit;                       // hand-over rows [boundary][parity][stream][row][channel]

@@ -224,25 +224,19 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     Lds &lds = *reinterpret_cast<Lds *>(lds_raw);
     const int tid = threadIdx.x, lane = tid & 63;
-    // Workgroups go to the eight XCDs in turn by their linear number.  The stages are dealt to the
-    // XCDs (with four stages, two XCDs each): a stage's weights are then fetched into the L2 of
-    // its XCDs only, not into all eight.
-    int si, stage;
-    {
-        const int id = blockIdx.x, n_st = ka.n_stages;
-        if ((8 % n_st) == 0 && ((sel.n * n_st) & 7) == 0) {
-            const int per = 8 / n_st, xcd = id & 7;
-            stage = xcd / per;
-            si = (id >> 3) * per + (xcd - stage * per);
-        } else {
-            stage = id / sel.n;
-            si = id - stage * sel.n;
-        }
-    }
+    // The grid is (streams side by side, stage, groups of streams).  Workgroups go to the eight XCDs
+    // in turn by their linear number; with `per` = 8 / stages streams side by side, stage s meets XCDs
+    // s*per .. s*per+per-1 only, so its weights are fetched into the L2 of its XCDs, not into all eight.
+    // The stage comes from the grid index and the stage's first layer from a copy indexed by stage:
+    // everything the first memory requests need is then one round of scalar loads away (looked up
+    // through the stage table it was three dependent rounds, about a microsecond per launch).
+    const int stage = blockIdx.y;
+    const int si = blockIdx.z * ka.per + blockIdx.x;
     const int stream = sel_stream(sel, si);
     const int n_layers = ka.n_layers;
     const int lb = ka.stage_lo[stage], le = ka.stage_lo[stage + 1];
-    if (ka.sched[lb].cnt <= 0) return;                           // nothing has reached this stage
+    const CascadeLayer &first = ka.first[stage];
+    if (first.cnt <= 0) return;                                  // nothing has reached this stage
 
     // The argument block (first kernel argument, offset 0 of the kernel-argument segment) goes to
     // LDS in one sweep: inside the chain a layer's descriptor then costs an LDS read instead of a
@@ -262,10 +256,10 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
         }
     }
     Wq wq;
-    WCur wc = cursor_of(ka.sched[lb], tid);
+    WCur wc = cursor_of(first, tid);
 #pragma unroll
     for (int p = 0; p < kAhead; ++p) fetch_w(wq.w[p], wc);
-    const int c0 = ka.sched[lb].c_in, n_in = ka.sched[lb].cnt * c0;   // at most 16 rows x 64 channels: two per lane
+    const int c0 = first.c_in, n_in = first.cnt * c0;            // at most 16 rows x 64 channels: two per lane
     float xin[2];
     {
         // the new segment, or the rows the stage before handed over in the previous launch
@@ -325,7 +319,7 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
             if (lane == 0) {
                 unsigned long long *dst = ka.stats + ((int64_t)stream * n_layers + lb) * 2;
                 atomicAdd(dst, (unsigned long long)ev);
-                atomicAdd(dst + 1, (unsigned long long)taps * ka.sched[lb].c_out);
+                atomicAdd(dst + 1, (unsigned long long)taps * first.c_out);
             }
         }
 #pragma unroll
@@ -510,7 +504,12 @@ hipError_t launch_cascade1d(const CascadeArgs &a, const StreamSel &sel, const La
     static hipError_t prepared = hipFuncSetAttribute(reinterpret_cast<const void *>(k_cascade1d),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Lds));
     if (prepared != hipSuccess) return prepared;
-    return launch(k_cascade1d, dim3(sel.n * a.n_stages), dim3(kCasThreads), sizeof(Lds), lc, a, sel);
+    CascadeArgs b = a;
+    for (int k = 0; k < b.n_stages; ++k) b.first[k] = b.sched[b.stage_lo[k]];
+    const bool spread = 8 % b.n_stages == 0 && sel.n % (8 / b.n_stages) == 0;
+    b.per = spread ? 8 / b.n_stages : sel.n;
+    if (sel.n / b.per > 65535) return hipErrorInvalidValue;
+    return launch(k_cascade1d, dim3(b.per, b.n_stages, sel.n / b.per), dim3(kCasThreads), sizeof(Lds), lc, b, sel);
 }
 
 }  // namespace idf
