@@ -231,19 +231,13 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
     // everything the first memory requests need is then one round of scalar loads away (looked up
     // through the stage table it was three dependent rounds, about a microsecond per launch).
     const int stage = blockIdx.y;
-    const int si = blockIdx.z * ka.per + blockIdx.x;
-    const int stream = sel_stream(sel, si);
-    const int n_layers = ka.n_layers;
-    const int lb = ka.stage_lo[stage], le = ka.stage_lo[stage + 1];
-    const CascadeLayer &first = ka.first[stage];
-    if (first.cnt <= 0) return;                                  // nothing has reached this stage
-
     // The argument block (first kernel argument, offset 0 of the kernel-argument segment) goes to
     // LDS in one sweep: inside the chain a layer's descriptor then costs an LDS read instead of a
     // memory round trip.  The prologue itself reads the arguments as scalars, so that everything
     // the chain needs from memory except the later weights is requested at once, next to that
     // sweep: the first weights, the new input rows, the rolling buffers and biases of the firing
     // layers.
+    // (Requested before anything else: its latency then runs under the scalar loads below.)
     constexpr int kArgPerLane = (kArgWords + kT - 1) / kT;
     uint32_t argw[kArgPerLane];
     {
@@ -255,6 +249,19 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
             argw[u] = kp[i < kArgWords ? i : kArgWords - 1];
         }
     }
+    __builtin_amdgcn_sched_barrier(0);
+    const int si = blockIdx.z * ka.per + blockIdx.x;
+    const int stream = sel_stream(sel, si);
+    const int n_layers = ka.n_layers;
+    const int lb = ka.stage_lo[stage], le = ka.stage_lo[stage + 1];
+    const CascadeLayer &first = ka.first[stage];
+    // First round of scalar loads, asked for in one batch with one wait (left to first use they
+    // end up behind conditions, one memory round trip each, one after the other).
+    asm volatile("" ::"s"(ka.per), "s"(sel.n), "s"(sel.base), "s"(sel.pos0), "s"(n_layers), "s"(lb), "s"(le), "s"(first.cnt),
+                 "s"(first.c_in), "s"(first.c_out), "s"(first.cp_log), "s"(first.steps), "s"(first.w), "s"(ka.in),
+                 "s"(ka.in_stream_stride), "s"(ka.transit), "s"(ka.transit_stream_stride), "s"(ka.transit_buf_stride),
+                 "s"(ka.transit_wr), "s"(ka.stats));
+    if (first.cnt <= 0) return;                                  // nothing has reached this stage
     Wq wq;
     WCur wc = cursor_of(first, tid);
 #pragma unroll
@@ -273,21 +280,35 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
             xin[u] = in[i < n_in ? i : n_in - 1];
         }
     }
-    float rv[kCasMaxLayers][2], bv[kCasMaxLayers];
+    // Second round: what the rolling-buffer requests of the stage's layers need.  The first
+    // kPinned layers of the stage in one batch; a stage with more layers (a deep net run without
+    // stages) fetches the rest as it goes.
+    constexpr int kPinned = 3;
+    const int l_last = n_layers - 1;
+    auto layer_of = [&](int j) -> const CascadeLayer & { return ka.sched[lb + j < l_last ? lb + j : l_last]; };
+    {
+        const CascadeLayer &q0 = layer_of(0), &q1 = layer_of(1), &q2 = layer_of(2);
+        static_assert(kPinned == 3, "one group of operands per pinned layer");
+        asm volatile("" ::"s"(q0.cnt), "s"(q0.ring), "s"(q0.ring_stride), "s"(q0.ring_floats), "s"(q0.bias), "s"(q0.c_out),
+                     "s"(q1.cnt), "s"(q1.ring), "s"(q1.ring_stride), "s"(q1.ring_floats), "s"(q1.bias), "s"(q1.c_out),
+                     "s"(q2.cnt), "s"(q2.ring), "s"(q2.ring_stride), "s"(q2.ring_floats), "s"(q2.bias), "s"(q2.c_out));
+    }
+
+    float rv[kCasMaxLayers][2], bv[kCasMaxLayers];             // by position in the stage: layer lb + j
 #pragma unroll
-    for (int l = 0; l < kCasMaxLayers; ++l) {
-        rv[l][0] = rv[l][1] = bv[l] = 0.f;
-        if (l >= lb && l < le && ka.sched[l].cnt > 0) {
-            const CascadeLayer &sl = ka.sched[l];
+    for (int j = 0; j < kCasMaxLayers; ++j) {
+        rv[j][0] = rv[j][1] = bv[j] = 0.f;
+        const CascadeLayer &sl = layer_of(j);
+        if (lb + j < le && sl.cnt > 0) {
             const gfloat *ring = as_global((const float *)sl.ring) + (int64_t)stream * sl.ring_stride;
             const int n_r = sl.ring_floats;
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
                 const int i = tid + u * kT;
-                rv[l][u] = ring[i < n_r ? i : n_r - 1];
+                rv[j][u] = ring[i < n_r ? i : n_r - 1];
             }
             const gfloat *bias = as_global((const float *)sl.bias);
-            if (bias) bv[l] = bias[tid < sl.c_out ? tid : sl.c_out - 1];
+            if (bias) bv[j] = bias[tid < sl.c_out ? tid : sl.c_out - 1];
         }
     }
     {
@@ -323,11 +344,11 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
             }
         }
 #pragma unroll
-        for (int l = 0; l < kCasMaxLayers; ++l) {
-            if (l >= lb && l < le && ka.sched[l].cnt > 0) {
-                lds.ring[l][tid] = rv[l][0];
-                if (tid + kT < kRingPerLayer) lds.ring[l][tid + kT] = rv[l][1];
-                if (tid < 64) lds.bias[l][tid] = bv[l];
+        for (int j = 0; j < kCasMaxLayers; ++j) {
+            if (lb + j < le && layer_of(j).cnt > 0) {
+                lds.ring[lb + j][tid] = rv[j][0];
+                if (tid + kT < kRingPerLayer) lds.ring[lb + j][tid + kT] = rv[j][1];
+                if (tid < 64) lds.bias[lb + j][tid] = bv[j];
             }
         }
     }
