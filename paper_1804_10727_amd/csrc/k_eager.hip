@@ -67,6 +67,12 @@ __global__ void __launch_bounds__(256) k_eager_input(const EagerStep a, const St
 }
 
 // Conv layer: cells of output rows [o_lo, o_hi) take in the delta rows [i_lo, i_hi) of the layer before.
+// A group of G lanes (G = c_out rounded up to a power of two, at most 64) owns one position and a
+// chunk of G output channels, one cell per lane.  For each tap the group reads the delta vector of the
+// position it looks at once, G input channels at a time, one value per lane; a ballot of the
+// non-zero values is the list of events, and only those are visited: the value comes from the lane
+// that holds it, the weight from memory, one multiply-add per cell.  A zero costs nothing but its
+// share of that one read.  The order of the additions is that of the footprint (ky, kx, channel).
 template <bool INT>
 __global__ void __launch_bounds__(256) k_eager_conv(const EagerStep a, const StreamSel sel)
 {
@@ -74,31 +80,66 @@ __global__ void __launch_bounds__(256) k_eager_conv(const EagerStep a, const Str
     using val_t = typename V::t;
     const Geom &g = a.g;
     const int stream = sel_stream(sel, blockIdx.z);
-    const int64_t n = (int64_t)(a.o_hi - a.o_lo) * g.w_out * g.c_out;
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    bool nz = false;
-    if (i < n) {
-        const int co = (int)(i % g.c_out);
-        const int64_t pos = i / g.c_out;
-        const int x = (int)(pos % g.w_out), o = a.o_lo + (int)(pos / g.w_out);
-        const val_t *din = (const val_t *)a.dlt_in + (int64_t)stream * a.in_map_stride;
-        const typename V::w_t *w = (const typename V::w_t *)a.w;
-        const int64_t cell = (int64_t)stream * a.map_stride + ((int64_t)o * g.w_out + x) * g.c_out + co;
-        val_t c = a.init_bias ? (a.bias ? ((const val_t *)a.bias)[co] : (val_t)0) : ((val_t *)a.c)[cell];
-        for (int ky = 0; ky < g.k_h; ++ky) {
-            const int iy = o * g.s_h - g.p_h + ky;
-            if (iy < a.i_lo || iy >= a.i_hi) continue;           // only the rows that carry this segment's events
-            for (int kx = 0; kx < g.k_w; ++kx) {
-                const int ix = x * g.s_w - g.p_w + kx;
-                if (ix < 0 || ix >= g.w_in) continue;
-                const val_t *dp = din + ((int64_t)iy * g.w_in + ix) * g.c_in;
-                const typename V::w_t *wp = w + ((int64_t)(ky * g.k_w + kx) * g.c_in) * g.c_out + co;
-                for (int ci = 0; ci < g.c_in; ++ci) {
-                    const val_t d = dp[ci];
-                    if (d != 0) c = V::mac(c, d, wp[(int64_t)ci * g.c_out]);   // zero: no event
+    const int lane = threadIdx.x & 63;
+    int g_log = 4;                                              // G = 16, 32 or 64
+    while ((1 << g_log) < g.c_out && g_log < 6) ++g_log;
+    const int G = 1 << g_log, per_wave = 64 >> g_log;
+    const int grp = lane >> g_log, col = lane & (G - 1);
+    const int co_chunks = (g.c_out + G - 1) >> g_log;
+    const int64_t units = (int64_t)(a.o_hi - a.o_lo) * g.w_out * co_chunks;      // (position, channel chunk)
+    const int64_t unit = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * per_wave + grp;
+    const bool have = unit < units;
+    const int64_t u = have ? unit : units - 1;                  // clamped: every lane stays in the loops
+    const int chunk = (int)(u % co_chunks);
+    const int64_t pos = u / co_chunks;
+    const int x = (int)(pos % g.w_out), o = a.o_lo + (int)(pos / g.w_out);
+    const int co = chunk * G + col;
+    const bool mine = have && co < g.c_out;
+    const int co_c = co < g.c_out ? co : g.c_out - 1;
+    const val_t *din = (const val_t *)a.dlt_in + (int64_t)stream * a.in_map_stride;
+    const typename V::w_t *w = (const typename V::w_t *)a.w;
+    const int64_t cell = (int64_t)stream * a.map_stride + ((int64_t)o * g.w_out + x) * g.c_out + co_c;
+    val_t c = a.init_bias ? (a.bias ? ((const val_t *)a.bias)[co_c] : (val_t)0) : ((val_t *)a.c)[cell];
+    const unsigned long long gbits = G == 64 ? ~0ull : ((1ull << G) - 1ull);
+    for (int ky = 0; ky < g.k_h; ++ky) {
+        const int iy = o * g.s_h - g.p_h + ky;
+        const bool row_ok = iy >= a.i_lo && iy < a.i_hi;        // only the rows that carry this segment's events
+        for (int kx = 0; kx < g.k_w; ++kx) {
+            const int ix = x * g.s_w - g.p_w + kx;
+            const bool tap_ok = row_ok && ix >= 0 && ix < g.w_in;
+            if (__ballot(tap_ok) == 0ull) continue;
+            const val_t *dp = din + ((int64_t)(tap_ok ? iy : a.i_lo) * g.w_in + (tap_ok ? ix : 0)) * g.c_in;
+            const typename V::w_t *wp = w + ((int64_t)(ky * g.k_w + kx) * g.c_in) * g.c_out + co_c;
+            for (int j0 = 0; j0 < g.c_in; j0 += G) {
+                const val_t dv = (tap_ok && j0 + col < g.c_in) ? dp[j0 + col] : (val_t)0;
+                const unsigned long long all = __ballot(dv != 0);
+                if (all == 0ull) continue;
+                unsigned long long ev = (all >> (grp << g_log)) & gbits;    // this group's events
+                while (__ballot(ev != 0ull) != 0ull) {
+                    // four events at a time: their values and weights are all asked for before
+                    // the first is used (a slot past the last event repeats the last one, adding nothing)
+                    constexpr int kE = 4;
+                    val_t d[kE];
+                    typename V::w_t wv[kE];
+                    int bit = 0;
+#pragma unroll
+                    for (int e = 0; e < kE; ++e) {
+                        const bool on = ev != 0ull;
+                        bit = on ? __builtin_ctzll(ev) : bit;
+                        const val_t dd = __shfl(dv, (grp << g_log) + bit);
+                        d[e] = on ? dd : (val_t)0;
+                        wv[e] = wp[(int64_t)(j0 + bit) * g.c_out];
+                        ev &= ev - 1ull;
+                    }
+#pragma unroll
+                    for (int e = 0; e < kE; ++e)
+                        if (d[e] != 0) c = V::mac(c, d[e], wv[e]);
                 }
             }
         }
+    }
+    bool nz = false;
+    if (mine) {
         ((val_t *)a.c)[cell] = c;
         const val_t h = V::act(g, c), d = h - ((val_t *)a.ann)[cell];
         ((val_t *)a.ann)[cell] = h;
@@ -144,8 +185,17 @@ hipError_t launch_eager(int prec, int what, const EagerStep &a, const StreamSel 
 {
     const int64_t n = (int64_t)(a.o_hi - a.o_lo) * (what == 0 ? (int64_t)a.w_out * a.c_out : (int64_t)a.g.w_out * a.g.c_out);
     if (n <= 0) return hipSuccess;
-    const dim3 grid((unsigned)((n + 255) / 256), 1, sel.n), block(256);
+    dim3 grid((unsigned)((n + 255) / 256), 1, sel.n);
+    const dim3 block(256);
     const bool is_int = prec == IDF_PREC_I8;
+    if (what == 1) {
+        // a group of G lanes per (position, chunk of G channels): see k_eager_conv
+        int G = 16;
+        while (G < a.g.c_out && G < 64) G *= 2;
+        const int64_t units = (int64_t)(a.o_hi - a.o_lo) * a.g.w_out * ((a.g.c_out + G - 1) / G);
+        const int per_block = 4 * (64 / G);
+        grid.x = (unsigned)((units + per_block - 1) / per_block);
+    }
     if (what == 0) {
         if (is_int) return launch(k_eager_input<true, int8_t>, grid, block, 0, lc, a, sel);
         return launch(k_eager_input<false, float>, grid, block, 0, lc, a, sel);
