@@ -106,6 +106,7 @@ struct idf_streams {
     // layer ("unit") the rows waiting for it, and where in the ring of hand-over rows they lie.
     struct StgRow { int64_t y; int slot; };
     bool stg2d = false;
+    std::vector<std::pair<int, int>> push_members;   // (position, id) of the streams of the push being checked
     std::vector<int> stg_unit;                  // conv layer of unit k
     std::vector<std::deque<StgRow>> stg_fifo;
     std::vector<int64_t> stg_seq;               // rows emitted by unit k so far
@@ -1168,8 +1169,14 @@ int idf_push_segment(idf_streams *s, const int32_t *stream_ids, int n_ids, const
     if (n_rows < 1 || n_rows > s->max_seg) return fail(IDF_EINVAL, "n_rows %d outside [1, %d]", n_rows, s->max_seg);
     if (s->eager.on) return eager_push(s, stream_ids, n_ids, dev_rows, n_rows);
     const idf_net &net = *s->net;
-    // validate everything before anything is enqueued
-    std::map<std::pair<int64_t, int64_t>, std::vector<std::pair<int, int>>> groups;
+    // Validate everything before anything is enqueued.  Streams pushed in step -- the usual case --
+    // share one row number and one output slot: they form one group, found without building the
+    // map, and what depends on the row number only is worked out once per distinct value.
+    std::vector<std::pair<int, int>> &members = s->push_members;
+    members.clear();
+    std::pair<int64_t, int64_t> key0{0, 0};
+    bool one_group = true;
+    int64_t memo_r = -1, memo_fresh = 0;
     for (int i = 0; i < n_ids; ++i) {
         const int id = stream_ids ? stream_ids[i] : i;
         const StreamHost &h = s->h[id];
@@ -1178,23 +1185,41 @@ int idf_push_segment(idf_streams *s, const int32_t *stream_ids, int n_ids, const
         if (net.in_h > 0 && h.r + n_rows > net.in_h)
             return fail(IDF_ESTATE, "stream %d: rows %lld..%lld run past the sample of %d rows", id,
                         (long long)h.r, (long long)(h.r + n_rows - 1), net.in_h);
-        const int64_t fresh = output_rows_of_push(net, h.r, n_rows);
+        if (h.r != memo_r) { memo_r = h.r; memo_fresh = output_rows_of_push(net, h.r, n_rows); }
+        const int64_t fresh = memo_fresh;
         if (h.out_written - h.out_read + fresh > s->out_cap)
             return fail(IDF_ESTATE, "stream %d: output area full (%lld rows waiting, %lld more would complete, room for %lld)",
                         id, (long long)(h.out_written - h.out_read), (long long)fresh, (long long)s->out_cap);
-        groups[{h.r, h.out_written % s->out_cap}].push_back({i, id});
+        const std::pair<int64_t, int64_t> key{h.r, h.out_written % s->out_cap};
+        if (i == 0) key0 = key;
+        else if (key != key0) one_group = false;
+        members.push_back({i, id});
     }
-    for (auto &kv : groups) {
-        const int64_t r = kv.first.first, slot0 = kv.first.second;
-        rc = for_each_selection(kv.second, [&](const StreamSel &sel) {
-            return enqueue_cascade(s, sel, dev_rows, n_rows, r, slot0);
+    if (one_group) {
+        rc = for_each_selection(members, [&](const StreamSel &sel) {
+            return enqueue_cascade(s, sel, dev_rows, n_rows, key0.first, key0.second);
         });
         if (rc != IDF_OK) return rc;
+    } else {
+        std::map<std::pair<int64_t, int64_t>, std::vector<std::pair<int, int>>> groups;
+        for (const auto &m : members) {
+            const StreamHost &h = s->h[m.second];
+            groups[{h.r, h.out_written % s->out_cap}].push_back(m);
+        }
+        for (auto &kv : groups) {
+            const int64_t r = kv.first.first, slot0 = kv.first.second;
+            rc = for_each_selection(kv.second, [&](const StreamSel &sel) {
+                return enqueue_cascade(s, sel, dev_rows, n_rows, r, slot0);
+            });
+            if (rc != IDF_OK) return rc;
+        }
     }
+    memo_r = -1;
     for (int i = 0; i < n_ids; ++i) {
         const int id = stream_ids ? stream_ids[i] : i;
         StreamHost &h = s->h[id];
-        h.out_written += output_rows_of_push(net, h.r, n_rows);
+        if (h.r != memo_r) { memo_r = h.r; memo_fresh = output_rows_of_push(net, h.r, n_rows); }
+        h.out_written += memo_fresh;
         h.r += n_rows;
         h.x_next = 0;
         if (net.in_h > 0 && h.r == net.in_h) h.r = 0;      // next sample
