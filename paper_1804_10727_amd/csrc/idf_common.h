@@ -119,7 +119,7 @@ struct PoolStep {
 };
 
 // Whole-net cascade for 1-D nets (one launch per push).
-constexpr int kCasThreads = 512;
+constexpr int kCasThreads = 256;     // four waves: two workgroups share a CU
 constexpr int kCasKMax = 9;        // kernel height at most
 constexpr int kCasRowsMax = 16;    // rows a layer receives per push at most
 constexpr int kCasMaxLayers = 8;
@@ -169,7 +169,7 @@ struct CascadeLayer {
 // The layers can be dealt to up to kCasMaxStages groups of workgroups (blockIdx.y) that run side
 // by side in one launch, stage s working on the segment pushed s launches earlier: its first
 // layer reads what stage s-1 wrote in the launch before (double-buffered by launch parity).
-constexpr int kCasMaxStages = 4;
+constexpr int kCasMaxStages = 8;
 
 struct CascadeArgs {
     int n_layers;

@@ -97,7 +97,7 @@ struct idf_streams {
     // launches earlier: the segments still on their way, newest first
     struct CasPush { bool valid = false; CascadeLayer sched[kCasMaxLayers]; int64_t out_slot0 = 0; };
     int cas_stages = 1;
-    int cas_lo[kCasMaxStages + 1] = {0, 0, 0, 0, 0};
+    int cas_lo[kCasMaxStages + 1] = {};
     CasPush cas_hist[kCasMaxStages - 1];
     int cas_parity = 0;
     size_t cas_transit_off = 0;
@@ -351,8 +351,8 @@ double conv_step_bytes(const idf_net &net, const ConvStep &a, int n_streams)
 }
 
 // Deals the cascade's layers to stages.  A stage costs a fixed part and a part per layer that
-// grows with the layer's steps; the split with the cheapest slowest stage wins, as long as every
-// workgroup of a launch (streams x stages) gets a compute unit of its own.
+// grows with the layer's steps; the split with the cheapest slowest stage wins, as long as all
+// workgroups of a launch (streams x stages) are resident at once, two to a compute unit.
 void plan_cascade_stages(idf_streams *s)
 {
     const idf_net &net = *s->net;
@@ -360,37 +360,31 @@ void plan_cascade_stages(idf_streams *s)
     int cus = 0, dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
         cus = 0;
-    int max_stages = std::min({kCasMaxStages, n, std::max(1, cus / std::max(1, s->B))});
+    int max_stages = std::min({kCasMaxStages, n, std::max(1, 2 * cus / std::max(1, s->B))});      // two workgroups fit a CU
     if (const char *e = getenv("IDF_CASCADE_STAGES")) max_stages = std::max(1, std::min(max_stages, atoi(e)));
     std::vector<double> cost(n);
     for (int l = 0; l < n; ++l) cost[l] = 2.5 + 0.2 * cascade1d_steps(net.g[l].c_in, net.g[l].c_out);
     const double fixed = 4.0;
-    double best = 1e30;
-    int best_lo[kCasMaxStages + 1] = {0, n, n, n, n}, best_n = 1;
-    // up to three cut points: try them all
-    for (int a = 1; a <= n; ++a)
-        for (int b = a; b <= n; ++b)
-            for (int c = b; c <= n; ++c) {
-                const int lo[5] = {0, a, b, c, n};
-                int stages = 0;
-                double worst = 0;
-                bool ok = true;
-                for (int k = 0; k < 4; ++k) {
-                    if (lo[k] == lo[k + 1]) { if (lo[k] != n) ok = false; continue; }
-                    ++stages;
-                    double t = fixed;
-                    for (int l = lo[k]; l < lo[k + 1]; ++l) t += cost[l];
-                    worst = std::max(worst, t);
-                }
-                if (!ok || stages > max_stages) continue;
-                worst += 0.3 * stages;                      // on a tie, fewer stages
-                if (worst < best) {
-                    best = worst; best_n = stages;
-                    int k2 = 0;
-                    for (int k = 0; k < 4; ++k) if (lo[k] != lo[k + 1]) best_lo[k2++] = lo[k];
-                    for (; k2 <= kCasMaxStages; ++k2) best_lo[k2] = n;
-                }
+    // Contiguous groups of layers, at most max_stages of them, the slowest as fast as possible
+    // (on a tie, fewer stages): best[k][i] = cost of the slowest of k stages over layers [0, i).
+    std::vector<std::vector<double>> best(max_stages + 1, std::vector<double>(n + 1, 1e30));
+    std::vector<std::vector<int>> cut(max_stages + 1, std::vector<int>(n + 1, 0));
+    best[0][0] = 0;
+    for (int k = 1; k <= max_stages; ++k)
+        for (int i = k; i <= n; ++i) {
+            double t = fixed;
+            for (int j = i - 1; j >= k - 1; --j) {         // the last stage is layers [j, i)
+                t += cost[j];
+                const double w = std::max(best[k - 1][j], t);
+                if (w < best[k][i]) { best[k][i] = w; cut[k][i] = j; }
             }
+        }
+    int best_n = 1;
+    for (int k = 2; k <= max_stages; ++k)
+        if (best[k][n] + 0.3 * k < best[best_n][n] + 0.3 * best_n) best_n = k;
+    int best_lo[kCasMaxStages + 1];
+    for (int k = 0; k <= kCasMaxStages; ++k) best_lo[k] = n;
+    for (int k = best_n, i = n; k >= 1; --k) { i = cut[k][i]; best_lo[k - 1] = i; }
     s->cas_stages = best_n;
     for (int k = 0; k <= kCasMaxStages; ++k) s->cas_lo[k] = best_lo[k];
 }

@@ -1,6 +1,6 @@
-// Depth-first cascade for 1-D nets: one launch per push, one workgroup per stream, every
-// layer the segment can influence handled in turn (Sec. 3 first paragraph: each segment goes
-// through all of the network it can influence before the next is looked at).
+// Depth-first cascade for 1-D nets: one launch per push, one workgroup per stream and stage,
+// every layer the segment can influence handled in turn (Sec. 3 first paragraph: each segment
+// goes through all of the network it can influence before the next is looked at).
 //
 // The stream's whole retained state -- the rolling buffer of K rows of pre-activations c of
 // every layer (Fig. 1) -- is brought into LDS when the kernel starts, lives there while the
@@ -19,8 +19,9 @@
 //      layer (LDS) -- a wave ballot of the non-zero values it emits gives the next layer's
 //      events and channel bits -- or keeps it for the rolling buffer.
 //
-// The kernel is a chain of dependent layers on one compute unit with two waves per SIMD, and
-// what limits it is the number of instructions a wave has to issue (one per four cycles):
+// A workgroup is a chain of dependent layers run by four waves (two workgroups share a compute
+// unit, so that the waiting of one runs under the arithmetic of the other), and what limits it
+// is the number of instructions a wave has to issue (one per four cycles):
 // hence per channel a handful of instructions besides the multiply-adds themselves -- running
 // offsets instead of address arithmetic, no per-row masks, one bit test for silence -- and
 // variants for 4, 8 and 16 new rows.  Every weight is needed exactly once per push; the
@@ -48,6 +49,9 @@ constexpr int kAhead = kCasAhead;                    // input channels whose wei
 constexpr int kBatch = 4;                            // input channels whose rows are read from LDS together
 constexpr int kArgWords = (sizeof(CascadeArgs) + 3) / 4;
 constexpr int kRingPerLayer = kKMax * 64;            // floats of rolling buffer per layer at most
+constexpr int kXinPerLane = (kCasRowsMax * 64 + kT - 1) / kT;      // values of a segment per lane at most
+constexpr int kRingPerLane = (kRingPerLayer + kT - 1) / kT;
+constexpr int kRedU = kT / 64 < 8 ? kT / 64 : 8;     // partial sums gathered per round: divides every number of lane groups
 
 constexpr int ceil_div_c(int a, int b) { return a >= 0 ? (a + b - 1) / b : -((-a) / b); }
 // Offset of accumulator slot 0 relative to floor((y0+p)/S), and number of slots.
@@ -219,7 +223,7 @@ size_t cascade1d_weight_index(int c_in, int c_out, int ci, int co, int ky)
 
 int cascade1d_slot_off(int S, int rho) { return ceil_div_c(rho - kKMax + 1, S); }
 
-__global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka, const StreamSel sel)
+__global__ void __launch_bounds__(kCasThreads, 2) k_cascade1d(const CascadeArgs ka, const StreamSel sel)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     Lds &lds = *reinterpret_cast<Lds *>(lds_raw);
@@ -266,8 +270,8 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
     WCur wc = cursor_of(first, tid);
 #pragma unroll
     for (int p = 0; p < kAhead; ++p) fetch_w(wq.w[p], wc);
-    const int c0 = first.c_in, n_in = first.cnt * c0;            // at most 16 rows x 64 channels: two per lane
-    float xin[2];
+    const int c0 = first.c_in, n_in = first.cnt * c0;            // at most 16 rows x 64 channels
+    float xin[kXinPerLane];
     {
         // the new segment, or the rows the stage before handed over in the previous launch
         const gfloat *in = stage == 0
@@ -275,7 +279,7 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
             : as_global((const float *)ka.transit) + ((stage - 1) * 2 + (ka.transit_wr ^ 1)) * ka.transit_buf_stride +
                   (int64_t)stream * ka.transit_stream_stride;
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
+        for (int u = 0; u < kXinPerLane; ++u) {
             const int i = tid + u * kT;
             xin[u] = in[i < n_in ? i : n_in - 1];
         }
@@ -294,16 +298,18 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
                      "s"(q2.cnt), "s"(q2.ring), "s"(q2.ring_stride), "s"(q2.ring_floats), "s"(q2.bias), "s"(q2.c_out));
     }
 
-    float rv[kCasMaxLayers][2], bv[kCasMaxLayers];             // by position in the stage: layer lb + j
+    float rv[kCasMaxLayers][kRingPerLane], bv[kCasMaxLayers];             // by position in the stage: layer lb + j
 #pragma unroll
     for (int j = 0; j < kCasMaxLayers; ++j) {
-        rv[j][0] = rv[j][1] = bv[j] = 0.f;
+        bv[j] = 0.f;
+#pragma unroll
+        for (int u = 0; u < kRingPerLane; ++u) rv[j][u] = 0.f;
         const CascadeLayer &sl = layer_of(j);
         if (lb + j < le && sl.cnt > 0) {
             const gfloat *ring = as_global((const float *)sl.ring) + (int64_t)stream * sl.ring_stride;
             const int n_r = sl.ring_floats;
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
+            for (int u = 0; u < kRingPerLane; ++u) {
                 const int i = tid + u * kT;
                 rv[j][u] = ring[i < n_r ? i : n_r - 1];
             }
@@ -326,7 +332,7 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
     {
         unsigned int ev = 0, taps = 0;                          // the network input's events (eventise step)
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
+        for (int u = 0; u < kXinPerLane; ++u) {
             const int i = tid + u * kT;
             if (i < n_in && xin[u] != 0.f) {
                 const int j = i / c0, c = i - j * c0;
@@ -346,8 +352,9 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
 #pragma unroll
         for (int j = 0; j < kCasMaxLayers; ++j) {
             if (lb + j < le && layer_of(j).cnt > 0) {
-                lds.ring[lb + j][tid] = rv[j][0];
-                if (tid + kT < kRingPerLayer) lds.ring[lb + j][tid + kT] = rv[j][1];
+#pragma unroll
+                for (int u = 0; u < kRingPerLane; ++u)
+                    if (tid + u * kT < kRingPerLayer) lds.ring[lb + j][tid + u * kT] = rv[j][u];
                 if (tid < 64) lds.bias[lb + j][tid] = bv[j];
             }
         }
@@ -371,7 +378,7 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
         const WCur nxt0 = cursor_of(a.sched[more ? l + 1 : l], tid);
         const int n_qp = uni(sl.steps);
         // groups of lanes beyond the input channels hold no partial sums (they write zeros): not read
-        const int n_red = (kT >> cp_log) < ((c_in + 7) & ~7) ? (kT >> cp_log) : ((c_in + 7) & ~7);
+        const int n_red = (kT >> cp_log) < ((c_in + kRedU - 1) & ~(kRedU - 1)) ? (kT >> cp_log) : ((c_in + kRedU - 1) & ~(kRedU - 1));
         const Lanes m = lanes_of(cp_log, tid);
 
         // this lane's view of the channel bits: bit q*n_grp of it belongs to its q-th channel
@@ -412,12 +419,12 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
             bool wave_has[kCellsPerThread];                   // some lane of this wave owns a live cell q
 #pragma unroll
             for (int q = 0; q < kCellsPerThread; ++q) wave_has[q] = __ballot(live[q]) != 0ull;
-            float part[kCellsPerThread][8];
+            float part[kCellsPerThread][kRedU];
 #pragma unroll
             for (int q = 0; q < kCellsPerThread; ++q)
                 if (wave_has[q]) {
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) part[q][u] = lds.red[(t_of[q] << cp_log) + c + u * g_stride];
+                    for (int u = 0; u < kRedU; ++u) part[q][u] = lds.red[(t_of[q] << cp_log) + c + u * g_stride];
                 }
 #pragma unroll
             for (int q = 0; q < kCellsPerThread; ++q) {
@@ -425,21 +432,21 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
                 sum[q] = fresh ? bias_c : ringv[q];
                 if (wave_has[q]) {
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) sum[q] += part[q][u];    // fixed order
+                    for (int u = 0; u < kRedU; ++u) sum[q] += part[q][u];    // fixed order
                 }
             }
-            for (int gi = 8; gi < n_red; gi += 8) {           // n_grp is a multiple of 8
+            for (int gi = kRedU; gi < n_red; gi += kRedU) {   // the number of groups is a multiple of kRedU
 #pragma unroll
                 for (int q = 0; q < kCellsPerThread; ++q)
                     if (wave_has[q]) {
 #pragma unroll
-                        for (int u = 0; u < 8; ++u) part[q][u] = lds.red[(t_of[q] << cp_log) + c + (gi + u) * g_stride];
+                        for (int u = 0; u < kRedU; ++u) part[q][u] = lds.red[(t_of[q] << cp_log) + c + (gi + u) * g_stride];
                     }
 #pragma unroll
                 for (int q = 0; q < kCellsPerThread; ++q)
                     if (wave_has[q]) {
 #pragma unroll
-                        for (int u = 0; u < 8; ++u) sum[q] += part[q][u];
+                        for (int u = 0; u < kRedU; ++u) sum[q] += part[q][u];
                     }
             }
         }
@@ -471,8 +478,11 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
         if (more && lane == 0) {
 #pragma unroll
             for (int q = 0; q < kCellsPerThread; ++q) lds.nzlog[l][tid >> 6][q] = nzb[q];
-            if (nzb[0] | nzb[1] | nzb[2]) {
-                const unsigned long long chans = fold_channels(nzb[0] | nzb[1] | nzb[2], m.cp);
+            unsigned long long any_nz = 0;
+#pragma unroll
+            for (int q = 0; q < kCellsPerThread; ++q) any_nz |= nzb[q];
+            if (any_nz) {
+                const unsigned long long chans = fold_channels(any_nz, m.cp);
                 if ((uint32_t)chans) atomicOr(&lds.chmask[cur_buf ^ 1][0], (uint32_t)chans);
                 if ((uint32_t)(chans >> 32)) atomicOr(&lds.chmask[cur_buf ^ 1][1], (uint32_t)(chans >> 32));
             }
@@ -505,7 +515,6 @@ __global__ void __launch_bounds__(kCasThreads) k_cascade1d(const CascadeArgs ka,
     }
 }
 
-static_assert(kCellsPerThread == 3, "the event ballots above are written for three cells per lane");
 
 bool cascade1d_eligible(int prec, const Geom *g, int n_layers, const int *rows_cap, int max_seg_rows)
 {
@@ -526,11 +535,20 @@ hipError_t launch_cascade1d(const CascadeArgs &a, const StreamSel &sel, const La
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Lds));
     if (prepared != hipSuccess) return prepared;
     CascadeArgs b = a;
-    for (int k = 0; k < b.n_stages; ++k) b.first[k] = b.sched[b.stage_lo[k]];
-    const bool spread = 8 % b.n_stages == 0 && sel.n % (8 / b.n_stages) == 0;
-    b.per = spread ? 8 / b.n_stages : sel.n;
+    // The stages are dealt to the eight XCDs when their number divides eight; a number that does
+    // not is filled up with empty stages (their workgroups return at once).
+    int grid_stages = b.n_stages;
+    for (int d = 1; d <= 8 && d <= kCasMaxStages; d *= 2)
+        if (d >= b.n_stages) { grid_stages = d; break; }
+    const bool spread = 8 % grid_stages == 0 && sel.n % (8 / grid_stages) == 0;
+    if (!spread) grid_stages = b.n_stages;
+    for (int k = 0; k < grid_stages; ++k) {
+        if (k < b.n_stages) b.first[k] = b.sched[b.stage_lo[k]];
+        else b.first[k] = CascadeLayer{};                   // cnt 0
+    }
+    b.per = spread ? 8 / grid_stages : sel.n;
     if (sel.n / b.per > 65535) return hipErrorInvalidValue;
-    return launch(k_cascade1d, dim3(b.per, b.n_stages, sel.n / b.per), dim3(kCasThreads), sizeof(Lds), lc, b, sel);
+    return launch(k_cascade1d, dim3(b.per, grid_stages, sel.n / b.per), dim3(kCasThreads), sizeof(Lds), lc, b, sel);
 }
 
 }  // namespace idf
