@@ -109,3 +109,42 @@ def test_single_stream_one_sample_per_push_with_bias():
     wl = wl_mod.make(1, length=300)
     outs, _ = _run(wl, 1, reads_at={0, 1, 2, 3, 10, 11})
     check_stream(wl, outs[0], 0)
+
+
+def _deep_1d(streams, length, seed=77):
+    """Eight conv1d layers (kernel 3, valid, one of them stride 2, biases on two): as many stages
+    as the kernel's descriptor table holds."""
+    rng = np.random.default_rng(seed)
+    x = rng.normal(0.0, 1.0, size=(streams, length, 1, 1)).astype(np.float32)
+    x[rng.random(x.shape) < 0.5] = 0.0
+    chans = (1, 8, 8, 16, 16, 16, 32, 32, 32)
+    layers = [wl_mod.conv(chans[i], chans[i + 1], 3, 1, s=(2 if i == 2 else 1)) for i in range(8)]
+    weights = wl_mod._normal_weights(rng, layers, 2.0)
+    biases = [None] * 8
+    for i in (0, 5):
+        biases[i] = rng.normal(0.0, 0.1, size=chans[i + 1]).astype(np.float32)
+    return wl_mod._finish("deep_1d_k3", "f32", length, 1, 1, layers, weights, biases, x, 4)
+
+
+def test_eight_layers_in_eight_stages():
+    wl = _deep_1d(4, 200)
+    a, sa = _run(wl, 4, reads_at={0, 5, 6, 30})
+    b, sb = _run(wl, 4, reads_at={5}, stages=1)
+    for i in range(4):
+        check_stream(wl, a[i], i)
+        assert np.array_equal(a[i], b[i])
+        assert sa[i]["events_in"].tolist() == sb[i]["events_in"].tolist()
+        assert sa[i]["macs"].tolist() == sb[i]["macs"].tolist()
+
+
+@pytest.mark.parametrize("streams", [130, 131])
+def test_more_streams_than_a_stage_per_layer_allows(streams):
+    # 2 x 256 workgroups fit at once: three stages for 130 streams (filled up to four for the XCD
+    # mapping when the stream count is even, not when it is odd)
+    wl = wl_mod.make(2, streams=streams, length=160, channels=(8, 8, 16, 16, 16, 16))
+    a, _ = _run(wl, 16, reads_at={2})
+    b, _ = _run(wl, 16, reads_at=set(), stages=1)
+    for i in (0, 1, 64, streams - 2, streams - 1):
+        check_stream(wl, a[i], i)
+    for i in range(streams):
+        assert np.array_equal(a[i], b[i])
