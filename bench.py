@@ -197,7 +197,15 @@ def run_workload(config, steps_arg=None, warmup_arg=None, eager=False):
             s = st.get_stats(b)
             ev += s["events_in"]; mc += s["macs"]
         return ev, mc
+
+    def issued_total():
+        if eager:
+            return None
+        return float(sum(float(st.get_issued_macs(b).sum()) for b in range(B)))
     ev0, mc0 = macs_total()
+    if not eager:
+        st.count_issued_macs(True)          # an atomic per wave: only in this extra step, not in the timed ones
+    is0 = issued_total()
     st.profile_begin()
     step()
     by_layer = st.profile_end()
@@ -208,6 +216,10 @@ def run_workload(config, steps_arg=None, warmup_arg=None, eager=False):
         f["launches"] += p["launches"]; f["total_ms"] += p["total_ms"]; f["algorithmic_bytes"] += p["algorithmic_bytes"]
     prof = list(prof.values())
     ev1, mc1 = macs_total()
+    is1 = issued_total()
+    if not eager:
+        st.count_issued_macs(False)
+    macs_issued = None if is0 is None else is1 - is0     # zeros inside visited fragments / channels included
     macs_exec_layer = mc1 - mc0
     macs_exec = float(macs_exec_layer.sum())
     macs_dense = float(workloads.dense_equivalent_macs(wl)) * B
@@ -243,7 +255,9 @@ def run_workload(config, steps_arg=None, warmup_arg=None, eager=False):
                    "layers": len(wl["layers"]), "state_bytes_per_stream": int(st.sizes.state_bytes_per_stream)},
         "gmacs_dense_equivalent": macs_dense / (dt / steps) / 1e9,
         "gmacs_executed": macs_exec / (dt / steps) / 1e9,
+        "gmacs_issued": None if macs_issued is None else macs_issued / (dt / steps) / 1e9,
         "executed_over_dense": macs_exec / macs_dense,
+        "issued_over_dense": None if macs_issued is None else macs_issued / macs_dense,
         "kernels": {p["name"]: {"launches": p["launches"], "total_ms": p["total_ms"]} for p in prof},
         "kernels_by_layer": {p["name"]: {"launches": p["launches"], "avg_us": p["total_ms"] * 1e3 / p["launches"],
                                          "alg_GBps": p["algorithmic_bytes"] / (p["total_ms"] * 1e-3) / 1e9}
@@ -292,7 +306,7 @@ def main():
             o, _ = run_workload(c, None, 1)
             res["other_workloads"][o["config"]["workload"]] = {
                 k: o[k] for k in ("value", "unit", "ms_per_step", "steps", "dtype", "gmacs_dense_equivalent",
-                                  "gmacs_executed", "roofline")}
+                                  "gmacs_executed", "gmacs_issued", "roofline")}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(res))

@@ -174,6 +174,20 @@ int idf_reset_streams(idf_streams *s, const int32_t *stream_ids, int n_ids);
 int idf_get_stats(idf_streams *s, int stream_id, uint64_t *events_in, uint64_t *macs_executed,
                   uint64_t *state_bytes);
 
+/* Multiply-adds the kernels issued for one stream, per layer (host array of n_layers): what the
+ * compaction of events (Sec. 1: zero values cause no arithmetic) leaves over.  Counted only while
+ * switched on with idf_count_issued_macs(s, 1) (off after open: the count costs an atomic per
+ * wave), since open/reset.
+ * The matrix-core kernel skips K-steps whose 32-position fragment holds no event and multiplies
+ * the zeros inside the others (a first layer of 1-4 input channels has one or two K-steps and
+ * visits them always); the 1-D cascade skips input channels without an event in the
+ * segment and computes all rows of the others; layers served by the generic kernels, which test
+ * every value, report their executed count.  Counted from open/reset on it is always >=
+ * macs_executed of idf_get_stats.  IDF_EUNSUPPORTED under eager emission.  idf_get_issued_macs
+ * synchronises the stream. */
+int idf_count_issued_macs(idf_streams *s, int on);
+int idf_get_issued_macs(idf_streams *s, int stream_id, uint64_t *macs_issued);
+
 /* Rows of the current sample a stream has been given so far (host bookkeeping, no device work). */
 int idf_rows_pushed(const idf_streams *s, int stream_id, int64_t *rows);
 

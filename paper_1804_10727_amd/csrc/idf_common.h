@@ -162,7 +162,7 @@ struct CascadeLayer {
     void *ring;              // this launch's first stream is at ring + stream * ring_stride floats
     int64_t ring_stride;
     int rcp_k;               // ceil(65536 / k_h): (v * rcp_k) >> 16 == v / k_h for the small v that occur
-    int pad_;
+    int fma_per_channel;     // multiply-adds a lane issues for one input channel that holds an event (all rows, all taps)
     unsigned char taps[kCasRowsMax];   // per new row: kernel taps landing inside the output
 };
 
@@ -187,6 +187,7 @@ struct CascadeArgs {
     void *out;                           // output area [stream][out_cap][c_out]
     int64_t out_stride, out_cap, out_slot0;
     unsigned long long *stats;
+    unsigned long long *issued;          // [stream][layer]: multiply-adds issued (all rows of every channel that holds an event)
 };
 
 // One arriving row of a 3x3 / stride 1 / same-padded conv layer on the matrix cores.
@@ -228,6 +229,7 @@ struct MfmaStep {
     const void *wfrag;                 // fragment-ordered weights
     const void *bias;
     unsigned long long *stats;
+    unsigned long long *issued;        // [stream][layer]: multiply-adds issued by the matrix instructions (zeros inside live steps included)
 };
 
 // Steps of several layers for one launch of the matrix-core kernel.

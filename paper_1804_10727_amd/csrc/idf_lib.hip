@@ -86,7 +86,8 @@ struct idf_streams {
     std::vector<int> mfma;           // per layer: 1 = matrix-core conv kernel, 2 = pool fused into the conv before it
     std::vector<int64_t> ring_stride, held_stride, transit_stride;   // elements per stream
     std::vector<int> transit_cap;                                    // rows per stream
-    size_t out_off = 0, stats_off = 0, head_off = 0;
+    size_t out_off = 0, stats_off = 0, issued_off = 0, head_off = 0;
+    bool count_issued = false;       // the kernels add up what they issue (an atomic per wave: switched on for measurements)
     bool head_on = false;
     int head_units = 0;              // fully connected output units (0: only the averaging units)
     char *head_units_ws = nullptr;   // caller's buffer: weights [unit][map], bias [unit], values [stream][unit]
@@ -166,7 +167,7 @@ struct Layout {
     std::vector<size_t> w_off, b_off, wm_off, ring_off, held_off, transit_off;
     std::vector<int64_t> ring_stride, held_stride, transit_stride;
     std::vector<int> transit_cap;
-    size_t out_off = 0, stats_off = 0, head_off = 0, total = 0;
+    size_t out_off = 0, stats_off = 0, issued_off = 0, head_off = 0, total = 0;
     int64_t out_stride = 0;
     bool cascade1d = false;          // the whole-net 1-D kernel serves this stream set
     size_t cas_transit_off = 0;      // hand-over rows between the cascade's stages
@@ -251,6 +252,7 @@ int make_layout(const idf_net &net, int B, int max_seg, int64_t out_cap, Layout 
     L.out_stride = out_cap * net.out_w * net.out_c;
     L.out_off = off; off = align_up(off + (size_t)L.out_stride * 4 * B);
     L.stats_off = off; off = align_up(off + (size_t)B * n * 2 * sizeof(unsigned long long));
+    L.issued_off = off; off = align_up(off + (size_t)B * n * sizeof(unsigned long long));
     L.head_off = off; off = align_up(off + (size_t)B * net.out_c * 2 * sizeof(double));   // sums, means
     if (L.cascade1d) {
         L.cas_transit_off = off;
@@ -419,6 +421,15 @@ int cascade_schedule(idf_streams *s, int n_rows, int64_t r, int n_streams, idf_s
             L.rho = (int)(y0p % g.s_h);
             const int64_t o_base = y0p / g.s_h + cascade1d_slot_off(g.s_h, L.rho);
             L.cnt = (int)cnt;
+            {   // what a lane issues per channel that holds an event: the kernel's variant for 4, 8 or 16
+                // new rows computes all of them, all nine tap positions that land on an output row
+                const int nin = cnt <= 4 ? 4 : cnt <= 8 ? 8 : 16;
+                int f = 0;
+                for (int j = 0; j < nin; ++j)
+                    for (int ky = 0; ky < kCasKMax; ++ky)
+                        if ((L.rho + j - ky) % g.s_h == 0) ++f;
+                L.fma_per_channel = f;
+            }
             L.t_lo = (int)(c.o_lo - o_base); L.t_fin = (int)(c.o_fin - o_base); L.t_hi = (int)(c.o_hi - o_base);
             L.slot0 = (int)(((o_base % g.k_h) + g.k_h) % g.k_h);
             L.d0 = (int)(o_base * g.s_h - g.p_h - y0);
@@ -468,6 +479,7 @@ int cascade_launch(idf_streams *s, const StreamSel &sel, const void *dev_rows, i
     a.out = s->ws + s->out_off; a.out_stride = s->out_stride; a.out_cap = s->out_cap;
     a.out_slot0 = last_stage ? last_stage->out_slot0 : 0;
     a.stats = (unsigned long long *)(s->ws + s->stats_off);
+    a.issued = s->count_issued ? (unsigned long long *)(s->ws + s->issued_off) : nullptr;
     hipError_t e = launch_cascade1d(a, sel, launch_ctx(s, kKindCascade1d, bytes));
     if (e != hipSuccess) return dev_fail(e, "cascade launch");
     if (staged) {
@@ -576,6 +588,7 @@ void make_mfma_step(idf_streams *s, int l, int64_t y, int n_streams, MfmaStep &a
     a.wfrag = s->ws + s->wm_off[l];
     a.bias = net.b_img[l].empty() ? nullptr : s->ws + s->b_off[l];
     a.stats = (unsigned long long *)(s->ws + s->stats_off);
+    a.issued = s->count_issued ? (unsigned long long *)(s->ws + s->issued_off) : nullptr;
     ConvStep c{};
     c.g = g; c.y0 = y; c.cnt = 1; c.o_lo = rows_final(g, y); c.o_fin = fin_after;
     c.o_hi = std::max(rows_touched(g, y + 1), c.o_fin);
@@ -793,6 +806,7 @@ template <class F> void for_each_state_piece(const idf_streams *s, int id, F &&f
         else f(s->held_off[l] + (size_t)id * s->held_stride[l] * eb, (size_t)s->held_stride[l] * eb);
     }
     f(s->stats_off + (size_t)id * n * 2 * sizeof(unsigned long long), (size_t)n * 2 * sizeof(unsigned long long));
+    f(s->issued_off + (size_t)id * n * sizeof(unsigned long long), (size_t)n * sizeof(unsigned long long));
     f(s->head_off + (size_t)id * net.out_c * sizeof(double), (size_t)net.out_c * sizeof(double));
 }
 // Layout of the eager-emission workspace for B streams; returns its size.
@@ -1084,7 +1098,7 @@ int idf_open_streams(idf_net *net, int n_streams, int max_seg_rows, int64_t out_
     s->w_off = L.w_off; s->b_off = L.b_off; s->wm_off = L.wm_off; s->ring_off = L.ring_off; s->held_off = L.held_off;
     s->transit_off = L.transit_off; s->ring_stride = L.ring_stride; s->held_stride = L.held_stride;
     s->transit_stride = L.transit_stride; s->transit_cap = L.transit_cap;
-    s->out_off = L.out_off; s->stats_off = L.stats_off; s->out_stride = L.out_stride; s->sizes = L.sizes;
+    s->out_off = L.out_off; s->stats_off = L.stats_off; s->issued_off = L.issued_off; s->out_stride = L.out_stride; s->sizes = L.sizes;
     s->use_cascade1d = L.cascade1d;
     s->head_off = L.head_off;
     s->cas_transit_off = L.cas_transit_off;
@@ -1322,6 +1336,7 @@ int idf_reset_streams(idf_streams *s, const int32_t *stream_ids, int n_ids)
     for (int i = 0; i < n_ids; ++i) {
         const int id = stream_ids ? stream_ids[i] : i;
         hipError_t e = hipMemsetAsync(s->ws + s->stats_off + per * id, 0, per, s->st);
+        if (e == hipSuccess) e = hipMemsetAsync(s->ws + s->issued_off + per / 2 * id, 0, per / 2, s->st);
         if (e == hipSuccess)
             e = hipMemsetAsync(s->ws + s->head_off + (size_t)id * s->net->out_c * sizeof(double), 0,
                                (size_t)s->net->out_c * sizeof(double), s->st);
@@ -1349,6 +1364,41 @@ int idf_get_stats(idf_streams *s, int stream_id, uint64_t *events_in, uint64_t *
         if (macs_executed) macs_executed[l] = buf[2 * l + 1];
         if (state_bytes)
             state_bytes[l] = s->net->g[l].kind == IDF_CONV ? (uint64_t)s->ring_stride[l] * 4 : (uint64_t)s->held_stride[l] * eb;
+    }
+    return IDF_OK;
+}
+
+int idf_count_issued_macs(idf_streams *s, int on)
+{
+    if (!s) return fail(IDF_EINVAL, "null argument");
+    if (s->eager.on) return fail(IDF_EUNSUPPORTED, "eager emission keeps no count of issued multiply-adds");
+    int rc = pipeline_drain(s);                 // what is on its way was pushed under the old setting
+    if (rc != IDF_OK) return rc;
+    s->count_issued = on != 0;
+    return IDF_OK;
+}
+
+int idf_get_issued_macs(idf_streams *s, int stream_id, uint64_t *macs_issued)
+{
+    if (!s || !macs_issued) return fail(IDF_EINVAL, "null argument");
+    if (stream_id < 0 || stream_id >= s->B) return fail(IDF_EINVAL, "stream id %d outside [0, %d)", stream_id, s->B);
+    if (s->eager.on) return fail(IDF_EUNSUPPORTED, "eager emission keeps no count of issued multiply-adds");
+    const int n = (int)s->net->g.size();
+    std::vector<unsigned long long> iss((size_t)n), st((size_t)n * 2);
+    if (int rc = pipeline_drain(s)) return rc;
+    hipError_t e = hipStreamSynchronize(s->st);
+    if (e == hipSuccess)
+        e = hipMemcpy(iss.data(), s->ws + s->issued_off + (size_t)stream_id * n * sizeof(unsigned long long),
+                      iss.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost);
+    if (e == hipSuccess)
+        e = hipMemcpy(st.data(), s->ws + s->stats_off + (size_t)stream_id * n * 2 * sizeof(unsigned long long),
+                      st.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return dev_fail(e, "get_issued_macs");
+    // the generic kernels test every value and keep no count of their own: they issue what they execute
+    const bool own_count = s->use_cascade1d || !s->mfma.empty();
+    for (int l = 0; l < n; ++l) {
+        const bool counted = s->use_cascade1d || (own_count && l < (int)s->mfma.size() && s->mfma[l] == 1);
+        macs_issued[l] = counted ? iss[l] : st[2 * l + 1];
     }
     return IDF_OK;
 }

@@ -223,6 +223,7 @@ size_t cascade1d_weight_index(int c_in, int c_out, int ci, int co, int ky)
 
 int cascade1d_slot_off(int S, int rho) { return ceil_div_c(rho - kKMax + 1, S); }
 
+template <bool COUNT>
 __global__ void __launch_bounds__(kCasThreads, 2) k_cascade1d(const CascadeArgs ka, const StreamSel sel)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
@@ -387,6 +388,10 @@ __global__ void __launch_bounds__(kCasThreads, 2) k_cascade1d(const CascadeArgs 
         // the other buffer is free (its readers are past the previous layer's first barrier):
         // clear it for the rows this layer emits
         for (int i = tid; i < 64 * kXStride / 4; i += kT) reinterpret_cast<float4 *>(xn)[i] = float4{0.f, 0.f, 0.f, 0.f};
+        if (COUNT && ka.issued && tid == 0) {
+            const int n_ev = __popc(lds.chmask[cur_buf][0]) + __popc(lds.chmask[cur_buf][1]);
+            if (n_ev) atomicAdd(ka.issued + (int64_t)stream * n_layers + l, (unsigned long long)n_ev * uni(sl.fma_per_channel) * c_out);
+        }
         if (tid < 2) lds.chmask[cur_buf ^ 1][tid] = 0;
 
         if (S == 1) accumulate_rows<1, 0>(x, cnt, m, n_qp, wc, nxt0, wq, visit, lds.red);
@@ -531,8 +536,14 @@ bool cascade1d_eligible(int prec, const Geom *g, int n_layers, const int *rows_c
 hipError_t launch_cascade1d(const CascadeArgs &a, const StreamSel &sel, const LaunchCtx &lc)
 {
     // more LDS than the default per-workgroup limit: raise it once
-    static hipError_t prepared = hipFuncSetAttribute(reinterpret_cast<const void *>(k_cascade1d),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Lds));
+    static hipError_t prepared = [] {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_cascade1d<false>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Lds));
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_cascade1d<true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Lds));
+        return e;
+    }();
     if (prepared != hipSuccess) return prepared;
     CascadeArgs b = a;
     // The stages are dealt to the eight XCDs when their number divides eight; a number that does
@@ -548,7 +559,9 @@ hipError_t launch_cascade1d(const CascadeArgs &a, const StreamSel &sel, const La
     }
     b.per = spread ? 8 / grid_stages : sel.n;
     if (sel.n / b.per > 65535) return hipErrorInvalidValue;
-    return launch(k_cascade1d, dim3(b.per, grid_stages, sel.n / b.per), dim3(kCasThreads), sizeof(Lds), lc, b, sel);
+    // the variant that adds up what it issues is a kernel of its own: the one that is timed carries none of it
+    if (b.issued) return launch(k_cascade1d<true>, dim3(b.per, grid_stages, sel.n / b.per), dim3(kCasThreads), sizeof(Lds), lc, b, sel);
+    return launch(k_cascade1d<false>, dim3(b.per, grid_stages, sel.n / b.per), dim3(kCasThreads), sizeof(Lds), lc, b, sel);
 }
 
 }  // namespace idf

@@ -143,7 +143,7 @@ template <class P> __device__ __forceinline__ P *at4(P *base, uint32_t byte_off)
 constexpr int kMaxPos = 128 + 2;                 // positions of the widest tile plus halo
 constexpr int kNzWords = (kMaxPos + 31) / 32 + 1;
 
-template <class T, int WM, int WN>
+template <class T, int WM, int WN, bool COUNT>
 __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &sel, const int bx, const int si)
 {
     using acc_t = typename T::acc_t; using st_t = typename T::st_t; using ev_t = typename T::ev_t;
@@ -352,6 +352,10 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
             }
         }
         live = __ballot(occ);
+        // what the matrix instructions of this wave will multiply, zeros inside a live step included
+        if (COUNT && a.issued && lane == 0 && live)
+            atomicAdd(a.issued + (int64_t)stream * a.n_layers + a.layer,
+                      (unsigned long long)__builtin_popcountll(live) * (3ull * 32 * 32 * KI));
     }
 
     // ---- contraction over the live K-steps ----------------------------------------------------
@@ -546,10 +550,10 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
     }
 }
 
-template <class T, int WM, int WN>
+template <class T, int WM, int WN, bool COUNT>
 __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a, const StreamSel sel)
 {
-    conv3x3_row<T, WM, WN>(a, sel, blockIdx.z, blockIdx.x);      // tile by tile, the streams of a tile side by side
+    conv3x3_row<T, WM, WN, COUNT>(a, sel, blockIdx.z, blockIdx.x);      // tile by tile, the streams of a tile side by side
 }
 
 // Several layers' steps in one launch (each on a row that was complete before the launch).  The grid
@@ -564,10 +568,10 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
 // streams close in time, and every step is spread evenly.  (Stream by stream with the tiles inside was
 // measured 8 % slower on the VGG-style workload; one contiguous eighth of the order per XCD slower
 // still: the steps differ too much in length.)
-template <class T, int WM, int WN>
+template <class T, int WM, int WN, bool COUNT>
 __global__ void __launch_bounds__(64 * WM * WN, T::kOcc) k_conv3x3_mfma_batch(const MfmaBatch b, const StreamSel sel)
 {
-    conv3x3_row<T, WM, WN>(b.st[blockIdx.z], sel, blockIdx.y, blockIdx.x);
+    conv3x3_row<T, WM, WN, COUNT>(b.st[blockIdx.z], sel, blockIdx.y, blockIdx.x);
 }
 
 template <class T, int WM, int WN>
@@ -583,7 +587,9 @@ hipError_t launch_batch_shape(const MfmaBatch &b, const StreamSel &sel, const La
         lds = std::max(lds, (size_t)MT * NC * T::EB);
     }
     if (b.n < 1 || tiles_max < 1 || tiles_max > 65535) return hipErrorInvalidValue;      // tiles are the grid's y extent
-    return launch(k_conv3x3_mfma_batch<T, WM, WN>, dim3(sel.n, tiles_max, b.n), dim3(64 * WM * WN), lds, lc, b, sel);
+    // the variant that adds up what it issues is a kernel of its own: the one that is timed carries none of it
+    if (b.st[0].issued) return launch(k_conv3x3_mfma_batch<T, WM, WN, true>, dim3(sel.n, tiles_max, b.n), dim3(64 * WM * WN), lds, lc, b, sel);
+    return launch(k_conv3x3_mfma_batch<T, WM, WN, false>, dim3(sel.n, tiles_max, b.n), dim3(64 * WM * WN), lds, lc, b, sel);
 }
 
 template <class T>
@@ -607,7 +613,8 @@ hipError_t launch_one(const MfmaStep &a, const StreamSel &sel, const LaunchCtx &
     const size_t stage = (size_t)MT * NC * T::EB;       // the epilogue reuses the space to stage emitted rows
     if (lds < stage) lds = stage;
     if (x_tiles * co_chunks > 65535) return hipErrorInvalidValue;      // tiles are the grid's z extent
-    return launch(k_conv3x3_mfma<T, WM, WN>, dim3(sel.n, 1, x_tiles * co_chunks), dim3(64 * WM * WN), lds, lc, a, sel);
+    if (a.issued) return launch(k_conv3x3_mfma<T, WM, WN, true>, dim3(sel.n, 1, x_tiles * co_chunks), dim3(64 * WM * WN), lds, lc, a, sel);
+    return launch(k_conv3x3_mfma<T, WM, WN, false>, dim3(sel.n, 1, x_tiles * co_chunks), dim3(64 * WM * WN), lds, lc, a, sel);
 }
 
 template <class T> hipError_t launch_prec(const MfmaStep &a, const StreamSel &sel, const LaunchCtx &lc)

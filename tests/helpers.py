@@ -35,7 +35,7 @@ def oracle_many(fn, wl, streams, threads=8, **kw):
         return list(ex.map(lambda b: fn(wl, b, **kw), streams))
 
 
-def gpu_run(wl, seg_rows=None, device="cuda:0", return_streams=False):
+def gpu_run(wl, seg_rows=None, device="cuda:0", return_streams=False, count_issued=False):
     """Whole sample of every stream through the GPU library, seg_rows rows per push."""
     import torch
     import paper_1804_10727_amd as idf
@@ -45,6 +45,8 @@ def gpu_run(wl, seg_rows=None, device="cuda:0", return_streams=False):
     st = idf.Streams(net, wl["streams"], max_seg_rows=seg, device=device)
     x = input_tensor(wl, device)
     H = wl["in_h"]
+    if count_issued:
+        st.count_issued_macs(True)
     for r in range(0, H, seg):
         st.push_segment(x[:, r:r + seg].contiguous())
     out, first, cnt = st.read_outputs(max_rows=int(st.sizes.out_h))
