@@ -203,9 +203,6 @@ def run_workload(config, steps_arg=None, warmup_arg=None, eager=False):
             return None
         return float(sum(float(st.get_issued_macs(b).sum()) for b in range(B)))
     ev0, mc0 = macs_total()
-    if not eager:
-        st.count_issued_macs(True)          # an atomic per wave: only in this extra step, not in the timed ones
-    is0 = issued_total()
     st.profile_begin()
     step()
     by_layer = st.profile_end()
@@ -216,10 +213,15 @@ def run_workload(config, steps_arg=None, warmup_arg=None, eager=False):
         f["launches"] += p["launches"]; f["total_ms"] += p["total_ms"]; f["algorithmic_bytes"] += p["algorithmic_bytes"]
     prof = list(prof.values())
     ev1, mc1 = macs_total()
-    is1 = issued_total()
+    macs_issued = None
     if not eager:
+        # one more step on the kernel variants that add up what they issue (an atomic per wave):
+        # neither the timed steps nor the bracketed one above run those
+        st.count_issued_macs(True)
+        is0 = issued_total()
+        step()
+        macs_issued = issued_total() - is0     # zeros inside visited fragments / channels included
         st.count_issued_macs(False)
-    macs_issued = None if is0 is None else is1 - is0     # zeros inside visited fragments / channels included
     macs_exec_layer = mc1 - mc0
     macs_exec = float(macs_exec_layer.sum())
     macs_dense = float(workloads.dense_equivalent_macs(wl)) * B
