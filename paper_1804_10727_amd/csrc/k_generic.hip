@@ -331,26 +331,38 @@ __global__ void __launch_bounds__(kGenThreads) k_copy_out(const CopyOut a, const
     const int stream = sel_stream(sel, si);
     const uint32_t *src = (const uint32_t *)a.src + (int64_t)stream * a.src_stream_stride;
     uint32_t *dst = (uint32_t *)a.dst + (int64_t)(sel.pos0 + si) * a.dst_stream_stride;
-    for (int r = blockIdx.y; r < n_rows; r += gridDim.y) {
-        int64_t slot = first_slot + r;
-        if (slot >= a.out_cap) slot -= a.out_cap;
-        const uint32_t *s_row = src + slot * a.row_elems;
-        uint32_t *d_row = dst + (int64_t)r * a.row_elems;
-        for (int64_t e = (int64_t)blockIdx.x * kGenThreads + threadIdx.x; e < a.row_elems;
-             e += (int64_t)gridDim.x * kGenThreads)
-            d_row[e] = s_row[e];
+    // The rows lie one after the other in both areas, except where the output ring wraps: at most
+    // two contiguous stretches, each copied flat, 16 bytes per lane where sizes and addresses allow
+    // it (the same for every lane).
+    const bool wide = a.row_elems % 4 == 0 && a.src_stream_stride % 4 == 0 && a.dst_stream_stride % 4 == 0 &&
+                      ((uintptr_t)a.src | (uintptr_t)a.dst) % 16 == 0;
+    const int64_t rows1 = n_rows < a.out_cap - first_slot ? n_rows : a.out_cap - first_slot;
+    const int64_t start = (int64_t)blockIdx.x * kGenThreads + threadIdx.x, step = (int64_t)gridDim.x * kGenThreads;
+    for (int part = 0; part < 2; ++part) {
+        const int64_t rows = part == 0 ? rows1 : n_rows - rows1;
+        if (rows <= 0) continue;
+        const uint32_t *sp = src + (part == 0 ? first_slot : 0) * a.row_elems;
+        uint32_t *dp = dst + (part == 0 ? 0 : rows1) * a.row_elems;
+        const int64_t n = rows * a.row_elems;
+        if (wide) {
+            const uint4 *s4 = reinterpret_cast<const uint4 *>(sp);
+            uint4 *d4 = reinterpret_cast<uint4 *>(dp);
+            for (int64_t e = start; e < n / 4; e += step) d4[e] = s4[e];
+        } else {
+            for (int64_t e = start; e < n; e += step) dp[e] = sp[e];
+        }
     }
 }
 
 hipError_t launch_copy_out(const CopyOut &a, const StreamSel &sel, int64_t first_slot, int n_rows,
                            const LaunchCtx &lc)
 {
-    int64_t blocks = (a.row_elems + kGenThreads - 1) / kGenThreads;
-    if (blocks > 64) blocks = 64;
+    if (first_slot < 0 || first_slot >= a.out_cap || n_rows > a.out_cap) return hipErrorInvalidValue;
+    const int64_t units = (int64_t)n_rows * a.row_elems / (a.row_elems % 4 == 0 ? 4 : 1);
+    int64_t blocks = (units + kGenThreads - 1) / kGenThreads;
+    if (blocks > 2048) blocks = 2048;
     if (blocks < 1) blocks = 1;
-    int rows = n_rows < 1024 ? n_rows : 1024;
-    return launch(k_copy_out, dim3((unsigned)blocks, (unsigned)rows, sel.n), dim3(kGenThreads), 0, lc, a, sel,
-                  first_slot, n_rows);
+    return launch(k_copy_out, dim3((unsigned)blocks, 1, sel.n), dim3(kGenThreads), 0, lc, a, sel, first_slot, n_rows);
 }
 
 // ---------------------------------------------------------------------------------------
