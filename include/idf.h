@@ -84,7 +84,17 @@ typedef struct {
     size_t state_bytes_per_stream;   /* of which, per stream: the retained state -- the rolling rows of
                                         c of every conv layer and the held row of every pool.  This is
                                         the footprint the paper bounds; it does not depend on in_h.  */
-    size_t transit_bytes_per_stream; /* per stream: rows in flight between layers during one push   */
+    size_t handover_bytes_per_stream;/* of which, per stream: rows a layer has completed that may wait, when a
+                                        call returns, for the next layer's step in a later call.  Only the
+                                        staged modes have such rows (the default for nets served by the
+                                        1-D cascade or throughout by the matrix-core kernel: layer l then
+                                        runs behind layer l-1 by one launch); 0 when the layers run strictly
+                                        depth-first within every call (environment IDF_CASCADE_STAGES=1,
+                                        IDF_NO_ROW_STAGES=1).  Independent of in_h as well.              */
+    size_t retained_bytes_per_stream;/* state_bytes_per_stream + handover_bytes_per_stream: everything of a
+                                        stream that survives from one call to the next                  */
+    size_t transit_bytes_per_stream; /* per stream: room for rows passed between layers (scratch during a
+                                        push; also where the hand-over rows above wait)                  */
     size_t output_bytes_per_stream;  /* per stream: completed rows waiting for idf_read_outputs      */
     int    out_w, out_c;             /* shape of one output row                                      */
     int64_t out_h;                   /* output rows per sample (0 if unbounded)                      */
@@ -94,8 +104,8 @@ typedef struct {
  *   weights[i] (host): for conv layer i an array [c_out][c_in][k_h][k_w] of float32 (F32),
  *                      bfloat16 bit patterns as uint16 (BF16) or int8 (I8); ignored for pools.
  *   biases  (host):    NULL, or per layer NULL / [c_out] float32 (F32, BF16) or int32 (I8).  A row
- *                      of c starts at the bias; the paper's "b = 0 without loss of generality" is
- *                      the special case NULL.
+ *                      of c starts at the bias; NULL is the bias-free case the paper restricts
+ *                      itself to in Sec. 3.
  * Everything is copied and repacked; the caller keeps ownership of its arrays.
  * IDF_EINVAL: inconsistent description (channel chain, kernel larger than its input, pool shape,
  *             padding on an unbounded stream, unknown enum).  IDF_EUNSUPPORTED: a valid network
@@ -110,8 +120,8 @@ int idf_destroy_net(idf_net *net);
 int idf_query_sizes(const idf_net *net, int n_streams, int max_seg_rows, int64_t out_cap_rows,
                     idf_sizes *out);
 
-/* Open n_streams streams, all at row 0 with zero state (Sec. 3: "initial state of the network
- * to be zero").  dev_workspace (device, 256-byte aligned, >= workspace_bytes) stays owned by
+/* Open n_streams streams, all at row 0 with zero state (Sec. 3 assumes the network starts
+ * from all-zero state).  dev_workspace (device, 256-byte aligned, >= workspace_bytes) stays owned by
  * the caller.  hip_stream: a hipStream_t (NULL = the default stream).  Enqueues the upload of
  * the packed weights. */
 int idf_open_streams(idf_net *net, int n_streams, int max_seg_rows, int64_t out_cap_rows,
@@ -120,8 +130,8 @@ int idf_open_streams(idf_net *net, int n_streams, int max_seg_rows, int64_t out_
 int idf_close_streams(idf_streams *s);
 
 /* Present the next n_rows rows to n_ids streams and push them depth-first through every layer
- * they can influence (Sec. 3 first paragraph; Sec. 5 "streaming core, taking inputs as they
- * arrive").
+ * they can influence (Sec. 3 first paragraph; Sec. 5, the method seen as a core that takes input
+ * as it arrives).
  *   stream_ids (host): n_ids distinct ids in [0, n_streams), or NULL for 0 .. n_ids-1.
  *   dev_rows (device): [n_ids][n_rows][in_w][in_c] in the input type; entry i belongs to
  *                      stream_ids[i].  It is read by the enqueued kernels: keep it unchanged
@@ -213,7 +223,10 @@ int idf_read_announced(idf_streams *s, int level, const int32_t *stream_ids, int
  * idf_enable_head: before the first push after open (IDF_ESTATE otherwise).
  * idf_read_head: mean (host) [n_ids][out_c], rows (host) [n_ids] = rows averaged.  Synchronises
  * the stream.  IDF_ESTATE if the head was not enabled. */
-/* The retained state of one stream -- the "hidden state" of the recurrent view of Sec. 5: rolling
+int idf_enable_head(idf_streams *s);
+int idf_read_head(idf_streams *s, const int32_t *stream_ids, int n_ids, double *mean, int64_t *rows);
+
+/* The retained state of one stream -- what the recurrent view of Sec. 5 would call the hidden state: rolling
  * buffers of c of every conv layer, held rows of the pools, the counters of idf_get_stats, the
  * averaging units, and where the stream stands -- copied to / from a caller-owned device buffer
  * of idf_snapshot_bytes() bytes.  A snapshot can be restored into any stream of the same set of
@@ -228,9 +241,6 @@ typedef struct {
 int idf_snapshot_bytes(const idf_streams *s, size_t *bytes);
 int idf_snapshot(idf_streams *s, int stream_id, void *dev_buf, idf_stream_pos *pos);
 int idf_restore(idf_streams *s, int stream_id, const void *dev_buf, const idf_stream_pos *pos);
-
-int idf_enable_head(idf_streams *s);
-int idf_read_head(idf_streams *s, const int32_t *stream_ids, int n_ids, double *mean, int64_t *rows);
 
 /* Fully connected output units over the last layer's map (Sec. 4: the class units whose values
  * settle as rows come in, Fig. 3 / Fig. 4): unit k holds bias[k] plus the sum, over the rows the

@@ -43,7 +43,8 @@ class KernelProfile(C.Structure):
 
 class Sizes(C.Structure):
     _fields_ = [("workspace_bytes", C.c_size_t), ("weights_bytes", C.c_size_t),
-                ("state_bytes_per_stream", C.c_size_t), ("transit_bytes_per_stream", C.c_size_t),
+                ("state_bytes_per_stream", C.c_size_t), ("handover_bytes_per_stream", C.c_size_t),
+                ("retained_bytes_per_stream", C.c_size_t), ("transit_bytes_per_stream", C.c_size_t),
                 ("output_bytes_per_stream", C.c_size_t), ("out_w", C.c_int), ("out_c", C.c_int),
                 ("out_h", C.c_int64)]
 

@@ -102,6 +102,7 @@ struct idf_streams {
     CasPush cas_hist[kCasMaxStages - 1];
     int cas_parity = 0;
     size_t cas_transit_off = 0;
+    int64_t cas_transit_stride = 0;
     // 2-D nets served by the matrix-core kernel throughout: one launch per arriving row holds a
     // step of every conv layer, each on a row that was complete before the launch.  Per conv
     // layer ("unit") the rows waiting for it, and where in the ring of hand-over rows they lie.
@@ -171,10 +172,22 @@ struct Layout {
     int64_t out_stride = 0;
     bool cascade1d = false;          // the whole-net 1-D kernel serves this stream set
     size_t cas_transit_off = 0;      // hand-over rows between the cascade's stages
+    int64_t cas_transit_stride = 0;  // floats per stream in one hand-over buffer
+    int cas_boundaries = 0;          // stage boundaries the block has room for
     idf_sizes sizes{};
 };
 
-constexpr int kStgSlots = 8;         // hand-over rows kept per layer and stream when layers are staged
+// Staged layers (one launch per arriving row, layer l a launch behind layer l-1): rows a layer has
+// completed wait for the next layer's step in a small ring per layer and stream.  The host never
+// leaves more than kStgWait rows waiting per layer when a call returns; a launch reads one slot,
+// leaves at most kStgWait - 1 waiting and writes at most two new rows, hence kStgSlots.
+constexpr int kStgWait = 2;
+constexpr int kStgSlots = 4;
+
+// The layers run strictly depth-first within each call (nothing waits between layers across
+// calls) when the staged modes are switched off.
+bool strict_rows() { return getenv("IDF_NO_MFMA") || getenv("IDF_NO_ROW_STAGES"); }
+bool strict_cascade() { const char *e = getenv("IDF_CASCADE_STAGES"); return e && atoi(e) <= 1; }
 
 // Every conv layer can run on the matrix-core kernel and every pool is fused behind one.
 bool net_all_mfma(const idf_net &net)
@@ -220,7 +233,8 @@ int make_layout(const idf_net &net, int B, int max_seg, int64_t out_cap, Layout 
         L.wm_off[l] = off; off = align_up(off + net.wm_img[l].size());
     }
     L.sizes.weights_bytes = off;
-    size_t state_per_stream = 0, transit_per_stream = 0;
+    size_t state_per_stream = 0, transit_per_stream = 0, handover_per_stream = 0;
+    const bool staged_rows = all_mfma && !strict_rows();
     int cap = max_seg;
     for (int l = 0; l < n; ++l) {
         const Geom &g = net.g[l];
@@ -234,12 +248,16 @@ int make_layout(const idf_net &net, int B, int max_seg, int64_t out_cap, Layout 
             state_per_stream += (size_t)L.held_stride[l] * eb;
         }
         cap = L.transit_cap[l];
-        if (l < n - 1) {
+        // (the 1-D cascade passes rows on inside LDS; a conv layer's rows go straight into a fused pool)
+        const bool into_fused_pool = all_mfma && !getenv("IDF_NO_MFMA") && l + 1 < n && net.g[l + 1].kind == IDF_MAXPOOL;
+        if (l < n - 1 && !L.cascade1d && !into_fused_pool) {
             // room for the hand-over ring when the layers are staged across pushes
             const int rows = all_mfma ? std::max(cap, kStgSlots) : cap;
             L.transit_stride[l] = (int64_t)rows * g.w_out * g.c_out;
             L.transit_off[l] = off; off = align_up(off + (size_t)L.transit_stride[l] * eb * B);
             transit_per_stream += (size_t)L.transit_stride[l] * eb;
+            // rows that can wait for the next conv layer when a call returns
+            if (staged_rows) handover_per_stream += (size_t)kStgWait * g.w_out * g.c_out * eb;
         }
     }
     if (out_cap <= 0) {
@@ -255,12 +273,25 @@ int make_layout(const idf_net &net, int B, int max_seg, int64_t out_cap, Layout 
     L.issued_off = off; off = align_up(off + (size_t)B * n * sizeof(unsigned long long));
     L.head_off = off; off = align_up(off + (size_t)B * net.out_c * 2 * sizeof(double));   // sums, means
     if (L.cascade1d) {
+        // Rows passed from one stage to the next, double-buffered by launch parity: room for a
+        // boundary behind every layer but the last, each as large as the largest hand-over.
+        int64_t most = 0;
+        for (int l = 0; l < n - 1; ++l) {
+            most = std::max<int64_t>(most, (int64_t)L.transit_cap[l] * net.g[l].c_out);
+            // what is alive between two pushes if every layer is a stage of its own
+            if (!strict_cascade()) handover_per_stream += (size_t)L.transit_cap[l] * net.g[l].c_out * 4;
+        }
+        L.cas_boundaries = std::min(kCasMaxStages, n) - 1;
+        L.cas_transit_stride = (most + 63) / 64 * 64;
         L.cas_transit_off = off;
-        off = align_up(off + (size_t)(kCasMaxStages - 1) * 2 * B * kCasRowsMax * 64 * 4);
+        off = align_up(off + (size_t)L.cas_boundaries * 2 * B * L.cas_transit_stride * 4);
+        transit_per_stream = (size_t)L.cas_boundaries * 2 * L.cas_transit_stride * 4;
     }
     L.total = off;
     L.sizes.workspace_bytes = off;
     L.sizes.state_bytes_per_stream = state_per_stream;
+    L.sizes.handover_bytes_per_stream = handover_per_stream;
+    L.sizes.retained_bytes_per_stream = state_per_stream + handover_per_stream;
     L.sizes.transit_bytes_per_stream = transit_per_stream;
     L.sizes.output_bytes_per_stream = (size_t)L.out_stride * 4;
     L.sizes.out_w = net.out_w; L.sizes.out_c = net.out_c; L.sizes.out_h = net.out_h;
@@ -364,6 +395,7 @@ void plan_cascade_stages(idf_streams *s)
         cus = 0;
     int max_stages = std::min({kCasMaxStages, n, std::max(1, 2 * cus / std::max(1, s->B))});      // two workgroups fit a CU
     if (const char *e = getenv("IDF_CASCADE_STAGES")) max_stages = std::max(1, std::min(max_stages, atoi(e)));
+    if (strict_cascade()) max_stages = 1;
     std::vector<double> cost(n);
     for (int l = 0; l < n; ++l) cost[l] = 2.5 + 0.2 * cascade1d_steps(net.g[l].c_in, net.g[l].c_out);
     const double fixed = 4.0;
@@ -474,7 +506,7 @@ int cascade_launch(idf_streams *s, const StreamSel &sel, const void *dev_rows, i
     }
     a.in = dev_rows; a.in_stream_stride = (int64_t)n_rows * s->net->in_c;
     a.transit = s->ws + s->cas_transit_off;
-    a.transit_stream_stride = (int64_t)kCasRowsMax * 64;
+    a.transit_stream_stride = s->cas_transit_stride;
     a.transit_buf_stride = a.transit_stream_stride * s->B;
     a.out = s->ws + s->out_off; a.out_stride = s->out_stride; a.out_cap = s->out_cap;
     a.out_slot0 = last_stage ? last_stage->out_slot0 : 0;
@@ -686,8 +718,8 @@ int enqueue_cascade(idf_streams *s, const StreamSel &sel, const void *dev_rows, 
             if (!stg_pending(s, 0)) s->stg_out_next = out_slot0;
             for (int j = 0; j < n_rows; ++j) {
                 int rc = stg_tick(s, dev_rows, n_rows, j, r);
-                // the hand-over rings hold kStgSlots rows: never let more than three wait
-                while (rc == IDF_OK && stg_pending(s, 3)) rc = stg_tick(s, nullptr, 0, -1, 0);
+                // the hand-over rings hold kStgSlots rows: never let more than kStgWait wait
+                while (rc == IDF_OK && stg_pending(s, kStgWait)) rc = stg_tick(s, nullptr, 0, -1, 0);
                 if (rc != IDF_OK) return rc;
             }
             return IDF_OK;
@@ -1102,6 +1134,7 @@ int idf_open_streams(idf_net *net, int n_streams, int max_seg_rows, int64_t out_
     s->use_cascade1d = L.cascade1d;
     s->head_off = L.head_off;
     s->cas_transit_off = L.cas_transit_off;
+    s->cas_transit_stride = L.cas_transit_stride;
     if (L.cascade1d) plan_cascade_stages(s);
     s->mfma.assign(net->g.size(), 0);
     if (!getenv("IDF_NO_MFMA")) {
@@ -1111,7 +1144,7 @@ int idf_open_streams(idf_net *net, int n_streams, int max_seg_rows, int64_t out_
             if (l + 1 < net->g.size() && net->g[l + 1].kind == IDF_MAXPOOL && net->g[l + 1].k_w == 2) s->mfma[l + 1] = 2;
         }
     }
-    s->stg2d = !getenv("IDF_NO_MFMA") && !getenv("IDF_NO_ROW_STAGES") && net_all_mfma(*net);
+    s->stg2d = !strict_rows() && net_all_mfma(*net);
     if (s->stg2d) {
         for (size_t l = 0; l < net->g.size(); ++l)
             if (net->g[l].kind == IDF_CONV) s->stg_unit.push_back((int)l);

@@ -7,7 +7,7 @@
 //   w * dh for every non-zero dh in its kernel footprint among the new rows (Sec. 3, the
 //   event-delivery rule; zero values are skipped, Sec. 1), and then either goes back to the
 //   ring or -- when no future row can reach it -- is activated and emitted (Sec. 3, stateful
-//   neuron and event definition; Fig. 2 "fully processed and can be forgotten").
+//   neuron and event definition; Fig. 2: a finished region is dropped).
 //
 // Ownership instead of scatter: two events never race for one cell, so float results are
 // reproducible run to run.

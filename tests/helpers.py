@@ -1,4 +1,5 @@
 """Shared by the tests: run a workload through the GPU library / through the CPU oracle."""
+import os
 from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
@@ -19,6 +20,22 @@ def rel_err(g, o):
     return float(np.max(np.abs(g.astype(np.float64) - o)) / max(float(np.max(np.abs(o))), 1e-30))
 
 
+# Element by element: |g - o| <= atol + rtol * |o|, with atol a small fraction of the stream's
+# largest output.  A sum of n products accumulated in float32 is off by up to about
+# n * 2^-24 * sum|terms| whatever its own size, so an output near zero (cancellation, or a ReLU
+# about to cut) cannot be held to a purely relative bound: atol covers that floor, five times
+# below the normalised tolerance for float32 and for bfloat16 events, rtol is the tolerance itself.
+ELEM = {"f32": (2e-5, 1e-4), "bf16_emul": (2e-3, 1e-2), "bf16_true": (4e-3, 2e-2)}
+
+
+def elem_excess(g, o, kind):
+    """Largest |g - o| / (atol + rtol |o|) over one stream's output: <= 1 passes."""
+    a, r = ELEM[kind]
+    o = np.asarray(o, dtype=np.float64)
+    bound = a * max(float(np.max(np.abs(o))), 1e-30) + r * np.abs(o)
+    return float(np.max(np.abs(g.astype(np.float64) - o) / bound))
+
+
 def oracle_dense(wl, b, emit_round=None, return_layers=False):
     return oracle.dense(wl["layers"], wl["x"][b], wl["weights"], wl["biases"],
                         integer=wl["precision"] == "i8", emit_round=emit_round, return_layers=return_layers)
@@ -30,7 +47,8 @@ def oracle_stream(wl, b, seg_rows=None, emit_round=None):
                              emit_round=emit_round)
 
 
-def oracle_many(fn, wl, streams, threads=8, **kw):
+def oracle_many(fn, wl, streams, threads=None, **kw):
+    threads = threads or max(1, min(16, os.cpu_count() or 1))
     with ThreadPoolExecutor(max_workers=threads) as ex:
         return list(ex.map(lambda b: fn(wl, b, **kw), streams))
 

@@ -82,6 +82,52 @@ def test_state_footprint_within_bound_and_independent_of_height(cfg, kw):
         net2.destroy()
 
 
+# rows a layer has completed that may wait for the next layer's step when a call returns, in the
+# staged modes: two rows behind every conv layer (or the pool fused behind it) but the last where
+# the matrix-core kernel serves the whole net; in the 1-D cascade, behind every layer but the
+# last, the rows one push can complete, as float32
+def handover_bytes(wl, staged_2d):
+    eb = {"f32": 4, "bf16": 2, "i8": 1}[wl["precision"]]
+    h, w = wl["in_h"], wl["in_w"]
+    rows = wl["seg_rows"]
+    total = 0
+    n = len(wl["layers"])
+    for i, L in enumerate(wl["layers"]):
+        h = wl_mod.out_size(h, L["k_h"], L["s_h"], L["p_h"])
+        w = wl_mod.out_size(w, L["k_w"], L["s_w"], L["p_w"])
+        if i == n - 1:
+            break
+        if staged_2d:
+            if wl["layers"][i + 1]["kind"] != "maxpool":
+                total += 2 * w * L["c_out"] * eb
+        else:
+            rows = -(-rows // L["s_h"]) if L["s_h"] > 1 else rows      # most rows one push completes
+            total += rows * L["c_out"] * 4
+    return total
+
+
+@pytest.mark.parametrize("cfg,staged_2d", [(1, False), (2, False), (3, True), (4, True), (5, True)])
+def test_retained_bytes_count_the_rows_waiting_between_layers(cfg, staged_2d, monkeypatch):
+    """Everything of a stream that survives from one call to the next: the rolling buffers and held
+    rows the paper's bound is about (Sec. 3 last two paragraphs, Fig. 1, Fig. 2), plus, in the
+    staged modes, the rows waiting between layers.  Strictly depth-first modes hold only the former."""
+    wl = wl_mod.make(cfg, streams=1)
+    for var in ("IDF_NO_MFMA", "IDF_NO_ROW_STAGES", "IDF_CASCADE_STAGES"):
+        monkeypatch.delenv(var, raising=False)
+    net = idf.net_from_workload(wl)
+    s = net.query_sizes(8, wl["seg_rows"], 0 if wl["in_h"] else 64)
+    assert s.state_bytes_per_stream <= bound_bytes(wl)
+    assert s.retained_bytes_per_stream == s.state_bytes_per_stream + s.handover_bytes_per_stream
+    assert s.handover_bytes_per_stream == handover_bytes(wl, staged_2d)
+    assert s.handover_bytes_per_stream <= s.transit_bytes_per_stream
+    monkeypatch.setenv("IDF_NO_ROW_STAGES", "1")
+    monkeypatch.setenv("IDF_CASCADE_STAGES", "1")
+    t = net.query_sizes(8, wl["seg_rows"], 0 if wl["in_h"] else 64)
+    assert t.handover_bytes_per_stream == 0
+    assert t.retained_bytes_per_stream == t.state_bytes_per_stream == s.state_bytes_per_stream <= bound_bytes(wl)
+    net.destroy()
+
+
 def test_full_size_state_figures():
     # per-stream retained state of the five full-size configurations never exceeds
     # K_h rows per conv layer + one row per pool

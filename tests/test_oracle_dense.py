@@ -168,3 +168,32 @@ def test_round_bf16_matches_torch_and_generator():
     assert oracle.round_bf16(1.01171875) == 1.015625
     # a double just above a tie must round up although float32 would first land on the tie
     assert oracle.round_bf16(1.00390625 + 1e-12) == 1.0078125
+
+
+def test_head_units_hand_worked():
+    """Fully connected output units (Sec. 4: the class units that settle as rows come in; the
+    weighted sum is the first equation of Sec. 3).  Two units over a 2x2x2 map, every weight
+    distinct per (unit, row, x, c), expected values written out by hand.
+
+    map  h[row][x][c]:  row 0: (1,2) (3,4)   row 1: (5,6) (7,8)
+    unit 0 weights:     row 0: (1,10) (100,1000)   row 1: (2,20) (200,2000)
+    unit 1 weights:     row 0: (-1,0) (0,1)        row 1: (3,0) (0,-2)
+    bias: (0.5, -0.25)
+
+    after row 0 only: u0 = 1*1 + 10*2 + 100*3 + 1000*4 = 4321 ; u1 = -1 + 4 = 3
+    after both rows:  u0 = 4321 + 2*5 + 20*6 + 200*7 + 2000*8 = 21851 ; u1 = 3 + 15 - 16 = 2
+    """
+    h = np.array([[[1, 2], [3, 4]], [[5, 6], [7, 8]]], dtype=np.float64)
+    w = np.array([[[[1, 10], [100, 1000]], [[2, 20], [200, 2000]]],
+                  [[[-1, 0], [0, 1]], [[3, 0], [0, -2]]]], dtype=np.float64)
+    b = np.array([0.5, -0.25])
+    assert oracle.head_units(h[:0], w, b).tolist() == [0.5, -0.25]          # nothing arrived: the bias alone
+    assert oracle.head_units(h[:1], w, b).tolist() == [4321.5, 2.75]
+    assert oracle.head_units(h, w, b).tolist() == [21851.5, 1.75]
+    assert oracle.head_units(h[:1], w).tolist() == [4321.0, 3.0]            # no bias
+    # a transposed (x, c) or (row, x) axis gives other numbers: swap the map's axes and the result must change
+    assert oracle.head_units(np.swapaxes(h, 1, 2), w).tolist() != [21851.0, 2.0]
+    assert oracle.head_units(np.swapaxes(h, 0, 1), w).tolist() != [21851.0, 2.0]
+    # after the last row it is the conventional network's dense layer: torch's linear on the flattened map
+    full = F.linear(torch.from_numpy(h.reshape(1, -1)), torch.from_numpy(w.reshape(2, -1)), torch.from_numpy(b))
+    assert np.array_equal(oracle.head_units(h, w, b), full[0].numpy())
