@@ -129,6 +129,24 @@ int idf_open_streams(idf_net *net, int n_streams, int max_seg_rows, int64_t out_
                      idf_streams **out);
 int idf_close_streams(idf_streams *s);
 
+/* idf_open_streams for callers that cannot allocate device memory at all (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same call without the
+ * workspace arguments.  The workspace -- packed weights, rolling buffers, rows between layers,
+ * output area, counters -- is an array of IDF_STATIC_WORKSPACE_BYTES bytes inside the library
+ * itself, one per GPU, held by every GPU the library runs on until the process ends; neither this
+ * call nor anything the returned streams do allocates or frees device memory.  Inputs and outputs
+ * are still the caller's (idf_push_segment, idf_read_outputs).
+ *   - The array belongs to the GPU that is current at the call.  It keeps what the previous
+ *     streams left in it; this call clears every byte it lays out before anything reads it.
+ *   - One set of streams per GPU can hold it at a time: IDF_ESTATE while another set opened this
+ *     way on the same GPU has not been closed (two sets would race for the same bytes).
+ *   - IDF_ENOMEM with the sizes in the message if idf_query_sizes(...).workspace_bytes exceeds
+ *     IDF_STATIC_WORKSPACE_BYTES: nothing is opened.
+ * Everything else is as for idf_open_streams; close with idf_close_streams. */
+#define IDF_STATIC_WORKSPACE_BYTES (32u << 20)
+int idf_open_streams_static(idf_net *net, int n_streams, int max_seg_rows, int64_t out_cap_rows,
+                            void *hip_stream, idf_streams **out);
+
 /* Present the next n_rows rows to n_ids streams and push them depth-first through every layer
  * they can influence (Sec. 3 first paragraph; Sec. 5, the method seen as a core that takes input
  * as it arrives).

@@ -14,7 +14,7 @@ PREC = {"f32": 0, "bf16": 1, "i8": 2}
 KIND = {"conv": 0, "maxpool": 1}
 ACT = {"none": 0, "relu": 1, "relu_shr_clamp": 2}
 
-EXPORTS = ["idf_create_net", "idf_destroy_net", "idf_query_sizes", "idf_open_streams", "idf_close_streams",
+EXPORTS = ["idf_create_net", "idf_destroy_net", "idf_query_sizes", "idf_open_streams", "idf_open_streams_static", "idf_close_streams",
            "idf_push_segment", "idf_read_outputs", "idf_reset_streams", "idf_get_stats", "idf_count_issued_macs", "idf_get_issued_macs", "idf_rows_pushed",
            "idf_layer_kernel", "idf_last_error", "idf_profile_begin", "idf_profile_end", "idf_enable_head",
            "idf_read_head", "idf_query_head_units_bytes", "idf_enable_head_units", "idf_read_head_units", "idf_push_pixels", "idf_query_eager_bytes", "idf_enable_eager", "idf_read_announced", "idf_snapshot_bytes", "idf_snapshot", "idf_restore"]
@@ -77,6 +77,7 @@ def load_library():
     L.idf_query_sizes.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int64, C.POINTER(Sizes)]
     L.idf_open_streams.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int64, C.c_void_p, C.c_size_t,
                                    C.c_void_p, C.POINTER(C.c_void_p)]
+    L.idf_open_streams_static.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int64, C.c_void_p, C.POINTER(C.c_void_p)]
     L.idf_close_streams.argtypes = [C.c_void_p]
     L.idf_push_segment.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int]
     L.idf_read_outputs.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int64,
@@ -164,18 +165,26 @@ class Streams:
     """idf_open_streams ... idf_close_streams.  Tensors are torch CUDA tensors; only their
     data pointers cross the boundary."""
 
-    def __init__(self, net: Net, n_streams, max_seg_rows=1, out_cap_rows=0, device="cuda:0", stream=None):
+    def __init__(self, net: Net, n_streams, max_seg_rows=1, out_cap_rows=0, device="cuda:0", stream=None,
+                 static_workspace=False):
         import torch
         self.net = net
         self.n_streams = n_streams
         self.sizes = net.query_sizes(n_streams, max_seg_rows, out_cap_rows)
         self.device = torch.device(device)
         with torch.cuda.device(self.device):
+            self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+            h = C.c_void_p()
+            if static_workspace:        # idf_open_streams_static: the library's own array, nothing allocated here
+                self.workspace = None
+                _check(load_library().idf_open_streams_static(net._h, n_streams, max_seg_rows, out_cap_rows,
+                                                              C.c_void_p(self.stream.cuda_stream), C.byref(h)))
+                self._h = h
+                self.out_dtype = torch.int32 if net.precision == "i8" else torch.float32
+                return
             self.workspace = torch.empty(self.sizes.workspace_bytes + 256, dtype=torch.uint8, device=self.device)
             base = self.workspace.data_ptr()
             self._ws_ptr = (base + 255) // 256 * 256
-            self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
-            h = C.c_void_p()
             _check(load_library().idf_open_streams(net._h, n_streams, max_seg_rows, out_cap_rows,
                                                    C.c_void_p(self._ws_ptr), self.sizes.workspace_bytes,
                                                    C.c_void_p(self.stream.cuda_stream), C.byref(h)))

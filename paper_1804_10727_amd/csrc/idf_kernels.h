@@ -48,6 +48,8 @@ hipError_t launch_head_units(const HeadUnits &a, const StreamSel &sel, int64_t f
 hipError_t launch_head_accumulate(const HeadAcc &a, const StreamSel &sel, int64_t first_slot, int n_rows, const LaunchCtx &lc);
 // what: 0 = pushed rows become the announced input, 1 = conv layer, 2 = pool layer
 hipError_t launch_eager(int prec, int what, const EagerStep &a, const StreamSel &sel, const LaunchCtx &lc);
+// Clears bytes (a multiple of 4, 4-byte aligned) with a kernel on stream st.
+hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t st);
 hipError_t launch_copy_out(const CopyOut &a, const StreamSel &sel, int64_t first_slot, int n_rows,
                            const LaunchCtx &lc);
 

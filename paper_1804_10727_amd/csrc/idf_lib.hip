@@ -10,6 +10,7 @@
 #include <cstring>
 #include <deque>
 #include <map>
+#include <mutex>
 #include <new>
 #include <string>
 #include <tuple>
@@ -37,6 +38,18 @@ int fail(int code, const char *fmt, ...)
 }
 
 size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+// Workspace of idf_open_streams_static: one array per GPU, living in the library's code object
+// until the process ends.  Its name is only a handle on the host side; the device address is
+// asked for once per device (scratch_of) and only that pointer is ever handed to kernels, fills
+// and copies.
+constexpr size_t kStaticScratchBytes = (size_t)IDF_STATIC_WORKSPACE_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+struct StaticScratch { unsigned char *ptr = nullptr; bool in_use = false; };
+StaticScratch g_scratch[kMaxDevices];
+std::mutex g_scratch_mutex;
 
 int ev_bytes(int prec) { return prec == IDF_PREC_F32 ? 4 : prec == IDF_PREC_BF16 ? 2 : 1; }
 int w_bytes(int prec) { return ev_bytes(prec); }
@@ -72,6 +85,7 @@ struct ProfRec {
 };
 
 struct idf_streams {
+    int static_dev = -1;             // >= 0: the workspace is that device's static array (given back at close)
     bool use_cascade1d = false;      // whole-net kernel for 1-D nets instead of one launch per layer
     bool prof_on = false;
     std::vector<ProfRec> prof;
@@ -933,10 +947,10 @@ int eager_push(idf_streams *s, const int32_t *stream_ids, int n_ids, const void 
                     const int first = sel.base >= 0 ? sel.base : sel.ids[k], cnt = sel.base >= 0 ? sel.n : 1;
                     for (int lv = 0; lv <= n; ++lv) {
                         const size_t per = (size_t)E.elems[lv] * 4, at = (size_t)first * per, bytes = per * cnt;
-                        hipError_t e = hipMemsetAsync(E.ws + E.ann_off[lv] + at, 0, bytes, s->st);
-                        if (e == hipSuccess) e = hipMemsetAsync(E.ws + E.dlt_off[lv] + at, 0, bytes, s->st);
+                        hipError_t e = launch_fill_zero(E.ws + E.ann_off[lv] + at, bytes, s->st);
+                        if (e == hipSuccess) e = launch_fill_zero(E.ws + E.dlt_off[lv] + at, bytes, s->st);
                         if (e == hipSuccess && lv > 0 && net.g[lv - 1].kind == IDF_CONV)
-                            e = hipMemsetAsync(E.ws + E.c_off[lv] + at, 0, bytes, s->st);
+                            e = launch_fill_zero(E.ws + E.c_off[lv] + at, bytes, s->st);
                         if (e != hipSuccess) return dev_fail(e, "eager reset");
                     }
                 }
@@ -1013,6 +1027,9 @@ int head_catch_up(idf_streams *s, const int32_t *stream_ids, int n_ids)
     }
     return IDF_OK;
 }
+
+int open_on(idf_net *net, int n_streams, int max_seg_rows, int64_t out_cap_rows, const Layout &L, void *dev_workspace,
+            size_t workspace_bytes, void *hip_stream, idf_streams **out);
 
 }  // namespace
 
@@ -1122,6 +1139,76 @@ int idf_open_streams(idf_net *net, int n_streams, int max_seg_rows, int64_t out_
     int rc = make_layout(*net, n_streams, max_seg_rows, out_cap_rows, L);
     if (rc != IDF_OK) return rc;
     if (workspace_bytes < L.total) return fail(IDF_EINVAL, "workspace of %zu bytes, %zu needed", workspace_bytes, L.total);
+    return open_on(net, n_streams, max_seg_rows, out_cap_rows, L, dev_workspace, workspace_bytes, hip_stream, out);
+}
+
+int idf_open_streams_static(idf_net *net, int n_streams, int max_seg_rows, int64_t out_cap_rows, void *hip_stream,
+                            idf_streams **out)
+{
+    if (!net || !out) return fail(IDF_EINVAL, "null argument");
+    *out = nullptr;
+    if (n_streams < 1 || max_seg_rows < 1) return fail(IDF_EINVAL, "n_streams and max_seg_rows must be >= 1");
+    Layout L;
+    int rc = make_layout(*net, n_streams, max_seg_rows, out_cap_rows, L);
+    if (rc != IDF_OK) return rc;
+    if (L.total > kStaticScratchBytes)
+        return fail(IDF_ENOMEM, "these streams need a workspace of %zu bytes, the static one holds %zu: fewer streams, "
+                                "or idf_open_streams with a workspace of the caller's", L.total, kStaticScratchBytes);
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return dev_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(IDF_EDEVICE, "device %d outside the %d this library keeps a static workspace for", dev, kMaxDevices);
+    unsigned char *ws = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        StaticScratch &sc = g_scratch[dev];
+        if (!sc.ptr) {
+            // this device's copy of the array: its address, asked for with the device current
+            void *p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !p) return dev_fail(e, "hipGetSymbolAddress(scratch)");
+            sc.ptr = (unsigned char *)p;
+        }
+        if (sc.in_use) return fail(IDF_ESTATE, "the static workspace of device %d is taken by another set of open streams", dev);
+        sc.in_use = true;
+        ws = sc.ptr;
+    }
+    // open_on clears every byte it lays out (the array keeps what the previous streams left there)
+    rc = open_on(net, n_streams, max_seg_rows, out_cap_rows, L, ws, kStaticScratchBytes, hip_stream, out);
+    if (rc != IDF_OK) {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        g_scratch[dev].in_use = false;
+        return rc;
+    }
+    (*out)->static_dev = dev;
+    return IDF_OK;
+}
+
+int idf_close_streams(idf_streams *s)
+{
+    if (!s) return IDF_OK;
+    (void)pipeline_drain(s);
+    hipError_t e = hipStreamSynchronize(s->st);
+    for (ProfRec &r : s->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+    for (hipEvent_t ev : s->ev_pool) (void)hipEventDestroy(ev);
+    if (s->static_dev >= 0) {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        g_scratch[s->static_dev].in_use = false;
+    }
+    s->net->open_count--;
+    delete s;
+    return e == hipSuccess ? IDF_OK : dev_fail(e, "close_streams");
+}
+
+}  // extern "C"
+
+namespace {
+
+// Binds n_streams streams to a workspace laid out by L: host bookkeeping, upload of the packed
+// weights, every laid-out byte cleared.
+int open_on(idf_net *net, int n_streams, int max_seg_rows, int64_t out_cap_rows, const Layout &L, void *dev_workspace,
+            size_t workspace_bytes, void *hip_stream, idf_streams **out)
+{
     idf_streams *s = new (std::nothrow) idf_streams;
     if (!s) return fail(IDF_ENOMEM, "out of host memory");
     s->net = net; s->B = n_streams; s->max_seg = max_seg_rows;
@@ -1159,7 +1246,7 @@ int idf_open_streams(idf_net *net, int n_streams, int max_seg_rows, int64_t out_
     }
     s->h.assign(n_streams, StreamHost{});
     s->stamp.assign(n_streams, 0);
-    hipError_t e = hipMemsetAsync(s->ws, 0, L.sizes.weights_bytes, s->st);     // zero padding of the weights
+    hipError_t e = launch_fill_zero(s->ws, L.sizes.weights_bytes, s->st);     // zero padding of the weights
     for (size_t l = 0; l < net->g.size() && e == hipSuccess; ++l) {
         if (net->g[l].kind != IDF_CONV) continue;
         if (L.cascade1d) {
@@ -1183,24 +1270,16 @@ int idf_open_streams(idf_net *net, int n_streams, int max_seg_rows, int64_t out_
     // State needs no clearing for correctness (a row of c is initialised when first touched);
     // it is zeroed once so that the workspace never exposes stale bytes.
     if (e == hipSuccess)
-        e = hipMemsetAsync(s->ws + L.sizes.weights_bytes, 0, L.total - L.sizes.weights_bytes, s->st);
+        e = launch_fill_zero(s->ws + L.sizes.weights_bytes, L.total - L.sizes.weights_bytes, s->st);
     if (e != hipSuccess) { delete s; return dev_fail(e, "open_streams"); }
     net->open_count++;
     *out = s;
     return IDF_OK;
 }
 
-int idf_close_streams(idf_streams *s)
-{
-    if (!s) return IDF_OK;
-    (void)pipeline_drain(s);
-    hipError_t e = hipStreamSynchronize(s->st);
-    for (ProfRec &r : s->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
-    for (hipEvent_t ev : s->ev_pool) (void)hipEventDestroy(ev);
-    s->net->open_count--;
-    delete s;
-    return e == hipSuccess ? IDF_OK : dev_fail(e, "close_streams");
-}
+}  // namespace
+
+extern "C" {
 
 int idf_push_segment(idf_streams *s, const int32_t *stream_ids, int n_ids, const void *dev_rows, int n_rows)
 {
@@ -1368,11 +1447,11 @@ int idf_reset_streams(idf_streams *s, const int32_t *stream_ids, int n_ids)
     const size_t per = s->net->g.size() * 2 * sizeof(unsigned long long);
     for (int i = 0; i < n_ids; ++i) {
         const int id = stream_ids ? stream_ids[i] : i;
-        hipError_t e = hipMemsetAsync(s->ws + s->stats_off + per * id, 0, per, s->st);
-        if (e == hipSuccess) e = hipMemsetAsync(s->ws + s->issued_off + per / 2 * id, 0, per / 2, s->st);
+        hipError_t e = launch_fill_zero(s->ws + s->stats_off + per * id, per, s->st);
+        if (e == hipSuccess) e = launch_fill_zero(s->ws + s->issued_off + per / 2 * id, per / 2, s->st);
         if (e == hipSuccess)
-            e = hipMemsetAsync(s->ws + s->head_off + (size_t)id * s->net->out_c * sizeof(double), 0,
-                               (size_t)s->net->out_c * sizeof(double), s->st);
+            e = launch_fill_zero(s->ws + s->head_off + (size_t)id * s->net->out_c * sizeof(double),
+                                 (size_t)s->net->out_c * sizeof(double), s->st);
         if (e != hipSuccess) return dev_fail(e, "reset_streams");
         s->h[id] = StreamHost{};
     }
@@ -1578,7 +1657,7 @@ int idf_enable_head_units(idf_streams *s, int n_units, const float *weights, con
     rc = idf_enable_head(s);                       // the units ride on the averaging units' bookkeeping
     if (rc != IDF_OK) return rc;
     const size_t map = (size_t)s->net->out_h * s->net->out_w * s->net->out_c;
-    hipError_t e = hipMemsetAsync(dev_buf, 0, need, s->st);
+    hipError_t e = launch_fill_zero(dev_buf, need, s->st);
     if (e == hipSuccess) e = hipMemcpyAsync(dev_buf, weights, (size_t)n_units * map * 4, hipMemcpyHostToDevice, s->st);
     if (e == hipSuccess && bias)
         e = hipMemcpyAsync((char *)dev_buf + (size_t)n_units * map * 4, bias, (size_t)n_units * 4, hipMemcpyHostToDevice, s->st);

@@ -366,6 +366,34 @@ hipError_t launch_copy_out(const CopyOut &a, const StreamSel &sel, int64_t first
 }
 
 // ---------------------------------------------------------------------------------------
+// Clears n 4-byte words: what the host side uses wherever state, counters or maps must start at
+// zero, so that a caller who records the library's work into a HIP graph records kernels only.
+// ---------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kGenThreads) k_fill_zero(uint32_t *p, int64_t n)
+{
+    const int64_t start = (int64_t)blockIdx.x * kGenThreads + threadIdx.x, step = (int64_t)gridDim.x * kGenThreads;
+    if (((uintptr_t)p & 15) == 0) {
+        uint4 *p4 = reinterpret_cast<uint4 *>(p);
+        for (int64_t e = start; e < n / 4; e += step) p4[e] = uint4{0u, 0u, 0u, 0u};
+        for (int64_t e = n / 4 * 4 + start; e < n; e += step) p[e] = 0u;
+    } else {
+        for (int64_t e = start; e < n; e += step) p[e] = 0u;
+    }
+}
+
+hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t st)
+{
+    if (bytes == 0) return hipSuccess;
+    if (((uintptr_t)p & 3) != 0 || (bytes & 3) != 0) return hipErrorInvalidValue;
+    const int64_t n = (int64_t)(bytes / 4);
+    int64_t blocks = (n / 4 + kGenThreads - 1) / kGenThreads;
+    blocks = blocks < 1 ? 1 : (blocks > 4096 ? 4096 : blocks);
+    LaunchCtx lc;
+    lc.st = st;
+    return launch(k_fill_zero, dim3((unsigned)blocks), dim3(kGenThreads), 0, lc, (uint32_t *)p, n);
+}
+
+// ---------------------------------------------------------------------------------------
 // Averaging output units (Fig. 1): per stream and channel, the sum over all positions of the
 // rows the last layer has completed, and the running mean.  One workgroup per (stream, block of
 // 64 channels); four groups of lanes take every fourth position and are added in a fixed order.
