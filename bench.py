@@ -105,6 +105,76 @@ def traffic_from_counters(config, fetch_dir, write_dir):
     print(json.dumps({WORKLOADS[config]: rec}, indent=1))
 
 
+def trace_summary(stats_csv, bench_log):
+    """Text summary of a `rocprofv3 --kernel-trace --stats` run of this bench: the kernel table of
+    the trace and the roofline position of the dominant kernel worked out from the TRACE's average
+    duration of that kernel (the bench's own line, printed in the same run, supplies the
+    algorithmic bytes and executed flops per launch)."""
+    import csv
+    rows = list(csv.DictReader(open(stats_csv)))
+    bench = None
+    for l in open(bench_log):
+        if l.startswith("{"):
+            bench = json.loads(l)
+    assert bench, f"no bench line in {bench_log}"
+    rf = bench["roofline"]
+    out = [f"rocprofv3 kernel-trace summary: bench.py workload {bench['config']['workload']} on one MI355X (gfx950)", "",
+           f"bench.py in that run: steps={bench['steps']} warmup={bench['warmup']} (+1 step bracketed by HIP events per launch, "
+           f"+1 step on the kernel variants that count issued multiply-adds, named <..., true>); ms_per_step={bench['ms_per_step']:.3f}", "",
+           "Kernel statistics (kernel_stats.csv), all launches of the process:",
+           f"  {'kernel':<52} {'calls':>7} {'total ms':>10} {'avg us':>9} {'min us':>8} {'max us':>8} {'%':>6}"]
+    sym = KERNEL_SYMBOL.get(rf["kernel"], rf["kernel"])
+    dom = None
+    for r in rows:
+        name = r["Name"]
+        short = name.replace("(anonymous namespace)::", "").replace("void ", "", 1).split("(")[0].replace("idf::", "")
+        short = short if len(short) <= 52 else short[:49] + "..."
+        out.append(f"  {short:<52} {int(r['Calls']):>7} {int(r['TotalDurationNs']) / 1e6:>10.3f} {float(r['AverageNs']) / 1e3:>9.2f} "
+                   f"{int(r['MinNs']) / 1e3:>8.2f} {int(r['MaxNs']) / 1e3:>8.2f} {float(r['Percentage']):>6.2f}")
+        if sym in name and "true>" not in short and (dom is None or int(r["TotalDurationNs"]) > int(dom["TotalDurationNs"])):
+            dom = r
+    assert dom, f"no {sym} kernel in the trace"
+    avg_s = float(dom["AverageNs"]) * 1e-9
+    if rf["bound"] == "hbm":
+        ach = rf["algorithmic_bytes_per_launch"] / avg_s / 1e9
+    else:
+        ach = rf["executed_flops_per_launch"] / avg_s / 1e12
+    out += ["", f"Dominant kernel: {sym}, trace average {avg_s * 1e6:.2f} us over {dom['Calls']} launches "
+                f"(the bench's own HIP-event brackets in an unprofiled run: see the committed bench line; under the profiler the "
+                f"brackets themselves are slower, the trace is not).",
+            f"Algorithmic bytes per launch {rf['algorithmic_bytes_per_launch']:.0f}; executed flops per launch "
+            f"{rf['executed_flops_per_launch']:.0f}; roofline bound '{rf['bound']}' from the trace average: achieved {ach:.1f} {rf['unit']} "
+            f"of {rf['peak']:.0f} (frac {ach / rf['peak']:.4f}).",
+            f"launches_per_step {rf['launches_per_step']} x trace average = {rf['launches_per_step'] * avg_s * 1e3:.3f} ms against "
+            f"ms_per_step {bench['ms_per_step']:.3f} (launches back to back can run shorter than the average of all, spaced ones included)."]
+    print("\n".join(out))
+
+
+def utilisation_from_counters(dirs):
+    """Averages per dispatch, for the library's main kernels, of whatever `rocprofv3 --pmc` runs of
+    this bench collected -- basic counters or the profiler's derived ones (MfmaUtil, VALUBusy,
+    LdsUtil: percent of the time the GPU was active during the dispatch; LdsBankConflict:
+    conflict cycles per LDS access cycle)."""
+    import csv
+    import glob
+    tot, cnt = {}, {}
+    for d in dirs:
+        for f in glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True):
+            for row in csv.DictReader(open(f)):
+                k = row["Kernel_Name"]
+                if not any(sym in k for sym in KERNEL_SYMBOL.values()) or "true>" in k.replace("(anonymous namespace)::", ""):
+                    continue
+                key = (k.replace("(anonymous namespace)::", "").replace("void ", "", 1).split("(")[0].replace("idf::", ""), row["Counter_Name"])
+                tot[key] = tot.get(key, 0.0) + float(row["Counter_Value"]); cnt[key] = cnt.get(key, 0) + 1
+    kernels = sorted({k for k, _ in tot}, key=lambda k: -max(cnt[(k, c)] for kk, c in tot if kk == k))
+    for k in kernels:
+        av = {c: tot[(kk, c)] / cnt[(kk, c)] for kk, c in tot if kk == k}
+        n = max(cnt[(kk, c)] for kk, c in tot if kk == k)
+        print(f"{k}: {n} dispatches, averages per dispatch")
+        for c in sorted(av):
+            print(f"    {c:<34} {av[c]:>16.1f}")
+
+
 def cpu_baseline(wl, budget_s=12.0):
     """The CPU oracle's event-by-event streaming scheme, as it stands, on this machine's cores."""
     import oracle
@@ -291,9 +361,20 @@ def main():
     ap.add_argument("--traffic-from", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"),
                     help="no GPU run: read two rocprofv3 --pmc outputs of this bench (FETCH_SIZE, WRITE_SIZE) "
                          "and store the dominant kernel's HBM bytes per launch in profiles/traffic.json")
+    ap.add_argument("--trace-summary", nargs=2, metavar=("KERNEL_STATS_CSV", "BENCH_LOG"),
+                    help="no GPU run: text summary of a rocprofv3 --kernel-trace --stats run of this bench "
+                         "(its kernel_stats.csv and the output of the bench in that run)")
+    ap.add_argument("--util-from", nargs="+", metavar="DIR",
+                    help="no GPU run: averages of rocprofv3 --pmc counter runs of this bench for the dominant kernels")
     args = ap.parse_args()
     if args.traffic_from:
         traffic_from_counters(args.config, *args.traffic_from)
+        return
+    if args.trace_summary:
+        trace_summary(*args.trace_summary)
+        return
+    if args.util_from:
+        utilisation_from_counters(args.util_from)
         return
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (streams are independent: more GPUs "
