@@ -112,6 +112,19 @@ typedef struct {
  *             this build cannot run (shr/clamp activation outside I8). */
 int idf_create_net(const idf_net_desc *desc, const void *const *weights, const void *const *biases,
                    idf_net **out);
+/* The same network presented column by column (Fig. 2: the input may arrive row by row or column
+ * by column; Sec. 3: any order of small segments): desc, weights and biases describe the network in
+ * image coordinates exactly as for idf_create_net, with in_w = 0 allowed for an unbounded number of
+ * columns (then every p_w must be 0) and in_h > 0 required.  The returned network streams along the
+ * other axis -- everything that says "row" for it means a column of the image:
+ *   idf_push_segment takes the next n_rows columns, dev_rows [n_ids][n_rows][in_h][in_c];
+ *   idf_read_outputs hands over completed columns of the output map, [n_ids][max_rows][out rows][out_c]
+ *   (idf_sizes: out_h = columns per sample, out_w = rows of the output map);
+ *   the retained state is proportional to the column length instead of the row width.
+ * The values are those of the conventional network, as for row-wise presentation.  Pools must be
+ * 2 x 2 (a 2 x 1 pool has no column-wise counterpart here: IDF_EINVAL). */
+int idf_create_net_columnwise(const idf_net_desc *desc, const void *const *weights, const void *const *biases,
+                              idf_net **out);
 int idf_destroy_net(idf_net *net);
 
 /* Sizes for n_streams streams that are pushed at most max_seg_rows rows per call and may hold up

@@ -14,7 +14,7 @@ PREC = {"f32": 0, "bf16": 1, "i8": 2}
 KIND = {"conv": 0, "maxpool": 1}
 ACT = {"none": 0, "relu": 1, "relu_shr_clamp": 2}
 
-EXPORTS = ["idf_create_net", "idf_destroy_net", "idf_query_sizes", "idf_open_streams", "idf_open_streams_static", "idf_close_streams",
+EXPORTS = ["idf_create_net", "idf_create_net_columnwise", "idf_destroy_net", "idf_query_sizes", "idf_open_streams", "idf_open_streams_static", "idf_close_streams",
            "idf_push_segment", "idf_read_outputs", "idf_reset_streams", "idf_get_stats", "idf_count_issued_macs", "idf_get_issued_macs", "idf_rows_pushed",
            "idf_layer_kernel", "idf_last_error", "idf_profile_begin", "idf_profile_end", "idf_enable_head",
            "idf_read_head", "idf_query_head_units_bytes", "idf_enable_head_units", "idf_read_head_units", "idf_push_pixels", "idf_query_eager_bytes", "idf_enable_eager", "idf_read_announced", "idf_snapshot_bytes", "idf_snapshot", "idf_restore"]
@@ -73,6 +73,7 @@ def load_library():
     L.idf_layer_kernel.argtypes = [C.c_void_p, C.c_int]
     L.idf_create_net.argtypes = [C.POINTER(_NetDesc), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
                                  C.POINTER(C.c_void_p)]
+    L.idf_create_net_columnwise.argtypes = L.idf_create_net.argtypes
     L.idf_destroy_net.argtypes = [C.c_void_p]
     L.idf_query_sizes.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int64, C.POINTER(Sizes)]
     L.idf_open_streams.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int64, C.c_void_p, C.c_size_t,
@@ -120,7 +121,7 @@ def _ids(stream_ids):
 class Net:
     """idf_create_net / idf_destroy_net."""
 
-    def __init__(self, precision, in_h, in_w, in_c, layers, weights, biases=None):
+    def __init__(self, precision, in_h, in_w, in_c, layers, weights, biases=None, columnwise=False):
         L = load_library()
         self.precision = precision
         self.layers = layers
@@ -147,7 +148,8 @@ class Net:
         wt = table(weights, wdt)
         bt = table(biases, bdt) if biases is not None else None
         h = C.c_void_p()
-        _check(L.idf_create_net(C.byref(desc), wt, bt, C.byref(h)))
+        create = L.idf_create_net_columnwise if columnwise else L.idf_create_net
+        _check(create(C.byref(desc), wt, bt, C.byref(h)))
         self._h = h
 
     def query_sizes(self, n_streams, max_seg_rows=1, out_cap_rows=0) -> Sizes:
@@ -343,14 +345,14 @@ def _bf16_bits(a):
     return (u >> 16).astype(np.uint16)
 
 
-def net_from_workload(wl) -> Net:
+def net_from_workload(wl, columnwise=False) -> Net:
     """Net from a workload dict (see the workloads module): only dtype marshalling."""
     prec = wl["precision"]
     if prec == "bf16":
         ws = [None if w is None else _bf16_bits(w) for w in wl["weights"]]
     else:
         ws = wl["weights"]
-    return Net(prec, wl["in_h"], wl["in_w"], wl["in_c"], wl["layers"], ws, wl["biases"])
+    return Net(prec, wl["in_h"], wl["in_w"], wl["in_c"], wl["layers"], ws, wl["biases"], columnwise=columnwise)
 
 
 def input_tensor(wl, device="cuda:0"):

@@ -1114,6 +1114,39 @@ int idf_create_net(const idf_net_desc *d, const void *const *weights, const void
     return IDF_OK;
 }
 
+int idf_create_net_columnwise(const idf_net_desc *d, const void *const *weights, const void *const *biases,
+                              idf_net **out)
+{
+    if (!d || !out || !d->layers) return fail(IDF_EINVAL, "null argument");
+    *out = nullptr;
+    if (d->n_layers < 1 || d->n_layers > kMaxLayers) return fail(IDF_EINVAL, "n_layers %d outside [1, %d]", d->n_layers, kMaxLayers);
+    if (d->precision < IDF_PREC_F32 || d->precision > IDF_PREC_I8) return fail(IDF_EINVAL, "unknown precision %d", d->precision);
+    // The same network with the two image axes exchanged: what streams in is then a column.
+    std::vector<idf_layer> lt(d->layers, d->layers + d->n_layers);
+    std::vector<std::vector<unsigned char>> wt(d->n_layers);
+    std::vector<const void *> wp(d->n_layers, nullptr);
+    const size_t wb = (size_t)w_bytes(d->precision);
+    for (int l = 0; l < d->n_layers; ++l) {
+        idf_layer &L = lt[l];
+        std::swap(L.k_h, L.k_w); std::swap(L.s_h, L.s_w); std::swap(L.p_h, L.p_w);
+        if (L.kind != IDF_CONV || !weights || !weights[l]) continue;
+        if (L.c_in < 1 || L.c_out < 1 || L.k_h < 1 || L.k_w < 1) return fail(IDF_EINVAL, "layer %d: bad shape", l);
+        // [c_out][c_in][k_h][k_w] of the image orientation -> the same with the two kernel axes exchanged
+        const int kh = L.k_w, kw = L.k_h;                      // of the image orientation
+        wt[l].resize((size_t)L.c_out * L.c_in * kh * kw * wb);
+        const unsigned char *src = (const unsigned char *)weights[l];
+        for (size_t oc = 0; oc < (size_t)L.c_out * L.c_in; ++oc)
+            for (int ky = 0; ky < kh; ++ky)
+                for (int kx = 0; kx < kw; ++kx)
+                    memcpy(&wt[l][((oc * kw + kx) * kh + ky) * wb], src + ((oc * kh + ky) * kw + kx) * wb, wb);
+        wp[l] = wt[l].data();
+    }
+    idf_net_desc t = *d;
+    t.in_h = d->in_w; t.in_w = d->in_h; t.layers = lt.data();
+    if (t.in_w < 1) return fail(IDF_EINVAL, "column-wise presentation needs the column length in_h");
+    return idf_create_net(&t, wp.data(), biases, out);
+}
+
 int idf_destroy_net(idf_net *net)
 {
     if (!net) return IDF_OK;

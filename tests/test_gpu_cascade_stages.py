@@ -148,3 +148,59 @@ def test_more_streams_than_a_stage_per_layer_allows(streams):
         check_stream(wl, a[i], i)
     for i in range(streams):
         assert np.array_equal(a[i], b[i])
+
+
+def test_reset_mid_flight_on_unbounded_streams():
+    """Unbounded 1-D streams (no sample length: they never flush), a small output ring read piece by
+    piece; one stream is reset while segments of all streams are still between the stages, starts a
+    new signal at row 0 and runs on beside the others, which must not notice."""
+    import torch
+    import paper_1804_10727_amd as idf
+    wl = wl_mod.make(2, streams=3, length=640, channels=(8, 8, 16, 16, 16, 16))
+    layers, ws = wl["layers"], wl["weights"]
+    net = idf.Net("f32", 0, 1, 1, layers, ws)                      # in_h = 0: unbounded
+    st = idf.Streams(net, 3, max_seg_rows=16, out_cap_rows=24)
+    assert st.sizes.out_h == 0
+    x = torch.from_numpy(wl["x"]).to("cuda:0")                     # [3][640][1][1]
+    second = torch.from_numpy(wl_mod.make(2, streams=1, length=640, channels=(8, 8, 16, 16, 16, 16), seed=5)["x"]).to("cuda:0")
+    got = [[], [], []]
+    new1 = []
+
+    def read_all():
+        for _ in range(3):
+            out, first, cnt = st.read_outputs(16)
+            o = out.cpu().numpy()
+            for b in range(3):
+                (got[b] if (b != 1 or not new1_started[0]) else new1).append(o[b, :cnt[b]])
+
+    new1_started = [False]
+    pos1 = 0
+    for i, r in enumerate(range(0, 640, 16)):
+        if i == 9:
+            # segments 6..8 of all streams are still on their way through the stages
+            read_all()
+            st.reset(stream_ids=[1])
+            new1_started[0] = True
+        if new1_started[0]:
+            seg = torch.cat([x[[0], r:r + 16], second[[0], pos1:pos1 + 16], x[[2], r:r + 16]]).contiguous()
+            pos1 += 16
+        else:
+            seg = x[:, r:r + 16].contiguous()
+        st.push_segment(seg)
+        if i % 2 == 1:
+            read_all()
+    read_all()
+    torch.cuda.synchronize()
+    import oracle
+    for b, sig in ((0, wl["x"][0]), (2, wl["x"][2])):
+        want = oracle.dense(layers, sig, ws, None)
+        g = np.concatenate(got[b])
+        assert g.shape == want.shape
+        assert rel_err(g, want) <= TOL["f32"], b
+    want_old = oracle.dense(layers, wl["x"][1][:9 * 16], ws, None)       # what stream 1 had completed before the reset
+    g_old = np.concatenate(got[1])
+    assert g_old.shape == want_old.shape and rel_err(g_old, want_old) <= TOL["f32"]
+    want_new = oracle.dense(layers, second.cpu().numpy()[0][:pos1], ws, None)
+    g_new = np.concatenate(new1)
+    assert g_new.shape == want_new.shape and rel_err(g_new, want_new) <= TOL["f32"]
+    st.close(); net.destroy()

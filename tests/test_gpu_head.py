@@ -138,3 +138,21 @@ def test_fully_connected_output_units_settle_row_by_row(cfg, kw, seg):
     with pytest.raises(idf.IdfError):
         st.snapshot(0)
     st.close(); net.destroy()
+
+
+def test_convergence_curve_matches_the_oracle_row_by_row():
+    """The accumulated-output curve of Sec. 4 (Fig. 3 / Fig. 4) as the package's script measures it:
+    every point against the oracle's class units on the rows the dense oracle says are complete."""
+    from paper_1804_10727_amd import convergence
+    from helpers import oracle_dense
+    wl = wl_mod.make(3, streams=6, size=16, channels=(16, 16, 32, 32))
+    seen, vals, w, b = convergence.curve(wl, n_units=5, seed=4)
+    dense = [oracle_dense(wl, s).astype(np.float64) for s in range(6)]
+    assert seen[-1] == dense[0].shape[0] and (np.diff(seen) >= 0).all() and seen[0] == 0
+    for r in range(wl["in_h"]):
+        for s in range(6):
+            want = oracle.head_units(dense[s][:seen[r]], w, b)
+            assert np.max(np.abs(vals[r, s] - want)) <= 1e-5 * max(1.0, np.max(np.abs(want))), (r, s)
+    table = convergence.summarise(seen, vals)
+    assert table[-1][2] == 1.0 and table[-1][3] == 0.0           # after the last row: the conventional network
+    assert table[0][3] > table[len(table) // 2][3] > 0.0          # and on the way the values close in on it
