@@ -342,6 +342,24 @@ def run_workload(config, steps_arg=None, warmup_arg=None, eager=False):
                              for p in by_layer},
         "roofline": roof,
     }
+    if eager:
+        # what eager emission costs against emission once per finished row: the state it keeps and
+        # the events it delivers (every change of a value is an event, not only its final value)
+        nb, kept = st.eager_state_bytes()
+        st.close()
+        st2 = idf.Streams(net, B, max_seg_rows=seg, device=dev)
+        for i in range(n_seg):
+            st2.push_segment(xs[i])
+        st2.read_outputs(out_h, out=out)
+        ev_rc = sum(st2.get_stats(b)["events_in"].astype(np.float64) for b in range(B))
+        res["eager"] = {"state_bytes_per_stream": int(nb), "rows_kept_per_level": [int(k) for k in kept],
+                        "row_complete_state_bytes_per_stream": int(st2.sizes.state_bytes_per_stream),
+                        "events_delivered_per_layer": [float(v) for v in (ev1 - ev0)],
+                        "row_complete_events_per_layer": [float(v) for v in ev_rc],
+                        "events_over_row_complete": float((ev1 - ev0).sum() / max(ev_rc.sum(), 1.0))}
+        st2.close()
+        net.destroy()
+        return res, wl
     st.close()
     net.destroy()
     return res, wl

@@ -235,16 +235,33 @@ int idf_rows_pushed(const idf_streams *s, int stream_id, int64_t *rows);
 /* Eager emission -- Sec. 3 taken literally: every neuron announces a change of f(c) at once, as an
  * event that the next layer takes in at once, so that after every pushed segment the announced
  * activations of every layer are those of the conventional network on the input seen so far (the
- * rest taken as zero; Sec. 4, Fig. 3).  Whole maps of state and announced values are kept per
- * stream, in a second caller-owned device workspace of idf_query_eager_bytes() bytes; bounded
- * samples, float32 or int8 nets (IDF_EUNSUPPORTED otherwise).  After idf_enable_eager (before the
- * first push) idf_push_segment delivers eagerly, idf_read_outputs is refused (IDF_ESTATE) and
- *   idf_read_announced(level, ...) copies the announced map [n_ids][H][W][C] of 4-byte values of
- *   level 0 (the input) .. n_layers (the last layer) to dev_out, in stream order.
- * idf_get_stats then counts, per layer, the non-zero changes delivered to it. */
-int idf_query_eager_bytes(const idf_net *net, int n_streams, size_t *bytes);
+ * rest taken as zero; Sec. 4, Fig. 3).  State lives in a second caller-owned device workspace of
+ * idf_query_eager_bytes() bytes; bounded samples only (IDF_EUNSUPPORTED otherwise); all three
+ * precisions (a bfloat16 net announces values rounded to bfloat16, the last layer unrounded, like
+ * its row-complete counterpart).
+ *   Nets without biases keep, per stream and level, only the rows that a future segment can still
+ *   change or that a pool still looks at -- the cone of Sec. 3: 1 + n(K-1) rows plus the segment at
+ *   depth n for K x K layers of stride 1 -- in a ring, so that the state does not depend on the sample
+ *   height; only the last level's announced map, the output, is kept whole.  A net with biases keeps
+ *   every level whole: every neuron announces f(bias ...) before any input arrives (Sec. 3 assumes
+ *   b = 0 for exactly this reason).
+ * After idf_enable_eager (before the first push) idf_push_segment delivers eagerly, idf_read_outputs
+ * is refused (IDF_ESTATE) and
+ *   idf_read_announced(level, ...) copies the announced map [n_ids][H][W][C] of 4-byte values of a
+ *     level that is kept whole -- the last level (n_layers) always, any level (0 = the input) of a net
+ *     with biases -- to dev_out, in stream order (IDF_ESTATE for a level kept as a ring);
+ *   idf_read_announced_rows(level, ...) copies the rows of a level that are still kept, oldest first,
+ *     to dev_out [n_ids][max_rows][W][C] and reports per stream the index of the first and how many
+ *     (at most max_rows).  Rows before them are final and forgotten, rows after them still all zero.
+ * idf_get_stats then counts, per layer, the non-zero changes delivered to it.
+ * idf_eager_state_bytes: state c and announced values retained per stream (without the output map);
+ * rows_kept (host, n_layers + 1 entries, may be NULL): rows kept per level. */
+int idf_query_eager_bytes(const idf_net *net, int n_streams, int max_seg_rows, size_t *bytes);
 int idf_enable_eager(idf_streams *s, void *dev_workspace, size_t workspace_bytes);
 int idf_read_announced(idf_streams *s, int level, const int32_t *stream_ids, int n_ids, void *dev_out);
+int idf_read_announced_rows(idf_streams *s, int level, const int32_t *stream_ids, int n_ids, void *dev_out,
+                            int max_rows, int64_t *first_row, int32_t *n_rows);
+int idf_eager_state_bytes(const idf_streams *s, size_t *per_stream, int *rows_kept);
 
 /* Averaging output units (Fig. 1: the output neuron that averages the last layer; Sec. 4: output
  * units whose value converges as rows come in): one accumulator per channel of the last layer,

@@ -17,7 +17,7 @@ ACT = {"none": 0, "relu": 1, "relu_shr_clamp": 2}
 EXPORTS = ["idf_create_net", "idf_create_net_columnwise", "idf_destroy_net", "idf_query_sizes", "idf_open_streams", "idf_open_streams_static", "idf_close_streams",
            "idf_push_segment", "idf_read_outputs", "idf_reset_streams", "idf_get_stats", "idf_count_issued_macs", "idf_get_issued_macs", "idf_rows_pushed",
            "idf_layer_kernel", "idf_last_error", "idf_profile_begin", "idf_profile_end", "idf_enable_head",
-           "idf_read_head", "idf_query_head_units_bytes", "idf_enable_head_units", "idf_read_head_units", "idf_push_pixels", "idf_query_eager_bytes", "idf_enable_eager", "idf_read_announced", "idf_snapshot_bytes", "idf_snapshot", "idf_restore"]
+           "idf_read_head", "idf_query_head_units_bytes", "idf_enable_head_units", "idf_read_head_units", "idf_push_pixels", "idf_query_eager_bytes", "idf_enable_eager", "idf_read_announced", "idf_read_announced_rows", "idf_eager_state_bytes", "idf_snapshot_bytes", "idf_snapshot", "idf_restore"]
 
 
 class IdfError(RuntimeError):
@@ -92,7 +92,9 @@ def load_library():
     L.idf_query_head_units_bytes.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_size_t)]
     L.idf_enable_head_units.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]
     L.idf_read_head_units.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
-    L.idf_query_eager_bytes.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_size_t)]
+    L.idf_query_eager_bytes.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_size_t)]
+    L.idf_read_announced_rows.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+    L.idf_eager_state_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t), C.c_void_p]
     L.idf_enable_eager.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
     L.idf_read_announced.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p]
     L.idf_push_pixels.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int]
@@ -172,6 +174,7 @@ class Streams:
         import torch
         self.net = net
         self.n_streams = n_streams
+        self.max_seg_rows = max_seg_rows
         self.sizes = net.query_sizes(n_streams, max_seg_rows, out_cap_rows)
         self.device = torch.device(device)
         with torch.cuda.device(self.device):
@@ -265,7 +268,7 @@ class Streams:
         import torch
         L = load_library()
         nb = C.c_size_t()
-        _check(L.idf_query_eager_bytes(self.net._h, self.n_streams, C.byref(nb)))
+        _check(L.idf_query_eager_bytes(self.net._h, self.n_streams, self.max_seg_rows, C.byref(nb)))
         self._eager_ws = torch.empty(max(1, nb.value), dtype=torch.uint8, device=self.device)
         _check(L.idf_enable_eager(self._h, C.c_void_p(self._eager_ws.data_ptr()), nb.value))
 
@@ -278,6 +281,26 @@ class Streams:
                           device=self.device)
         _check(load_library().idf_read_announced(self._h, level, ptr, n, C.c_void_p(out.data_ptr())))
         return out
+
+    def read_announced_rows(self, level, row_shape, max_rows, stream_ids=None):
+        """Rows of a level that are still kept: (tensor [n][max_rows][W][C], first row [n], rows [n]);
+        row_shape = (W, C) of that level."""
+        import torch
+        keep, ptr = _ids(stream_ids)
+        n = self.n_streams if stream_ids is None else len(keep)
+        out = torch.zeros((n, max_rows) + tuple(row_shape), dtype=torch.int32 if self.net.precision == "i8" else torch.float32,
+                          device=self.device)
+        first = np.zeros(n, dtype=np.int64); cnt = np.zeros(n, dtype=np.int32)
+        _check(load_library().idf_read_announced_rows(self._h, level, ptr, n, C.c_void_p(out.data_ptr()), max_rows,
+                                                      first.ctypes.data, cnt.ctypes.data))
+        return out, first, cnt
+
+    def eager_state_bytes(self):
+        """(bytes of state and announced values retained per stream, rows kept per level)."""
+        nb = C.c_size_t()
+        rows = np.zeros(len(self.net.layers) + 1, dtype=np.int32)
+        _check(load_library().idf_eager_state_bytes(self._h, C.byref(nb), rows.ctypes.data))
+        return nb.value, rows
 
     def enable_head_units(self, weights, bias=None):
         """weights [n_units][out_h][out_w][out_c] (float32), bias [n_units] or None."""

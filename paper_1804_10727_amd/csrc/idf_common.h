@@ -251,20 +251,28 @@ struct CopyOut {
 };
 
 // One layer's step in eager emission: output rows [o_lo, o_hi) take in the delta rows
-// [i_lo, i_hi) of the layer before.  Per stream every layer keeps whole maps [H][W][C] of 4-byte
-// values: state c, announced value, and the deltas it emitted for the segment in flight.
+// [i_lo, i_hi) of the layer before.  Per stream every level (0 = the input) keeps rows of 4-byte
+// values [rows kept][W][C]: state c (conv layers), announced value, and the deltas it emitted for
+// the segment in flight.  Row r lies in slot r mod (rows kept): a ring of the rows that can still
+// change or be looked at (the cone of Sec. 3), or the whole map when as many rows are kept as the
+// level has.
 struct EagerStep {
     Geom g;                      // unused for the input step
     int layer, n_layers;
     int o_lo, o_hi, i_lo, i_hi;
     int w_out, c_out;            // input step: shape of an input row
     int init_bias;               // the state starts from the bias (first pass of a sample)
+    int fresh_lo;                // rows >= fresh_lo of this level are reached for the first time: state and
+                                 // announced value start from zero whatever their slots hold
+    int in_hi;                   // rows >= in_hi of the level before have not been reached yet: they read as zero
+    int round_bf16;              // announced values are rounded to bfloat16 (events of a bfloat16 net)
+    int in_rows, c_rows, ann_rows, dlt_rows;   // rows kept: of the level before (announced and deltas alike), of this level's maps
     const void *in;              // input step: pushed rows [position][rows][w][c], event type
     int64_t in_stream_stride;
     const void *dlt_in, *ann_in; // maps of the layer before
     int64_t in_map_stride;       // elements per stream of those
     void *c, *ann, *dlt_out;     // this layer's maps
-    int64_t map_stride;
+    int64_t c_stride, ann_stride, dlt_stride;   // elements per stream
     const void *w, *bias;
     unsigned long long *stats;
 };

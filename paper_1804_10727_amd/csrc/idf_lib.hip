@@ -76,6 +76,7 @@ struct StreamHost {
     int64_t head_done = 0;    // output rows the averaging units have taken in
     int64_t head_base = 0;    // first of the rows they average (start of the current sample)
     int x_next = 0;           // columns of the current row received (pixel segments)
+    int64_t eager_rows = 0;   // eager emission: input rows of the sample last presented that the levels have seen
 };
 
 struct ProfRec {
@@ -128,11 +129,16 @@ struct idf_streams {
     std::vector<int64_t> stg_seq;               // rows emitted by unit k so far
     int64_t stg_out_next = 0;                   // output slot of the next completed row
     int stg_tile = kMfmaTile64x64;              // tile shape of the staged launches
-    // eager emission: whole maps per stream and level (0 = input) in a workspace of its own
+    // eager emission: per stream and level (0 = input) rows of state, announced values and deltas in a
+    // workspace of its own -- rings of the rows that can still change or be looked at (nets without
+    // biases) or whole maps
     struct Eager {
         bool on = false;
+        bool ring = false;
         char *ws = nullptr;
-        std::vector<int64_t> elems;               // per level: H*W*C of one stream
+        std::vector<int64_t> row_elems;           // per level: W*C of one row
+        std::vector<int> rows;                    // per level: rows the level has (H)
+        std::vector<int> ann_rows, cd_rows;       // per level: rows kept of the announced values / of state and deltas
         std::vector<size_t> ann_off, c_off, dlt_off;   // per level (c: conv layers only)
     } eager;
     // a pixel segment being pushed: columns [x_lo, x_hi) of the current row of layer 0 (else the whole row)
@@ -860,21 +866,75 @@ template <class F> void for_each_state_piece(const idf_streams *s, int id, F &&f
     f(s->issued_off + (size_t)id * n * sizeof(unsigned long long), (size_t)n * sizeof(unsigned long long));
     f(s->head_off + (size_t)id * net.out_c * sizeof(double), (size_t)net.out_c * sizeof(double));
 }
-// Layout of the eager-emission workspace for B streams; returns its size.
-size_t eager_layout(const idf_net &net, int B, idf_streams::Eager *e)
+// The band of rows of every level that the input rows [a, b) reach: lo[lv], hi[lv] for lv = 0 ..
+// n_layers (level 0 is the input itself).  With `everything` every row of every level.
+void eager_bands(const idf_net &net, int64_t a, int64_t b, bool everything, std::vector<int64_t> &lo, std::vector<int64_t> &hi)
 {
     const int n = (int)net.g.size();
-    std::vector<int64_t> elems(n + 1);
-    elems[0] = (int64_t)net.in_h * net.in_w * net.in_c;
-    for (int l = 0; l < n; ++l) elems[l + 1] = (int64_t)net.g[l].h_out * net.g[l].w_out * net.g[l].c_out;
+    lo.assign(n + 1, 0); hi.assign(n + 1, 0);
+    lo[0] = a; hi[0] = b;
+    for (int l = 0; l < n; ++l) {
+        const Geom &g = net.g[l];
+        int64_t oa = 0, ob = 0;
+        if (b > a) {
+            if (g.kind == IDF_CONV) {
+                // output rows whose footprint meets [a, b)
+                const int64_t t = a + g.p_h - g.k_h + 1;
+                oa = t <= 0 ? 0 : (t + g.s_h - 1) / g.s_h;
+                ob = std::min<int64_t>(g.h_out, (b - 1 + g.p_h) / g.s_h + 1);
+            } else {
+                oa = a / 2; ob = std::min<int64_t>(g.h_out, (b - 1) / 2 + 1);
+            }
+            if (ob < oa) ob = oa;
+        }
+        if (everything) { oa = 0; ob = g.h_out; }
+        lo[l + 1] = oa; hi[l + 1] = ob;
+        a = oa; b = ob;
+    }
+}
+
+// Layout of the eager-emission workspace for B streams pushed at most max_seg rows at a time;
+// returns its size.  Nets without biases keep, per level, a ring of the rows a push can reach plus
+// those a pool still looks at (every other row is final and forgotten, or still all zero); the
+// last level's announced values -- the output -- are kept whole.  With biases every neuron of the
+// net announces a value before any input arrives, so every level is kept whole.
+size_t eager_layout(const idf_net &net, int B, int max_seg, idf_streams::Eager *e)
+{
+    const int n = (int)net.g.size();
+    bool ring = true;
+    for (int l = 0; l < n; ++l) ring = ring && net.b_img[l].empty();
+    std::vector<int64_t> row_elems(n + 1);
+    std::vector<int> rows(n + 1), ann_rows(n + 1), cd_rows(n + 1);
+    row_elems[0] = (int64_t)net.in_w * net.in_c; rows[0] = net.in_h;
+    for (int l = 0; l < n; ++l) { row_elems[l + 1] = (int64_t)net.g[l].w_out * net.g[l].c_out; rows[l + 1] = net.g[l].h_out; }
+    for (int lv = 0; lv <= n; ++lv) ann_rows[lv] = cd_rows[lv] = rows[lv];
+    if (ring) {
+        std::vector<int64_t> need(n + 1, 1), lo, hi;
+        for (int64_t a = 0; a < net.in_h; ++a) {
+            eager_bands(net, a, std::min<int64_t>(a + max_seg, net.in_h), false, lo, hi);
+            for (int lv = 0; lv <= n; ++lv) {
+                int64_t first = lo[lv];
+                // a pool re-evaluates whole windows: it also looks at the row before its band begins
+                if (lv < n && net.g[lv].kind == IDF_MAXPOOL && hi[lv + 1] > lo[lv + 1]) first = std::min(first, 2 * lo[lv + 1]);
+                need[lv] = std::max(need[lv], hi[lv] - first);
+            }
+        }
+        for (int lv = 0; lv <= n; ++lv) {
+            cd_rows[lv] = (int)std::min<int64_t>(rows[lv], need[lv]);
+            ann_rows[lv] = lv == n ? rows[lv] : cd_rows[lv];
+        }
+    }
     size_t off = 0;
     std::vector<size_t> ann(n + 1), c(n + 1, 0), dlt(n + 1);
     for (int lv = 0; lv <= n; ++lv) {
-        ann[lv] = off; off = align_up(off + (size_t)elems[lv] * 4 * B);
-        dlt[lv] = off; off = align_up(off + (size_t)elems[lv] * 4 * B);
-        if (lv > 0 && net.g[lv - 1].kind == IDF_CONV) { c[lv] = off; off = align_up(off + (size_t)elems[lv] * 4 * B); }
+        ann[lv] = off; off = align_up(off + (size_t)ann_rows[lv] * row_elems[lv] * 4 * B);
+        dlt[lv] = off; off = align_up(off + (size_t)cd_rows[lv] * row_elems[lv] * 4 * B);
+        if (lv > 0 && net.g[lv - 1].kind == IDF_CONV) { c[lv] = off; off = align_up(off + (size_t)cd_rows[lv] * row_elems[lv] * 4 * B); }
     }
-    if (e) { e->elems = elems; e->ann_off = ann; e->c_off = c; e->dlt_off = dlt; }
+    if (e) {
+        e->ring = ring; e->row_elems = row_elems; e->rows = rows; e->ann_rows = ann_rows; e->cd_rows = cd_rows;
+        e->ann_off = ann; e->c_off = c; e->dlt_off = dlt;
+    }
     return off;
 }
 
@@ -886,42 +946,48 @@ int eager_pass(idf_streams *s, const StreamSel &sel, const void *dev_rows, int n
     const int n = (int)net.g.size();
     idf_streams::Eager &E = s->eager;
     unsigned long long *stats = (unsigned long long *)(s->ws + s->stats_off);
+    std::vector<int64_t> lo, hi, seen_lo, seen_hi;
+    eager_bands(net, a, b, init_bias, lo, hi);
+    eager_bands(net, 0, a, false, seen_lo, seen_hi);          // seen_hi[lv]: rows of level lv reached before this pass
+    const int round_bf16 = net.precision == IDF_PREC_BF16;
+    auto fresh_from = [&](int lv) { return E.ring ? (int)seen_hi[lv] : (int)E.rows[lv]; };    // whole maps are cleared when a sample begins
     if (dev_rows) {
         EagerStep st{};
         st.layer = 0; st.n_layers = n; st.o_lo = (int)a; st.o_hi = (int)b; st.w_out = net.in_w; st.c_out = net.in_c;
         st.in = dev_rows; st.in_stream_stride = (int64_t)n_rows * net.in_w * net.in_c;
-        st.ann = E.ws + E.ann_off[0]; st.dlt_out = E.ws + E.dlt_off[0]; st.map_stride = E.elems[0];
+        st.ann = E.ws + E.ann_off[0]; st.dlt_out = E.ws + E.dlt_off[0];
+        st.ann_rows = E.ann_rows[0]; st.dlt_rows = E.cd_rows[0];
+        st.ann_stride = (int64_t)E.ann_rows[0] * E.row_elems[0]; st.dlt_stride = (int64_t)E.cd_rows[0] * E.row_elems[0];
+        st.fresh_lo = fresh_from(0);
         st.stats = stats;
         hipError_t e = launch_eager(net.precision, 0, st, sel,
                                     launch_ctx(s, kKindEager, (double)(b - a) * net.in_w * net.in_c * sel.n * 9.0, 0));
         if (e != hipSuccess) return dev_fail(e, "eager input launch");
     }
-    for (int l = 0; l < n && b > a; ++l) {
+    for (int l = 0; l < n && hi[l] > lo[l]; ++l) {
         const Geom &g = net.g[l];
+        if (hi[l + 1] <= lo[l + 1]) break;
         EagerStep st{};
-        st.g = g; st.layer = l; st.n_layers = n; st.i_lo = (int)a; st.i_hi = (int)b; st.init_bias = init_bias;
-        int64_t oa, ob;
-        if (g.kind == IDF_CONV) {
-            // output rows whose footprint meets [a, b)
-            const int64_t t = a + g.p_h - g.k_h + 1;
-            oa = t <= 0 ? 0 : (t + g.s_h - 1) / g.s_h;
-            ob = std::min<int64_t>(g.h_out, (b - 1 + g.p_h) / g.s_h + 1);
-        } else {
-            oa = a / 2; ob = std::min<int64_t>(g.h_out, (b - 1) / 2 + 1);
-        }
-        if (init_bias) { oa = 0; ob = g.h_out; }               // every neuron states its bias
-        st.o_lo = (int)oa; st.o_hi = (int)ob;
-        st.dlt_in = E.ws + E.dlt_off[l]; st.ann_in = E.ws + E.ann_off[l]; st.in_map_stride = E.elems[l];
+        st.g = g; st.layer = l; st.n_layers = n; st.i_lo = (int)lo[l]; st.i_hi = (int)hi[l]; st.init_bias = init_bias;
+        st.o_lo = (int)lo[l + 1]; st.o_hi = (int)hi[l + 1];
+        st.fresh_lo = fresh_from(l + 1);
+        st.in_hi = E.ring ? (int)hi[l] : (int)E.rows[l];
+        st.round_bf16 = round_bf16 && l + 1 < n;              // the last layer's output is not rounded
+        st.dlt_in = E.ws + E.dlt_off[l]; st.ann_in = E.ws + E.ann_off[l];
+        st.in_rows = E.cd_rows[l];                              // (announced values of a level that feeds a layer are kept as long as its deltas)
+        st.in_map_stride = (int64_t)E.cd_rows[l] * E.row_elems[l];
         st.c = g.kind == IDF_CONV ? E.ws + E.c_off[l + 1] : nullptr;
-        st.ann = E.ws + E.ann_off[l + 1]; st.dlt_out = E.ws + E.dlt_off[l + 1]; st.map_stride = E.elems[l + 1];
+        st.ann = E.ws + E.ann_off[l + 1]; st.dlt_out = E.ws + E.dlt_off[l + 1];
+        st.c_rows = st.dlt_rows = E.cd_rows[l + 1]; st.ann_rows = E.ann_rows[l + 1];
+        st.c_stride = st.dlt_stride = (int64_t)E.cd_rows[l + 1] * E.row_elems[l + 1];
+        st.ann_stride = (int64_t)E.ann_rows[l + 1] * E.row_elems[l + 1];
         st.w = g.kind == IDF_CONV ? s->ws + s->w_off[l] : nullptr;
         st.bias = (g.kind == IDF_CONV && !net.b_img[l].empty()) ? s->ws + s->b_off[l] : nullptr;
         st.stats = stats;
-        const double cells = (double)std::max<int64_t>(0, ob - oa) * g.w_out * g.c_out * sel.n;
+        const double cells = (double)(hi[l + 1] - lo[l + 1]) * g.w_out * g.c_out * sel.n;
         hipError_t e = launch_eager(net.precision, g.kind == IDF_CONV ? 1 : 2, st, sel,
                                     launch_ctx(s, kKindEager, cells * 16.0, l));
         if (e != hipSuccess) return dev_fail(e, "eager layer launch");
-        a = oa; b = ob;
     }
     return IDF_OK;
 }
@@ -945,17 +1011,24 @@ int eager_push(idf_streams *s, const int32_t *stream_ids, int n_ids, const void 
     for (auto &kv : groups) {
         const int64_t r = kv.first;
         if (r == 0) {
-            // a sample begins: all state zero (Sec. 3), then the biases announce themselves
+            // a sample begins: all state zero (Sec. 3), then the biases announce themselves.  Rings need
+            // no clearing (a row starts from zero when it is first reached); what is kept whole does.
             int rc0 = for_each_selection(kv.second, [&](const StreamSel &sel) {
                 // streams lie side by side in every map: one fill per map and run of streams
                 for (int k = 0; k < (sel.base >= 0 ? 1 : sel.n); ++k) {
                     const int first = sel.base >= 0 ? sel.base : sel.ids[k], cnt = sel.base >= 0 ? sel.n : 1;
                     for (int lv = 0; lv <= n; ++lv) {
-                        const size_t per = (size_t)E.elems[lv] * 4, at = (size_t)first * per, bytes = per * cnt;
-                        hipError_t e = launch_fill_zero(E.ws + E.ann_off[lv] + at, bytes, s->st);
-                        if (e == hipSuccess) e = launch_fill_zero(E.ws + E.dlt_off[lv] + at, bytes, s->st);
-                        if (e == hipSuccess && lv > 0 && net.g[lv - 1].kind == IDF_CONV)
-                            e = launch_fill_zero(E.ws + E.c_off[lv] + at, bytes, s->st);
+                        hipError_t e = hipSuccess;
+                        if (!E.ring || lv == n) {
+                            const size_t per = (size_t)E.ann_rows[lv] * E.row_elems[lv] * 4;
+                            e = launch_fill_zero(E.ws + E.ann_off[lv] + (size_t)first * per, per * cnt, s->st);
+                        }
+                        if (!E.ring) {
+                            const size_t per = (size_t)E.cd_rows[lv] * E.row_elems[lv] * 4, at = (size_t)first * per;
+                            if (e == hipSuccess) e = launch_fill_zero(E.ws + E.dlt_off[lv] + at, per * cnt, s->st);
+                            if (e == hipSuccess && lv > 0 && net.g[lv - 1].kind == IDF_CONV)
+                                e = launch_fill_zero(E.ws + E.c_off[lv] + at, per * cnt, s->st);
+                        }
                         if (e != hipSuccess) return dev_fail(e, "eager reset");
                     }
                 }
@@ -975,6 +1048,7 @@ int eager_push(idf_streams *s, const int32_t *stream_ids, int n_ids, const void 
     for (int i = 0; i < n_ids; ++i) {
         StreamHost &h = s->h[stream_ids ? stream_ids[i] : i];
         h.r += n_rows;
+        h.eager_rows = h.r;                      // rows of the current sample the levels have seen
         if (h.r == net.in_h) h.r = 0;
     }
     return IDF_OK;
@@ -1623,12 +1697,11 @@ int idf_restore(idf_streams *s, int stream_id, const void *dev_buf, const idf_st
     return IDF_OK;
 }
 
-int idf_query_eager_bytes(const idf_net *net, int n_streams, size_t *bytes)
+int idf_query_eager_bytes(const idf_net *net, int n_streams, int max_seg_rows, size_t *bytes)
 {
-    if (!net || !bytes || n_streams < 1) return fail(IDF_EINVAL, "bad argument");
-    if (net->in_h <= 0) return fail(IDF_EUNSUPPORTED, "eager emission keeps whole maps: the sample height must be known");
-    if (net->precision == IDF_PREC_BF16) return fail(IDF_EUNSUPPORTED, "eager emission is built for float32 and int8 nets");
-    *bytes = eager_layout(*net, n_streams, nullptr);
+    if (!net || !bytes || n_streams < 1 || max_seg_rows < 1) return fail(IDF_EINVAL, "bad argument");
+    if (net->in_h <= 0) return fail(IDF_EUNSUPPORTED, "eager emission keeps the output map whole: the sample height must be known");
+    *bytes = eager_layout(*net, n_streams, max_seg_rows, nullptr);
     return IDF_OK;
 }
 
@@ -1636,15 +1709,32 @@ int idf_enable_eager(idf_streams *s, void *dev_workspace, size_t workspace_bytes
 {
     if (!s || !dev_workspace) return fail(IDF_EINVAL, "null argument");
     size_t need = 0;
-    int rc = idf_query_eager_bytes(s->net, s->B, &need);
+    int rc = idf_query_eager_bytes(s->net, s->B, s->max_seg, &need);
     if (rc != IDF_OK) return rc;
     if (workspace_bytes < need) return fail(IDF_EINVAL, "eager workspace of %zu bytes, %zu needed", workspace_bytes, need);
     if (s->head_on) return fail(IDF_EUNSUPPORTED, "the averaging units read completed rows, eager emission has none");
     for (const StreamHost &h : s->h)
         if (h.r != 0 || h.out_written != 0 || h.x_next != 0) return fail(IDF_ESTATE, "eager emission must be enabled before the first push");
-    eager_layout(*s->net, s->B, &s->eager);
+    eager_layout(*s->net, s->B, s->max_seg, &s->eager);
     s->eager.ws = (char *)dev_workspace;
     s->eager.on = true;
+    return IDF_OK;
+}
+
+int idf_eager_state_bytes(const idf_streams *s, size_t *per_stream, int *rows_kept)
+{
+    if (!s || !per_stream) return fail(IDF_EINVAL, "null argument");
+    if (!s->eager.on) return fail(IDF_ESTATE, "eager emission is not enabled");
+    const idf_streams::Eager &E = s->eager;
+    const int n = (int)s->net->g.size();
+    size_t total = 0;
+    for (int lv = 0; lv <= n; ++lv) {
+        const bool has_c = lv > 0 && s->net->g[lv - 1].kind == IDF_CONV;
+        // state c and the announced values; the deltas live only during a push, the last level's announced map is the output
+        total += (size_t)E.row_elems[lv] * 4 * ((has_c ? E.cd_rows[lv] : 0) + (lv < n ? E.ann_rows[lv] : 0));
+        if (rows_kept) rows_kept[lv] = E.cd_rows[lv];
+    }
+    *per_stream = total;
     return IDF_OK;
 }
 
@@ -1654,14 +1744,49 @@ int idf_read_announced(idf_streams *s, int level, const int32_t *stream_ids, int
     if (!s->eager.on) return fail(IDF_ESTATE, "eager emission is not enabled");
     const int n = (int)s->net->g.size();
     if (level < 0 || level > n) return fail(IDF_EINVAL, "level %d outside [0, %d]", level, n);
+    if (s->eager.ring && level != n)
+        return fail(IDF_ESTATE, "level %d keeps a ring of %d rows, not its whole map: read them with idf_read_announced_rows", level,
+                    s->eager.ann_rows[level]);
     int rc = check_ids(s, stream_ids, n_ids);
     if (rc != IDF_OK) return rc;
-    const size_t bytes = (size_t)s->eager.elems[level] * 4;
+    const size_t bytes = (size_t)s->eager.rows[level] * s->eager.row_elems[level] * 4;
     for (int i = 0; i < n_ids; ++i) {
         const int id = stream_ids ? stream_ids[i] : i;
         hipError_t e = hipMemcpyAsync((char *)dev_out + (size_t)i * bytes, s->eager.ws + s->eager.ann_off[level] + (size_t)id * bytes,
                                       bytes, hipMemcpyDeviceToDevice, s->st);
         if (e != hipSuccess) return dev_fail(e, "read_announced");
+    }
+    return IDF_OK;
+}
+
+int idf_read_announced_rows(idf_streams *s, int level, const int32_t *stream_ids, int n_ids, void *dev_out, int max_rows,
+                            int64_t *first_row, int32_t *n_rows)
+{
+    if (!s || !dev_out || !first_row || !n_rows) return fail(IDF_EINVAL, "null argument");
+    if (!s->eager.on) return fail(IDF_ESTATE, "eager emission is not enabled");
+    const idf_streams::Eager &E = s->eager;
+    const int n = (int)s->net->g.size();
+    if (level < 0 || level > n) return fail(IDF_EINVAL, "level %d outside [0, %d]", level, n);
+    if (max_rows < 1) return fail(IDF_EINVAL, "max_rows must be >= 1");
+    int rc = check_ids(s, stream_ids, n_ids);
+    if (rc != IDF_OK) return rc;
+    const size_t row_bytes = (size_t)E.row_elems[level] * 4;
+    std::vector<int64_t> lo, hi;
+    for (int i = 0; i < n_ids; ++i) {
+        const int id = stream_ids ? stream_ids[i] : i;
+        // rows of the level reached by the input rows seen so far; the newest `rows kept` of them are still there
+        eager_bands(*s->net, 0, s->h[id].eager_rows, false, lo, hi);
+        const bool whole = !E.ring || level == n;             // kept whole and cleared when the sample began
+        const int64_t reached = whole ? (s->h[id].eager_rows > 0 ? E.rows[level] : 0) : hi[level];
+        const int64_t first = whole ? 0 : std::max<int64_t>(0, reached - E.ann_rows[level]);
+        const int64_t cnt = std::min<int64_t>(reached - first, max_rows);
+        first_row[i] = first; n_rows[i] = (int32_t)cnt;
+        const char *src = s->eager.ws + E.ann_off[level] + (size_t)id * E.ann_rows[level] * row_bytes;
+        for (int64_t r = first; r < first + cnt; ++r) {         // (a ring wraps: row by row)
+            hipError_t e = hipMemcpyAsync((char *)dev_out + ((size_t)i * max_rows + (size_t)(r - first)) * row_bytes,
+                                          src + (size_t)(r % E.ann_rows[level]) * row_bytes, row_bytes, hipMemcpyDeviceToDevice, s->st);
+            if (e != hipSuccess) return dev_fail(e, "read_announced_rows");
+        }
     }
     return IDF_OK;
 }

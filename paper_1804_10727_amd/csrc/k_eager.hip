@@ -10,10 +10,11 @@
 // each cell of the band a layer can reach gathers w * delta over its footprint inside the band
 // of the layer before (zero deltas are skipped), announces f(c) minus what it announced last, and
 // writes that difference into its own delta band.  A max-pool is a stateful node that
-// re-evaluates its window of announced values.  Whole feature maps of c and of the announced
-// values are kept per stream (a ring of cone rows would do; this mode is about the output being
-// valid after every segment, not about the footprint).  All values are 4 bytes: float32, or
-// int32 for the quantised nets.
+// re-evaluates its window of announced values.  Per stream and level the rows that can still
+// change or be looked at are kept in a ring (row r in slot r mod rows kept: the cone of Sec. 3),
+// or every row when the net has biases; a row reached for the first time starts from zero
+// whatever its slot held.  All values are 4 bytes: float32, or int32 for the quantised nets; a
+// bfloat16 net announces values rounded to bfloat16 (the last layer unrounded).
 #include "idf.h"
 #include "idf_kernels.h"
 
@@ -21,15 +22,31 @@ namespace idf {
 
 namespace {
 
-template <bool INT> struct Val;
-template <> struct Val<false> {
-    using t = float; using w_t = float;
-    static __device__ __forceinline__ t act(const Geom &g, t c) { return g.act == IDF_ACT_NONE ? c : fmaxf(c, 0.f); }
+enum { kF32 = 0, kI8 = 1, kBf16 = 2 };
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+template <int P> struct Val;
+template <> struct Val<kF32> {
+    using t = float; using w_t = float; using in_t = float;
+    static __device__ __forceinline__ t from_in(in_t v) { return v; }
+    static __device__ __forceinline__ t act(const Geom &g, t c, int) { return g.act == IDF_ACT_NONE ? c : fmaxf(c, 0.f); }
     static __device__ __forceinline__ t mac(t acc, t d, w_t w) { return fmaf(d, w, acc); }
 };
-template <> struct Val<true> {
-    using t = int32_t; using w_t = int8_t;
-    static __device__ __forceinline__ t act(const Geom &g, t c)
+template <> struct Val<kBf16> {
+    using t = float; using w_t = uint16_t; using in_t = uint16_t;
+    static __device__ __forceinline__ t from_in(in_t v) { return bf16_bits_to_float(v); }
+    static __device__ __forceinline__ t act(const Geom &g, t c, int round)
+    {
+        const t h = g.act == IDF_ACT_NONE ? c : fmaxf(c, 0.f);
+        return round ? (t)(__bf16)h : h;                        // to nearest, ties to even
+    }
+    static __device__ __forceinline__ t mac(t acc, t d, w_t w) { return fmaf(d, bf16_bits_to_float(w), acc); }
+};
+template <> struct Val<kI8> {
+    using t = int32_t; using w_t = int8_t; using in_t = int8_t;
+    static __device__ __forceinline__ t from_in(in_t v) { return v; }
+    static __device__ __forceinline__ t act(const Geom &g, t c, int)
     {
         if (g.act == IDF_ACT_NONE) return c;
         t r = c > 0 ? c : 0;
@@ -47,20 +64,23 @@ __device__ __forceinline__ void count_events(bool nz, unsigned long long *dst)
 }
 
 // The pushed rows become the announced input; what changed goes out as the input's events.
-template <bool INT, class IN>
+template <int P>
 __global__ void __launch_bounds__(256) k_eager_input(const EagerStep a, const StreamSel sel)
 {
-    using V = Val<INT>;
+    using V = Val<P>;
+    using val_t = typename V::t;
     const int stream = sel_stream(sel, blockIdx.z);
     const int64_t row_elems = (int64_t)a.w_out * a.c_out, n = (int64_t)(a.o_hi - a.o_lo) * row_elems;
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     bool nz = false;
     if (i < n) {
-        const IN *in = (const IN *)a.in + (int64_t)(sel.pos0 + blockIdx.z) * a.in_stream_stride;
-        typename V::t *ann = (typename V::t *)a.ann + (int64_t)stream * a.map_stride + a.o_lo * row_elems;
-        typename V::t *dlt = (typename V::t *)a.dlt_out + (int64_t)stream * a.map_stride + a.o_lo * row_elems;
-        const typename V::t v = (typename V::t)in[i], d = v - ann[i];
-        ann[i] = v; dlt[i] = d;
+        const typename V::in_t *in = (const typename V::in_t *)a.in + (int64_t)(sel.pos0 + blockIdx.z) * a.in_stream_stride;
+        const int row = a.o_lo + (int)(i / row_elems);
+        const int64_t col = i - (int64_t)(row - a.o_lo) * row_elems;
+        val_t *ann = (val_t *)a.ann + (int64_t)stream * a.ann_stride + (int64_t)(row % a.ann_rows) * row_elems + col;
+        val_t *dlt = (val_t *)a.dlt_out + (int64_t)stream * a.dlt_stride + (int64_t)(row % a.dlt_rows) * row_elems + col;
+        const val_t v = V::from_in(in[i]), d = v - (row >= a.fresh_lo ? (val_t)0 : *ann);
+        *ann = v; *dlt = d;
         nz = d != 0;
     }
     count_events(nz, a.stats ? a.stats + ((int64_t)stream * a.n_layers + a.layer) * 2 : nullptr);
@@ -73,10 +93,10 @@ __global__ void __launch_bounds__(256) k_eager_input(const EagerStep a, const St
 // non-zero values is the list of events, and only those are visited: the value comes from the lane
 // that holds it, the weight from memory, one multiply-add per cell.  A zero costs nothing but its
 // share of that one read.  The order of the additions is that of the footprint (ky, kx, channel).
-template <bool INT>
+template <int P>
 __global__ void __launch_bounds__(256) k_eager_conv(const EagerStep a, const StreamSel sel)
 {
-    using V = Val<INT>;
+    using V = Val<P>;
     using val_t = typename V::t;
     const Geom &g = a.g;
     const int stream = sel_stream(sel, blockIdx.z);
@@ -98,8 +118,12 @@ __global__ void __launch_bounds__(256) k_eager_conv(const EagerStep a, const Str
     const int co_c = co < g.c_out ? co : g.c_out - 1;
     const val_t *din = (const val_t *)a.dlt_in + (int64_t)stream * a.in_map_stride;
     const typename V::w_t *w = (const typename V::w_t *)a.w;
-    const int64_t cell = (int64_t)stream * a.map_stride + ((int64_t)o * g.w_out + x) * g.c_out + co_c;
-    val_t c = a.init_bias ? (a.bias ? ((const val_t *)a.bias)[co_c] : (val_t)0) : ((val_t *)a.c)[cell];
+    const int64_t in_row = (int64_t)x * g.c_out + co_c;         // cell within its row
+    const int64_t c_cell = (int64_t)stream * a.c_stride + (int64_t)(o % a.c_rows) * g.w_out * g.c_out + in_row;
+    const int64_t ann_cell = (int64_t)stream * a.ann_stride + (int64_t)(o % a.ann_rows) * g.w_out * g.c_out + in_row;
+    const int64_t dlt_cell = (int64_t)stream * a.dlt_stride + (int64_t)(o % a.dlt_rows) * g.w_out * g.c_out + in_row;
+    const bool fresh = o >= a.fresh_lo;                         // reached for the first time: starts from zero
+    val_t c = a.init_bias ? (a.bias ? ((const val_t *)a.bias)[co_c] : (val_t)0) : (fresh ? (val_t)0 : ((val_t *)a.c)[c_cell]);
     const unsigned long long gbits = G == 64 ? ~0ull : ((1ull << G) - 1ull);
     for (int ky = 0; ky < g.k_h; ++ky) {
         const int iy = o * g.s_h - g.p_h + ky;
@@ -108,7 +132,7 @@ __global__ void __launch_bounds__(256) k_eager_conv(const EagerStep a, const Str
             const int ix = x * g.s_w - g.p_w + kx;
             const bool tap_ok = row_ok && ix >= 0 && ix < g.w_in;
             if (__ballot(tap_ok) == 0ull) continue;
-            const val_t *dp = din + ((int64_t)(tap_ok ? iy : a.i_lo) * g.w_in + (tap_ok ? ix : 0)) * g.c_in;
+            const val_t *dp = din + ((int64_t)((tap_ok ? iy : a.i_lo) % a.in_rows) * g.w_in + (tap_ok ? ix : 0)) * g.c_in;
             const typename V::w_t *wp = w + ((int64_t)(ky * g.k_w + kx) * g.c_in) * g.c_out + co_c;
             for (int j0 = 0; j0 < g.c_in; j0 += G) {
                 const val_t dv = (tap_ok && j0 + col < g.c_in) ? dp[j0 + col] : (val_t)0;
@@ -140,20 +164,20 @@ __global__ void __launch_bounds__(256) k_eager_conv(const EagerStep a, const Str
     }
     bool nz = false;
     if (mine) {
-        ((val_t *)a.c)[cell] = c;
-        const val_t h = V::act(g, c), d = h - ((val_t *)a.ann)[cell];
-        ((val_t *)a.ann)[cell] = h;
-        ((val_t *)a.dlt_out)[cell] = d;
+        ((val_t *)a.c)[c_cell] = c;
+        const val_t h = V::act(g, c, a.round_bf16), d = h - (fresh && !a.init_bias ? (val_t)0 : ((val_t *)a.ann)[ann_cell]);
+        ((val_t *)a.ann)[ann_cell] = h;
+        ((val_t *)a.dlt_out)[dlt_cell] = d;
         nz = d != 0;
     }
     count_events(nz, a.stats && a.layer + 1 < a.n_layers ? a.stats + ((int64_t)stream * a.n_layers + a.layer + 1) * 2 : nullptr);
 }
 
 // 2x2 max-pool as a stateful node: re-evaluates its window of announced values.
-template <bool INT>
+template <int P>
 __global__ void __launch_bounds__(256) k_eager_pool(const EagerStep a, const StreamSel sel)
 {
-    using val_t = typename Val<INT>::t;
+    using val_t = typename Val<P>::t;
     const Geom &g = a.g;
     const int stream = sel_stream(sel, blockIdx.z);
     const int64_t n = (int64_t)(a.o_hi - a.o_lo) * g.w_out * g.c_out;
@@ -164,16 +188,22 @@ __global__ void __launch_bounds__(256) k_eager_pool(const EagerStep a, const Str
         const int64_t pos = i / g.c_out;
         const int x = (int)(pos % g.w_out), o = a.o_lo + (int)(pos / g.w_out);
         const val_t *ain = (const val_t *)a.ann_in + (int64_t)stream * a.in_map_stride;
-        val_t m = ain[((int64_t)(2 * o) * g.w_in + x * g.s_w) * g.c_out + ch];
+        // a row of the window that has not been reached yet announces zero (the net starts from zero state)
+        bool first = true;
+        val_t m = 0;
         for (int dy = 0; dy < 2; ++dy)
             for (int dx = 0; dx < g.k_w; ++dx) {
-                const val_t v = ain[((int64_t)(2 * o + dy) * g.w_in + x * g.s_w + dx) * g.c_out + ch];
-                m = v > m ? v : m;
+                const int r = 2 * o + dy;
+                const val_t v = r >= a.in_hi ? (val_t)0 : ain[((int64_t)(r % a.in_rows) * g.w_in + x * g.s_w + dx) * g.c_out + ch];
+                m = (first || v > m) ? v : m;
+                first = false;
             }
-        const int64_t cell = (int64_t)stream * a.map_stride + ((int64_t)o * g.w_out + x) * g.c_out + ch;
-        const val_t d = m - ((val_t *)a.ann)[cell];
-        ((val_t *)a.ann)[cell] = m;
-        ((val_t *)a.dlt_out)[cell] = d;
+        const int64_t in_row = (int64_t)x * g.c_out + ch;
+        const int64_t ann_cell = (int64_t)stream * a.ann_stride + (int64_t)(o % a.ann_rows) * g.w_out * g.c_out + in_row;
+        const int64_t dlt_cell = (int64_t)stream * a.dlt_stride + (int64_t)(o % a.dlt_rows) * g.w_out * g.c_out + in_row;
+        const val_t d = m - (o >= a.fresh_lo && !a.init_bias ? (val_t)0 : ((val_t *)a.ann)[ann_cell]);
+        ((val_t *)a.ann)[ann_cell] = m;
+        ((val_t *)a.dlt_out)[dlt_cell] = d;
         nz = d != 0;
     }
     count_events(nz, a.stats && a.layer + 1 < a.n_layers ? a.stats + ((int64_t)stream * a.n_layers + a.layer + 1) * 2 : nullptr);
@@ -187,7 +217,6 @@ hipError_t launch_eager(int prec, int what, const EagerStep &a, const StreamSel 
     if (n <= 0) return hipSuccess;
     dim3 grid((unsigned)((n + 255) / 256), 1, sel.n);
     const dim3 block(256);
-    const bool is_int = prec == IDF_PREC_I8;
     if (what == 1) {
         // a group of G lanes per (position, chunk of G channels): see k_eager_conv
         int G = 16;
@@ -196,16 +225,19 @@ hipError_t launch_eager(int prec, int what, const EagerStep &a, const StreamSel 
         const int per_block = 4 * (64 / G);
         grid.x = (unsigned)((units + per_block - 1) / per_block);
     }
-    if (what == 0) {
-        if (is_int) return launch(k_eager_input<true, int8_t>, grid, block, 0, lc, a, sel);
-        return launch(k_eager_input<false, float>, grid, block, 0, lc, a, sel);
+    if (prec == IDF_PREC_I8) {
+        if (what == 0) return launch(k_eager_input<kI8>, grid, block, 0, lc, a, sel);
+        if (what == 1) return launch(k_eager_conv<kI8>, grid, block, 0, lc, a, sel);
+        return launch(k_eager_pool<kI8>, grid, block, 0, lc, a, sel);
     }
-    if (what == 1) {
-        if (is_int) return launch(k_eager_conv<true>, grid, block, 0, lc, a, sel);
-        return launch(k_eager_conv<false>, grid, block, 0, lc, a, sel);
+    if (prec == IDF_PREC_BF16) {
+        if (what == 0) return launch(k_eager_input<kBf16>, grid, block, 0, lc, a, sel);
+        if (what == 1) return launch(k_eager_conv<kBf16>, grid, block, 0, lc, a, sel);
+        return launch(k_eager_pool<kBf16>, grid, block, 0, lc, a, sel);
     }
-    if (is_int) return launch(k_eager_pool<true>, grid, block, 0, lc, a, sel);
-    return launch(k_eager_pool<false>, grid, block, 0, lc, a, sel);
+    if (what == 0) return launch(k_eager_input<kF32>, grid, block, 0, lc, a, sel);
+    if (what == 1) return launch(k_eager_conv<kF32>, grid, block, 0, lc, a, sel);
+    return launch(k_eager_pool<kF32>, grid, block, 0, lc, a, sel);
 }
 
 }  // namespace idf

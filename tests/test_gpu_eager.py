@@ -41,7 +41,7 @@ def _tiny(prec, seed, layers, H, W, C0, with_bias):
                 seg_rows=1, streams=2)
 
 
-@pytest.mark.parametrize("prec,with_bias", [("f32", True), ("f32", False), ("i8", True)])
+@pytest.mark.parametrize("prec,with_bias", [("f32", True), ("f32", False), ("i8", True), ("i8", False)])
 def test_every_layer_after_every_row_against_the_literal_scheme(prec, with_bias):
     import torch
     import paper_1804_10727_amd as idf
@@ -57,18 +57,41 @@ def test_every_layer_after_every_row_against_the_literal_scheme(prec, with_bias)
     x = input_tensor(wl)
     dt = np.int64 if prec == "i8" else np.float64
     refs = [EagerNet(layers, 10, 8, 2, wl["weights"], wl["biases"], dtype=dt) for _ in range(2)]
+    nb, kept = st.eager_state_bytes()
+    whole = [shp[lv][0] for lv in range(len(layers) + 1)]
+    if with_bias:
+        assert kept.tolist() == whole                 # every neuron announces its bias before any input: all levels whole
+    else:
+        # the cone: the pushed row; the 3 rows it reaches in the first layer plus one the pool still looks at;
+        # 2 pooled rows; the 4 rows those reach; the last level has 2 rows in all
+        assert kept.tolist() == [1, 4, 2, 4, 2]
+        assert nb < sum(4 * (2 if lv in (0, 2) else 3) * shp[lv][0] * shp[lv][1] * shp[lv][2] for lv in range(4))
     for r in range(10):
         st.push_segment(x[:, r:r + 1].contiguous())
         for b in range(2):
             refs[b].present_row(r, wl["x"][b, r])
         for lv in range(len(layers) + 1):
-            got = st.read_announced(lv, shp[lv]).cpu().numpy()
+            got, first, cnt = st.read_announced_rows(lv, shp[lv][1:], shp[lv][0])
+            got = got.cpu().numpy()
             for b in range(2):
+                lo, n = int(first[b]), int(cnt[b])
                 want = refs[b].announced[lv]
+                assert n >= 1, (r, lv)
                 if prec == "i8":
-                    assert np.array_equal(got[b].astype(np.int64), want), (r, lv, b)
+                    assert np.array_equal(got[b, :n].astype(np.int64), want[lo:lo + n]), (r, lv, b)
                 else:
-                    assert np.max(np.abs(got[b] - want)) <= 1e-5 * max(1.0, np.max(np.abs(want))), (r, lv, b)
+                    assert np.max(np.abs(got[b, :n] - want[lo:lo + n])) <= 1e-5 * max(1.0, np.max(np.abs(want))), (r, lv, b)
+                if not with_bias:
+                    assert not want[lo + n:].any(), (r, lv, b)      # rows not reached yet are all zero: nothing to keep
+                elif lv == len(layers):
+                    assert lo == 0 and n == shp[lv][0]
+        # the output (last level) is also there as a whole map
+        got = st.read_announced(len(layers), shp[-1]).cpu().numpy()
+        for b in range(2):
+            assert np.max(np.abs(got[b].astype(np.float64) - refs[b].announced[-1])) <= 1e-5 * max(1.0, np.max(np.abs(refs[b].announced[-1])))
+    if not with_bias:
+        with pytest.raises(idf.IdfError):
+            st.read_announced(1, shp[1])                 # an inner level is a ring, not a map
     ev = st.get_stats(0)["events_in"]
     assert ev[0] == np.count_nonzero(wl["x"][0]) and (ev[1:] > 0).all()
     with pytest.raises(idf.IdfError):
@@ -80,6 +103,8 @@ def test_every_layer_after_every_row_against_the_literal_scheme(prec, with_bias)
     (3, dict(streams=3, size=16, channels=(8, 8, 16, 16)), 1),
     (3, dict(streams=2, size=16, channels=(8, 8, 16, 16)), 3),
     (4, dict(streams=2, size=24, channels=(4, 4, 8, 8, 16, 16, 16, 16)), 2),
+    (5, dict(streams=2, size=24, channels=(8, 8, 16, 16, 16, 16, 16)), 1),
+    (5, dict(streams=2, size=24, channels=(8, 8, 16, 16, 16, 16, 16)), 5),
 ])
 def test_output_after_a_prefix_is_the_network_on_the_prefix(cfg, kw, seg):
     import paper_1804_10727_amd as idf
@@ -100,15 +125,23 @@ def test_output_after_a_prefix_is_the_network_on_the_prefix(cfg, kw, seg):
         for b in range(B):
             xp = wl["x"][b].copy()
             xp[r + seg:] = 0
-            want = oracle.dense(wl["layers"], xp, wl["weights"], wl["biases"], integer=wl["precision"] == "i8")
+            bf16 = wl["precision"] == "bf16"
+            want = oracle.dense(wl["layers"], xp, wl["weights"], wl["biases"], integer=wl["precision"] == "i8",
+                                emit_round="bf16" if bf16 else None)
             if wl["precision"] == "i8":
                 assert np.array_equal(got[b].astype(np.int64), want), (i, b)
             else:
-                assert np.max(np.abs(got[b] - want)) <= TOL["f32"] * max(np.max(np.abs(want)), 1e-30), (i, b)
+                tol = TOL["bf16_emul"] if bf16 else TOL["f32"]
+                assert np.max(np.abs(got[b] - want)) <= tol * max(np.max(np.abs(want)), 1e-30), (i, b)
+                if bf16:        # and within the wider bound of the net that rounds nothing
+                    true = oracle.dense(wl["layers"], xp, wl["weights"], wl["biases"])
+                    assert np.max(np.abs(got[b] - true)) <= TOL["bf16_true"] * max(np.max(np.abs(true)), 1e-30), (i, b)
     # second sample in the same streams: everything starts from zero again
     st.push_segment(x[:, 0:seg].contiguous())
     got = st.read_announced(len(wl["layers"]), shp[-1]).cpu().numpy()
     xp = wl["x"][0].copy(); xp[seg:] = 0
-    want = oracle.dense(wl["layers"], xp, wl["weights"], wl["biases"], integer=wl["precision"] == "i8")
-    assert np.max(np.abs(got[0].astype(np.float64) - want)) <= TOL["f32"] * max(np.max(np.abs(want)), 1e-30)
+    want = oracle.dense(wl["layers"], xp, wl["weights"], wl["biases"], integer=wl["precision"] == "i8",
+                        emit_round="bf16" if wl["precision"] == "bf16" else None)
+    tol = TOL["bf16_emul"] if wl["precision"] == "bf16" else TOL["f32"]
+    assert np.max(np.abs(got[0].astype(np.float64) - want)) <= tol * max(np.max(np.abs(want)), 1e-30)
     st.close(); net.destroy()

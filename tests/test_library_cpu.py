@@ -157,16 +157,49 @@ def test_query_sizes_errors():
 def test_eager_workspace_size_and_refusals():
     import ctypes as C
     L = idf.load_library()
-    wl = wl_mod.make(3, streams=2, size=8, channels=(4, 4, 4, 4))
-    net = idf.net_from_workload(wl)
     nb = C.c_size_t()
-    assert L.idf_query_eager_bytes(net._h, 2, C.byref(nb)) == 0
-    # announced value and delta per level (input + 5 layers), state for the 4 conv layers, 4 bytes each
+    # a net with a bias keeps every level whole: announced value and delta per level (input + 5
+    # layers), state for the 4 conv layers, 4 bytes each
+    wl = wl_mod.make(3, streams=2, size=8, channels=(4, 4, 4, 4))
+    wl["biases"][0] = np.zeros(4, dtype=np.float32)
+    net = idf.net_from_workload(wl)
+    assert L.idf_query_eager_bytes(net._h, 2, 1, C.byref(nb)) == 0
     maps = [8 * 8 * 3, 8 * 8 * 4, 8 * 8 * 4, 4 * 4 * 4, 4 * 4 * 4, 4 * 4 * 4]
     least = 2 * 4 * (2 * sum(maps) + maps[1] + maps[2] + maps[4] + maps[5])
     assert least <= nb.value <= least + 20 * 256
     net.destroy()
     wl1 = wl_mod.make(2, streams=1, length=200, channels=(4, 4, 4, 4, 4, 4))
-    net1 = idf.Net("f32", 0, 1, 1, wl1["layers"], wl1["weights"])       # unbounded: no whole maps
-    assert L.idf_query_eager_bytes(net1._h, 1, C.byref(nb)) == binding.IDF_EUNSUPPORTED
+    net1 = idf.Net("f32", 0, 1, 1, wl1["layers"], wl1["weights"])       # unbounded: no output map to keep
+    assert L.idf_query_eager_bytes(net1._h, 1, 1, C.byref(nb)) == binding.IDF_EUNSUPPORTED
     net1.destroy()
+
+
+def test_eager_rings_do_not_grow_with_the_sample_height():
+    """Without biases eager emission keeps per level only the cone of rows a later segment can still
+    reach (Sec. 3: a single input component reaches a patch that widens by K-1 per layer; Sec. 3
+    last paragraph, Fig. 2: a row of cones for 2-D input): everything but the output map, which is
+    kept whole, is independent of the height and grows with the rows pushed at once."""
+    import ctypes as C
+    L = idf.load_library()
+
+    def need(size_h, seg):
+        wl = wl_mod.make(3, streams=1, size=16, channels=(4, 4, 4, 4))
+        # same net on a taller sample: only in_h differs
+        net = idf.Net("f32", size_h, 16, 3, wl["layers"], wl["weights"], wl["biases"])
+        nb = C.c_size_t()
+        assert L.idf_query_eager_bytes(net._h, 1, seg, C.byref(nb)) == 0
+        out_map = (size_h // 2) * 8 * 4 * 4                     # last level's announced values, kept whole
+        net.destroy()
+        return nb.value, out_map
+    a, oa = need(32, 1)
+    b, ob = need(64, 1)
+    c, oc = need(64, 4)
+    assert abs((b - ob) - (a - oa)) <= 16 * 256                 # (alignment of the pieces aside)
+    assert c > b
+    # rows kept at depth n of 3 x 3 layers: 1 + 2 n cone rows (one push of one row), halved by the pool
+    # level: 0 input, 1 conv, 2 conv, 3 pool, 4 conv, 5 conv
+    cone = [1, 3, 5, 3, 5, 7]
+    row = [16 * 3, 16 * 4, 16 * 4, 8 * 4, 8 * 4, 8 * 4]
+    # announced + delta per level, state for conv levels; level 2 keeps one more row for the pool's window
+    least = sum(4 * r * k * (3 if lv in (1, 2, 4, 5) else 2) for lv, (r, k) in enumerate(zip(row, cone))) - 4 * row[5] * cone[5]
+    assert least <= a - oa <= 2 * least + 16 * 256
