@@ -200,7 +200,7 @@ def cpu_baseline(wl, budget_s=12.0):
                       f"scalar event-by-event fp64/int64, one stream per thread, {dt:.1f} s"}
 
 
-def run_workload(config, steps_arg=None, warmup_arg=None, eager=False):
+def run_workload(config, steps_arg=None, warmup_arg=None, eager=False, push_batch=1):
     """Times `steps` whole batches of one workload; returns (result dict, workload)."""
     import numpy as np
     import torch
@@ -221,6 +221,8 @@ def run_workload(config, steps_arg=None, warmup_arg=None, eager=False):
     st = idf.Streams(net, B, max_seg_rows=seg, device=dev)
     if eager:
         st.enable_eager()
+    if push_batch > 1:          # throughput mode of the 1-D cascade: several pushes in step share a launch
+        st.set_push_batching(push_batch)
     x = input_tensor(wl, dev)
     # segment-major copy in HBM: xs[i] is the contiguous block [B][seg][W][C] of push i
     xs = x.view(B, n_seg, seg, W, C0).permute(1, 0, 2, 3, 4).contiguous()
@@ -323,7 +325,7 @@ def run_workload(config, steps_arg=None, warmup_arg=None, eager=False):
         "warmup": warmup, "ms_per_step": ms_per_step, "host_enqueue_ms_per_step": t_enq / steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": DTYPE[wl["precision"]], "data": "synthetic",
         "config": {"workload": WORKLOADS[config] + ("_eager_emission" if eager else ""), "streams": B, "rows_per_sample": H, "row_width": W,
-                   "in_channels": C0, "rows_per_push": seg, "pushes_per_step": n_seg,
+                   "in_channels": C0, "rows_per_push": seg, "pushes_per_step": n_seg, "pushes_per_launch": push_batch,
                    "layers": len(wl["layers"]),
                    # rolling buffers + held rows (what the paper bounds), the rows waiting between layers
                    # across calls in the staged mode that was timed, and their sum
@@ -373,6 +375,8 @@ def main():
     ap.add_argument("--config", type=int, default=5,
                     help="workload 1..5 (default 5: the largest configuration, 64 streams of 224x224x3 bfloat16)")
     ap.add_argument("--eager", action="store_true", help="eager emission (configs 3 and 4): output valid after every push")
+    ap.add_argument("--push-batch", type=int, default=1,
+                    help="1-D workloads: hold back up to this many pushes in step per launch (throughput mode; 1 = a launch per push)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", dest="others", action="store_false",
                     help="skip the short runs of the other workloads (reported under other_workloads)")
@@ -401,7 +405,7 @@ def main():
 
     import torch
     assert torch.cuda.is_available(), "bench.py needs the GPU"
-    res, wl = run_workload(args.config, args.steps, args.warmup, eager=args.eager)
+    res, wl = run_workload(args.config, args.steps, args.warmup, eager=args.eager, push_batch=args.push_batch)
     if args.eager:
         print(json.dumps(res))
         return
@@ -416,6 +420,9 @@ def main():
                                      "gmacs_executed", "gmacs_issued", "issued_over_dense", "executed_over_dense",
                                      "roofline")}
             rec["state"] = o["config"]["state"]
+            if c in (1, 2):     # the 1-D workloads also in throughput mode: eight pushes in step per launch
+                t, _ = run_workload(c, None, 1, push_batch=8)
+                rec["throughput_mode_8_pushes_per_launch"] = {k: t[k] for k in ("value", "unit", "ms_per_step", "roofline")}
             if not args.no_cpu_baseline:
                 rec["cpu_baseline"] = cpu_baseline(owl, budget_s=3.0)
             res["other_workloads"][o["config"]["workload"]] = rec

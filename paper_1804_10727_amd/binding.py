@@ -15,7 +15,7 @@ KIND = {"conv": 0, "maxpool": 1}
 ACT = {"none": 0, "relu": 1, "relu_shr_clamp": 2}
 
 EXPORTS = ["idf_create_net", "idf_create_net_columnwise", "idf_destroy_net", "idf_query_sizes", "idf_open_streams", "idf_open_streams_static", "idf_close_streams",
-           "idf_push_segment", "idf_read_outputs", "idf_reset_streams", "idf_get_stats", "idf_count_issued_macs", "idf_get_issued_macs", "idf_rows_pushed",
+           "idf_push_segment", "idf_set_push_batching", "idf_read_outputs", "idf_reset_streams", "idf_get_stats", "idf_count_issued_macs", "idf_get_issued_macs", "idf_rows_pushed",
            "idf_layer_kernel", "idf_last_error", "idf_profile_begin", "idf_profile_end", "idf_enable_head",
            "idf_read_head", "idf_query_head_units_bytes", "idf_enable_head_units", "idf_read_head_units", "idf_push_pixels", "idf_query_eager_bytes", "idf_enable_eager", "idf_read_announced", "idf_read_announced_rows", "idf_eager_state_bytes", "idf_snapshot_bytes", "idf_snapshot", "idf_restore"]
 
@@ -81,6 +81,7 @@ def load_library():
     L.idf_open_streams_static.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int64, C.c_void_p, C.POINTER(C.c_void_p)]
     L.idf_close_streams.argtypes = [C.c_void_p]
     L.idf_push_segment.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int]
+    L.idf_set_push_batching.argtypes = [C.c_void_p, C.c_int]
     L.idf_read_outputs.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int64,
                                    C.c_void_p, C.c_void_p]
     L.idf_reset_streams.argtypes = [C.c_void_p, C.c_void_p, C.c_int]
@@ -203,6 +204,9 @@ class Streams:
         n_rows = rows.shape[1] if n_rows is None else n_rows
         assert rows.is_contiguous() and rows.is_cuda
         _check(load_library().idf_push_segment(self._h, ptr, n_ids, C.c_void_p(rows.data_ptr()), n_rows))
+
+    def set_push_batching(self, k):
+        _check(load_library().idf_set_push_batching(self._h, int(k)))
 
     def push_pixels(self, pixels, x0, stream_ids=None):
         """pixels: device tensor [n_ids][n_px][in_c] -- the next columns of the current row."""

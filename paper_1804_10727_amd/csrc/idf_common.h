@@ -145,47 +145,61 @@ IDF_HD int cascade1d_cin_pad(int c_in, int c_out)
     return kCasThreads / cp * cascade1d_steps(c_in, c_out);
 }
 
-// One layer's step in small integers.  Accumulator slot t stands for output row o_base + t.
+// What a cascade launch needs to know of a layer whatever the segment.
 struct CascadeLayer {
-    int cnt;                 // new input rows (0: the layer does not fire)
-    int t_lo, t_fin, t_hi;   // slots [t_lo, t_hi) are live; those below t_fin become final
-    int d0;                  // first input row of slot 0 minus the first new row
-    int at_start;            // 1: the first new row is row 0 of the sample
-    int rho;                 // (first new row + padding) mod stride
     int cp_log;              // log2 of c_out rounded up to a power of two
     int c_in, c_out, k_h, s_h, act;
     int steps;               // cascade1d_steps(c_in, c_out)
     int ring_floats;         // k_h * c_out
-    int slot0;               // ring slot of accumulator slot 0 (slot of t is (slot0 + t) mod k_h)
+    int rcp_k;               // ceil(65536 / k_h): (v * rcp_k) >> 16 == v / k_h for the small v that occur
     const void *w;           // cascade packing, see cascade1d_weight_index
     const void *bias;
     void *ring;              // this launch's first stream is at ring + stream * ring_stride floats
     int64_t ring_stride;
-    int rcp_k;               // ceil(65536 / k_h): (v * rcp_k) >> 16 == v / k_h for the small v that occur
-    int fma_per_channel;     // multiply-adds a lane issues for one input channel that holds an event (all rows, all taps)
+};
+
+// One layer's step for one segment, in small integers.  Accumulator slot t stands for output row
+// o_base + t.
+struct CascadeStep {
+    signed char cnt;             // new input rows (0: the layer does not fire)
+    signed char t_lo, t_fin, t_hi;   // slots [t_lo, t_hi) are live; those below t_fin become final
+    signed char d0;              // first input row of slot 0 minus the first new row
+    signed char at_start;        // 1: the first new row is row 0 of the sample
+    signed char rho;             // (first new row + padding) mod stride
+    signed char slot0;           // ring slot of accumulator slot 0 (slot of t is (slot0 + t) mod k_h)
+    short fma_per_channel;       // multiply-adds a lane issues for one input channel that holds an event (all rows, all taps)
+    short reserved;
     unsigned char taps[kCasRowsMax];   // per new row: kernel taps landing inside the output
 };
 
 // The layers can be dealt to up to kCasMaxStages groups of workgroups (blockIdx.y) that run side
-// by side in one launch, stage s working on the segment pushed s launches earlier: its first
+// by side in one launch, stage s working on the segments pushed s launches earlier: its first
 // layer reads what stage s-1 wrote in the launch before (double-buffered by launch parity).
+// A launch can take several segments of every stream at once (segments pushed in step and held
+// back until there are enough of them): a workgroup then runs them one after the other with its
+// layers' rolling buffers staying in LDS in between.
 constexpr int kCasMaxStages = 8;
+constexpr int kCasSegMax = 8;
 
 struct CascadeArgs {
     int n_layers;
     int n_stages;
     int stage_lo[kCasMaxStages + 1];     // stage s runs layers [stage_lo[s], stage_lo[s+1])
+    int stage_segs[kCasMaxStages];       // segments of the launch stage s works on (0: nothing has reached it)
     int transit_wr;                      // parity of the hand-over buffers written by this launch
-    CascadeLayer sched[kCasMaxLayers];   // sched[l] describes the segment layer l's stage works on
-    CascadeLayer first[kCasMaxStages];   // filled by the launcher: first[s] = sched[stage_lo[s]], so that a
-                                         // workgroup finds it from its stage alone, in its first round of loads
     int per;                             // filled by the launcher: streams side by side in blockIdx.x
-    const void *in;                      // stage 0: [position][rows][c0]
-    int64_t in_stream_stride;
-    void *transit;                       // hand-over rows [boundary][parity][stream][row][channel]
+    CascadeLayer layer[kCasMaxLayers];
+    CascadeStep step[kCasSegMax][kCasMaxLayers];   // step[q][l]: layer l on segment q of the launch its stage works on
+    CascadeLayer first[kCasMaxStages];   // filled by the launcher: first[s] = layer[stage_lo[s]], first_step[s] = step[0][stage_lo[s]],
+    CascadeStep first_step[kCasMaxStages];   // so that a workgroup finds them from its stage alone, in its first round of loads
+    const void *in[kCasSegMax];          // stage 0: segment q as [position][rows][c0]
+    int in_stream_stride[kCasSegMax];    // elements
+    void *transit;                       // hand-over rows [boundary][parity][stream][segment][row][channel]
     int64_t transit_stream_stride, transit_buf_stride;   // floats
+    int transit_seg_stride;
     void *out;                           // output area [stream][out_cap][c_out]
-    int64_t out_stride, out_cap, out_slot0;
+    int64_t out_stride, out_cap;
+    int64_t out_slot0[kCasSegMax];       // of the segments the last stage works on
     unsigned long long *stats;
     unsigned long long *issued;          // [stream][layer]: multiply-adds issued (all rows of every channel that holds an event)
 };

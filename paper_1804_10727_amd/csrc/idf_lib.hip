@@ -109,12 +109,18 @@ struct idf_streams {
     bool head_units_bias = false;
     int64_t out_stride = 0;
     std::vector<std::vector<float>> cas_w;      // cascade packing of the weights (kept until the upload has run)
-    // 1-D cascade, layers dealt to stages that run side by side, stage k on the segment pushed k
-    // launches earlier: the segments still on their way, newest first
-    struct CasPush { bool valid = false; CascadeLayer sched[kCasMaxLayers]; int64_t out_slot0 = 0; };
+    // 1-D cascade, layers dealt to stages that run side by side, stage k on the segments of the
+    // launch k launches earlier: the launches still on their way, newest first.  A launch holds
+    // one segment of every stream, or up to cas_batch of them when pushes in step are held back
+    // (idf_set_push_batching); cas_pending are the segments waiting for their launch.
+    struct CasSeg { CascadeStep st[kCasMaxLayers]; int64_t out_slot0 = 0; const void *dev_rows = nullptr; int n_rows = 0; };
+    struct CasGroup { int n = 0; double bytes = 0; CasSeg seg[kCasSegMax]; };       // n = 0: none
     int cas_stages = 1;
     int cas_lo[kCasMaxStages + 1] = {};
-    CasPush cas_hist[kCasMaxStages - 1];
+    CasGroup cas_hist[kCasMaxStages - 1];
+    CasGroup cas_pending;
+    int cas_batch = 1;
+    CascadeLayer cas_layer[kCasMaxLayers];
     int cas_parity = 0;
     size_t cas_transit_off = 0;
     int64_t cas_transit_stride = 0;
@@ -302,10 +308,10 @@ int make_layout(const idf_net &net, int B, int max_seg, int64_t out_cap, Layout 
             if (!strict_cascade()) handover_per_stream += (size_t)L.transit_cap[l] * net.g[l].c_out * 4;
         }
         L.cas_boundaries = std::min(kCasMaxStages, n) - 1;
-        L.cas_transit_stride = (most + 63) / 64 * 64;
+        L.cas_transit_stride = (most + 63) / 64 * 64;          // of one segment; a launch can hold kCasSegMax of them
         L.cas_transit_off = off;
-        off = align_up(off + (size_t)L.cas_boundaries * 2 * B * L.cas_transit_stride * 4);
-        transit_per_stream = (size_t)L.cas_boundaries * 2 * L.cas_transit_stride * 4;
+        off = align_up(off + (size_t)L.cas_boundaries * 2 * B * kCasSegMax * L.cas_transit_stride * 4);
+        transit_per_stream = (size_t)L.cas_boundaries * 2 * kCasSegMax * L.cas_transit_stride * 4;
     }
     L.total = off;
     L.sizes.workspace_bytes = off;
@@ -443,15 +449,13 @@ void plan_cascade_stages(idf_streams *s)
     for (int k = 0; k <= kCasMaxStages; ++k) s->cas_lo[k] = best_lo[k];
 }
 
-// The step of every layer for a segment of n_rows rows arriving at row r.
-int cascade_schedule(idf_streams *s, int n_rows, int64_t r, int n_streams, idf_streams::CasPush &p, double &bytes)
+// What a cascade launch needs to know of every layer whatever the segment.
+void cascade_layers(idf_streams *s)
 {
     const idf_net &net = *s->net;
-    const int n = (int)net.g.size();
-    int64_t y0 = r, cnt = n_rows;
-    for (int l = 0; l < n; ++l) {
+    for (int l = 0; l < (int)net.g.size() && l < kCasMaxLayers; ++l) {
         const Geom &g = net.g[l];
-        CascadeLayer &L = p.sched[l];
+        CascadeLayer &L = s->cas_layer[l];
         L = CascadeLayer{};
         L.c_in = g.c_in; L.c_out = g.c_out; L.k_h = g.k_h; L.s_h = g.s_h; L.act = g.act;
         L.steps = cascade1d_steps(g.c_in, g.c_out);
@@ -463,28 +467,45 @@ int cascade_schedule(idf_streams *s, int n_rows, int64_t r, int n_streams, idf_s
         L.ring_stride = s->ring_stride[l];
         L.cp_log = 0;
         while ((1 << L.cp_log) < g.c_out) ++L.cp_log;
+    }
+}
+
+// The step of every layer for a segment of n_rows rows arriving at row r.
+int cascade_schedule(idf_streams *s, int n_rows, int64_t r, int n_streams, idf_streams::CasSeg &p, double &bytes)
+{
+    const idf_net &net = *s->net;
+    const int n = (int)net.g.size();
+    int64_t y0 = r, cnt = n_rows;
+    for (int l = 0; l < n; ++l) {
+        const Geom &g = net.g[l];
+        CascadeStep &L = p.st[l];
+        L = CascadeStep{};
         if (cnt > 0) {
             ConvStep c{};
             c.g = g; c.y0 = y0; c.cnt = (int)cnt; c.o_lo = rows_final(g, y0); c.o_fin = rows_final(g, y0 + cnt);
             c.o_hi = std::max(rows_touched(g, y0 + cnt), c.o_fin);
-            c.in_by_position = l == 0; c.to_output = l == n - 1; c.bias = L.bias;
+            c.in_by_position = l == 0; c.to_output = l == n - 1; c.bias = s->cas_layer[l].bias;
             bytes += conv_step_bytes(net, c, n_streams);
             const int64_t y0p = y0 + g.p_h;
-            L.rho = (int)(y0p % g.s_h);
-            const int64_t o_base = y0p / g.s_h + cascade1d_slot_off(g.s_h, L.rho);
-            L.cnt = (int)cnt;
+            const int rho = (int)(y0p % g.s_h);
+            const int64_t o_base = y0p / g.s_h + cascade1d_slot_off(g.s_h, rho);
             {   // what a lane issues per channel that holds an event: the kernel's variant for 4, 8 or 16
                 // new rows computes all of them, all nine tap positions that land on an output row
                 const int nin = cnt <= 4 ? 4 : cnt <= 8 ? 8 : 16;
                 int f = 0;
                 for (int j = 0; j < nin; ++j)
                     for (int ky = 0; ky < kCasKMax; ++ky)
-                        if ((L.rho + j - ky) % g.s_h == 0) ++f;
-                L.fma_per_channel = f;
+                        if ((rho + j - ky) % g.s_h == 0) ++f;
+                L.fma_per_channel = (short)f;
             }
-            L.t_lo = (int)(c.o_lo - o_base); L.t_fin = (int)(c.o_fin - o_base); L.t_hi = (int)(c.o_hi - o_base);
-            L.slot0 = (int)(((o_base % g.k_h) + g.k_h) % g.k_h);
-            L.d0 = (int)(o_base * g.s_h - g.p_h - y0);
+            const int64_t t_lo = c.o_lo - o_base, t_fin = c.o_fin - o_base, t_hi = c.o_hi - o_base;
+            const int64_t d0 = o_base * g.s_h - g.p_h - y0;
+            if (cnt > kCasRowsMax || t_lo < 0 || t_hi > kCasSlotsMax || d0 < -127 || d0 > 127)
+                return fail(IDF_ESTATE, "internal: cascade schedule of layer %d out of range", l);
+            L.cnt = (signed char)cnt; L.rho = (signed char)rho;
+            L.t_lo = (signed char)t_lo; L.t_fin = (signed char)t_fin; L.t_hi = (signed char)t_hi;
+            L.slot0 = (signed char)(((o_base % g.k_h) + g.k_h) % g.k_h);
+            L.d0 = (signed char)d0;
             L.at_start = y0 == 0;
             for (int j = 0; j < cnt && j < kCasRowsMax; ++j) {
                 int t = 0;
@@ -496,18 +517,15 @@ int cascade_schedule(idf_streams *s, int n_rows, int64_t r, int n_streams, idf_s
                 }
                 L.taps[j] = (unsigned char)t;
             }
-            if (cnt > kCasRowsMax || L.t_lo < 0 || L.t_hi > kCasSlotsMax)
-                return fail(IDF_ESTATE, "internal: cascade schedule of layer %d out of range", l);
             y0 = c.o_lo; cnt = c.o_fin - c.o_lo;
         }
     }
     return IDF_OK;
 }
 
-// One launch: stage 0 takes the new segment (none: the stages only move on), stage k the segment
-// pushed k launches earlier.  staged == false: all layers in one stage, nothing may be on its way.
-int cascade_launch(idf_streams *s, const StreamSel &sel, const void *dev_rows, int n_rows,
-                   const idf_streams::CasPush *fresh, bool staged, double bytes)
+// One launch: stage 0 takes the new segments (none: the stages only move on), stage k those of
+// the launch k launches earlier.  staged == false: all layers in one stage, nothing may be on its way.
+int cascade_launch(idf_streams *s, const StreamSel &sel, const idf_streams::CasGroup *fresh, bool staged)
 {
     const int n = (int)s->net->g.size();
     CascadeArgs a{};
@@ -515,45 +533,62 @@ int cascade_launch(idf_streams *s, const StreamSel &sel, const void *dev_rows, i
     a.n_stages = staged ? s->cas_stages : 1;
     for (int k = 0; k <= kCasMaxStages; ++k) a.stage_lo[k] = staged ? s->cas_lo[k] : (k == 0 ? 0 : n);
     a.transit_wr = s->cas_parity;
-    const idf_streams::CasPush *last_stage = fresh;       // whose output rows this launch completes
+    for (int l = 0; l < n; ++l) a.layer[l] = s->cas_layer[l];
+    const idf_streams::CasGroup *last_stage = fresh;       // whose output rows this launch completes
     for (int k = 0; k < a.n_stages; ++k) {
-        const idf_streams::CasPush *src = k == 0 ? fresh : (s->cas_hist[k - 1].valid ? &s->cas_hist[k - 1] : nullptr);
-        for (int l = a.stage_lo[k]; l < a.stage_lo[k + 1]; ++l) {
-            if (src) a.sched[l] = src->sched[l];
-            else a.sched[l] = CascadeLayer{};               // cnt 0: the stage has nothing to do
-        }
+        const idf_streams::CasGroup *src = k == 0 ? fresh : (s->cas_hist[k - 1].n > 0 ? &s->cas_hist[k - 1] : nullptr);
+        a.stage_segs[k] = src ? src->n : 0;
+        for (int q = 0; src && q < src->n; ++q)
+            for (int l = a.stage_lo[k]; l < a.stage_lo[k + 1]; ++l) a.step[q][l] = src->seg[q].st[l];
         if (k == a.n_stages - 1) last_stage = src;
     }
-    a.in = dev_rows; a.in_stream_stride = (int64_t)n_rows * s->net->in_c;
+    for (int q = 0; fresh && q < fresh->n; ++q) {
+        a.in[q] = fresh->seg[q].dev_rows;
+        a.in_stream_stride[q] = fresh->seg[q].n_rows * s->net->in_c;
+    }
     a.transit = s->ws + s->cas_transit_off;
-    a.transit_stream_stride = s->cas_transit_stride;
+    a.transit_seg_stride = (int)s->cas_transit_stride;
+    a.transit_stream_stride = (int64_t)kCasSegMax * s->cas_transit_stride;
     a.transit_buf_stride = a.transit_stream_stride * s->B;
     a.out = s->ws + s->out_off; a.out_stride = s->out_stride; a.out_cap = s->out_cap;
-    a.out_slot0 = last_stage ? last_stage->out_slot0 : 0;
+    for (int q = 0; last_stage && q < last_stage->n; ++q) a.out_slot0[q] = last_stage->seg[q].out_slot0;
     a.stats = (unsigned long long *)(s->ws + s->stats_off);
     a.issued = s->count_issued ? (unsigned long long *)(s->ws + s->issued_off) : nullptr;
-    hipError_t e = launch_cascade1d(a, sel, launch_ctx(s, kKindCascade1d, bytes));
+    hipError_t e = launch_cascade1d(a, sel, launch_ctx(s, kKindCascade1d, fresh ? fresh->bytes : 0.0));
     if (e != hipSuccess) return dev_fail(e, "cascade launch");
     if (staged) {
         for (int k = kCasMaxStages - 2; k > 0; --k) s->cas_hist[k] = s->cas_hist[k - 1];
-        if (fresh) s->cas_hist[0] = *fresh; else s->cas_hist[0].valid = false;
-        for (int k = s->cas_stages - 1; k < kCasMaxStages - 1; ++k) s->cas_hist[k].valid = false;   // left the last stage
+        if (fresh) s->cas_hist[0] = *fresh; else s->cas_hist[0].n = 0;
+        for (int k = s->cas_stages - 1; k < kCasMaxStages - 1; ++k) s->cas_hist[k].n = 0;   // left the last stage
         s->cas_parity ^= 1;
     }
     return IDF_OK;
 }
 
-// Runs the segments still on their way through the remaining stages.
+// Segments held back (pushes in step, idf_set_push_batching) get their launch.
+int cascade_flush(idf_streams *s)
+{
+    if (s->cas_pending.n == 0) return IDF_OK;
+    StreamSel all{};
+    all.n = s->B; all.base = 0; all.pos0 = 0;
+    int rc = cascade_launch(s, all, &s->cas_pending, s->cas_stages > 1);
+    s->cas_pending.n = 0; s->cas_pending.bytes = 0;
+    return rc;
+}
+
+// Runs the segments still held back or on their way through the remaining stages.
 int cascade_drain(idf_streams *s)
 {
     if (!s->use_cascade1d) return IDF_OK;
+    int rc = cascade_flush(s);
+    if (rc != IDF_OK) return rc;
     StreamSel all{};
     all.n = s->B; all.base = 0; all.pos0 = 0;
     for (;;) {
         bool pending = false;
-        for (int k = 0; k < kCasMaxStages - 1; ++k) pending |= s->cas_hist[k].valid;
+        for (int k = 0; k < kCasMaxStages - 1; ++k) pending |= s->cas_hist[k].n > 0;
         if (!pending) return IDF_OK;
-        int rc = cascade_launch(s, all, nullptr, 0, nullptr, true, 0.0);
+        rc = cascade_launch(s, all, nullptr, true);
         if (rc != IDF_OK) return rc;
     }
 }
@@ -562,19 +597,27 @@ int cascade_drain(idf_streams *s)
 int enqueue_cascade1d(idf_streams *s, const StreamSel &sel, const void *dev_rows, int n_rows, int64_t r,
                       int64_t out_slot0)
 {
-    idf_streams::CasPush p;
-    double bytes = 0;
-    int rc = cascade_schedule(s, n_rows, r, sel.n, p, bytes);
-    if (rc != IDF_OK) return rc;
-    p.valid = true; p.out_slot0 = out_slot0;
-    // Stages hold segments of all streams together: a push of all streams in step joins them, any
-    // other first lets them finish and then runs through all layers at once.
-    const bool in_step = s->cas_stages > 1 && sel.base == 0 && sel.pos0 == 0 && sel.n == s->B;
+    // All streams in step: the segment joins those of its launch (stages hold segments of all streams
+    // together; held-back segments are segments of all streams).  Any other push first lets everything
+    // finish and then runs through all layers at once.
+    const bool in_step = sel.base == 0 && sel.pos0 == 0 && sel.n == s->B && (s->cas_stages > 1 || s->cas_batch > 1);
     if (!in_step) {
-        rc = cascade_drain(s);
+        int rc = cascade_drain(s);
         if (rc != IDF_OK) return rc;
+        idf_streams::CasGroup g;
+        g.n = 1;
+        rc = cascade_schedule(s, n_rows, r, sel.n, g.seg[0], g.bytes);
+        if (rc != IDF_OK) return rc;
+        g.seg[0].out_slot0 = out_slot0; g.seg[0].dev_rows = dev_rows; g.seg[0].n_rows = n_rows;
+        return cascade_launch(s, sel, &g, false);
     }
-    return cascade_launch(s, sel, dev_rows, n_rows, &p, in_step, bytes);
+    idf_streams::CasGroup &p = s->cas_pending;
+    idf_streams::CasSeg &seg = p.seg[p.n];
+    int rc = cascade_schedule(s, n_rows, r, sel.n, seg, p.bytes);
+    if (rc != IDF_OK) return rc;
+    seg.out_slot0 = out_slot0; seg.dev_rows = dev_rows; seg.n_rows = n_rows;
+    ++p.n;
+    return p.n >= s->cas_batch ? cascade_flush(s) : IDF_OK;
 }
 
 // The matrix-core step of conv layer l (with the pool fused behind it, if any) for input row y:
@@ -1334,7 +1377,7 @@ int open_on(idf_net *net, int n_streams, int max_seg_rows, int64_t out_cap_rows,
     s->head_off = L.head_off;
     s->cas_transit_off = L.cas_transit_off;
     s->cas_transit_stride = L.cas_transit_stride;
-    if (L.cascade1d) plan_cascade_stages(s);
+    if (L.cascade1d) { plan_cascade_stages(s); cascade_layers(s); }
     s->mfma.assign(net->g.size(), 0);
     if (!getenv("IDF_NO_MFMA")) {
         for (size_t l = 0; l < net->g.size(); ++l) {
@@ -1624,6 +1667,18 @@ int idf_get_issued_macs(idf_streams *s, int stream_id, uint64_t *macs_issued)
         const bool counted = s->use_cascade1d || (own_count && l < (int)s->mfma.size() && s->mfma[l] == 1);
         macs_issued[l] = counted ? iss[l] : st[2 * l + 1];
     }
+    return IDF_OK;
+}
+
+int idf_set_push_batching(idf_streams *s, int k)
+{
+    if (!s) return fail(IDF_EINVAL, "null argument");
+    if (k < 1 || k > kCasSegMax) return fail(IDF_EINVAL, "segments per launch %d outside [1, %d]", k, kCasSegMax);
+    if (!s->use_cascade1d) return fail(IDF_EUNSUPPORTED, "holding back pushes is built for nets served by the 1-D cascade");
+    if (s->eager.on) return fail(IDF_EUNSUPPORTED, "eager emission delivers every segment at once");
+    int rc = pipeline_drain(s);                  // what is held back was pushed under the old setting
+    if (rc != IDF_OK) return rc;
+    s->cas_batch = k;
     return IDF_OK;
 }
 

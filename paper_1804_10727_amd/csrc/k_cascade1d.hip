@@ -259,46 +259,54 @@ __global__ void __launch_bounds__(kCasThreads, 2) k_cascade1d(const CascadeArgs 
     const int stream = sel_stream(sel, si);
     const int n_layers = ka.n_layers;
     const int lb = ka.stage_lo[stage], le = ka.stage_lo[stage + 1];
+    const int n_seg = ka.stage_segs[stage];                      // segments this stage runs one after the other
     const CascadeLayer &first = ka.first[stage];
+    const CascadeStep &first_step = ka.first_step[stage];
     // First round of scalar loads, asked for in one batch with one wait (left to first use they
     // end up behind conditions, one memory round trip each, one after the other).
-    asm volatile("" ::"s"(ka.per), "s"(sel.n), "s"(sel.base), "s"(sel.pos0), "s"(n_layers), "s"(lb), "s"(le), "s"(first.cnt),
-                 "s"(first.c_in), "s"(first.c_out), "s"(first.cp_log), "s"(first.steps), "s"(first.w), "s"(ka.in),
-                 "s"(ka.in_stream_stride), "s"(ka.transit), "s"(ka.transit_stream_stride), "s"(ka.transit_buf_stride),
-                 "s"(ka.transit_wr), "s"(ka.stats));
-    if (first.cnt <= 0) return;                                  // nothing has reached this stage
+    asm volatile("" ::"s"(ka.per), "s"(sel.n), "s"(sel.base), "s"(sel.pos0), "s"(n_layers), "s"(lb), "s"(le), "s"(n_seg),
+                 "s"((int)first_step.cnt), "s"(first.c_in), "s"(first.c_out), "s"(first.cp_log), "s"(first.steps), "s"(first.w),
+                 "s"(ka.in[0]), "s"(ka.in_stream_stride[0]), "s"(ka.transit), "s"(ka.transit_stream_stride),
+                 "s"(ka.transit_buf_stride), "s"(ka.transit_wr), "s"(ka.stats));
+    if (n_seg <= 0) return;                                      // nothing has reached this stage
     Wq wq;
     WCur wc = cursor_of(first, tid);
 #pragma unroll
     for (int p = 0; p < kAhead; ++p) fetch_w(wq.w[p], wc);
-    const int c0 = first.c_in, n_in = first.cnt * c0;            // at most 16 rows x 64 channels
+    const int c0 = first.c_in;
+    // The new rows of segment q for this stage's first layer: the pushed segment, or the rows the
+    // stage before handed over in the previous launch.  Asked for one segment ahead of their use.
+    const gfloat *tr_in = as_global((const float *)ka.transit) + ((stage - 1) * 2 + (ka.transit_wr ^ 1)) * ka.transit_buf_stride +
+                          (int64_t)stream * ka.transit_stream_stride;
     float xin[kXinPerLane];
-    {
-        // the new segment, or the rows the stage before handed over in the previous launch
+    auto request_rows = [&](int q, int cnt_q) {
+        const int n_in = cnt_q * c0;                             // at most 16 rows x 64 channels
         const gfloat *in = stage == 0
-            ? as_global((const float *)ka.in) + (int64_t)(sel.pos0 + si) * ka.in_stream_stride
-            : as_global((const float *)ka.transit) + ((stage - 1) * 2 + (ka.transit_wr ^ 1)) * ka.transit_buf_stride +
-                  (int64_t)stream * ka.transit_stream_stride;
+            ? as_global((const float *)ka.in[q]) + (int64_t)(sel.pos0 + si) * ka.in_stream_stride[q]
+            : tr_in + q * ka.transit_seg_stride;
 #pragma unroll
         for (int u = 0; u < kXinPerLane; ++u) {
             const int i = tid + u * kT;
-            xin[u] = in[i < n_in ? i : n_in - 1];
+            xin[u] = in[n_in > 0 ? (i < n_in ? i : n_in - 1) : 0];
         }
-    }
+    };
+    request_rows(0, first_step.cnt);
     // Second round: what the rolling-buffer requests of the stage's layers need.  The first
     // kPinned layers of the stage in one batch; a stage with more layers (a deep net run without
     // stages) fetches the rest as it goes.
     constexpr int kPinned = 3;
     const int l_last = n_layers - 1;
-    auto layer_of = [&](int j) -> const CascadeLayer & { return ka.sched[lb + j < l_last ? lb + j : l_last]; };
+    auto layer_of = [&](int j) -> const CascadeLayer & { return ka.layer[lb + j < l_last ? lb + j : l_last]; };
     {
         const CascadeLayer &q0 = layer_of(0), &q1 = layer_of(1), &q2 = layer_of(2);
         static_assert(kPinned == 3, "one group of operands per pinned layer");
-        asm volatile("" ::"s"(q0.cnt), "s"(q0.ring), "s"(q0.ring_stride), "s"(q0.ring_floats), "s"(q0.bias), "s"(q0.c_out),
-                     "s"(q1.cnt), "s"(q1.ring), "s"(q1.ring_stride), "s"(q1.ring_floats), "s"(q1.bias), "s"(q1.c_out),
-                     "s"(q2.cnt), "s"(q2.ring), "s"(q2.ring_stride), "s"(q2.ring_floats), "s"(q2.bias), "s"(q2.c_out));
+        asm volatile("" ::"s"(q0.ring), "s"(q0.ring_stride), "s"(q0.ring_floats), "s"(q0.bias), "s"(q0.c_out),
+                     "s"(q1.ring), "s"(q1.ring_stride), "s"(q1.ring_floats), "s"(q1.bias), "s"(q1.c_out),
+                     "s"(q2.ring), "s"(q2.ring_stride), "s"(q2.ring_floats), "s"(q2.bias), "s"(q2.c_out));
     }
 
+    // The rolling buffers of the stage's layers come into LDS once and stay there while the
+    // launch's segments run through (rows left unfinished are written to LDS and to memory alike).
     float rv[kCasMaxLayers][kRingPerLane], bv[kCasMaxLayers];             // by position in the stage: layer lb + j
 #pragma unroll
     for (int j = 0; j < kCasMaxLayers; ++j) {
@@ -306,7 +314,7 @@ __global__ void __launch_bounds__(kCasThreads, 2) k_cascade1d(const CascadeArgs 
 #pragma unroll
         for (int u = 0; u < kRingPerLane; ++u) rv[j][u] = 0.f;
         const CascadeLayer &sl = layer_of(j);
-        if (lb + j < le && sl.cnt > 0) {
+        if (lb + j < le) {
             const gfloat *ring = as_global((const float *)sl.ring) + (int64_t)stream * sl.ring_stride;
             const int n_r = sl.ring_floats;
 #pragma unroll
@@ -327,10 +335,24 @@ __global__ void __launch_bounds__(kCasThreads, 2) k_cascade1d(const CascadeArgs 
             const int i = tid + u * kT;
             if (i < kArgWords) lds.args[i] = argw[u];
         }
+#pragma unroll
+        for (int j = 0; j < kCasMaxLayers; ++j) {
+            if (lb + j < le) {
+#pragma unroll
+                for (int u = 0; u < kRingPerLane; ++u)
+                    if (tid + u * kT < kRingPerLayer) lds.ring[lb + j][tid + u * kT] = rv[j][u];
+                if (tid < 64) lds.bias[lb + j][tid] = bv[j];
+            }
+        }
     }
     lds_barrier();
     const CascadeArgs &a = *reinterpret_cast<const CascadeArgs *>(lds.args);
-    {
+
+    for (int seg = 0; seg < n_seg; ++seg) {
+    const int cnt0 = uni(a.step[seg][lb].cnt);
+    // (x[0] and its channel bits are clear here: by the prologue, or by the end of the segment before)
+    if (cnt0 > 0) {
+        const int n_in = cnt0 * c0;
         unsigned int ev = 0, taps = 0;                          // the network input's events (eventise step)
 #pragma unroll
         for (int u = 0; u < kXinPerLane; ++u) {
@@ -339,7 +361,7 @@ __global__ void __launch_bounds__(kCasThreads, 2) k_cascade1d(const CascadeArgs 
                 const int j = i / c0, c = i - j * c0;
                 lds.x[0][c * kXStride + j] = xin[u];
                 atomicOr(&lds.chmask[0][c >> 5], 1u << (c & 31));
-                ev += 1; taps += a.sched[lb].taps[j];
+                ev += 1; taps += a.step[seg][lb].taps[j];
             }
         }
         if (ka.stats && __ballot(ev != 0)) {
@@ -350,33 +372,28 @@ __global__ void __launch_bounds__(kCasThreads, 2) k_cascade1d(const CascadeArgs 
                 atomicAdd(dst + 1, (unsigned long long)taps * first.c_out);
             }
         }
-#pragma unroll
-        for (int j = 0; j < kCasMaxLayers; ++j) {
-            if (lb + j < le && layer_of(j).cnt > 0) {
-#pragma unroll
-                for (int u = 0; u < kRingPerLane; ++u)
-                    if (tid + u * kT < kRingPerLayer) lds.ring[lb + j][tid + u * kT] = rv[j][u];
-                if (tid < 64) lds.bias[lb + j][tid] = bv[j];
-            }
-        }
     }
+    if (seg + 1 < n_seg) request_rows(seg + 1, uni(a.step[seg + 1][lb].cnt));    // the next segment's rows, on their way while this one runs
     lds_barrier();
 
     int cur_buf = 0;
     for (int l = lb; l < le; ++l) {
         // this layer's step: scalars copied out of LDS once (the barriers below would force re-reads)
-        const CascadeLayer &sl = a.sched[l];
-        const int cnt = uni(sl.cnt);
+        const CascadeLayer &sl = a.layer[l];
+        const CascadeStep &ss = a.step[seg][l];
+        const int cnt = uni(ss.cnt);
         if (cnt <= 0) break;
-        const int t_lo = uni(sl.t_lo), t_fin = uni(sl.t_fin), t_hi = uni(sl.t_hi), d0 = uni(sl.d0);
-        const int at_start = uni(sl.at_start), rho = uni(sl.rho), cp_log = uni(sl.cp_log);
+        const int t_lo = uni(ss.t_lo), t_fin = uni(ss.t_fin), t_hi = uni(ss.t_hi), d0 = uni(ss.d0);
+        const int at_start = uni(ss.at_start), rho = uni(ss.rho), cp_log = uni(sl.cp_log);
         const int c_out = uni(sl.c_out), c_in = uni(sl.c_in), S = uni(sl.s_h), act = uni(sl.act);
-        const int K = uni(sl.k_h), slot0 = uni(sl.slot0), rcp_k = uni(sl.rcp_k);
+        const int K = uni(sl.k_h), slot0 = uni(ss.slot0), rcp_k = uni(sl.rcp_k);
         gfloat *ringg = (gfloat *)uniform_global(sl.ring) + (int64_t)stream * sl.ring_stride;
         const float *x = lds.x[cur_buf];
         float *xn = lds.x[cur_buf ^ 1];
-        const bool more = l + 1 < le && uni(a.sched[l + 1].cnt) > 0;
-        const WCur nxt0 = cursor_of(a.sched[more ? l + 1 : l], tid);
+        const bool more = l + 1 < le && uni(a.step[seg][l + 1].cnt) > 0;
+        // whose weights the tail of this layer asks for: the next layer's, or, when the segment ends
+        // here and another follows, those of the stage's first layer again
+        const WCur nxt0 = cursor_of(a.layer[more ? l + 1 : (seg + 1 < n_seg ? lb : l)], tid);
         const int n_qp = uni(sl.steps);
         // groups of lanes beyond the input channels hold no partial sums (they write zeros): not read
         const int n_red = (kT >> cp_log) < ((c_in + kRedU - 1) & ~(kRedU - 1)) ? (kT >> cp_log) : ((c_in + kRedU - 1) & ~(kRedU - 1));
@@ -390,7 +407,7 @@ __global__ void __launch_bounds__(kCasThreads, 2) k_cascade1d(const CascadeArgs 
         for (int i = tid; i < 64 * kXStride / 4; i += kT) reinterpret_cast<float4 *>(xn)[i] = float4{0.f, 0.f, 0.f, 0.f};
         if (COUNT && ka.issued && tid == 0) {
             const int n_ev = __popc(lds.chmask[cur_buf][0]) + __popc(lds.chmask[cur_buf][1]);
-            if (n_ev) atomicAdd(ka.issued + (int64_t)stream * n_layers + l, (unsigned long long)n_ev * uni(sl.fma_per_channel) * c_out);
+            if (n_ev) atomicAdd(ka.issued + (int64_t)stream * n_layers + l, (unsigned long long)n_ev * uni(ss.fma_per_channel) * c_out);
         }
         if (tid < 2) lds.chmask[cur_buf ^ 1][tid] = 0;
 
@@ -403,7 +420,7 @@ __global__ void __launch_bounds__(kCasThreads, 2) k_cascade1d(const CascadeArgs 
         // all its cells are issued before anything is summed.
         const bool last = l == n_layers - 1, hand_over = l == le - 1 && !last;
         gfloat *tr = (gfloat *)ka.transit + (stage * 2 + ka.transit_wr) * ka.transit_buf_stride +
-                     (int64_t)stream * ka.transit_stream_stride;
+                     (int64_t)stream * ka.transit_stream_stride + seg * ka.transit_seg_stride;
         const int rows_per_pass = kT >> cp_log;
         const int c = tid & (m.cp - 1), cc = c < c_out ? c : c_out - 1;
         int t_of[kCellsPerThread], at[kCellsPerThread];
@@ -463,7 +480,7 @@ __global__ void __launch_bounds__(kCasThreads, 2) k_cascade1d(const CascadeArgs 
                 if (t_of[q] < t_fin) {
                     const float h = act == IDF_ACT_NONE ? sum[q] : fmaxf(sum[q], 0.f);
                     if (last) {
-                        int64_t slot = ka.out_slot0 + (t_of[q] - t_lo);
+                        int64_t slot = ka.out_slot0[seg] + (t_of[q] - t_lo);
                         if (slot >= ka.out_cap) slot -= ka.out_cap;
                         ((gfloat *)ka.out)[(int64_t)stream * ka.out_stride + slot * c_out + c] = h;
                     } else if (hand_over) {
@@ -473,7 +490,8 @@ __global__ void __launch_bounds__(kCasThreads, 2) k_cascade1d(const CascadeArgs 
                         emitted_nz = true;
                     }
                 } else {
-                    ringg[at[q]] = sum[q];                    // stays in the rolling buffer
+                    ringg[at[q]] = sum[q];                    // stays in the rolling buffer: in memory,
+                    lds.ring[l][at[q]] = sum[q];              // and here for the launch's next segment
                 }
             }
             nzb[q] = more ? __ballot(emitted_nz) : 0ull;
@@ -501,23 +519,33 @@ __global__ void __launch_bounds__(kCasThreads, 2) k_cascade1d(const CascadeArgs 
     if (ka.stats && tid < (le - 1 - lb) * (kT / 64) * kCellsPerThread) {
         const int l = lb + tid / ((kT / 64) * kCellsPerThread), r = tid - (l - lb) * ((kT / 64) * kCellsPerThread);
         const int wv = r / kCellsPerThread, q = r - wv * kCellsPerThread;
-        if (a.sched[l].cnt > 0 && a.sched[l + 1].cnt > 0) {
+        if (a.step[seg][l].cnt > 0 && a.step[seg][l + 1].cnt > 0) {
             const unsigned long long nz = lds.nzlog[l][wv][q];
             if (nz) {
-                const int cp_log = a.sched[l].cp_log, cp = 1 << cp_log;
+                const int cp_log = a.layer[l].cp_log, cp = 1 << cp_log;
                 const int j0 = ((wv * 64) >> cp_log) + q * (kT >> cp_log);
                 const unsigned long long rowmask = cp == 64 ? ~0ull : ((1ull << cp) - 1ull);
                 unsigned int ev = 0, taps = 0;
                 for (int rr = 0; rr < (64 >> cp_log); ++rr) {
                     const int n = __popcll((nz >> (rr << cp_log)) & rowmask);
-                    if (n) { ev += n; taps += n * a.sched[l + 1].taps[j0 + rr]; }
+                    if (n) { ev += n; taps += n * a.step[seg][l + 1].taps[j0 + rr]; }
                 }
                 unsigned long long *dst = ka.stats + ((int64_t)stream * n_layers + l + 1) * 2;
                 atomicAdd(dst, (unsigned long long)ev);
-                atomicAdd(dst + 1, (unsigned long long)taps * a.sched[l + 1].c_out);
+                atomicAdd(dst + 1, (unsigned long long)taps * a.layer[l + 1].c_out);
             }
         }
     }
+    if (seg + 1 < n_seg) {
+        // The next segment starts in x[0] with clear channel bits.  Whatever this segment left in
+        // the two row buffers is no longer read (every layer ended in a barrier), and the weights in
+        // flight are the first channels of the stage's first layer again: the last layer a segment
+        // reaches asks for them in its tail, a segment that reached none has left them untouched.
+        for (int i = tid; i < 64 * kXStride / 4; i += kT) reinterpret_cast<float4 *>(lds.x[0])[i] = float4{0.f, 0.f, 0.f, 0.f};
+        if (tid < 4) lds.chmask[tid >> 1][tid & 1] = 0;
+        lds_barrier();
+    }
+    }   // segments
 }
 
 
@@ -554,8 +582,8 @@ hipError_t launch_cascade1d(const CascadeArgs &a, const StreamSel &sel, const La
     const bool spread = 8 % grid_stages == 0 && sel.n % (8 / grid_stages) == 0;
     if (!spread) grid_stages = b.n_stages;
     for (int k = 0; k < grid_stages; ++k) {
-        if (k < b.n_stages) b.first[k] = b.sched[b.stage_lo[k]];
-        else b.first[k] = CascadeLayer{};                   // cnt 0
+        if (k < b.n_stages) { b.first[k] = b.layer[b.stage_lo[k]]; b.first_step[k] = b.step[0][b.stage_lo[k]]; }
+        else { b.first[k] = CascadeLayer{}; b.first_step[k] = CascadeStep{}; b.stage_segs[k] = 0; }      // nothing to do
     }
     b.per = spread ? 8 / grid_stages : sel.n;
     if (sel.n / b.per > 65535) return hipErrorInvalidValue;

@@ -12,8 +12,9 @@ from helpers import TOL, check_stream, oracle_dense, oracle_stream, rel_err
 pytestmark = pytest.mark.gpu
 
 
-def _run(wl, seg, reads_at, stages=None, ids_plan=None):
-    """Push the whole sample seg rows at a time, reading after the pushes listed in reads_at."""
+def _run(wl, seg, reads_at, stages=None, ids_plan=None, batch=None):
+    """Push the whole sample seg rows at a time, reading after the pushes listed in reads_at.
+    batch: hold back up to that many pushes per launch (idf_set_push_batching)."""
     import torch
     import paper_1804_10727_amd as idf
     from paper_1804_10727_amd.binding import input_tensor
@@ -33,6 +34,10 @@ def _run(wl, seg, reads_at, stages=None, ids_plan=None):
     x = input_tensor(wl)
     B, H = wl["streams"], wl["in_h"]
     got = [[] for _ in range(B)]
+    if batch:
+        st.set_push_batching(batch)
+    # a held-back segment is read when its launch runs: every segment stays alive until the end
+    segs = [x[:, r:r + seg].contiguous() for r in range(0, H, seg)]
 
     def read():
         out, first, cnt = st.read_outputs(int(st.sizes.out_h))
@@ -43,7 +48,7 @@ def _run(wl, seg, reads_at, stages=None, ids_plan=None):
                 assert first[b] == sum(len(c) for c in got[b])
                 got[b].append(o[b, :cnt[b]].copy())
     for i, r in enumerate(range(0, H, seg)):
-        st.push_segment(x[:, r:r + seg].contiguous())
+        st.push_segment(segs[i])
         if i in reads_at:
             read()
     read()
@@ -204,3 +209,67 @@ def test_reset_mid_flight_on_unbounded_streams():
     g_new = np.concatenate(new1)
     assert g_new.shape == want_new.shape and rel_err(g_new, want_new) <= TOL["f32"]
     st.close(); net.destroy()
+
+
+@pytest.mark.parametrize("seg,batch", [(16, 8), (5, 3), (1, 8), (16, 2)])
+def test_pushes_held_back_and_run_several_per_launch(seg, batch):
+    """Throughput mode: up to `batch` pushes in step share one launch, the rolling buffers staying in
+    LDS from one segment to the next.  Outputs and counters are those of one launch per push, bit for
+    bit, with reads falling between launches and inside a group of held-back pushes, with a number of
+    pushes that leaves a remainder, staged and unstaged."""
+    wl = wl_mod.make(2, streams=3, length=400, channels=(8, 8, 16, 16, 32, 64))
+    n_push = (400 + seg - 1) // seg
+    ref, sref = _run(wl, seg, reads_at={3}, stages=1)
+    a, sa = _run(wl, seg, reads_at={1, 2, 10, n_push - 2}, batch=batch)
+    b, sb = _run(wl, seg, reads_at=set(), batch=batch)
+    c, sc = _run(wl, seg, reads_at={4}, stages=1, batch=batch)
+    for i in range(3):
+        check_stream(wl, a[i], i)
+        assert np.array_equal(a[i], ref[i]) and np.array_equal(b[i], ref[i]) and np.array_equal(c[i], ref[i])
+        for sx in (sa, sb, sc):
+            assert sx[i]["events_in"].tolist() == sref[i]["events_in"].tolist()
+            assert sx[i]["macs"].tolist() == sref[i]["macs"].tolist()
+
+
+def test_held_back_pushes_and_pushes_of_some_streams():
+    import torch
+    import paper_1804_10727_amd as idf
+    from paper_1804_10727_amd.binding import input_tensor
+    wl = wl_mod.make(2, streams=4, length=320, channels=(8, 8, 8, 16, 16, 16))
+    net = idf.net_from_workload(wl)
+    st = idf.Streams(net, 4, max_seg_rows=16)
+    st.set_push_batching(4)
+    x = input_tensor(wl)
+    keep = []
+
+    def push(rows, ids=None):
+        keep.append(rows)
+        st.push_segment(rows, stream_ids=ids)
+    for r in range(0, 96, 16):                    # six pushes in step: one full group, two held back
+        push(x[:, r:r + 16].contiguous())
+    ahead = np.array([2, 0], dtype=np.int32)      # a push of two streams: what is held back runs first
+    for r in range(96, 160, 16):
+        push(x[[2, 0], r:r + 16].contiguous(), ahead)
+    behind = np.array([1, 3], dtype=np.int32)
+    for r in range(96, 160, 8):
+        push(x[[1, 3], r:r + 8].contiguous(), behind)
+    for r in range(160, 320, 16):
+        push(x[:, r:r + 16].contiguous())
+    out, first, cnt = st.read_outputs(int(st.sizes.out_h))
+    torch.cuda.synchronize()
+    o = out.cpu().numpy()
+    for b in range(4):
+        d = oracle_dense(wl, b)
+        assert cnt[b] == d.shape[0]
+        assert rel_err(o[b, :cnt[b]], d) <= TOL["f32"]
+    with pytest.raises(idf.IdfError):
+        st.set_push_batching(9)
+    st.close(); net.destroy()
+
+
+def test_single_stream_one_sample_per_push_held_back():
+    wl = wl_mod.make(1, length=300)
+    ref, _ = _run(wl, 1, reads_at=set(), stages=1)
+    outs, _ = _run(wl, 1, reads_at={0, 1, 2, 3, 10, 11, 100}, batch=8)
+    check_stream(wl, outs[0], 0)
+    assert np.array_equal(outs[0], ref[0])
