@@ -182,16 +182,20 @@ int idf_push_segment(idf_streams *s, const int32_t *stream_ids, int n_ids, const
                      int n_rows);
 
 /* Throughput mode for 1-D nets whose streams are pushed in step (idf_push_segment with all streams
- * at the same row): up to k such segments are held back and run by one launch, a workgroup taking
- * its stream's k segments one after the other with the rolling buffers staying on chip in between
- * (Sec. 3 first paragraph still holds per segment: each goes through everything it can influence
- * before the next is looked at).  k = 1 (the default) launches with every push.
+ * at the same row): up to k such segments are held back and run by one launch.  A workgroup takes
+ * its stream's held-back segments in order, consecutive ones together while their rows fit one
+ * step of a layer (16 rows), with the rolling buffers staying on chip in between; every segment
+ * still goes through everything it can influence before the next is looked at (Sec. 3 first
+ * paragraph).  k = 1 (the default) launches with every push.
  *   - A held-back segment's dev_rows is read when its launch runs: keep it unchanged until k - 1
  *     further pushes in step or any of the calls below have been made AND the stream's work has run.
  *   - idf_read_outputs, idf_get_stats, idf_get_issued_macs, idf_reset_streams, idf_snapshot,
  *     idf_restore, idf_read_head*, idf_close_streams, idf_profile_end, this call, and any push that is
  *     not of all streams in step first launch what is held back: what they return never shows it.
- * 1 <= k <= 8.  IDF_EUNSUPPORTED for nets the 1-D cascade does not serve and under eager emission. */
+ *   - Rows of segments taken together are added in one pass: the float32 sums are associated
+ *     differently than with a launch per push, so results agree with k = 1 to rounding, not bit for bit.
+ *   - A launch is also due as soon as a further segment could make some layer need more than 8 steps.
+ * 1 <= k <= 16.  IDF_EUNSUPPORTED for nets the 1-D cascade does not serve and under eager emission. */
 int idf_set_push_batching(idf_streams *s, int k);
 
 /* Present the next n_px pixels of the current row (Sec. 3: segments can be arbitrarily small, down

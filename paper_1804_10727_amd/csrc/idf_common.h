@@ -158,8 +158,8 @@ struct CascadeLayer {
     int64_t ring_stride;
 };
 
-// One layer's step for one segment, in small integers.  Accumulator slot t stands for output row
-// o_base + t.
+// One step of one layer, in small integers: the new input rows of one pushed segment or of
+// several consecutive ones taken together.  Accumulator slot t stands for output row o_base + t.
 struct CascadeStep {
     signed char cnt;             // new input rows (0: the layer does not fire)
     signed char t_lo, t_fin, t_hi;   // slots [t_lo, t_hi) are live; those below t_fin become final
@@ -167,41 +167,46 @@ struct CascadeStep {
     signed char at_start;        // 1: the first new row is row 0 of the sample
     signed char rho;             // (first new row + padding) mod stride
     signed char slot0;           // ring slot of accumulator slot 0 (slot of t is (slot0 + t) mod k_h)
+    signed char seg0, seg_rows;  // first layer of stage 0: the new rows are seg_rows rows each of the pushed segments seg0, seg0 + 1, ...
     short fma_per_channel;       // multiply-adds a lane issues for one input channel that holds an event (all rows, all taps)
-    short reserved;
-    unsigned char taps[kCasRowsMax];   // per new row: kernel taps landing inside the output
+    short in_off, out_off;       // rows: where a stage's first layer finds its rows in the hand-over buffer of the stage before,
+                                 // and where its last layer puts the rows it hands over (both counted from the launch's first row)
+    unsigned char taps4[kCasRowsMax / 2];   // per new row, four bits each: kernel taps landing inside the output
 };
+IDF_HD int cascade_taps(const CascadeStep &s, int j) { return (s.taps4[j >> 1] >> ((j & 1) * 4)) & 15; }
 
 // The layers can be dealt to up to kCasMaxStages groups of workgroups (blockIdx.y) that run side
 // by side in one launch, stage s working on the segments pushed s launches earlier: its first
 // layer reads what stage s-1 wrote in the launch before (double-buffered by launch parity).
 // A launch can take several segments of every stream at once (segments pushed in step and held
-// back until there are enough of them): a workgroup then runs them one after the other with its
+// back until there are enough of them): a stage then takes as many consecutive ones together as
+// fit the rows one step can take, and runs the resulting steps one after the other with its
 // layers' rolling buffers staying in LDS in between.
 constexpr int kCasMaxStages = 8;
-constexpr int kCasSegMax = 8;
+constexpr int kCasSegMax = 16;       // pushed segments one launch can take
+constexpr int kCasStepMax = 8;       // steps a stage runs in one launch
 
 struct CascadeArgs {
     int n_layers;
     int n_stages;
     int stage_lo[kCasMaxStages + 1];     // stage s runs layers [stage_lo[s], stage_lo[s+1])
-    int stage_segs[kCasMaxStages];       // segments of the launch stage s works on (0: nothing has reached it)
+    int stage_steps[kCasMaxStages];      // steps stage s runs in this launch (0: nothing has reached it)
+    int steps_max;                       // the largest of them
     int transit_wr;                      // parity of the hand-over buffers written by this launch
     int per;                             // filled by the launcher: streams side by side in blockIdx.x
     CascadeLayer layer[kCasMaxLayers];
-    CascadeStep step[kCasSegMax][kCasMaxLayers];   // step[q][l]: layer l on segment q of the launch its stage works on
     CascadeLayer first[kCasMaxStages];   // filled by the launcher: first[s] = layer[stage_lo[s]], first_step[s] = step[0][stage_lo[s]],
     CascadeStep first_step[kCasMaxStages];   // so that a workgroup finds them from its stage alone, in its first round of loads
-    const void *in[kCasSegMax];          // stage 0: segment q as [position][rows][c0]
+    const void *in[kCasSegMax];          // stage 0: pushed segment q as [position][rows][c0]
     int in_stream_stride[kCasSegMax];    // elements
-    void *transit;                       // hand-over rows [boundary][parity][stream][segment][row][channel]
+    void *transit;                       // hand-over rows [boundary][parity][stream][row][channel]
     int64_t transit_stream_stride, transit_buf_stride;   // floats
-    int transit_seg_stride;
     void *out;                           // output area [stream][out_cap][c_out]
     int64_t out_stride, out_cap;
-    int64_t out_slot0[kCasSegMax];       // of the segments the last stage works on
+    int64_t out_slot0[kCasStepMax];      // of the steps the last stage runs
     unsigned long long *stats;
     unsigned long long *issued;          // [stream][layer]: multiply-adds issued (all rows of every channel that holds an event)
+    CascadeStep step[kCasStepMax][kCasMaxLayers];   // step[m][l]: step m of layer l's stage (last: a launch copies only the steps in use on chip)
 };
 
 // One arriving row of a 3x3 / stride 1 / same-padded conv layer on the matrix cores.

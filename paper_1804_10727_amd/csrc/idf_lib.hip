@@ -113,11 +113,20 @@ struct idf_streams {
     // launch k launches earlier: the launches still on their way, newest first.  A launch holds
     // one segment of every stream, or up to cas_batch of them when pushes in step are held back
     // (idf_set_push_batching); cas_pending are the segments waiting for their launch.
-    struct CasSeg { CascadeStep st[kCasMaxLayers]; int64_t out_slot0 = 0; const void *dev_rows = nullptr; int n_rows = 0; };
-    struct CasGroup { int n = 0; double bytes = 0; CasSeg seg[kCasSegMax]; };       // n = 0: none
+    struct CasSeg {
+        int64_t y0[kCasMaxLayers + 1];       // per layer: first of the rows the segment brings it (entry n_layers: first output row)
+        int cnt[kCasMaxLayers + 1];          // and how many
+        int64_t out_slot0 = 0; const void *dev_rows = nullptr; int n_rows = 0;
+    };
+    struct CasGroup {                                                            // n = 0: none
+        int n = 0; double bytes = 0; CasSeg seg[kCasSegMax];
+        void take(const CasGroup &o) { n = o.n; bytes = o.bytes; for (int q = 0; q < o.n; ++q) seg[q] = o.seg[q]; }
+    };
     int cas_stages = 1;
     int cas_lo[kCasMaxStages + 1] = {};
-    CasGroup cas_hist[kCasMaxStages - 1];
+    CasGroup cas_ring[kCasMaxStages];        // the launches on their way: the one k launches back is hist(k - 1)
+    int cas_head = 0;
+    CasGroup &hist(int k) { return cas_ring[(cas_head + k) % kCasMaxStages]; }
     CasGroup cas_pending;
     int cas_batch = 1;
     CascadeLayer cas_layer[kCasMaxLayers];
@@ -312,6 +321,8 @@ int make_layout(const idf_net &net, int B, int max_seg, int64_t out_cap, Layout 
         L.cas_transit_off = off;
         off = align_up(off + (size_t)L.cas_boundaries * 2 * B * kCasSegMax * L.cas_transit_stride * 4);
         transit_per_stream = (size_t)L.cas_boundaries * 2 * kCasSegMax * L.cas_transit_stride * 4;
+        // (a launch of held-back segments hands over the rows of all of them: kCasSegMax times the
+        // rows of one; with a launch per push only the first of these is ever in use)
     }
     L.total = off;
     L.sizes.workspace_bytes = off;
@@ -470,96 +481,147 @@ void cascade_layers(idf_streams *s)
     }
 }
 
-// The step of every layer for a segment of n_rows rows arriving at row r.
-int cascade_schedule(idf_streams *s, int n_rows, int64_t r, int n_streams, idf_streams::CasSeg &p, double &bytes)
+// Which rows a segment of n_rows rows arriving at row r brings to every layer.
+void cascade_propagate(idf_streams *s, int n_rows, int64_t r, int n_streams, idf_streams::CasSeg &p, double &bytes)
 {
     const idf_net &net = *s->net;
     const int n = (int)net.g.size();
     int64_t y0 = r, cnt = n_rows;
     for (int l = 0; l < n; ++l) {
         const Geom &g = net.g[l];
-        CascadeStep &L = p.st[l];
-        L = CascadeStep{};
+        p.y0[l] = y0; p.cnt[l] = (int)cnt;
         if (cnt > 0) {
             ConvStep c{};
             c.g = g; c.y0 = y0; c.cnt = (int)cnt; c.o_lo = rows_final(g, y0); c.o_fin = rows_final(g, y0 + cnt);
             c.o_hi = std::max(rows_touched(g, y0 + cnt), c.o_fin);
             c.in_by_position = l == 0; c.to_output = l == n - 1; c.bias = s->cas_layer[l].bias;
             bytes += conv_step_bytes(net, c, n_streams);
-            const int64_t y0p = y0 + g.p_h;
-            const int rho = (int)(y0p % g.s_h);
-            const int64_t o_base = y0p / g.s_h + cascade1d_slot_off(g.s_h, rho);
-            {   // what a lane issues per channel that holds an event: the kernel's variant for 4, 8 or 16
-                // new rows computes all of them, all nine tap positions that land on an output row
-                const int nin = cnt <= 4 ? 4 : cnt <= 8 ? 8 : 16;
-                int f = 0;
-                for (int j = 0; j < nin; ++j)
-                    for (int ky = 0; ky < kCasKMax; ++ky)
-                        if ((rho + j - ky) % g.s_h == 0) ++f;
-                L.fma_per_channel = (short)f;
-            }
-            const int64_t t_lo = c.o_lo - o_base, t_fin = c.o_fin - o_base, t_hi = c.o_hi - o_base;
-            const int64_t d0 = o_base * g.s_h - g.p_h - y0;
-            if (cnt > kCasRowsMax || t_lo < 0 || t_hi > kCasSlotsMax || d0 < -127 || d0 > 127)
-                return fail(IDF_ESTATE, "internal: cascade schedule of layer %d out of range", l);
-            L.cnt = (signed char)cnt; L.rho = (signed char)rho;
-            L.t_lo = (signed char)t_lo; L.t_fin = (signed char)t_fin; L.t_hi = (signed char)t_hi;
-            L.slot0 = (signed char)(((o_base % g.k_h) + g.k_h) % g.k_h);
-            L.d0 = (signed char)d0;
-            L.at_start = y0 == 0;
-            for (int j = 0; j < cnt && j < kCasRowsMax; ++j) {
-                int t = 0;
-                for (int ky = 0; ky < g.k_h; ++ky) {
-                    const int64_t u = y0 + j + g.p_h - ky;
-                    if (u < 0 || u % g.s_h != 0) continue;
-                    if (g.h_out > 0 && u / g.s_h >= g.h_out) continue;
-                    ++t;
-                }
-                L.taps[j] = (unsigned char)t;
-            }
             y0 = c.o_lo; cnt = c.o_fin - c.o_lo;
         }
     }
+    p.y0[n] = y0; p.cnt[n] = (int)cnt;
+}
+
+// The step of layer l for input rows [y0, y0 + cnt).
+int cascade_step(const idf_net &net, int l, int64_t y0, int64_t cnt, CascadeStep &L)
+{
+    const Geom &g = net.g[l];
+    L = CascadeStep{};
+    if (cnt <= 0) return IDF_OK;
+    const int64_t o_lo = rows_final(g, y0), o_fin = rows_final(g, y0 + cnt);
+    const int64_t o_hi = std::max(rows_touched(g, y0 + cnt), o_fin);
+    const int64_t y0p = y0 + g.p_h;
+    const int rho = (int)(y0p % g.s_h);
+    const int64_t o_base = y0p / g.s_h + cascade1d_slot_off(g.s_h, rho);
+    {   // what a lane issues per channel that holds an event: the kernel's variant for 4, 8 or 16
+        // new rows computes all of them, all nine tap positions that land on an output row
+        const int nin = cnt <= 4 ? 4 : cnt <= 8 ? 8 : 16;
+        int f = 0;
+        for (int j = 0; j < nin; ++j)
+            for (int ky = 0; ky < kCasKMax; ++ky)
+                if ((rho + j - ky) % g.s_h == 0) ++f;
+        L.fma_per_channel = (short)f;
+    }
+    const int64_t t_lo = o_lo - o_base, t_fin = o_fin - o_base, t_hi = o_hi - o_base;
+    const int64_t d0 = o_base * g.s_h - g.p_h - y0;
+    if (cnt > kCasRowsMax || t_lo < 0 || t_hi > kCasSlotsMax || d0 < -127 || d0 > 127)
+        return fail(IDF_ESTATE, "internal: cascade schedule of layer %d out of range", l);
+    L.cnt = (signed char)cnt; L.rho = (signed char)rho;
+    L.t_lo = (signed char)t_lo; L.t_fin = (signed char)t_fin; L.t_hi = (signed char)t_hi;
+    L.slot0 = (signed char)(((o_base % g.k_h) + g.k_h) % g.k_h);
+    L.d0 = (signed char)d0;
+    L.at_start = y0 == 0;
+    for (int j = 0; j < cnt && j < kCasRowsMax; ++j) {
+        int t = 0;
+        for (int ky = 0; ky < g.k_h; ++ky) {
+            const int64_t u = y0 + j + g.p_h - ky;
+            if (u < 0 || u % g.s_h != 0) continue;
+            if (g.h_out > 0 && u / g.s_h >= g.h_out) continue;
+            ++t;
+        }
+        L.taps4[j >> 1] |= (unsigned char)(t << ((j & 1) * 4));
+    }
     return IDF_OK;
+}
+
+// How a stage whose first layer is l0 takes the segments of a launch: consecutive segments
+// together while their rows fit one step (stage 0 gathers the rows of several pushed segments
+// itself: those must bring the same number of rows each).  first[m] = first segment of step m.
+int cascade_steps_of(const idf_streams::CasGroup &g, int l0, bool merge, int first[kCasSegMax + 1])
+{
+    int m = 0, q = 0;
+    while (q < g.n) {
+        int rows = g.seg[q].cnt[l0], e = q + 1;
+        while (merge && e < g.n && rows + g.seg[e].cnt[l0] <= kCasRowsMax &&
+               (l0 > 0 || g.seg[e].n_rows == g.seg[q].n_rows))
+            rows += g.seg[e++].cnt[l0];
+        first[m++] = q;
+        q = e;
+    }
+    first[m] = g.n;
+    return m;
 }
 
 // One launch: stage 0 takes the new segments (none: the stages only move on), stage k those of
 // the launch k launches earlier.  staged == false: all layers in one stage, nothing may be on its way.
 int cascade_launch(idf_streams *s, const StreamSel &sel, const idf_streams::CasGroup *fresh, bool staged)
 {
-    const int n = (int)s->net->g.size();
+    const idf_net &net = *s->net;
+    const int n = (int)net.g.size();
     CascadeArgs a{};
     a.n_layers = n;
     a.n_stages = staged ? s->cas_stages : 1;
     for (int k = 0; k <= kCasMaxStages; ++k) a.stage_lo[k] = staged ? s->cas_lo[k] : (k == 0 ? 0 : n);
     a.transit_wr = s->cas_parity;
     for (int l = 0; l < n; ++l) a.layer[l] = s->cas_layer[l];
-    const idf_streams::CasGroup *last_stage = fresh;       // whose output rows this launch completes
     for (int k = 0; k < a.n_stages; ++k) {
-        const idf_streams::CasGroup *src = k == 0 ? fresh : (s->cas_hist[k - 1].n > 0 ? &s->cas_hist[k - 1] : nullptr);
-        a.stage_segs[k] = src ? src->n : 0;
-        for (int q = 0; src && q < src->n; ++q)
-            for (int l = a.stage_lo[k]; l < a.stage_lo[k + 1]; ++l) a.step[q][l] = src->seg[q].st[l];
-        if (k == a.n_stages - 1) last_stage = src;
+        const idf_streams::CasGroup *src = k == 0 ? fresh : (s->hist(k - 1).n > 0 ? &s->hist(k - 1) : nullptr);
+        if (!src) continue;
+        const int l0 = a.stage_lo[k], l1 = a.stage_lo[k + 1];
+        int first[kCasSegMax + 1];
+        const int n_steps = cascade_steps_of(*src, l0, src->n > 1, first);
+        if (n_steps > kCasStepMax) return fail(IDF_ESTATE, "internal: %d steps in one cascade launch", n_steps);
+        a.stage_steps[k] = n_steps;
+        a.steps_max = std::max(a.steps_max, n_steps);
+        int in_rows = 0, out_rows = 0;                  // rows of the launch before this step: into the stage, out of it
+        for (int m = 0; m < n_steps; ++m) {
+            const int q0 = first[m], q1 = first[m + 1];
+            int64_t y0 = 0, cnt = 0;
+            for (int q = q0; q < q1; ++q) {
+                if (cnt == 0) y0 = src->seg[q].y0[l0];          // (where a segment brings the layer no row, its y0 says nothing)
+                cnt += src->seg[q].cnt[l0];
+            }
+            for (int l = l0; l < l1; ++l) {
+                CascadeStep &st = a.step[m][l];
+                int rc = cascade_step(net, l, y0, cnt, st);
+                if (rc != IDF_OK) return rc;
+                if (l == l0) { st.in_off = (short)in_rows; st.seg0 = (signed char)q0; st.seg_rows = (signed char)src->seg[q0].n_rows; }
+                if (l == l1 - 1) st.out_off = (short)out_rows;
+                const int64_t o_lo = cnt > 0 ? rows_final(net.g[l], y0) : y0, o_fin = cnt > 0 ? rows_final(net.g[l], y0 + cnt) : y0;
+                if (cnt <= 0) break;
+                y0 = o_lo; cnt = o_fin - o_lo;
+            }
+            for (int q = q0; q < q1; ++q) { in_rows += src->seg[q].cnt[l0]; out_rows += src->seg[q].cnt[l1]; }
+            if (k == a.n_stages - 1) a.out_slot0[m] = src->seg[q0].out_slot0;
+        }
     }
     for (int q = 0; fresh && q < fresh->n; ++q) {
         a.in[q] = fresh->seg[q].dev_rows;
-        a.in_stream_stride[q] = fresh->seg[q].n_rows * s->net->in_c;
+        a.in_stream_stride[q] = fresh->seg[q].n_rows * net.in_c;
     }
     a.transit = s->ws + s->cas_transit_off;
-    a.transit_seg_stride = (int)s->cas_transit_stride;
     a.transit_stream_stride = (int64_t)kCasSegMax * s->cas_transit_stride;
     a.transit_buf_stride = a.transit_stream_stride * s->B;
     a.out = s->ws + s->out_off; a.out_stride = s->out_stride; a.out_cap = s->out_cap;
-    for (int q = 0; last_stage && q < last_stage->n; ++q) a.out_slot0[q] = last_stage->seg[q].out_slot0;
     a.stats = (unsigned long long *)(s->ws + s->stats_off);
     a.issued = s->count_issued ? (unsigned long long *)(s->ws + s->issued_off) : nullptr;
     hipError_t e = launch_cascade1d(a, sel, launch_ctx(s, kKindCascade1d, fresh ? fresh->bytes : 0.0));
     if (e != hipSuccess) return dev_fail(e, "cascade launch");
     if (staged) {
-        for (int k = kCasMaxStages - 2; k > 0; --k) s->cas_hist[k] = s->cas_hist[k - 1];
-        if (fresh) s->cas_hist[0] = *fresh; else s->cas_hist[0].n = 0;
-        for (int k = s->cas_stages - 1; k < kCasMaxStages - 1; ++k) s->cas_hist[k].n = 0;   // left the last stage
+        // every launch on its way is one launch older now; the new one takes the place of the oldest
+        s->cas_head = (s->cas_head + kCasMaxStages - 1) % kCasMaxStages;
+        if (fresh) s->hist(0).take(*fresh); else s->hist(0).n = 0;
+        for (int k = s->cas_stages - 1; k < kCasMaxStages; ++k) s->hist(k).n = 0;   // left the last stage
         s->cas_parity ^= 1;
     }
     return IDF_OK;
@@ -586,7 +648,7 @@ int cascade_drain(idf_streams *s)
     all.n = s->B; all.base = 0; all.pos0 = 0;
     for (;;) {
         bool pending = false;
-        for (int k = 0; k < kCasMaxStages - 1; ++k) pending |= s->cas_hist[k].n > 0;
+        for (int k = 0; k < kCasMaxStages - 1; ++k) pending |= s->hist(k).n > 0;
         if (!pending) return IDF_OK;
         rc = cascade_launch(s, all, nullptr, true);
         if (rc != IDF_OK) return rc;
@@ -606,18 +668,21 @@ int enqueue_cascade1d(idf_streams *s, const StreamSel &sel, const void *dev_rows
         if (rc != IDF_OK) return rc;
         idf_streams::CasGroup g;
         g.n = 1;
-        rc = cascade_schedule(s, n_rows, r, sel.n, g.seg[0], g.bytes);
-        if (rc != IDF_OK) return rc;
+        cascade_propagate(s, n_rows, r, sel.n, g.seg[0], g.bytes);
         g.seg[0].out_slot0 = out_slot0; g.seg[0].dev_rows = dev_rows; g.seg[0].n_rows = n_rows;
         return cascade_launch(s, sel, &g, false);
     }
     idf_streams::CasGroup &p = s->cas_pending;
     idf_streams::CasSeg &seg = p.seg[p.n];
-    int rc = cascade_schedule(s, n_rows, r, sel.n, seg, p.bytes);
-    if (rc != IDF_OK) return rc;
+    cascade_propagate(s, n_rows, r, sel.n, seg, p.bytes);
     seg.out_slot0 = out_slot0; seg.dev_rows = dev_rows; seg.n_rows = n_rows;
     ++p.n;
-    return p.n >= s->cas_batch ? cascade_flush(s) : IDF_OK;
+    // the launch is due when enough segments are held back, or when one more could need more steps
+    // than a stage runs in one launch (every stage merges at least as well as the one that merges nothing)
+    if (p.n >= s->cas_batch || p.n >= kCasSegMax) return cascade_flush(s);
+    int first[kCasSegMax + 1], worst = 0;
+    for (int l = 0; l < (int)s->net->g.size(); ++l) worst = std::max(worst, cascade_steps_of(p, l, true, first));
+    return worst >= kCasStepMax ? cascade_flush(s) : IDF_OK;
 }
 
 // The matrix-core step of conv layer l (with the pool fused behind it, if any) for input row y:
@@ -1673,7 +1738,7 @@ int idf_get_issued_macs(idf_streams *s, int stream_id, uint64_t *macs_issued)
 int idf_set_push_batching(idf_streams *s, int k)
 {
     if (!s) return fail(IDF_EINVAL, "null argument");
-    if (k < 1 || k > kCasSegMax) return fail(IDF_EINVAL, "segments per launch %d outside [1, %d]", k, kCasSegMax);
+    if (k < 1 || k > kCasSegMax) return fail(IDF_EINVAL, "pushes per launch %d outside [1, %d]", k, kCasSegMax);
     if (!s->use_cascade1d) return fail(IDF_EUNSUPPORTED, "holding back pushes is built for nets served by the 1-D cascade");
     if (s->eager.on) return fail(IDF_EUNSUPPORTED, "eager emission delivers every segment at once");
     int rc = pipeline_drain(s);                  // what is held back was pushed under the old setting

@@ -35,6 +35,7 @@
 // padded with zeros so that every lane can run the same number of steps.
 #include "idf.h"
 #include "idf_kernels.h"
+#include <cstddef>
 
 namespace idf {
 
@@ -48,6 +49,9 @@ constexpr int kXStride = 20;                         // floats per channel in LD
 constexpr int kAhead = kCasAhead;                    // input channels whose weights are in flight
 constexpr int kBatch = 4;                            // input channels whose rows are read from LDS together
 constexpr int kArgWords = (sizeof(CascadeArgs) + 3) / 4;
+constexpr int kArgWordsFixed = offsetof(CascadeArgs, step) / 4;              // what every launch needs on chip
+constexpr int kArgWordsPerStep = sizeof(CascadeStep) * kCasMaxLayers / 4;     // plus this per step in use
+static_assert(offsetof(CascadeArgs, step) % 4 == 0 && (sizeof(CascadeStep) * kCasMaxLayers) % 4 == 0, "copied word by word");
 constexpr int kRingPerLayer = kKMax * 64;            // floats of rolling buffer per layer at most
 constexpr int kXinPerLane = (kCasRowsMax * 64 + kT - 1) / kT;      // values of a segment per lane at most
 constexpr int kRingPerLane = (kRingPerLayer + kT - 1) / kT;
@@ -259,7 +263,7 @@ __global__ void __launch_bounds__(kCasThreads, 2) k_cascade1d(const CascadeArgs 
     const int stream = sel_stream(sel, si);
     const int n_layers = ka.n_layers;
     const int lb = ka.stage_lo[stage], le = ka.stage_lo[stage + 1];
-    const int n_seg = ka.stage_segs[stage];                      // segments this stage runs one after the other
+    const int n_seg = ka.stage_steps[stage];                     // steps this stage runs one after the other
     const CascadeLayer &first = ka.first[stage];
     const CascadeStep &first_step = ka.first_step[stage];
     // First round of scalar loads, asked for in one batch with one wait (left to first use they
@@ -279,18 +283,50 @@ __global__ void __launch_bounds__(kCasThreads, 2) k_cascade1d(const CascadeArgs 
     const gfloat *tr_in = as_global((const float *)ka.transit) + ((stage - 1) * 2 + (ka.transit_wr ^ 1)) * ka.transit_buf_stride +
                           (int64_t)stream * ka.transit_stream_stride;
     float xin[kXinPerLane];
-    auto request_rows = [&](int q, int cnt_q) {
-        const int n_in = cnt_q * c0;                             // at most 16 rows x 64 channels
-        const gfloat *in = stage == 0
-            ? as_global((const float *)ka.in[q]) + (int64_t)(sel.pos0 + si) * ka.in_stream_stride[q]
-            : tr_in + q * ka.transit_seg_stride;
+    // A step of stage 0 takes the rows of one pushed segment or gathers those of several; the table of
+    // segments is read as scalars for the launch's first step when that is one segment (the usual
+    // launch per push: nothing may wait for the copy of the arguments on chip), from that copy later.
+    const __attribute__((address_space(4))) char *kargs = (const __attribute__((address_space(4))) char *)__builtin_amdgcn_kernarg_segment_ptr();
+    auto request_rows = [&](const CascadeStep &st, const CascadeArgs *on_chip) {
+        const int n_in = st.cnt * c0;                            // at most 16 rows x 64 channels
+        if (stage == 0 && !on_chip && st.cnt <= st.seg_rows) {
+            const gfloat *in = as_global((const float *)ka.in[0]) + (int64_t)(sel.pos0 + si) * ka.in_stream_stride[0];
 #pragma unroll
-        for (int u = 0; u < kXinPerLane; ++u) {
-            const int i = tid + u * kT;
-            xin[u] = in[n_in > 0 ? (i < n_in ? i : n_in - 1) : 0];
+            for (int u = 0; u < kXinPerLane; ++u) {
+                const int i = tid + u * kT;
+                xin[u] = in[n_in > 0 ? (i < n_in ? i : n_in - 1) : 0];
+            }
+        } else if (stage == 0) {
+            const int per_seg = st.seg_rows * c0;                // values one pushed segment brings (at most 16 x 64)
+            // i / per_seg through a float: (i + 0.5) / per_seg is at least 0.5 / 1024 away from every integer,
+            // the rounding of the product stays far below that
+            const float inv = 1.0f / (float)(per_seg > 0 ? per_seg : 1);
+#pragma unroll
+            for (int u = 0; u < kXinPerLane; ++u) {
+                int i = tid + u * kT;
+                i = n_in > 0 ? (i < n_in ? i : n_in - 1) : 0;
+                const int sq = (int)(((float)i + 0.5f) * inv), within = i - sq * per_seg;
+                const int q = st.seg0 + (n_in > 0 ? sq : 0);
+                uint64_t base;
+                int stride;
+                if (on_chip) {
+                    base = (uint64_t)on_chip->in[q]; stride = on_chip->in_stream_stride[q];
+                } else {
+                    base = *(const __attribute__((address_space(4))) uint64_t *)(kargs + offsetof(CascadeArgs, in) + q * 8);
+                    stride = *(const __attribute__((address_space(4))) int *)(kargs + offsetof(CascadeArgs, in_stream_stride) + q * 4);
+                }
+                xin[u] = ((const gfloat *)base)[(int64_t)(sel.pos0 + si) * stride + within];
+            }
+        } else {
+            const gfloat *in = tr_in + st.in_off * c0;
+#pragma unroll
+            for (int u = 0; u < kXinPerLane; ++u) {
+                const int i = tid + u * kT;
+                xin[u] = in[n_in > 0 ? (i < n_in ? i : n_in - 1) : 0];
+            }
         }
     };
-    request_rows(0, first_step.cnt);
+    request_rows(first_step, nullptr);
     // Second round: what the rolling-buffer requests of the stage's layers need.  The first
     // kPinned layers of the stage in one batch; a stage with more layers (a deep net run without
     // stages) fetches the rest as it goes.
@@ -361,7 +397,7 @@ __global__ void __launch_bounds__(kCasThreads, 2) k_cascade1d(const CascadeArgs 
                 const int j = i / c0, c = i - j * c0;
                 lds.x[0][c * kXStride + j] = xin[u];
                 atomicOr(&lds.chmask[0][c >> 5], 1u << (c & 31));
-                ev += 1; taps += a.step[seg][lb].taps[j];
+                ev += 1; taps += cascade_taps(a.step[seg][lb], j);
             }
         }
         if (ka.stats && __ballot(ev != 0)) {
@@ -373,7 +409,7 @@ __global__ void __launch_bounds__(kCasThreads, 2) k_cascade1d(const CascadeArgs 
             }
         }
     }
-    if (seg + 1 < n_seg) request_rows(seg + 1, uni(a.step[seg + 1][lb].cnt));    // the next segment's rows, on their way while this one runs
+    if (seg + 1 < n_seg) request_rows(a.step[seg + 1][lb], &a);  // the next step's rows, on their way while this one runs
     lds_barrier();
 
     int cur_buf = 0;
@@ -420,7 +456,7 @@ __global__ void __launch_bounds__(kCasThreads, 2) k_cascade1d(const CascadeArgs 
         // all its cells are issued before anything is summed.
         const bool last = l == n_layers - 1, hand_over = l == le - 1 && !last;
         gfloat *tr = (gfloat *)ka.transit + (stage * 2 + ka.transit_wr) * ka.transit_buf_stride +
-                     (int64_t)stream * ka.transit_stream_stride + seg * ka.transit_seg_stride;
+                     (int64_t)stream * ka.transit_stream_stride + uni(ss.out_off) * c_out;
         const int rows_per_pass = kT >> cp_log;
         const int c = tid & (m.cp - 1), cc = c < c_out ? c : c_out - 1;
         int t_of[kCellsPerThread], at[kCellsPerThread];
@@ -528,7 +564,7 @@ __global__ void __launch_bounds__(kCasThreads, 2) k_cascade1d(const CascadeArgs 
                 unsigned int ev = 0, taps = 0;
                 for (int rr = 0; rr < (64 >> cp_log); ++rr) {
                     const int n = __popcll((nz >> (rr << cp_log)) & rowmask);
-                    if (n) { ev += n; taps += n * a.step[seg][l + 1].taps[j0 + rr]; }
+                    if (n) { ev += n; taps += n * cascade_taps(a.step[seg][l + 1], j0 + rr); }
                 }
                 unsigned long long *dst = ka.stats + ((int64_t)stream * n_layers + l + 1) * 2;
                 atomicAdd(dst, (unsigned long long)ev);
@@ -583,7 +619,7 @@ hipError_t launch_cascade1d(const CascadeArgs &a, const StreamSel &sel, const La
     if (!spread) grid_stages = b.n_stages;
     for (int k = 0; k < grid_stages; ++k) {
         if (k < b.n_stages) { b.first[k] = b.layer[b.stage_lo[k]]; b.first_step[k] = b.step[0][b.stage_lo[k]]; }
-        else { b.first[k] = CascadeLayer{}; b.first_step[k] = CascadeStep{}; b.stage_segs[k] = 0; }      // nothing to do
+        else { b.first[k] = CascadeLayer{}; b.first_step[k] = CascadeStep{}; b.stage_steps[k] = 0; }      // nothing to do
     }
     b.per = spread ? 8 / grid_stages : sel.n;
     if (sel.n / b.per > 65535) return hipErrorInvalidValue;
