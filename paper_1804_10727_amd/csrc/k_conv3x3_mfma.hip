@@ -654,6 +654,29 @@ int conv3x3_mfma_tile(const Geom &g, int n_streams)
     return kMfmaTile64x64;
 }
 
+namespace {
+void tile_shape(int tile, int &wm, int &wn)
+{
+    wm = tile == kMfmaTile64x64 || tile == kMfmaTile64x32 ? 2 : tile == kMfmaTile128x32 ? 4 : 1;
+    wn = tile == kMfmaTile64x64 || tile == kMfmaTile32x64 ? 2 : 1;
+}
+}  // namespace
+
+int conv3x3_mfma_tiles(int tile, int w, int c_out)
+{
+    int wm, wn;
+    tile_shape(tile, wm, wn);
+    return ((w + 32 * wm - 1) / (32 * wm)) * ((c_out + 32 * wn - 1) / (32 * wn));
+}
+
+int conv3x3_mfma_batch_resident(int prec, int tile)
+{
+    int wm, wn;
+    tile_shape(tile, wm, wn);
+    const int per_simd = prec == IDF_PREC_BF16 ? TraitsBf16::kOcc : prec == IDF_PREC_I8 ? TraitsI8::kOcc : TraitsF32::kOcc;
+    return std::max(1, 4 * per_simd / (wm * wn));
+}
+
 // Weights [k_h][k_w][c_in][c_out] -> fragment order [ky][k/VL][c_out_pad][VL] with k = kx*c_in + ci,
 // zero padded to whole K-steps and to a multiple of 64 output channels.
 size_t conv3x3_mfma_pack(int prec, const Geom &g, const void *w_khkwcico, void *out)
