@@ -200,7 +200,7 @@ def cpu_baseline(wl, budget_s=12.0):
                       f"scalar event-by-event fp64/int64, one stream per thread, {dt:.1f} s"}
 
 
-def run_workload(config, steps_arg=None, warmup_arg=None, eager=False, push_batch=1):
+def run_workload(config, steps_arg=None, warmup_arg=None, eager=False, push_batch=1, event_path=0):
     """Times `steps` whole batches of one workload; returns (result dict, workload)."""
     import numpy as np
     import torch
@@ -223,6 +223,8 @@ def run_workload(config, steps_arg=None, warmup_arg=None, eager=False, push_batc
         st.enable_eager()
     if push_batch > 1:          # throughput mode of the 1-D cascade: several pushes in step share a launch
         st.set_push_batching(push_batch)
+    if event_path > 0:          # int8: sparse tiles visit a packed event list on the vector units instead of contracting
+        st.set_event_path(event_path)
     x = input_tensor(wl, dev)
     # segment-major copy in HBM: xs[i] is the contiguous block [B][seg][W][C] of push i
     xs = x.view(B, n_seg, seg, W, C0).permute(1, 0, 2, 3, 4).contiguous()
@@ -325,7 +327,7 @@ def run_workload(config, steps_arg=None, warmup_arg=None, eager=False, push_batc
         "warmup": warmup, "ms_per_step": ms_per_step, "host_enqueue_ms_per_step": t_enq / steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": DTYPE[wl["precision"]], "data": "synthetic",
         "config": {"workload": WORKLOADS[config] + ("_eager_emission" if eager else ""), "streams": B, "rows_per_sample": H, "row_width": W,
-                   "in_channels": C0, "rows_per_push": seg, "pushes_per_step": n_seg, "pushes_per_launch": push_batch,
+                   "in_channels": C0, "rows_per_push": seg, "pushes_per_step": n_seg, "pushes_per_launch": push_batch, "event_list_events_per_kstep": event_path,
                    "layers": len(wl["layers"]),
                    # rolling buffers + held rows (what the paper bounds), the rows waiting between layers
                    # across calls in the staged mode that was timed, and their sum
@@ -377,6 +379,8 @@ def main():
     ap.add_argument("--eager", action="store_true", help="eager emission (configs 3 and 4): output valid after every push")
     ap.add_argument("--push-batch", type=int, default=1,
                     help="1-D workloads: hold back up to this many pushes in step per launch (throughput mode; 1 = a launch per push)")
+    ap.add_argument("--event-path", type=int, default=0,
+                    help="int8 workloads: tiles with at most this many events per K-step take the event-list path (0 = off, the library's default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", dest="others", action="store_false",
                     help="skip the short runs of the other workloads (reported under other_workloads)")
@@ -405,7 +409,7 @@ def main():
 
     import torch
     assert torch.cuda.is_available(), "bench.py needs the GPU"
-    res, wl = run_workload(args.config, args.steps, args.warmup, eager=args.eager, push_batch=args.push_batch)
+    res, wl = run_workload(args.config, args.steps, args.warmup, eager=args.eager, push_batch=args.push_batch, event_path=args.event_path)
     if args.eager:
         print(json.dumps(res))
         return

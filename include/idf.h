@@ -246,6 +246,19 @@ int idf_get_stats(idf_streams *s, int stream_id, uint64_t *events_in, uint64_t *
 int idf_count_issued_macs(idf_streams *s, int on);
 int idf_get_issued_macs(idf_streams *s, int stream_id, uint64_t *macs_issued);
 
+/* Event-list variant of the int8 matrix-core kernel (Sec. 1 and Sec. 3: work in proportion to the
+ * events, one visit per event and tap).  A tile whose stretch holds at most events_per_kstep events
+ * per K-step of its contraction (and at most 256 in all; a first layer of 1-4 input channels: at
+ * most 256) packs them into a list in LDS and visits them on the vector units -- three multiply-adds
+ * per event and output channel -- instead of contracting; layers of more than 16 input channels and
+ * the other precisions always contract.  The sums are the same integers either way, so outputs do
+ * not change bit for bit; only idf_get_issued_macs and the time do.  0 (the setting after open)
+ * switches it off: on MI355X one K-step of the contraction costs a wave less than the visit of a
+ * single event's three taps for 32 channels, so the list only pays below about one event per 16
+ * positions and channels, far sparser than rectified feature maps are.  Takes effect for segments
+ * pushed after the call (drains what is on its way).  IDF_EUNSUPPORTED under eager emission. */
+int idf_set_event_path(idf_streams *s, int events_per_kstep);
+
 /* Rows of the current sample a stream has been given so far (host bookkeeping, no device work). */
 int idf_rows_pushed(const idf_streams *s, int stream_id, int64_t *rows);
 

@@ -15,7 +15,7 @@ KIND = {"conv": 0, "maxpool": 1}
 ACT = {"none": 0, "relu": 1, "relu_shr_clamp": 2}
 
 EXPORTS = ["idf_create_net", "idf_create_net_columnwise", "idf_destroy_net", "idf_query_sizes", "idf_open_streams", "idf_open_streams_static", "idf_close_streams",
-           "idf_push_segment", "idf_set_push_batching", "idf_read_outputs", "idf_reset_streams", "idf_get_stats", "idf_count_issued_macs", "idf_get_issued_macs", "idf_rows_pushed",
+           "idf_push_segment", "idf_set_push_batching", "idf_read_outputs", "idf_reset_streams", "idf_get_stats", "idf_count_issued_macs", "idf_get_issued_macs", "idf_set_event_path", "idf_rows_pushed",
            "idf_layer_kernel", "idf_last_error", "idf_profile_begin", "idf_profile_end", "idf_enable_head",
            "idf_read_head", "idf_query_head_units_bytes", "idf_enable_head_units", "idf_read_head_units", "idf_push_pixels", "idf_query_eager_bytes", "idf_enable_eager", "idf_read_announced", "idf_read_announced_rows", "idf_eager_state_bytes", "idf_snapshot_bytes", "idf_snapshot", "idf_restore"]
 
@@ -88,6 +88,7 @@ def load_library():
     L.idf_get_stats.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
     L.idf_get_issued_macs.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
     L.idf_count_issued_macs.argtypes = [C.c_void_p, C.c_int]
+    L.idf_set_event_path.argtypes = [C.c_void_p, C.c_int]
     L.idf_rows_pushed.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_int64)]
     L.idf_enable_head.argtypes = [C.c_void_p]
     L.idf_query_head_units_bytes.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_size_t)]
@@ -241,6 +242,9 @@ class Streams:
 
     def count_issued_macs(self, on=True):
         _check(load_library().idf_count_issued_macs(self._h, int(bool(on))))
+
+    def set_event_path(self, events_per_kstep):
+        _check(load_library().idf_set_event_path(self._h, int(events_per_kstep)))
 
     def get_issued_macs(self, stream_id):
         iss = np.zeros(len(self.net.layers), dtype=np.uint64)

@@ -246,6 +246,8 @@ struct MfmaStep {
     void *dst;   int64_t dst_stream_stride;
     int to_output;
     const void *wfrag;                 // fragment-ordered weights
+    const void *w_ev;                  // int8 nets: weights for the event path, [kx][c_in][c_out_pad] words of the three ky taps
+    int ev_limit;                      // a tile with at most this many events (its halo included) goes the event path (0: never)
     const void *bias;
     unsigned long long *stats;
     unsigned long long *issued;        // [stream][layer]: multiply-adds issued by the matrix instructions (zeros inside live steps included)

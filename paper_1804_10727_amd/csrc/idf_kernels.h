@@ -66,6 +66,10 @@ bool conv3x3_mfma_eligible(int prec, const Geom &g);
 int conv3x3_mfma_tile(const Geom &g, int n_streams);
 // Packs weights [k_h][k_w][c_in][c_out] into fragment order; returns the size (out may be null).
 size_t conv3x3_mfma_pack(int prec, const Geom &g, const void *w_khkwcico, void *out);
+// Where in that packing the event-path weights of an int8 layer begin (0: the layer has none), and the
+// most events (tile and halo) the event path takes.
+size_t conv3x3_mfma_event_weights(int prec, const Geom &g);
+int conv3x3_mfma_event_cap();
 // Tiles of one stream's row of w positions x c_out channels in a launch of that tile shape, and how many
 // workgroups of such a launch one compute unit holds at once (by the registers the kernel is built for).
 int conv3x3_mfma_tiles(int tile, int w, int c_out);

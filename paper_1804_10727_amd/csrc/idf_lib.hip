@@ -88,6 +88,7 @@ struct ProfRec {
 struct idf_streams {
     int static_dev = -1;             // >= 0: the workspace is that device's static array (given back at close)
     int cus = 0;                     // compute units of the device the streams were opened on
+    int ev_per_step = 0;             // int8 event path (idf_set_event_path): events a tile may hold per K-step of its contraction and still go that way; 0: off
     bool use_cascade1d = false;      // whole-net kernel for 1-D nets instead of one launch per layer
     bool prof_on = false;
     std::vector<ProfRec> prof;
@@ -747,6 +748,18 @@ void make_mfma_step(idf_streams *s, int l, int64_t y, int n_streams, MfmaStep &a
     a.dst_stream_stride = last_out ? s->out_stride : s->transit_stride[lp];
     a.to_output = last_out;
     a.wfrag = s->ws + s->wm_off[l];
+    if (const size_t ev_at = conv3x3_mfma_event_weights(net.precision, g)) {
+        // Up to how many events a tile goes the event path, once the caller has switched it on: a first
+        // layer of a few channels whenever the list holds them, elsewhere ev_per_step events per K-step
+        // that the contraction would take.
+        a.w_ev = s->ws + s->wm_off[l] + ev_at;
+        const int vl = conv3x3_mfma_vl(net.precision);
+        const int steps = (3 * g.c_in + 2 * vl - 1) / (2 * vl);
+        // (layers of more than 16 input channels never take it: their share of the weights would crowd
+        // the LDS of every workgroup of the launch for tiles too sparse to exist in practice)
+        a.ev_limit = s->ev_per_step == 0 || g.c_in > 16 ? 0
+                     : g.c_in < vl ? conv3x3_mfma_event_cap() : std::min(conv3x3_mfma_event_cap(), steps * s->ev_per_step);
+    }
     a.bias = net.b_img[l].empty() ? nullptr : s->ws + s->b_off[l];
     a.stats = (unsigned long long *)(s->ws + s->stats_off);
     a.issued = s->count_issued ? (unsigned long long *)(s->ws + s->issued_off) : nullptr;
@@ -1717,6 +1730,17 @@ int idf_count_issued_macs(idf_streams *s, int on)
     int rc = pipeline_drain(s);                 // what is on its way was pushed under the old setting
     if (rc != IDF_OK) return rc;
     s->count_issued = on != 0;
+    return IDF_OK;
+}
+
+int idf_set_event_path(idf_streams *s, int events_per_kstep)
+{
+    if (!s) return fail(IDF_EINVAL, "null argument");
+    if (events_per_kstep < 0) return fail(IDF_EINVAL, "events per K-step %d is negative", events_per_kstep);
+    if (s->eager.on) return fail(IDF_EUNSUPPORTED, "eager emission has one kernel per layer kind and no event-list variant");
+    int rc = pipeline_drain(s);                 // what is on its way was pushed under the old setting
+    if (rc != IDF_OK) return rc;
+    s->ev_per_step = std::min(events_per_kstep, 1 << 16);
     return IDF_OK;
 }
 

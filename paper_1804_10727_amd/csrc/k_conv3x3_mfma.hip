@@ -33,6 +33,7 @@ typedef __attribute__((ext_vector_type(16))) int i32x16;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 
 struct TraitsBf16 {
+    static constexpr bool kEvents = false;
     static constexpr int kOcc = 3;           // waves per SIMD the batch kernel is compiled for (168 registers)
     static constexpr int kDepth = 3;         // K-steps whose operands are in flight: three waves hide more than six steps did for two
     static constexpr int VL = 8;             // elements per 16-byte lane fragment
@@ -65,6 +66,7 @@ struct TraitsBf16 {
 };
 
 struct TraitsI8 {
+    static constexpr bool kEvents = true;    // sparse tiles take the event-list path on the vector units
     static constexpr int kOcc = 2;           // three gain nothing where a launch is one short round of workgroups
     static constexpr int kDepth = 3;           // measured against 4 and 6 on the event workload
     static constexpr int VL = 16;
@@ -103,6 +105,7 @@ struct TraitsI8 {
 // 32x32x2 matrix instructions (instruction i pairs element i of the two half-waves' fragments;
 // which two k share an instruction does not matter to the sum).
 struct TraitsF32 {
+    static constexpr bool kEvents = false;
     static constexpr int kOcc = 2;
     static constexpr int kDepth = 3;         // a step is twelve long matrix instructions here: little to hide
     static constexpr int VL = 4;
@@ -141,9 +144,15 @@ template <class P> __device__ __forceinline__ P *at4(P *base, uint32_t byte_off)
 }
 
 constexpr int kMaxPos = 128 + 2;                 // positions of the widest tile plus halo
+constexpr int kEvCap = 256;                      // events (tile and halo) the event path takes at most
+
+// LDS the event path needs behind the stretch / staging area: offsets and counts per position, the
+// packed event list, and the sums it hands to the accumulators.
+// and the tile's share of the layer's weights (three words per input channel and output channel).
+constexpr size_t event_lds_bytes(int mt, int nc, int c_in) { return (size_t)(2 * (mt + 4) + kEvCap + 3 * mt * nc + 3 * c_in * nc) * 4; }
 constexpr int kNzWords = (kMaxPos + 31) / 32 + 1;
 
-template <class T, int WM, int WN, bool COUNT>
+template <class T, int WM, int WN, bool COUNT, bool EV>
 __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &sel, const int bx, const int si)
 {
     using acc_t = typename T::acc_t; using st_t = typename T::st_t; using ev_t = typename T::ev_t;
@@ -152,6 +161,7 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     __shared__ uint32_t nz[64][kNzWords];          // per channel chunk: positions with a non-zero cell
     __shared__ unsigned long long red[2][WM * WN];
+    __shared__ unsigned int red_ev[WM * WN];       // events of the tile and its halo, per wave (event path)
 
     // Every argument the kernel uses is asked for here, in one batch of scalar loads with one
     // wait: left to first use, the loads end up behind conditions and cost one memory round
@@ -277,7 +287,9 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
     lds_barrier();                               // occupancy bits are cleared
     {
         const bool count = co_chunk == 0 && a.stats;
+        const bool weigh = EV && a.ev_limit > 0;   // the tile's events decide which way it goes
         unsigned int ev = 0, taps = 0;               // per lane: a few cells
+        unsigned int ev_all = 0;                     // halo included
         if (!small_c) {
             for (int base = 0; base < cells; base += NT * kBatch) {
                 if (base > 0) tile_issue(base);
@@ -291,10 +303,13 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
                     *reinterpret_cast<i32x4 *>(smem + p * xs_stride + c * 16) = tv[b];
                     if (T::cell_nonzero(tv[b])) {
                         atomicOr(&nz[c][p >> 5], 1u << (p & 31));
-                        if (count && p >= 1 && p <= MT) {
+                        if (weigh || (count && p >= 1 && p <= MT)) {
                             const int n = T::count_nonzero(tv[b]);
-                            ev += n;
-                            taps += n * (3 - (x == 0) - (x == W - 1));
+                            ev_all += n;
+                            if (count && p >= 1 && p <= MT) {
+                                ev += n;
+                                taps += n * (3 - (x == 0) - (x == W - 1));
+                            }
                         }
                     }
                 }
@@ -310,15 +325,22 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
                 ev_t v = 0;
                 if (x >= a.x_lo && x < a.x_hi) v = *at4(in_e, (uint32_t)((x * C_in + (i - p * C_in)) * EB));
                 xs_e[i] = v;
-                if (count && p >= 1 && p <= MT && T::ev_nonzero(v)) {
-                    ev += 1;
-                    taps += 3 - (x == 0) - (x == W - 1);
+                if (T::ev_nonzero(v)) {
+                    ev_all += 1;
+                    if (count && p >= 1 && p <= MT) {
+                        ev += 1;
+                        taps += 3 - (x == 0) - (x == W - 1);
+                    }
                 }
             }
         }
         if (count) {
             for (int off = 32; off > 0; off >>= 1) { ev += __shfl_down(ev, off); taps += __shfl_down(taps, off); }
             if (lane == 0) { red[0][wave] = ev; red[1][wave] = taps; }
+        }
+        if (weigh) {
+            for (int off = 32; off > 0; off >>= 1) ev_all += __shfl_down(ev_all, off);
+            if (lane == 0) red_ev[wave] = ev_all;
         }
         lds_barrier();
         if (count && tid == 0) {
@@ -334,9 +356,125 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
 #pragma unroll
     for (int d = 0; d < kDepth; ++d) fetch_b(d, d < steps ? d : steps - 1);
 
+    // ---- sparse tiles: the event-list path ------------------------------------------------------
+    // Zero values are not events (Sec. 1): where a tile and its halo hold few of them, the update is
+    // done event by event on the vector units instead of as a contraction that multiplies the zeros.
+    //   1. Every position's non-zero values are counted (one lane per position), an exclusive prefix
+    //      sum over the positions gives each its place in a packed list, and the events (channel,
+    //      value) are written there position by position: a compressed row.
+    //   2. If the list is short enough (the host's cost model says up to how many events the vector
+    //      units are the faster way), lanes = output channels take the tile's output positions in
+    //      turn; for a position the events of its three input positions lie one after the other in
+    //      the list; each event costs one weight word (the three ky taps of its (kx, channel) for
+    //      this lane's output channel) and three multiply-adds.  The sums go to the matrix path's
+    //      accumulators through LDS, and everything after is common.
+    bool use_events = false;
+    if constexpr (EV) {
+        if (a.ev_limit > 0) {
+            const size_t front = (size_t)(MT + 2) * (small_c ? C_in * EB : xs_stride), stg = (size_t)MT * NC * EB;
+            int32_t *ev_cnt = reinterpret_cast<int32_t *>(smem + (((front > stg ? front : stg) + 15) & ~(size_t)15));
+            int32_t *ev_off = ev_cnt + (MT + 4);
+            uint32_t *ev_list = reinterpret_cast<uint32_t *>(ev_off + (MT + 4));
+            int32_t *dsum = reinterpret_cast<int32_t *>(ev_list + kEvCap);
+            uint32_t *wlds = reinterpret_cast<uint32_t *>(dsum + 3 * MT * NC);      // [kx][c_in][NC]
+            const ev_t *xs_flat = reinterpret_cast<const ev_t *>(smem);
+            // visits every non-zero value of stretch position p in channel order
+            auto for_events = [&](int p, auto &&f) {
+                if (small_c) {
+                    for (int ci = 0; ci < C_in; ++ci) {
+                        const ev_t v = xs_flat[p * C_in + ci];
+                        if (T::ev_nonzero(v)) f(ci, v);
+                    }
+                } else {
+                    for (int c = 0; c < chunks; ++c) {
+                        if (!(nz[c][p >> 5] >> (p & 31) & 1u)) continue;
+                        const ev_t *cell = reinterpret_cast<const ev_t *>(smem + p * xs_stride + c * 16);
+                        for (int e = 0; e < VL; ++e)
+                            if (T::ev_nonzero(cell[e])) f(c * VL + e, cell[e]);
+                    }
+                }
+            };
+            unsigned int n_ev = 0;
+            for (int wv = 0; wv < WM * WN; ++wv) n_ev += red_ev[wv];
+            use_events = n_ev <= (unsigned)a.ev_limit && n_ev <= (unsigned)kEvCap;
+            if (use_events && n_ev > 0) {
+                // the tile's share of the weights, asked for first: on its way while the list is made
+                {
+                    const uint32_t *wsrc = reinterpret_cast<const uint32_t *>(a.w_ev) + co0;
+                    for (int i = tid; i < 3 * C_in * NC; i += NT) {
+                        const int row = i / NC, col = i - row * NC;
+                        wlds[i] = wsrc[(size_t)row * a.c_out_pad + col];
+                    }
+                }
+                int my_cnt = 0;
+                if (tid < MT + 2) {
+                    for_events(tid, [&](int, ev_t) { ++my_cnt; });
+                    ev_cnt[tid] = my_cnt;
+                }
+                lds_barrier();
+                if (tid <= MT + 2) {                 // exclusive prefix: where position tid's events begin (entry MT+2: the total)
+                    int o = 0;
+                    for (int q = 0; q < tid; ++q) o += ev_cnt[q];
+                    ev_off[tid] = o;
+                }
+                lds_barrier();
+            }
+            if (use_events && n_ev > 0) {
+                if (tid < MT + 2) {
+                    int at = ev_off[tid];
+                    for_events(tid, [&](int ci, ev_t v) { ev_list[at++] = ((uint32_t)ci << 8) | (T::bits(v) & 0xffu); });
+                }
+                lds_barrier();
+                constexpr int PG = NT / NC;              // output positions worked on side by side
+                const int co_l = tid % NC, pg = tid / NC;
+                const uint32_t *wev = wlds + co_l;
+                unsigned long long visits = 0;
+                for (int r = pg; r < MT; r += PG) {
+                    const int i0 = ev_off[r], i1 = ev_off[r + 1], i2 = ev_off[r + 2], i3 = ev_off[r + 3];
+                    int32_t d0 = 0, d1 = 0, d2 = 0;
+                    for (int idx = i0; idx < i3; idx += 4) {
+                        uint32_t wv[4];
+                        int32_t vv[4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {        // the four weight words are asked for before the first is used
+                            const int id = idx + u;
+                            const bool ok = id < i3;
+                            const uint32_t e = ev_list[ok ? id : i0];
+                            const int kx = (id >= i1) + (id >= i2);
+                            const int ci = (int)(e >> 8);
+                            vv[u] = ok ? (int32_t)(int8_t)(e & 0xffu) : 0;
+                            wv[u] = wev[(ok ? kx * C_in + ci : 0) * NC];
+                        }
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            d0 += vv[u] * (int32_t)(int8_t)(wv[u] & 0xffu);
+                            d1 += vv[u] * (int32_t)(int8_t)((wv[u] >> 8) & 0xffu);
+                            d2 += vv[u] * (int32_t)(int8_t)((wv[u] >> 16) & 0xffu);
+                        }
+                    }
+                    dsum[(0 * MT + r) * NC + co_l] = d0;
+                    dsum[(1 * MT + r) * NC + co_l] = d1;
+                    dsum[(2 * MT + r) * NC + co_l] = d2;
+                    visits += (unsigned long long)(i3 - i0);
+                }
+                if (COUNT && a.issued && co_l == 0 && visits)
+                    atomicAdd(a.issued + (int64_t)stream * a.n_layers + a.layer, visits * (3ull * NC));
+                lds_barrier();
+                const int dcol = wn * 32 + (lane & 31), drow = wm * 32 + row_lane;
+#pragma unroll
+                for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            acc[ky][i * 4 + j] += (st_t)dsum[(ky * MT + drow + 8 * i + j) * NC + dcol];
+            }
+        }
+    }
+
     // ---- which K-steps have anything in them for this wave's 32 positions -------------------
     unsigned long long live;
-    {
+    if (!use_events) {
         bool occ = small_c && lane < steps;          // few channels: every step is visited
         if (!small_c && lane < steps) {
 #pragma unroll
@@ -358,8 +496,12 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
                       (unsigned long long)__builtin_popcountll(live) * (3ull * 32 * 32 * KI));
     }
 
+    else live = 0;
+
     // ---- contraction over the live K-steps ----------------------------------------------------
-    if (small_c) {
+    if (use_events) {
+        // done above, event by event
+    } else if (small_c) {
         // first layers: K = 3*C_in <= 12, one or two steps (all prefetched); the fragment is gathered
         // element by element
         const ev_t *xs_e = reinterpret_cast<const ev_t *>(smem) + r * C_in;
@@ -550,10 +692,10 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
     }
 }
 
-template <class T, int WM, int WN, bool COUNT>
-__global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a, const StreamSel sel)
+template <class T, int WM, int WN, bool COUNT, bool EV>
+__global__ void __launch_bounds__(64 * WM * WN, 2) k_conv3x3_mfma(const MfmaStep a, const StreamSel sel)
 {
-    conv3x3_row<T, WM, WN, COUNT>(a, sel, blockIdx.z, blockIdx.x);      // tile by tile, the streams of a tile side by side
+    conv3x3_row<T, WM, WN, COUNT, EV>(a, sel, blockIdx.z, blockIdx.x);      // tile by tile, the streams of a tile side by side
 }
 
 // Several layers' steps in one launch (each on a row that was complete before the launch).  The grid
@@ -568,10 +710,10 @@ __global__ void __launch_bounds__(64 * WM * WN) k_conv3x3_mfma(const MfmaStep a,
 // streams close in time, and every step is spread evenly.  (Stream by stream with the tiles inside was
 // measured 8 % slower on the VGG-style workload; one contiguous eighth of the order per XCD slower
 // still: the steps differ too much in length.)
-template <class T, int WM, int WN, bool COUNT>
+template <class T, int WM, int WN, bool COUNT, bool EV>
 __global__ void __launch_bounds__(64 * WM * WN, T::kOcc) k_conv3x3_mfma_batch(const MfmaBatch b, const StreamSel sel)
 {
-    conv3x3_row<T, WM, WN, COUNT>(b.st[blockIdx.z], sel, blockIdx.y, blockIdx.x);
+    conv3x3_row<T, WM, WN, COUNT, EV>(b.st[blockIdx.z], sel, blockIdx.y, blockIdx.x);
 }
 
 template <class T, int WM, int WN>
@@ -587,9 +729,27 @@ hipError_t launch_batch_shape(const MfmaBatch &b, const StreamSel &sel, const La
         lds = std::max(lds, (size_t)MT * NC * T::EB);
     }
     if (b.n < 1 || tiles_max < 1 || tiles_max > 65535) return hipErrorInvalidValue;      // tiles are the grid's y extent
+    const dim3 grid(sel.n, tiles_max, b.n), block(64 * WM * WN);
+    if constexpr (T::kEvents) {
+        // room for the event path behind a step's stretch / staging area, or no event path for that step; the kernel
+        // that carries the event path is a separate one, so a launch without it pays nothing for it
+        MfmaBatch bb = b;
+        const size_t base = (lds + 15) & ~(size_t)15;
+        bool any = false;
+        for (int k = 0; k < bb.n; ++k) {
+            if (bb.st[k].ev_limit <= 0) continue;
+            const size_t need = base + event_lds_bytes(MT, NC, bb.st[k].c_in);
+            if (need <= 64 * 1024) { lds = std::max(lds, need); any = true; }
+            else bb.st[k].ev_limit = 0;
+        }
+        if (any) {
+            if (b.st[0].issued) return launch(k_conv3x3_mfma_batch<T, WM, WN, true, true>, grid, block, lds, lc, bb, sel);
+            return launch(k_conv3x3_mfma_batch<T, WM, WN, false, true>, grid, block, lds, lc, bb, sel);
+        }
+    }
     // the variant that adds up what it issues is a kernel of its own: the one that is timed carries none of it
-    if (b.st[0].issued) return launch(k_conv3x3_mfma_batch<T, WM, WN, true>, dim3(sel.n, tiles_max, b.n), dim3(64 * WM * WN), lds, lc, b, sel);
-    return launch(k_conv3x3_mfma_batch<T, WM, WN, false>, dim3(sel.n, tiles_max, b.n), dim3(64 * WM * WN), lds, lc, b, sel);
+    if (b.st[0].issued) return launch(k_conv3x3_mfma_batch<T, WM, WN, true, false>, grid, block, lds, lc, b, sel);
+    return launch(k_conv3x3_mfma_batch<T, WM, WN, false, false>, grid, block, lds, lc, b, sel);
 }
 
 template <class T>
@@ -613,8 +773,16 @@ hipError_t launch_one(const MfmaStep &a, const StreamSel &sel, const LaunchCtx &
     const size_t stage = (size_t)MT * NC * T::EB;       // the epilogue reuses the space to stage emitted rows
     if (lds < stage) lds = stage;
     if (x_tiles * co_chunks > 65535) return hipErrorInvalidValue;      // tiles are the grid's z extent
-    if (a.issued) return launch(k_conv3x3_mfma<T, WM, WN, true>, dim3(sel.n, 1, x_tiles * co_chunks), dim3(64 * WM * WN), lds, lc, a, sel);
-    return launch(k_conv3x3_mfma<T, WM, WN, false>, dim3(sel.n, 1, x_tiles * co_chunks), dim3(64 * WM * WN), lds, lc, a, sel);
+    const dim3 grid(sel.n, 1, x_tiles * co_chunks), block(64 * WM * WN);
+    if constexpr (T::kEvents) {
+        const size_t with_events = ((lds + 15) & ~(size_t)15) + event_lds_bytes(MT, NC, a.c_in);
+        if (a.ev_limit > 0 && with_events <= 64 * 1024) {
+            if (a.issued) return launch(k_conv3x3_mfma<T, WM, WN, true, true>, grid, block, with_events, lc, a, sel);
+            return launch(k_conv3x3_mfma<T, WM, WN, false, true>, grid, block, with_events, lc, a, sel);
+        }
+    }
+    if (a.issued) return launch(k_conv3x3_mfma<T, WM, WN, true, false>, grid, block, lds, lc, a, sel);
+    return launch(k_conv3x3_mfma<T, WM, WN, false, false>, grid, block, lds, lc, a, sel);
 }
 
 template <class T> hipError_t launch_prec(const MfmaStep &a, const StreamSel &sel, const LaunchCtx &lc)
@@ -684,11 +852,20 @@ size_t conv3x3_mfma_pack(int prec, const Geom &g, const void *w_khkwcico, void *
     const int vl = conv3x3_mfma_vl(prec), eb = 16 / vl;
     const int KT = 3 * g.c_in, steps = (KT + 2 * vl - 1) / (2 * vl), kc = 2 * steps;
     const int cop = (g.c_out + 63) / 64 * 64;
-    const size_t bytes = (size_t)3 * kc * cop * 16;
+    const size_t frag_bytes = (size_t)3 * kc * cop * 16;
+    // int8: behind the fragments the same weights for the event path, [kx][c_in][cop] words holding the taps ky = 0, 1, 2 of
+    // (kx, c_in, c_out) in their three low bytes
+    const size_t bytes = frag_bytes + (prec == IDF_PREC_I8 ? (size_t)3 * g.c_in * cop * 4 : 0);
     if (!out) return bytes;
     unsigned char *o = (unsigned char *)out;
     const unsigned char *src = (const unsigned char *)w_khkwcico;
     for (size_t i = 0; i < bytes; ++i) o[i] = 0;
+    if (prec == IDF_PREC_I8)
+        for (int ky = 0; ky < 3; ++ky)
+            for (int kx = 0; kx < 3; ++kx)
+                for (int ci = 0; ci < g.c_in; ++ci)
+                    for (int co = 0; co < g.c_out; ++co)
+                        o[frag_bytes + (((size_t)kx * g.c_in + ci) * cop + co) * 4 + ky] = src[(((size_t)ky * 3 + kx) * g.c_in + ci) * g.c_out + co];
     for (int ky = 0; ky < 3; ++ky)
         for (int k = 0; k < KT; ++k) {
             const int kx = k / g.c_in, ci = k % g.c_in;
@@ -700,6 +877,16 @@ size_t conv3x3_mfma_pack(int prec, const Geom &g, const void *w_khkwcico, void *
         }
     return bytes;
 }
+
+size_t conv3x3_mfma_event_weights(int prec, const Geom &g)
+{
+    if (prec != IDF_PREC_I8) return 0;
+    const int vl = conv3x3_mfma_vl(prec);
+    const int KT = 3 * g.c_in, steps = (KT + 2 * vl - 1) / (2 * vl);
+    return (size_t)3 * 2 * steps * ((g.c_out + 63) / 64 * 64) * 16;
+}
+
+int conv3x3_mfma_event_cap() { return kEvCap; }
 
 hipError_t launch_conv3x3_mfma_batch(int prec, const MfmaBatch &b, const StreamSel &sel, const LaunchCtx &lc)
 {

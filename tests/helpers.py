@@ -56,7 +56,7 @@ def oracle_many(fn, wl, streams, threads=None, **kw):
         return list(ex.map(lambda b: fn(wl, b, **kw), streams))
 
 
-def gpu_run(wl, seg_rows=None, device="cuda:0", return_streams=False, count_issued=False):
+def gpu_run(wl, seg_rows=None, device="cuda:0", return_streams=False, count_issued=False, events_per_kstep=None):
     """Whole sample of every stream through the GPU library, seg_rows rows per push."""
     import torch
     import paper_1804_10727_amd as idf
@@ -68,6 +68,8 @@ def gpu_run(wl, seg_rows=None, device="cuda:0", return_streams=False, count_issu
     H = wl["in_h"]
     if count_issued:
         st.count_issued_macs(True)
+    if events_per_kstep is not None:
+        st.set_event_path(events_per_kstep)
     for r in range(0, H, seg):
         st.push_segment(x[:, r:r + seg].contiguous())
     out, first, cnt = st.read_outputs(max_rows=int(st.sizes.out_h))
