@@ -342,6 +342,7 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
             for (int off = 32; off > 0; off >>= 1) ev_all += __shfl_down(ev_all, off);
             if (lane == 0) red_ev[wave] = ev_all;
         }
+        if (!small_c && tid == 0) *reinterpret_cast<i32x4 *>(smem + C_in * EB) = i32x4{0, 0, 0, 0};      // the padding behind position 0: a cell of zeros
         lds_barrier();
         if (count && tid == 0) {
             unsigned long long e = 0, t = 0;
@@ -524,8 +525,10 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
         // loop body is straight-line code and each slot waits for exactly its own operands.
         const int n_live = __builtin_popcountll(live);
         int s_last = 0;
+        bool any_left = true;
         auto next_step = [&]() {
             const int f = __builtin_ffsll((long long)live);           // 0 when nothing is left
+            any_left = f != 0;
             const int sn = f ? f - 1 : s_last;
             s_last = sn;
             live &= live - 1;
@@ -535,28 +538,38 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
             const int k0 = sn * KI + hlf * VL;
             const int kx = (int)__umulhi((unsigned)k0, a.c_in_rcp);   // k0 / C_in
             const int ci = k0 - kx * C_in;
-            const bool ok = k0 < KT;                                  // half a step of padding at the end of K
-            const i32x4 v = *reinterpret_cast<const i32x4 *>(smem + (r + (ok ? kx : 0)) * xs_stride + (ok ? ci : 0) * EB);
-            aq[d] = ok ? v : i32x4{0, 0, 0, 0};
+            // half a step of padding at the end of K, and slots past the last live step: these read the cell of zeros
+            // behind position 0 (no select after the read, so nothing waits for it before the slot's turn comes)
+            const bool ok = any_left && k0 < KT;
+            aq[d] = *reinterpret_cast<const i32x4 *>(smem + (ok ? (r + kx) * xs_stride + ci * EB : C_in * EB));
         };
         if (n_live > 0) {
+            int sn0[kDepth];
+            bool guessed = true;
 #pragma unroll
             for (int d = 0; d < kDepth; ++d) {
-                const int sn = next_step();
-                fetch_a(d, sn);
-                if (sn != (d < steps ? d : steps - 1)) fetch_b(d, sn);   // the guess was another step
+                sn0[d] = next_step();
+                fetch_a(d, sn0[d]);
+                guessed &= sn0[d] == (d < steps ? d : steps - 1);
+            }
+            // a wrong guess: all slots again, in slot order -- whichever way the loop is entered, the youngest requests
+            // are then slot 0's, 1's, ... in turn, and each slot's wait inside the loop can leave the others in flight
+            if (!guessed) {
+#pragma unroll
+                for (int d = 0; d < kDepth; ++d) fetch_b(d, sn0[d]);
             }
             for (int it = 0; it < n_live; it += kDepth) {
 #pragma unroll
                 for (int d = 0; d < kDepth; ++d) {
-                    if (it + d < n_live) {
-                        acc[0] = T::mfma(aq[d], bq[d][0], acc[0]);
-                        acc[1] = T::mfma(aq[d], bq[d][1], acc[1]);
-                        acc[2] = T::mfma(aq[d], bq[d][2], acc[2]);
-                    }
+                    // no branch around these: past the last live step the slot multiplies zeros, and the loop body stays
+                    // one straight line in which every slot's wait leaves the younger slots' requests in flight
+                    acc[0] = T::mfma(aq[d], bq[d][0], acc[0]);
+                    acc[1] = T::mfma(aq[d], bq[d][1], acc[1]);
+                    acc[2] = T::mfma(aq[d], bq[d][2], acc[2]);
                     const int sn = next_step();
                     fetch_a(d, sn);
                     fetch_b(d, sn);
+                    __builtin_amdgcn_sched_barrier(0);      // the slots stay in this order: requests go out right behind their slot's matrix instructions
                 }
             }
         }
