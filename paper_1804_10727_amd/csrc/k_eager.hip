@@ -15,6 +15,8 @@
 // or every row when the net has biases; a row reached for the first time starts from zero
 // whatever its slot held.  All values are 4 bytes: float32, or int32 for the quantised nets; a
 // bfloat16 net announces values rounded to bfloat16 (the last layer unrounded).
+#include <cstdlib>
+
 #include "idf.h"
 #include "idf_kernels.h"
 
@@ -53,7 +55,7 @@ template <> struct Val<kI8> {
         if (g.act == IDF_ACT_RELU_SHR_CLAMP) { r >>= g.shr; r = r > g.clamp_hi ? g.clamp_hi : r; }
         return r;
     }
-    static __device__ __forceinline__ t mac(t acc, t d, w_t w) { return acc + d * (t)w; }
+    static __device__ __forceinline__ t mac(t acc, t d, w_t w) { return acc + __mul24(d, (t)w); }     // differences of announced int8 values: well inside 24 bits
 };
 
 // Non-zero differences announced by this workgroup: the events delivered to the next layer.
@@ -173,6 +175,371 @@ __global__ void __launch_bounds__(256) k_eager_conv(const EagerStep a, const Str
     count_events(nz, a.stats && a.layer + 1 < a.n_layers ? a.stats + ((int64_t)stream * a.n_layers + a.layer + 1) * 2 : nullptr);
 }
 
+// 3x3 / stride 1 / padding 1 conv layers: the same update, laid out for the vector units.  A lane
+// owns a chunk's output channel for POS neighbouring positions of every output row the segment's
+// delta rows reach, and its cells stay in registers from the first delta to the announcement; a
+// workgroup is one stream's row stretch of up to 256 / G lane groups.  The delta rows are staged
+// in LDS, all input channels at once if they fit (else 16 at a time), as [row][channel][position],
+// so that a lane reads the deltas its positions look at through one tap row as one or two wide
+// reads of a single address per group; a weight is fetched once per lane and used for every cell
+// it owns.  Zero deltas are multiplied like any other here: among the rows a segment's events
+// reach, about half of the announced values change, and a multiply-add costs less than finding
+// out.  (The sum of a cell is taken channel by channel, delta row by delta row: float results
+// differ from k_eager_conv's in the last bits.)
+//   k_eager_conv3x3_band: NIN delta rows, NIN + 2 output rows (those outside the map are worked out
+//     and dropped), no test anywhere in the loop over the channels;
+//   k_eager_conv3x3_rows: any band, eight output rows per workgroup, a bit test per (delta row, tap row).
+constexpr int kEagLds = 60 * 1024;
+// Input channels staged at a time: all of them when the staged rows fit the LDS budget, else 16.
+__host__ __device__ inline int eager_chunk(int rows, int c_in, int xtp) { return (size_t)rows * c_in * xtp * 4 <= (size_t)kEagLds ? c_in : 16; }
+
+// What a workgroup of either kernel knows about itself.
+template <int P, int POS> struct EagerTile {
+    using val_t = typename Val<P>::t;
+    int tid, nt, G, XT, XTP, x0, gi, xb, co, co_c, W;
+    bool co_ok;
+    __device__ __forceinline__ EagerTile(const Geom &g)
+    {
+        tid = threadIdx.x; nt = blockDim.x;
+        int g_log = 4;                                          // G = 16, 32 or 64 lanes: the channels of a chunk
+        while ((1 << g_log) < g.c_out && g_log < 6) ++g_log;
+        G = 1 << g_log;
+        XT = (nt >> g_log) * POS;                               // positions per workgroup
+        XTP = (XT + 2 + 3) & ~3;                                // a staged row: one position of halo either side, 16-byte rows
+        const int co_chunks = (g.c_out + G - 1) >> g_log;
+        const int x_tile = blockIdx.x / co_chunks, chunk = blockIdx.x - x_tile * co_chunks;
+        x0 = x_tile * XT;
+        gi = tid >> g_log;
+        xb = x0 + gi * POS;
+        co = chunk * G + (tid & (G - 1));
+        co_ok = co < g.c_out;
+        co_c = co_ok ? co : g.c_out - 1;
+        W = g.w_out;                                            // = g.w_in
+    }
+    // n_rows delta rows from row i_first on go to LDS rows lds_row0 .. as [row][channel][position], channels [ci0, ci0 + ck)
+    __device__ __forceinline__ void stage(const EagerStep &a, const val_t *din, val_t *lds, int i_first, int n_rows, int lds_row0, int ckm, int ci0, int ck) const
+    {
+        typedef val_t v4 __attribute__((ext_vector_type(4)));
+        const Geom &g = a.g;
+        const int spots = n_rows * (XT + 2);                    // (row, position) of the staged stretch
+        for (int i = tid; i < spots; i += nt) {
+            const int r = i / (XT + 2), xi = i - r * (XT + 2);
+            const int x = x0 - 1 + xi;
+            const bool in = x >= 0 && x < W;
+            const val_t *src = din + ((int64_t)((i_first + r) % a.in_rows) * W + (in ? x : 0)) * g.c_in + ci0;
+            val_t *dst = lds + ((lds_row0 + r) * ckm) * XTP + xi;
+            if ((ck & 15) == 0 && (g.c_in & 3) == 0) {
+                for (int q0 = 0; q0 < ck; q0 += 16) {
+                    v4 v[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) v[q] = *reinterpret_cast<const v4 *>(src + q0 + 4 * q);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        if (!in) v[q] = v4{0, 0, 0, 0};
+                        val_t *d4 = dst + (q0 + 4 * q) * XTP;
+                        d4[0] = v[q].x; d4[XTP] = v[q].y; d4[2 * XTP] = v[q].z; d4[3 * XTP] = v[q].w;
+                    }
+                }
+            } else {
+                for (int cc = 0; cc < ck; ++cc) dst[cc * XTP] = in ? src[cc] : (val_t)0;
+            }
+        }
+    }
+    // the POS + 2 deltas this lane's positions look at in one staged row of one channel
+    __device__ __forceinline__ void window(const val_t *wp, val_t (&win)[POS + 2]) const
+    {
+        typedef val_t v4 __attribute__((ext_vector_type(4)));
+        typedef val_t v2 __attribute__((ext_vector_type(2)));
+        const v4 q0 = *reinterpret_cast<const v4 *>(wp);
+        win[0] = q0.x; win[1] = q0.y; win[2] = q0.z; win[3] = q0.w;
+        if (POS == 8) {
+            const v4 q1 = *reinterpret_cast<const v4 *>(wp + 4);
+            win[4] = q1.x; win[5] = q1.y; win[6] = q1.z; win[7] = q1.w;
+        }
+        const v2 q2 = *reinterpret_cast<const v2 *>(wp + POS);
+        win[POS] = q2.x; win[POS + 1] = q2.y;
+    }
+};
+
+// Rows o_first .. o_first + ROWS - 1 of the lane's cells (bit j of rows_on: row j exists and belongs to
+// this workgroup): the state as it was, or zero / the bias where it starts.
+template <int P, int ROWS, int POS>
+__device__ __forceinline__ void eager_load_state(const EagerStep &a, const EagerTile<P, POS> &t, int stream, int o_first, unsigned int rows_on,
+                                                 typename Val<P>::t (&acc)[ROWS][POS])
+{
+    using val_t = typename Val<P>::t;
+    const Geom &g = a.g;
+    const val_t bias_v = a.init_bias && a.bias ? ((const val_t *)a.bias)[t.co_c] : (val_t)0;
+    const val_t *c_old = (const val_t *)a.c + (int64_t)stream * a.c_stride;
+    const int64_t row_elems = (int64_t)t.W * g.c_out;
+    int slot = (o_first % a.c_rows + a.c_rows) % a.c_rows;      // (o_first may be -1: the row above the map)
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) {
+        const int o = o_first + j;
+        const bool keep = ((rows_on >> j) & 1u) && !a.init_bias && o < a.fresh_lo && t.co_ok;    // a row reached before: its state continues
+#pragma unroll
+        for (int p = 0; p < POS; ++p) {
+            acc[j][p] = bias_v;
+            if (keep && t.xb + p < t.W) acc[j][p] = c_old[(int64_t)slot * row_elems + (int64_t)(t.xb + p) * g.c_out + t.co];
+        }
+        slot = slot + 1 == a.c_rows ? 0 : slot + 1;
+    }
+}
+
+// The same rows go back; every cell announces f(c) minus what it announced last.  What was announced
+// is asked for first, for all cells at once: taken cell by cell between the stores, every request
+// would wait out a memory round trip of its own.  Returns this lane's events.
+template <int P, int ROWS, int POS>
+__device__ __forceinline__ unsigned int eager_announce(const EagerStep &a, const EagerTile<P, POS> &t, int stream, int o_first, unsigned int rows_on,
+                                                       const typename Val<P>::t (&acc)[ROWS][POS])
+{
+    using V = Val<P>;
+    using val_t = typename V::t;
+    const Geom &g = a.g;
+    val_t *c_new = (val_t *)a.c + (int64_t)stream * a.c_stride;
+    val_t *ann = (val_t *)a.ann + (int64_t)stream * a.ann_stride;
+    val_t *dlt = (val_t *)a.dlt_out + (int64_t)stream * a.dlt_stride;
+    const int64_t row_elems = (int64_t)t.W * g.c_out;
+    uint32_t cell[POS];
+    bool have[POS];
+#pragma unroll
+    for (int p = 0; p < POS; ++p) {
+        have[p] = t.co_ok && t.xb + p < t.W;
+        cell[p] = (uint32_t)((have[p] ? t.xb + p : 0) * g.c_out + t.co_c);
+    }
+    val_t old[ROWS][POS];
+    int slot = (o_first % a.ann_rows + a.ann_rows) % a.ann_rows;
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) {
+        const bool first = o_first + j >= a.fresh_lo && !a.init_bias;           // nothing announced so far
+        const bool on = ((rows_on >> j) & 1u) && !first;
+#pragma unroll
+        for (int p = 0; p < POS; ++p) {
+            old[j][p] = 0;
+            if (on && have[p]) old[j][p] = ann[(int64_t)slot * row_elems + cell[p]];
+        }
+        slot = slot + 1 == a.ann_rows ? 0 : slot + 1;
+    }
+    unsigned int events = 0;
+    int s_c = (o_first % a.c_rows + a.c_rows) % a.c_rows, s_d = (o_first % a.dlt_rows + a.dlt_rows) % a.dlt_rows;
+    slot = (o_first % a.ann_rows + a.ann_rows) % a.ann_rows;
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) {
+        if ((rows_on >> j) & 1u) {
+#pragma unroll
+            for (int p = 0; p < POS; ++p) {
+                if (!have[p]) continue;
+                c_new[(int64_t)s_c * row_elems + cell[p]] = acc[j][p];
+                const val_t h = V::act(g, acc[j][p], a.round_bf16), d = h - old[j][p];
+                ann[(int64_t)slot * row_elems + cell[p]] = h;
+                dlt[(int64_t)s_d * row_elems + cell[p]] = d;
+                events += d != 0;
+            }
+        }
+        s_c = s_c + 1 == a.c_rows ? 0 : s_c + 1;
+        s_d = s_d + 1 == a.dlt_rows ? 0 : s_d + 1;
+        slot = slot + 1 == a.ann_rows ? 0 : slot + 1;
+    }
+    return events;
+}
+
+// The workgroup's events: one addition to the stream's counter of the next layer.
+__device__ __forceinline__ void eager_count(const EagerStep &a, int stream, unsigned int events, unsigned int *ev_sum)
+{
+    if (!a.stats || a.layer + 1 >= a.n_layers) return;
+    __syncthreads();
+    if (events) atomicAdd(ev_sum, events);
+    __syncthreads();
+    if (threadIdx.x == 0 && *ev_sum) atomicAdd(a.stats + ((int64_t)stream * a.n_layers + a.layer + 1) * 2, (unsigned long long)*ev_sum);
+}
+
+template <int P, int NIN, int POS>
+__global__ void __launch_bounds__(256) k_eager_conv3x3_band(const EagerStep a, const StreamSel sel)
+{
+    using V = Val<P>;
+    using val_t = typename V::t;
+    using w_t = typename V::w_t;
+    extern __shared__ __attribute__((aligned(16))) unsigned char eag_smem[];
+    val_t *lds = reinterpret_cast<val_t *>(eag_smem);
+    __shared__ unsigned int ev_sum;
+    const Geom &g = a.g;
+    const int stream = sel_stream(sel, blockIdx.z);
+    const EagerTile<P, POS> t(g);
+    if (t.tid == 0) ev_sum = 0;
+    // delta rows [i_lo, i_lo + NIN) reach output rows i_lo - 1 .. i_lo + NIN: row j of the lane's cells is row i_lo - 1 + j
+    const int o_first = a.i_lo - 1;
+    unsigned int rows_on = 0;
+#pragma unroll
+    for (int j = 0; j < NIN + 2; ++j)
+        if (o_first + j >= a.o_lo && o_first + j < a.o_hi) rows_on |= 1u << j;
+    rows_on = __builtin_amdgcn_readfirstlane(rows_on);
+    val_t acc[NIN + 2][POS];
+    eager_load_state<P, NIN + 2, POS>(a, t, stream, o_first, rows_on, acc);
+
+    const val_t *din = (const val_t *)a.dlt_in + (int64_t)stream * a.in_map_stride;
+    // this lane's nine weights of an input channel: byte offsets from a base that moves on channel by channel
+    uint32_t woff[9];
+#pragma unroll
+    for (int k = 0; k < 9; ++k) woff[k] = (uint32_t)(((size_t)k * g.c_in * g.c_out + t.co_c) * sizeof(w_t));
+    const uint32_t w_step = (uint32_t)(g.c_out * sizeof(w_t));
+    auto weight = [&](const unsigned char *base, int k) { return *reinterpret_cast<const w_t *>(base + woff[k]); };
+    const int ckm = eager_chunk(NIN, g.c_in, t.XTP);
+    for (int ci0 = 0; ci0 < g.c_in; ci0 += ckm) {
+        const int ck = g.c_in - ci0 < ckm ? g.c_in - ci0 : ckm;
+        __syncthreads();                                        // the chunk before has been read by every lane
+        t.stage(a, din, lds, a.i_lo, NIN, 0, ckm, ci0, ck);
+        __syncthreads();
+        const unsigned char *wb = (const unsigned char *)a.w + (size_t)ci0 * w_step;
+        w_t wn[9];                                              // the next channel's weights are on their way while this one's are used
+#pragma unroll
+        for (int k = 0; k < 9; ++k) wn[k] = weight(wb, k);
+        const val_t *lrow = lds + t.gi * POS;
+        for (int cc = 0; cc < ck; ++cc) {
+            w_t wv[9];
+            if (cc + 1 < ck) wb += w_step;
+#pragma unroll
+            for (int k = 0; k < 9; ++k) { wv[k] = wn[k]; wn[k] = weight(wb, k); }
+#pragma unroll
+            for (int r = 0; r < NIN; ++r) {
+                val_t win[POS + 2];
+                t.window(lrow + (r * ckm + cc) * t.XTP, win);
+#pragma unroll
+                for (int ky = 0; ky < 3; ++ky)                  // delta row i_lo + r is what row i_lo + r + 1 - ky sees through tap row ky
+#pragma unroll
+                    for (int kx = 0; kx < 3; ++kx)
+#pragma unroll
+                        for (int p = 0; p < POS; ++p) acc[r + 2 - ky][p] = V::mac(acc[r + 2 - ky][p], win[p + kx], wv[ky * 3 + kx]);
+            }
+        }
+    }
+    const unsigned int events = eager_announce<P, NIN + 2, POS>(a, t, stream, o_first, rows_on, acc);
+    eager_count(a, stream, events, &ev_sum);
+}
+
+template <int P, int POS>
+__global__ void __launch_bounds__(256) k_eager_conv3x3_rows(const EagerStep a, const StreamSel sel)
+{
+    constexpr int R = 8;
+    using V = Val<P>;
+    using val_t = typename V::t;
+    using w_t = typename V::w_t;
+    extern __shared__ __attribute__((aligned(16))) unsigned char eag_smem[];
+    val_t *lds = reinterpret_cast<val_t *>(eag_smem);
+    __shared__ unsigned int ev_sum;
+    const Geom &g = a.g;
+    const int stream = sel_stream(sel, blockIdx.z);
+    const EagerTile<P, POS> t(g);
+    if (t.tid == 0) ev_sum = 0;
+    const int oa = a.o_lo + blockIdx.y * R;
+    const int nr = (a.o_hi - oa) < R ? (a.o_hi - oa) : R;
+    // the delta rows of the layer before that reach rows [oa, oa + nr)
+    const int ia = oa - 1 > a.i_lo ? oa - 1 : a.i_lo;
+    const int ib = oa + nr + 1 < a.i_hi ? oa + nr + 1 : a.i_hi;
+    const int n_in = ib > ia ? ib - ia : 0;
+    const unsigned int rows_on = __builtin_amdgcn_readfirstlane((1u << nr) - 1u);
+    val_t acc[R][POS];
+    eager_load_state<P, R, POS>(a, t, stream, oa, rows_on, acc);
+    // which (delta row, tap row) pairs exist for this workgroup: bit ri * 3 + ky, delta row oa - 1 + ri
+    // seen by output row oa + ri - ky
+    unsigned int pairs_on = 0;
+#pragma unroll
+    for (int ri = 0; ri < R + 2; ++ri)
+#pragma unroll
+        for (int ky = 0; ky < 3; ++ky) {
+            const int iy = oa - 1 + ri, rr = ri - ky;
+            if (iy >= ia && iy < ib && rr >= 0 && rr < nr) pairs_on |= 1u << (ri * 3 + ky);
+        }
+    pairs_on = __builtin_amdgcn_readfirstlane(pairs_on);        // one scalar word: a bit test and a scalar branch per pair
+
+    const val_t *din = (const val_t *)a.dlt_in + (int64_t)stream * a.in_map_stride;
+    uint32_t woff[9];
+#pragma unroll
+    for (int k = 0; k < 9; ++k) woff[k] = (uint32_t)(((size_t)k * g.c_in * g.c_out + t.co_c) * sizeof(w_t));
+    const uint32_t w_step = (uint32_t)(g.c_out * sizeof(w_t));
+    auto weight = [&](const unsigned char *base, int k) { return *reinterpret_cast<const w_t *>(base + woff[k]); };
+    const int ckm = eager_chunk(R + 2, g.c_in, t.XTP);
+    for (int ci0 = 0; ci0 < g.c_in && n_in > 0; ci0 += ckm) {
+        const int ck = g.c_in - ci0 < ckm ? g.c_in - ci0 : ckm;
+        __syncthreads();                                        // the chunk before has been read by every lane
+        t.stage(a, din, lds, ia, n_in, ia - (oa - 1), ckm, ci0, ck);            // a row is staged by its place among the R + 2
+        __syncthreads();
+        const unsigned char *wb = (const unsigned char *)a.w + (size_t)ci0 * w_step;
+        w_t wn[9];
+#pragma unroll
+        for (int k = 0; k < 9; ++k) wn[k] = weight(wb, k);
+        const val_t *lrow = lds + t.gi * POS;
+        for (int cc = 0; cc < ck; ++cc) {
+            w_t wv[9];
+            if (cc + 1 < ck) wb += w_step;
+#pragma unroll
+            for (int k = 0; k < 9; ++k) { wv[k] = wn[k]; wn[k] = weight(wb, k); }
+            // (kept from being tested once and for all outside the loop: some thirty lane masks held in scalar registers
+            // across it cost more, spilled and reloaded, than a bit test per pair)
+            unsigned int on = pairs_on;
+            asm volatile("" : "+s"(on));
+#pragma unroll
+            for (int ri = 0; ri < R + 2; ++ri) {
+                if (((on >> (ri * 3)) & 7u) == 0) continue;                     // the same for every lane
+                val_t win[POS + 2];
+                t.window(lrow + (ri * ckm + cc) * t.XTP, win);
+#pragma unroll
+                for (int ky = 0; ky < 3; ++ky) {
+                    const int rr = ri - ky;                     // output row oa + rr looks at this delta row through tap row ky
+                    if (rr < 0 || rr >= R) continue;
+                    if (!((on >> (ri * 3 + ky)) & 1u)) continue;
+#pragma unroll
+                    for (int kx = 0; kx < 3; ++kx)
+#pragma unroll
+                        for (int p = 0; p < POS; ++p) acc[rr][p] = V::mac(acc[rr][p], win[p + kx], wv[ky * 3 + kx]);
+                }
+            }
+        }
+    }
+    const unsigned int events = eager_announce<P, R, POS>(a, t, stream, oa, rows_on, acc);
+    eager_count(a, stream, events, &ev_sum);
+}
+
+template <int P, int POS>
+hipError_t launch_eager_band(int n_in, dim3 grid, dim3 block, size_t lds, const LaunchCtx &lc, const EagerStep &a, const StreamSel &sel)
+{
+    switch (n_in) {
+    case 1: return launch(k_eager_conv3x3_band<P, 1, POS>, grid, block, lds, lc, a, sel);
+    case 2: return launch(k_eager_conv3x3_band<P, 2, POS>, grid, block, lds, lc, a, sel);
+    case 3: return launch(k_eager_conv3x3_band<P, 3, POS>, grid, block, lds, lc, a, sel);
+    case 4: return launch(k_eager_conv3x3_band<P, 4, POS>, grid, block, lds, lc, a, sel);
+    case 5: return launch(k_eager_conv3x3_band<P, 5, POS>, grid, block, lds, lc, a, sel);
+    case 6: return launch(k_eager_conv3x3_band<P, 6, POS>, grid, block, lds, lc, a, sel);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+template <int P>
+hipError_t launch_eager_conv3x3(const EagerStep &a, const StreamSel &sel, const LaunchCtx &lc)
+{
+    const Geom &g = a.g;
+    int G = 16;
+    while (G < g.c_out && G < 64) G *= 2;
+    const int rows = a.o_hi - a.o_lo, n_in = a.i_hi - a.i_lo;
+    const int co_chunks = (g.c_out + G - 1) / G;
+    // one workgroup for the whole band when it is what a short segment gives: up to six delta rows and exactly the rows they reach
+    const int top = a.i_lo - 1 > 0 ? a.i_lo - 1 : 0, bottom = a.i_hi + 1 < g.h_out ? a.i_hi + 1 : g.h_out;
+    const bool band = n_in >= 1 && n_in <= 6 && a.o_lo == top && a.o_hi == bottom;
+    const int row_groups = band ? 1 : (rows + 7) / 8;
+    // eight positions per lane reuse a weight for more cells; four give twice the waves while the launch is small
+    const int64_t waves8 = (int64_t)row_groups * co_chunks * sel.n * (((int64_t)((g.w_out + 7) / 8) * G + 63) / 64);
+    const char *force = getenv("IDF_EAGER_POS");               // "4" or "8": for tests of the shape the sizes at hand would not pick
+    const bool wide = force ? force[0] == '8' : waves8 >= 2048;
+    const int pos = wide ? 8 : 4;
+    int groups = (g.w_out + pos - 1) / pos;
+    if (groups > 256 / G) groups = 256 / G;
+    const int XT = groups * pos, x_tiles = (g.w_out + XT - 1) / XT, XTP = (XT + 2 + 3) & ~3;
+    const int staged = band ? n_in : 10;
+    const size_t lds = (size_t)staged * eager_chunk(staged, g.c_in, XTP) * XTP * 4;
+    const dim3 grid((unsigned)(x_tiles * co_chunks), (unsigned)row_groups, sel.n), block((unsigned)(groups * G));
+    if (band) return wide ? launch_eager_band<P, 8>(n_in, grid, block, lds, lc, a, sel) : launch_eager_band<P, 4>(n_in, grid, block, lds, lc, a, sel);
+    return wide ? launch(k_eager_conv3x3_rows<P, 8>, grid, block, lds, lc, a, sel) : launch(k_eager_conv3x3_rows<P, 4>, grid, block, lds, lc, a, sel);
+}
+
 // 2x2 max-pool as a stateful node: re-evaluates its window of announced values.
 template <int P>
 __global__ void __launch_bounds__(256) k_eager_pool(const EagerStep a, const StreamSel sel)
@@ -218,9 +585,18 @@ hipError_t launch_eager(int prec, int what, const EagerStep &a, const StreamSel 
     dim3 grid((unsigned)((n + 255) / 256), 1, sel.n);
     const dim3 block(256);
     if (what == 1) {
-        // a group of G lanes per (position, chunk of G channels): see k_eager_conv
         int G = 16;
         while (G < a.g.c_out && G < 64) G *= 2;
+        const Geom &g = a.g;
+        // Float nets take the register-tiled kernels, which multiply every delta of the band.  The quantised nets stay with
+        // the kernel below that visits the non-zero deltas only: announced values clamped to a few levels change rarely
+        // (a tenth of the deltas are events on the int8 workload, where it is the faster of the two in the deep layers),
+        // unless IDF_EAGER_TILED asks otherwise; IDF_EAGER_PLAIN sends every net there.
+        const bool tiled = g.k_h == 3 && g.k_w == 3 && g.s_h == 1 && g.s_w == 1 && g.p_h == 1 && g.p_w == 1 && !getenv("IDF_EAGER_PLAIN");
+        if (tiled && prec == IDF_PREC_I8 && getenv("IDF_EAGER_TILED")) return launch_eager_conv3x3<kI8>(a, sel, lc);
+        if (tiled && prec == IDF_PREC_BF16) return launch_eager_conv3x3<kBf16>(a, sel, lc);
+        if (tiled && prec == IDF_PREC_F32) return launch_eager_conv3x3<kF32>(a, sel, lc);
+        // a group of G lanes per (position, chunk of G channels): see k_eager_conv
         const int64_t units = (int64_t)(a.o_hi - a.o_lo) * a.g.w_out * ((a.g.c_out + G - 1) / G);
         const int per_block = 4 * (64 / G);
         grid.x = (unsigned)((units + per_block - 1) / per_block);

@@ -41,9 +41,18 @@ def _tiny(prec, seed, layers, H, W, C0, with_bias):
                 seg_rows=1, streams=2)
 
 
+# which of the conv kernels serves the 3x3 / stride 1 / same-padded layers: the library's choice (register-tiled for float
+# nets, event by event for quantised ones), or forced: tiled with eight positions per lane, tiled for a quantised net,
+# event by event for a float net
+KERNELS = [{}, {"IDF_EAGER_POS": "8"}, {"IDF_EAGER_TILED": "1"}, {"IDF_EAGER_TILED": "1", "IDF_EAGER_POS": "8"}, {"IDF_EAGER_PLAIN": "1"}]
+
+
+@pytest.mark.parametrize("env", KERNELS, ids=lambda e: "+".join(f"{k[10:].lower()}{v}" for k, v in e.items()) or "default")
 @pytest.mark.parametrize("prec,with_bias", [("f32", True), ("f32", False), ("i8", True), ("i8", False)])
-def test_every_layer_after_every_row_against_the_literal_scheme(prec, with_bias):
+def test_every_layer_after_every_row_against_the_literal_scheme(prec, with_bias, env, monkeypatch):
     import torch
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
     import paper_1804_10727_amd as idf
     from paper_1804_10727_amd.binding import input_tensor
     q = dict(act="relu_shr_clamp", shr=2, clamp_hi=15) if prec == "i8" else {}
@@ -106,8 +115,11 @@ def test_every_layer_after_every_row_against_the_literal_scheme(prec, with_bias)
     (5, dict(streams=2, size=24, channels=(8, 8, 16, 16, 16, 16, 16)), 1),
     (5, dict(streams=2, size=24, channels=(8, 8, 16, 16, 16, 16, 16)), 5),
 ])
-def test_output_after_a_prefix_is_the_network_on_the_prefix(cfg, kw, seg):
+@pytest.mark.parametrize("env", KERNELS[:4], ids=lambda e: "+".join(f"{k[10:].lower()}{v}" for k, v in e.items()) or "default")
+def test_output_after_a_prefix_is_the_network_on_the_prefix(cfg, kw, seg, env, monkeypatch):
     import paper_1804_10727_amd as idf
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
     from paper_1804_10727_amd.binding import input_tensor
     wl = wl_mod.make(cfg, **kw)
     shp = _shapes(wl)
