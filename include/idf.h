@@ -204,8 +204,9 @@ int idf_set_push_batching(idf_streams *s, int k);
  * The pixels are taken into the first layer's rolling buffer at once; rows can only become final,
  * and the deeper layers fire, with the segment that makes the row whole (x0 + n_px == in_w), which
  * then does everything a pushed row does.  A row begun this way must be finished this way.
- * IDF_EUNSUPPORTED unless the first layer is a 3x3 / stride 1 / same-padded convolution (the one the
- * matrix-core kernel serves); IDF_ESTATE: x0 is not the next column. */
+ * Any convolution can be the first layer (any kernel size, stride and padding, all precisions).
+ * IDF_EUNSUPPORTED when the first layer is a pool, and under eager emission; IDF_ESTATE: x0 is not
+ * the next column. */
 int idf_push_pixels(idf_streams *s, const int32_t *stream_ids, int n_ids, const void *dev_pixels, int x0,
                     int n_px);
 

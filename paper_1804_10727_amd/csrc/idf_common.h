@@ -94,6 +94,10 @@ struct ConvStep {
     unsigned long long *stats;   // [stream][layer][2]: events_in, macs
     int n_layers;
     int tile_x, tile_c, cells_per_thread;
+    // A pixel segment of the network input (one row, cnt == 1): only columns [x_lo, x_hi) of the row are there,
+    // column x_lo first in the buffer; x_hi == 0: the whole row.  cont: an earlier segment of the same row has
+    // started the rows it touches, so every cell continues from the ring.
+    int x_lo, x_hi, cont;
 };
 
 struct PoolStep {

@@ -951,6 +951,10 @@ int enqueue_cascade(idf_streams *s, const StreamSel &sel, const void *dev_rows, 
                 a.w = s->ws + s->w_off[l];
                 a.bias = net.b_img[l].empty() ? nullptr : s->ws + s->b_off[l];
                 a.stats = stats; a.n_layers = n;
+                if (l == 0 && s->part.on) {       // the pixel segment that completes a row (c == 1): layer 0 takes only its columns
+                    a.x_lo = s->part.x_lo; a.x_hi = s->part.x_hi; a.cont = !s->part.first;
+                    a.in_stream_stride = (int64_t)(s->part.x_hi - s->part.x_lo) * net.in_c;
+                }
                 conv_generic_plan(a);
                 hipError_t e = launch_conv_generic(net.precision, a, sel,
                                                    launch_ctx(s, kKindConvGeneric, conv_step_bytes(net, a, sel.n), l));
@@ -1597,8 +1601,8 @@ int idf_push_pixels(idf_streams *s, const int32_t *stream_ids, int n_ids, const 
     if (n_px < 1 || x0 < 0 || x0 + n_px > net.in_w) return fail(IDF_EINVAL, "columns %d..%d outside the row of %d", x0, x0 + n_px - 1, net.in_w);
     if (s->eager.on) return fail(IDF_EUNSUPPORTED, "pixel segments are not built for eager emission");
     if (x0 == 0 && n_px == net.in_w) return idf_push_segment(s, stream_ids, n_ids, dev_pixels, 1);
-    if (s->mfma.empty() || s->mfma[0] != 1)
-        return fail(IDF_EUNSUPPORTED, "pixel segments need a first layer served by the matrix-core kernel (3x3, stride 1, same padding)");
+    const bool first_mfma = !s->mfma.empty() && s->mfma[0] == 1;
+    if (net.g[0].kind != IDF_CONV) return fail(IDF_EUNSUPPORTED, "pixel segments need a convolution as the first layer");
     int rc = check_ids(s, stream_ids, n_ids);
     if (rc != IDF_OK) return rc;
     for (int i = 0; i < n_ids; ++i) {
@@ -1623,6 +1627,27 @@ int idf_push_pixels(idf_streams *s, const int32_t *stream_ids, int n_ids, const 
     for (auto &kv : groups) {
         const int64_t r = kv.first;
         rc = for_each_selection(kv.second, [&](const StreamSel &sel) {
+            if (!first_mfma) {
+                // any other first convolution: the generic kernel with the segment's column range; every row the input
+                // row touches goes back to the rolling buffer
+                const Geom &g = net.g[0];
+                ConvStep c{};
+                c.g = g; c.layer = 0; c.y0 = r; c.cnt = 1;
+                c.o_lo = rows_final(g, r); c.o_fin = c.o_lo;
+                c.o_hi = std::max(rows_touched(g, r + 1), rows_final(g, r + 1));
+                if (c.o_hi <= c.o_lo) return (int)IDF_OK;          // the row reaches no output row (stride and padding skip it)
+                c.ring_rows = g.k_h;
+                c.in = dev_pixels; c.in_stream_stride = (int64_t)n_px * net.in_c; c.in_row0 = r; c.in_by_position = 1;
+                c.ring = s->ws + s->ring_off[0]; c.ring_stream_stride = s->ring_stride[0];
+                c.dst = nullptr; c.dst_row0 = c.o_lo; c.out_cap = s->out_cap;
+                c.w = s->ws + s->w_off[0];
+                c.bias = net.b_img[0].empty() ? nullptr : s->ws + s->b_off[0];
+                c.stats = (unsigned long long *)(s->ws + s->stats_off); c.n_layers = (int)net.g.size();
+                c.x_lo = x0; c.x_hi = x0 + n_px; c.cont = x0 != 0;
+                conv_generic_plan(c);
+                hipError_t e = launch_conv_generic(net.precision, c, sel, launch_ctx(s, kKindConvGeneric, conv_step_bytes(net, c, sel.n), 0));
+                return e == hipSuccess ? (int)IDF_OK : dev_fail(e, "pixel segment launch");
+            }
             MfmaStep a;
             int64_t rows_out[3];
             double bytes = 0;

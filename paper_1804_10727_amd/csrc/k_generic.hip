@@ -129,12 +129,15 @@ __global__ void __launch_bounds__(kGenThreads) k_conv_generic(const ConvStep a, 
     const st_t *bias = (const st_t *)a.bias;
     const int row_in = g.w_in * g.c_in, row_out = g.w_out * g.c_out;
 
+    // a pixel segment holds only columns [px_lo, px_hi) of its one row
+    const int px_lo = a.x_hi > 0 ? a.x_lo : 0, px_hi = a.x_hi > 0 ? a.x_hi : g.w_in;
     if (blockIdx.x == 0 && blockIdx.y == 0 && a.stats) {
         unsigned long long ev = 0, macs = 0;
         const ev_t *rows = in + (a.y0 - a.in_row0) * row_in;
-        for (int i = threadIdx.x; i < a.cnt * row_in; i += kGenThreads) {
+        const int row_have = (px_hi - px_lo) * g.c_in;            // == row_in for whole rows
+        for (int i = threadIdx.x; i < a.cnt * row_have; i += kGenThreads) {
             if (!T::nz(rows[i])) continue;
-            int r = i / row_in, x = (i % row_in) / g.c_in;
+            int r = i / row_have, x = px_lo + (i % row_have) / g.c_in;
             int ty = taps_1d(a.y0 + r, g.k_h, g.s_h, g.p_h, g.h_out);
             int tx = taps_1d(x, g.k_w, g.s_w, g.p_w, g.w_out);
             ev += 1;
@@ -168,7 +171,7 @@ __global__ void __launch_bounds__(kGenThreads) k_conv_generic(const ConvStep a, 
         int xi = rem / a.tile_c;
         int co = c_base + rem - xi * a.tile_c, xo = x_base + xi;
         if (co >= g.c_out || xo >= g.w_out) continue;
-        const bool fresh = d0 + oi * g.s_h >= 0 || at_start;
+        const bool fresh = (d0 + oi * g.s_h >= 0 || at_start) && !a.cont;
         if (fresh) acc[j] = bias ? bias[co] : (st_t)0;
         else acc[j] = ring[((slot_lo + oi) % a.ring_rows) * row_out + xo * g.c_out + co];
     }
@@ -189,8 +192,8 @@ __global__ void __launch_bounds__(kGenThreads) k_conv_generic(const ConvStep a, 
             const ev_t *row = in + (int64_t)(yr + in_off) * row_in;
             for (int kx = 0; kx < g.k_w; ++kx) {
                 int x = xo * g.s_w - g.p_w + kx;
-                if (x < 0 || x >= g.w_in) continue;
-                const ev_t *px = row + x * g.c_in;
+                if (x < px_lo || x >= px_hi) continue;
+                const ev_t *px = row + (x - px_lo) * g.c_in;
                 const w_t *wp = w + ((int64_t)(ky * g.k_w + kx) * g.c_in) * g.c_out + co;
                 for (int ci = 0; ci < g.c_in; ++ci) {
                     ev_t v = px[ci];

@@ -59,6 +59,33 @@ def test_float_and_bf16_rows_in_pixel_segments():
     _run_in_pixel_segments(wl, seed=4)
 
 
+def test_first_layers_the_matrix_core_kernel_does_not_serve(monkeypatch):
+    """Pixel segments into a first layer on the generic kernel: every layer on it (the matrix-core kernels
+    switched off), and first layers of other shapes -- 5x5 with stride 2 and no padding, 3x3 with stride 2
+    and same padding, a 1x3 kernel -- in front of layers the matrix-core kernel takes."""
+    from workloads import conv, maxpool
+    monkeypatch.setenv("IDF_NO_MFMA", "1")
+    _run_in_pixel_segments(wl_mod.make(4, streams=3, size=24, channels=(16, 16, 16, 16, 32, 32, 32, 32)), seed=5)
+    _run_in_pixel_segments(wl_mod.make(3, streams=2, size=20, channels=(16, 16, 32, 32)), seed=6)
+    monkeypatch.delenv("IDF_NO_MFMA")
+    rng = np.random.default_rng(11)
+    q = dict(act="relu_shr_clamp", shr=4, clamp_hi=15)
+    for first, hw in ((conv(2, 16, 5, 5, s=2, **q), (31, 29)), (conv(2, 16, 3, 3, s=2, p_h=1, p_w=1, **q), (30, 27)),
+                      (conv(2, 16, 1, 3, p_w=1, **q), (12, 21))):
+        H, W = hw
+        layers = [first, conv(16, 16, 3, 3, p_h=1, p_w=1, **q), maxpool(16), conv(16, 32, 3, 3, p_h=1, p_w=1, act="relu")]
+        ws = [rng.integers(-8, 8, size=(L["c_out"], L["c_in"], L["k_h"], L["k_w"])).astype(np.int8) if L["kind"] == "conv" else None for L in layers]
+        x = (rng.integers(0, 16, size=(2, H, W, 2)) * (rng.random((2, H, W, 2)) < 0.4)).astype(np.int8)
+        wl = dict(name="first_layer_shapes", precision="i8", in_h=H, in_w=W, in_c=2, layers=layers, weights=ws,
+                  biases=[None] * len(layers), x=x, seg_rows=1, streams=2)
+        import oracle
+        o, stats = _run_in_pixel_segments(wl, seed=12)
+        for b in range(2):
+            _, e_st = oracle.stream_run(layers, x[b], ws, wl["biases"], seg_rows=1, integer=True)
+            assert stats[b]["events_in"].tolist() == e_st["events_in"].tolist()
+            assert stats[b]["macs"].tolist() == e_st["macs"].tolist()
+
+
 def test_pixel_segment_errors():
     import paper_1804_10727_amd as idf
     from paper_1804_10727_amd.binding import input_tensor
