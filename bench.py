@@ -118,7 +118,16 @@ def trace_summary(stats_csv, bench_log):
             bench = json.loads(l)
     assert bench, f"no bench line in {bench_log}"
     rf = bench["roofline"]
+    eager = bench["config"]["workload"].endswith("_eager_emission")
+    cfg_no = {v: k for k, v in WORKLOADS.items()}[bench["config"]["workload"].replace("_eager_emission", "")]
     out = [f"rocprofv3 kernel-trace summary: bench.py workload {bench['config']['workload']} on one MI355X (gfx950)", "",
+           "Commands (the first run from /tmp with TMPDIR=/tmp on the GPU box, the second anywhere; $R = repository root):",
+           (f"  rocprofv3 --kernel-trace --stats -d $R/gpurun_out/prof_eager{cfg_no} -o eager{cfg_no} --output-format csv -- python3 $R/bench.py --config {cfg_no} --eager --no-cpu-baseline > $R/gpurun_out/prof_eager{cfg_no}.log"
+            if eager else
+            f"  rocprofv3 --kernel-trace --stats -d $R/gpurun_out/prof_cfg{cfg_no} -o cfg{cfg_no} --output-format csv -- python3 $R/bench.py --config {cfg_no} --no-cpu-baseline --no-others > $R/gpurun_out/prof_cfg{cfg_no}.log"),
+           (f"  python3 $R/bench.py --config {cfg_no} --trace-summary $R/gpurun_out/prof_eager{cfg_no}/eager{cfg_no}_kernel_stats.csv $R/gpurun_out/prof_eager{cfg_no}.log"
+            if eager else
+            f"  python3 $R/bench.py --config {cfg_no} --trace-summary $R/gpurun_out/prof_cfg{cfg_no}/cfg{cfg_no}_kernel_stats.csv $R/gpurun_out/prof_cfg{cfg_no}.log"), "",
            f"bench.py in that run: steps={bench['steps']} warmup={bench['warmup']} (+1 step bracketed by HIP events per launch, "
            f"+1 step on the kernel variants that count issued multiply-adds, named <..., true>); ms_per_step={bench['ms_per_step']:.3f}", "",
            "Kernel statistics (kernel_stats.csv), all launches of the process:",
@@ -146,7 +155,9 @@ def trace_summary(stats_csv, bench_log):
             f"{rf['executed_flops_per_launch']:.0f}; roofline bound '{rf['bound']}' from the trace average: achieved {ach:.1f} {rf['unit']} "
             f"of {rf['peak']:.0f} (frac {ach / rf['peak']:.4f}).",
             f"launches_per_step {rf['launches_per_step']} x trace average = {rf['launches_per_step'] * avg_s * 1e3:.3f} ms against "
-            f"ms_per_step {bench['ms_per_step']:.3f} (launches back to back can run shorter than the average of all, spaced ones included)."]
+            f"ms_per_step {bench['ms_per_step']:.3f} of this profiled run (launches back to back can run shorter than the average of all, spaced ones "
+            f"included; where the host's enqueue is what a batch waits for, the profiler's own cost per launch makes the profiled run's ms_per_step larger "
+            f"than the unprofiled bench line's)."]
     print("\n".join(out))
 
 
