@@ -286,7 +286,10 @@ def run_workload(config, steps_arg=None, warmup_arg=None, eager=False, push_batc
     def issued_total():
         if eager:
             return None
-        return float(sum(float(st.get_issued_macs(b).sum()) for b in range(B)))
+        tot = np.zeros(len(wl["layers"]), dtype=np.float64)
+        for b in range(B):
+            tot += st.get_issued_macs(b).astype(np.float64)
+        return tot
     ev0, mc0 = macs_total()
     st.profile_begin()
     step()
@@ -305,7 +308,8 @@ def run_workload(config, steps_arg=None, warmup_arg=None, eager=False, push_batc
         st.count_issued_macs(True)
         is0 = issued_total()
         step()
-        macs_issued = issued_total() - is0     # zeros inside visited fragments / channels included
+        issued_layer = issued_total() - is0    # zeros inside visited fragments / channels included
+        macs_issued = float(issued_layer.sum())
         st.count_issued_macs(False)
     macs_exec_layer = mc1 - mc0
     macs_exec = float(macs_exec_layer.sum())
@@ -351,6 +355,10 @@ def run_workload(config, steps_arg=None, warmup_arg=None, eager=False, push_batc
         "gmacs_issued": None if macs_issued is None else macs_issued / (dt / steps) / 1e9,
         "executed_over_dense": macs_exec / macs_dense,
         "issued_over_dense": None if macs_issued is None else macs_issued / macs_dense,
+        # conv layers in order: what each issues and executes, as fractions of its own dense-equivalent multiply-adds
+        "issued_over_dense_by_layer": None if macs_issued is None else
+        [round(float(i) / (d * B), 4) for i, d in zip(issued_layer, workloads.dense_equivalent_macs_by_layer(wl)) if d],
+        "executed_over_dense_by_layer": [round(float(e) / (d * B), 4) for e, d in zip(macs_exec_layer, workloads.dense_equivalent_macs_by_layer(wl)) if d],
         "kernels": {p["name"]: {"launches": p["launches"], "total_ms": p["total_ms"]} for p in prof},
         "kernels_by_layer": {p["name"]: {"launches": p["launches"], "avg_us": p["total_ms"] * 1e3 / p["launches"],
                                          "alg_GBps": p["algorithmic_bytes"] / (p["total_ms"] * 1e-3) / 1e9}
@@ -432,7 +440,7 @@ def main():
                 continue
             o, owl = run_workload(c, None, 1)
             rec = {k: o[k] for k in ("value", "unit", "ms_per_step", "steps", "dtype", "gmacs_dense_equivalent",
-                                     "gmacs_executed", "gmacs_issued", "issued_over_dense", "executed_over_dense",
+                                     "gmacs_executed", "gmacs_issued", "issued_over_dense", "executed_over_dense", "issued_over_dense_by_layer", "executed_over_dense_by_layer",
                                      "roofline")}
             rec["state"] = o["config"]["state"]
             if c in (1, 2):     # the 1-D workloads also in throughput mode: up to 16 pushes in step per launch

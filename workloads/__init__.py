@@ -69,16 +69,20 @@ def output_shape(wl):
     return h, w, c
 
 
-def dense_equivalent_macs(wl):
-    """Multiply-adds of the conventional network for one sample, padding taps included."""
+def dense_equivalent_macs_by_layer(wl):
+    """Multiply-adds of the conventional network for one sample, layer by layer (0 for pools), padding taps included."""
     h, w = wl["in_h"], wl["in_w"]
-    total = 0
+    per = []
     for L in wl["layers"]:
         h = out_size(h, L["k_h"], L["s_h"], L["p_h"])
         w = out_size(w, L["k_w"], L["s_w"], L["p_w"])
-        if L["kind"] == "conv":
-            total += h * w * L["k_h"] * L["k_w"] * L["c_in"] * L["c_out"]
-    return total
+        per.append(h * w * L["k_h"] * L["k_w"] * L["c_in"] * L["c_out"] if L["kind"] == "conv" else 0)
+    return per
+
+
+def dense_equivalent_macs(wl):
+    """Multiply-adds of the conventional network for one sample, padding taps included."""
+    return sum(dense_equivalent_macs_by_layer(wl))
 
 
 def _normal_weights(rng, layers, var_num, dtype=np.float32):
