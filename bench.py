@@ -121,13 +121,13 @@ def trace_summary(stats_csv, bench_log):
     eager = bench["config"]["workload"].endswith("_eager_emission")
     cfg_no = {v: k for k, v in WORKLOADS.items()}[bench["config"]["workload"].replace("_eager_emission", "")]
     out = [f"rocprofv3 kernel-trace summary: bench.py workload {bench['config']['workload']} on one MI355X (gfx950)", "",
-           "Commands (the first run from /tmp with TMPDIR=/tmp on the GPU box, the second anywhere; $R = repository root):",
-           (f"  rocprofv3 --kernel-trace --stats -d $R/gpurun_out/prof_eager{cfg_no} -o eager{cfg_no} --output-format csv -- python3 $R/bench.py --config {cfg_no} --eager --no-cpu-baseline > $R/gpurun_out/prof_eager{cfg_no}.log"
+           "Commands (the first run from /tmp with TMPDIR=/tmp on the GPU machine, the second anywhere; $R = repository root, $OUT = a scratch directory):",
+           (f"  rocprofv3 --kernel-trace --stats -d $OUT/prof_eager{cfg_no} -o eager{cfg_no} --output-format csv -- python3 $R/bench.py --config {cfg_no} --eager --no-cpu-baseline > $OUT/prof_eager{cfg_no}.log"
             if eager else
-            f"  rocprofv3 --kernel-trace --stats -d $R/gpurun_out/prof_cfg{cfg_no} -o cfg{cfg_no} --output-format csv -- python3 $R/bench.py --config {cfg_no} --no-cpu-baseline --no-others > $R/gpurun_out/prof_cfg{cfg_no}.log"),
-           (f"  python3 $R/bench.py --config {cfg_no} --trace-summary $R/gpurun_out/prof_eager{cfg_no}/eager{cfg_no}_kernel_stats.csv $R/gpurun_out/prof_eager{cfg_no}.log"
+            f"  rocprofv3 --kernel-trace --stats -d $OUT/prof_cfg{cfg_no} -o cfg{cfg_no} --output-format csv -- python3 $R/bench.py --config {cfg_no} --no-cpu-baseline --no-others > $OUT/prof_cfg{cfg_no}.log"),
+           (f"  python3 $R/bench.py --config {cfg_no} --trace-summary $OUT/prof_eager{cfg_no}/eager{cfg_no}_kernel_stats.csv $OUT/prof_eager{cfg_no}.log"
             if eager else
-            f"  python3 $R/bench.py --config {cfg_no} --trace-summary $R/gpurun_out/prof_cfg{cfg_no}/cfg{cfg_no}_kernel_stats.csv $R/gpurun_out/prof_cfg{cfg_no}.log"), "",
+            f"  python3 $R/bench.py --config {cfg_no} --trace-summary $OUT/prof_cfg{cfg_no}/cfg{cfg_no}_kernel_stats.csv $OUT/prof_cfg{cfg_no}.log"), "",
            f"bench.py in that run: steps={bench['steps']} warmup={bench['warmup']} (+1 step bracketed by HIP events per launch, "
            f"+1 step on the kernel variants that count issued multiply-adds, named <..., true>); ms_per_step={bench['ms_per_step']:.3f}", "",
            "Kernel statistics (kernel_stats.csv), all launches of the process:",
