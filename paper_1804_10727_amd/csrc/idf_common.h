@@ -190,7 +190,8 @@ constexpr int kCasMaxStages = 8;
 constexpr int kCasSegMax = 16;       // pushed segments one launch can take
 constexpr int kCasStepMax = 8;       // steps a stage runs in one launch
 
-struct CascadeArgs {
+// (NSTEP: steps of room in the block; a launch of one step per stage passes the short form, whose fields lie where the long one's do)
+template <int NSTEP> struct CascadeArgsT {
     int n_layers;
     int n_stages;
     int stage_lo[kCasMaxStages + 1];     // stage s runs layers [stage_lo[s], stage_lo[s+1])
@@ -210,8 +211,9 @@ struct CascadeArgs {
     int64_t out_slot0[kCasStepMax];      // of the steps the last stage runs
     unsigned long long *stats;
     unsigned long long *issued;          // [stream][layer]: multiply-adds issued (all rows of every channel that holds an event)
-    CascadeStep step[kCasStepMax][kCasMaxLayers];   // step[m][l]: step m of layer l's stage (last: a launch copies only the steps in use on chip)
+    CascadeStep step[NSTEP][kCasMaxLayers];   // step[m][l]: step m of layer l's stage (last in the block)
 };
+using CascadeArgs = CascadeArgsT<kCasStepMax>;
 
 // One arriving row of a 3x3 / stride 1 / same-padded conv layer on the matrix cores.
 // Tap ky of input row y lands on output row o = y + 1 - ky.

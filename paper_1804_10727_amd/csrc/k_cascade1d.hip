@@ -33,6 +33,8 @@
 // come in a packing of their own (cascade1d_weight_index): two 16-byte loads and one 4-byte
 // load per channel pair, each wave-wide load covering whole cache lines, input channels
 // padded with zeros so that every lane can run the same number of steps.
+#include <cstring>
+
 #include "idf.h"
 #include "idf_kernels.h"
 #include <cstddef>
@@ -49,9 +51,9 @@ constexpr int kXStride = 20;                         // floats per channel in LD
 constexpr int kAhead = kCasAhead;                    // input channels whose weights are in flight
 constexpr int kBatch = 4;                            // input channels whose rows are read from LDS together
 constexpr int kArgWords = (sizeof(CascadeArgs) + 3) / 4;
-constexpr int kArgWordsFixed = offsetof(CascadeArgs, step) / 4;              // what every launch needs on chip
-constexpr int kArgWordsPerStep = sizeof(CascadeStep) * kCasMaxLayers / 4;     // plus this per step in use
 static_assert(offsetof(CascadeArgs, step) % 4 == 0 && (sizeof(CascadeStep) * kCasMaxLayers) % 4 == 0, "copied word by word");
+static_assert(offsetof(CascadeArgsT<1>, step) == offsetof(CascadeArgs, step) && offsetof(CascadeArgsT<1>, in) == offsetof(CascadeArgs, in) &&
+              offsetof(CascadeArgsT<1>, in_stream_stride) == offsetof(CascadeArgs, in_stream_stride), "the short block is a prefix of the long one");
 constexpr int kRingPerLayer = kKMax * 64;            // floats of rolling buffer per layer at most
 constexpr int kXinPerLane = (kCasRowsMax * 64 + kT - 1) / kT;      // values of a segment per lane at most
 constexpr int kRingPerLane = (kRingPerLayer + kT - 1) / kT;
@@ -227,9 +229,10 @@ size_t cascade1d_weight_index(int c_in, int c_out, int ci, int co, int ky)
 
 int cascade1d_slot_off(int S, int rho) { return ceil_div_c(rho - kKMax + 1, S); }
 
-template <bool COUNT>
-__global__ void __launch_bounds__(kCasThreads, 2) k_cascade1d(const CascadeArgs ka, const StreamSel sel)
+template <bool COUNT, int NSTEP>
+__global__ void __launch_bounds__(kCasThreads, 2) k_cascade1d(const CascadeArgsT<NSTEP> ka, const StreamSel sel)
 {
+    constexpr int kArgWords = (sizeof(CascadeArgsT<NSTEP>) + 3) / 4;         // this launch's block: the short one when every stage runs one step
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     Lds &lds = *reinterpret_cast<Lds *>(lds_raw);
     const int tid = threadIdx.x, lane = tid & 63;
@@ -601,12 +604,13 @@ hipError_t launch_cascade1d(const CascadeArgs &a, const StreamSel &sel, const La
 {
     // more LDS than the default per-workgroup limit: raise it once
     static hipError_t prepared = [] {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_cascade1d<false>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Lds));
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_cascade1d<true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Lds));
-        return e;
+        const void *kernels[4] = {reinterpret_cast<const void *>(k_cascade1d<false, 1>), reinterpret_cast<const void *>(k_cascade1d<true, 1>),
+                                  reinterpret_cast<const void *>(k_cascade1d<false, kCasStepMax>), reinterpret_cast<const void *>(k_cascade1d<true, kCasStepMax>)};
+        for (const void *k : kernels) {
+            hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Lds));
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
     }();
     if (prepared != hipSuccess) return prepared;
     CascadeArgs b = a;
@@ -624,8 +628,16 @@ hipError_t launch_cascade1d(const CascadeArgs &a, const StreamSel &sel, const La
     b.per = spread ? 8 / grid_stages : sel.n;
     if (sel.n / b.per > 65535) return hipErrorInvalidValue;
     // the variant that adds up what it issues is a kernel of its own: the one that is timed carries none of it
-    if (b.issued) return launch(k_cascade1d<true>, dim3(b.per, grid_stages, sel.n / b.per), dim3(kCasThreads), sizeof(Lds), lc, b, sel);
-    return launch(k_cascade1d<false>, dim3(b.per, grid_stages, sel.n / b.per), dim3(kCasThreads), sizeof(Lds), lc, b, sel);
+    const dim3 grid(b.per, grid_stages, sel.n / b.per), block(kCasThreads);
+    if (b.steps_max <= 1) {
+        // one step per stage (a launch per push): the short argument block, a third of the bytes to hand over and to sweep on chip
+        CascadeArgsT<1> s1;
+        memcpy(&s1, &b, sizeof(s1));
+        if (b.issued) return launch(k_cascade1d<true, 1>, grid, block, sizeof(Lds), lc, s1, sel);
+        return launch(k_cascade1d<false, 1>, grid, block, sizeof(Lds), lc, s1, sel);
+    }
+    if (b.issued) return launch(k_cascade1d<true, kCasStepMax>, grid, block, sizeof(Lds), lc, b, sel);
+    return launch(k_cascade1d<false, kCasStepMax>, grid, block, sizeof(Lds), lc, b, sel);
 }
 
 }  // namespace idf
