@@ -517,11 +517,12 @@ int cascade_step(const idf_net &net, int l, int64_t y0, int64_t cnt, CascadeStep
     const int64_t o_base = y0p / g.s_h + cascade1d_slot_off(g.s_h, rho);
     {   // what a lane issues per channel that holds an event: the kernel's variant for 4, 8 or 16
         // new rows computes all of them, all nine tap positions that land on an output row
-        const int nin = cnt <= 4 ? 4 : cnt <= 8 ? 8 : 16;
+        // (the cascade takes strides 1 and 2 only: parity by mask, no division in what runs with every push)
+        const int nin = cnt <= 4 ? 4 : cnt <= 8 ? 8 : 16, par = g.s_h - 1;
         int f = 0;
         for (int j = 0; j < nin; ++j)
             for (int ky = 0; ky < kCasKMax; ++ky)
-                if ((rho + j - ky) % g.s_h == 0) ++f;
+                if (((rho + j - ky) & par) == 0) ++f;
         L.fma_per_channel = (short)f;
     }
     const int64_t t_lo = o_lo - o_base, t_fin = o_fin - o_base, t_hi = o_hi - o_base;
@@ -535,10 +536,11 @@ int cascade_step(const idf_net &net, int l, int64_t y0, int64_t cnt, CascadeStep
     L.at_start = y0 == 0;
     for (int j = 0; j < cnt && j < kCasRowsMax; ++j) {
         int t = 0;
+        const int64_t v = y0 + j + g.p_h, par = g.s_h - 1, sh = g.s_h - 1;      // stride 1 or 2: u % s = u & par, u / s = u >> sh
         for (int ky = 0; ky < g.k_h; ++ky) {
-            const int64_t u = y0 + j + g.p_h - ky;
-            if (u < 0 || u % g.s_h != 0) continue;
-            if (g.h_out > 0 && u / g.s_h >= g.h_out) continue;
+            const int64_t u = v - ky;
+            if (u < 0 || (u & par) != 0) continue;
+            if (g.h_out > 0 && (u >> sh) >= g.h_out) continue;
             ++t;
         }
         L.taps4[j >> 1] |= (unsigned char)(t << ((j & 1) * 4));
