@@ -43,8 +43,9 @@ def _tiny(prec, seed, layers, H, W, C0, with_bias):
 
 # which of the conv kernels serves the 3x3 / stride 1 / same-padded layers: the library's choice (register-tiled for float
 # nets, event by event for quantised ones), or forced: tiled with eight positions per lane, tiled for a quantised net,
-# event by event for a float net
-KERNELS = [{}, {"IDF_EAGER_POS": "8"}, {"IDF_EAGER_TILED": "1"}, {"IDF_EAGER_TILED": "1", "IDF_EAGER_POS": "8"}, {"IDF_EAGER_PLAIN": "1"}]
+# event by event for a float net (the sizes of these tests pick two positions per lane by themselves)
+KERNELS = [{}, {"IDF_EAGER_POS": "8"}, {"IDF_EAGER_TILED": "1"}, {"IDF_EAGER_TILED": "1", "IDF_EAGER_POS": "8"}, {"IDF_EAGER_POS": "4"},
+           {"IDF_EAGER_TILED": "1", "IDF_EAGER_POS": "4"}, {"IDF_EAGER_PLAIN": "1"}]
 
 
 @pytest.mark.parametrize("env", KERNELS, ids=lambda e: "+".join(f"{k[10:].lower()}{v}" for k, v in e.items()) or "default")
@@ -115,7 +116,7 @@ def test_every_layer_after_every_row_against_the_literal_scheme(prec, with_bias,
     (5, dict(streams=2, size=24, channels=(8, 8, 16, 16, 16, 16, 16)), 1),
     (5, dict(streams=2, size=24, channels=(8, 8, 16, 16, 16, 16, 16)), 5),
 ])
-@pytest.mark.parametrize("env", KERNELS[:4], ids=lambda e: "+".join(f"{k[10:].lower()}{v}" for k, v in e.items()) or "default")
+@pytest.mark.parametrize("env", KERNELS[:6], ids=lambda e: "+".join(f"{k[10:].lower()}{v}" for k, v in e.items()) or "default")
 def test_output_after_a_prefix_is_the_network_on_the_prefix(cfg, kw, seg, env, monkeypatch):
     import paper_1804_10727_amd as idf
     for k, v in env.items():
