@@ -125,6 +125,42 @@ int idf_create_net(const idf_net_desc *desc, const void *const *weights, const v
  * 2 x 2 (a 2 x 1 pool has no column-wise counterpart here: IDF_EINVAL). */
 int idf_create_net_columnwise(const idf_net_desc *desc, const void *const *weights, const void *const *biases,
                               idf_net **out);
+/* A network over volumes [slab][row][column][channel] presented slab by slab (Sec. 3 names inputs of
+ * more than two dimensions as a further case of the same scheme: the rolling buffer of a layer then
+ * holds k_d slabs of c, and a slab is emitted once no later slab can change it).  All layers are
+ * convolutions.
+ *   weights[i] (host): [c_out][c_in][k_d][k_h][k_w], element type as for idf_create_net;
+ *   biases as for idf_create_net.
+ * The returned network is used like any other, with "row" meaning slab:
+ *   idf_push_segment takes the next n_rows slabs, dev_rows [n_ids][n_rows][in_h][in_w][in_c];
+ *   idf_read_outputs hands over completed slabs [n_ids][max_rows][out rows][out columns][c_out]
+ *   (idf_sizes: out_h = slabs per sample, out_w = rows of a slab, out_c = columns x channels);
+ *   the retained state is k_d slabs per layer, whatever the number of slabs.
+ * How it is served: the column axis is folded into the channels (a slab row of in_w x c_in values is
+ * one position with in_w * c_in channels; the weights become banded over that axis), so the two
+ * streaming axes slab and row run on the kernels of the 2-D case and the values are those of the
+ * conventional 3-D network.  The multiply-add counters of idf_get_stats count what those kernels
+ * execute per event, i.e. they include the zero entries of the band: (columns of the layer's
+ * output) x c_out per tap instead of (taps along the column axis) x c_out.
+ * IDF_EINVAL as for idf_create_net; IDF_EUNSUPPORTED if a folded layer is wider than the kernels
+ * take (in_w * c_in or out columns * c_out too large). */
+typedef struct {
+    int c_in, c_out;
+    int k_d, k_h, k_w;
+    int s_d, s_h, s_w;
+    int p_d, p_h, p_w; /* zero padding, same amount on both sides of an axis */
+    int act;           /* IDF_ACT_* */
+    int shr, clamp_hi; /* parameters of IDF_ACT_RELU_SHR_CLAMP */
+} idf_volume_layer;
+typedef struct {
+    int precision;     /* IDF_PREC_* */
+    int in_d;          /* slabs per sample (> 0) */
+    int in_h, in_w, in_c;
+    int n_layers;
+    const idf_volume_layer *layers;   /* host */
+} idf_volume_desc;
+int idf_create_net_volume(const idf_volume_desc *desc, const void *const *weights, const void *const *biases,
+                      idf_net **out);
 int idf_destroy_net(idf_net *net);
 
 /* Sizes for n_streams streams that are pushed at most max_seg_rows rows per call and may hold up

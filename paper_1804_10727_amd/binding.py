@@ -17,7 +17,7 @@ ACT = {"none": 0, "relu": 1, "relu_shr_clamp": 2}
 EXPORTS = ["idf_create_net", "idf_create_net_columnwise", "idf_destroy_net", "idf_query_sizes", "idf_open_streams", "idf_open_streams_static", "idf_close_streams",
            "idf_push_segment", "idf_set_push_batching", "idf_read_outputs", "idf_reset_streams", "idf_get_stats", "idf_count_issued_macs", "idf_get_issued_macs", "idf_set_event_path", "idf_rows_pushed",
            "idf_layer_kernel", "idf_last_error", "idf_profile_begin", "idf_profile_end", "idf_enable_head",
-           "idf_read_head", "idf_query_head_units_bytes", "idf_enable_head_units", "idf_read_head_units", "idf_push_pixels", "idf_query_eager_bytes", "idf_enable_eager", "idf_read_announced", "idf_read_announced_rows", "idf_eager_state_bytes", "idf_snapshot_bytes", "idf_snapshot", "idf_restore"]
+           "idf_read_head", "idf_query_head_units_bytes", "idf_enable_head_units", "idf_read_head_units", "idf_push_pixels", "idf_query_eager_bytes", "idf_enable_eager", "idf_read_announced", "idf_read_announced_rows", "idf_eager_state_bytes", "idf_snapshot_bytes", "idf_snapshot", "idf_restore", "idf_create_net_volume"]
 
 
 class IdfError(RuntimeError):
@@ -34,6 +34,16 @@ class _Layer(C.Structure):
 class _NetDesc(C.Structure):
     _fields_ = [("precision", C.c_int), ("in_h", C.c_int), ("in_w", C.c_int), ("in_c", C.c_int),
                 ("n_layers", C.c_int), ("layers", C.POINTER(_Layer))]
+
+
+class _Layer3d(C.Structure):
+    _fields_ = [(n, C.c_int) for n in
+                ("c_in", "c_out", "k_d", "k_h", "k_w", "s_d", "s_h", "s_w", "p_d", "p_h", "p_w", "act", "shr", "clamp_hi")]
+
+
+class _Net3dDesc(C.Structure):
+    _fields_ = [("precision", C.c_int), ("in_d", C.c_int), ("in_h", C.c_int), ("in_w", C.c_int), ("in_c", C.c_int),
+                ("n_layers", C.c_int), ("layers", C.POINTER(_Layer3d))]
 
 
 class KernelProfile(C.Structure):
@@ -74,6 +84,8 @@ def load_library():
     L.idf_create_net.argtypes = [C.POINTER(_NetDesc), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
                                  C.POINTER(C.c_void_p)]
     L.idf_create_net_columnwise.argtypes = L.idf_create_net.argtypes
+    L.idf_create_net_volume.argtypes = [C.POINTER(_Net3dDesc), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
+                                    C.POINTER(C.c_void_p)]
     L.idf_destroy_net.argtypes = [C.c_void_p]
     L.idf_query_sizes.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int64, C.POINTER(Sizes)]
     L.idf_open_streams.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int64, C.c_void_p, C.c_size_t,
@@ -165,6 +177,41 @@ class Net:
         if self._h:
             _check(load_library().idf_destroy_net(self._h))
             self._h = None
+
+
+class VolumeNet(Net):
+    """idf_create_net_volume: volumes [slab][row][column][channel] presented slab by slab.  layers: dicts with c_in,
+    c_out, k, s, p (triples over slab, row, column), act (, shr, clamp_hi); weights [c_out][c_in][k_d][k_h][k_w]."""
+
+    def __init__(self, precision, in_d, in_h, in_w, in_c, layers, weights, biases=None):
+        L = load_library()
+        self.precision = precision
+        self.layers = layers
+        n = len(layers)
+        arr = (_Layer3d * n)()
+        for i, d in enumerate(layers):
+            arr[i] = _Layer3d(d["c_in"], d["c_out"], *d["k"], *d["s"], *d["p"], ACT[d.get("act", "none")],
+                              d.get("shr", 0), d.get("clamp_hi", 0))
+        desc = _Net3dDesc(PREC[precision], in_d, in_h, in_w, in_c, n, arr)
+        wdt = {"f32": np.float32, "bf16": np.uint16, "i8": np.int8}[precision]
+        bdt = np.int32 if precision == "i8" else np.float32
+        keep = []
+
+        def table(arrays, dt):
+            t = (C.c_void_p * n)()
+            for i, a in enumerate(arrays):
+                if a is None:
+                    t[i] = None
+                else:
+                    a = np.ascontiguousarray(a, dtype=dt)
+                    keep.append(a)
+                    t[i] = a.ctypes.data
+            return t
+        wt = table(weights, wdt)
+        bt = table(biases, bdt) if biases is not None else None
+        h = C.c_void_p()
+        _check(L.idf_create_net_volume(C.byref(desc), wt, bt, C.byref(h)))
+        self._h = h
 
 
 class Streams:

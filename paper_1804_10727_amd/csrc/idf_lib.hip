@@ -1354,6 +1354,66 @@ int idf_create_net_columnwise(const idf_net_desc *d, const void *const *weights,
     return idf_create_net(&t, wp.data(), biases, out);
 }
 
+int idf_create_net_volume(const idf_volume_desc *d, const void *const *weights, const void *const *biases, idf_net **out)
+{
+    if (!d || !out || !d->layers) return fail(IDF_EINVAL, "null argument");
+    *out = nullptr;
+    if (d->n_layers < 1 || d->n_layers > kMaxLayers) return fail(IDF_EINVAL, "n_layers %d outside [1, %d]", d->n_layers, kMaxLayers);
+    if (d->precision < IDF_PREC_F32 || d->precision > IDF_PREC_I8) return fail(IDF_EINVAL, "unknown precision %d", d->precision);
+    if (d->in_d < 1 || d->in_h < 1 || d->in_w < 1 || d->in_c < 1)
+        return fail(IDF_EINVAL, "bad input shape %d x %d x %d x %d", d->in_d, d->in_h, d->in_w, d->in_c);
+    // The column axis goes into the channels: position (row) x channel (column, c).  A layer's weights
+    // become [(w_o, c_out)][(w_i, c_in)][k_d][k_h] with the entry of (w_i, w_o) taken from tap
+    // kw = w_i - (w_o * s_w - p_w) where that is a tap, zero elsewhere; the bias is repeated per column.
+    std::vector<idf_layer> lt(d->n_layers);
+    std::vector<std::vector<unsigned char>> wt(d->n_layers), bt(d->n_layers);
+    std::vector<const void *> wp(d->n_layers, nullptr), bp(d->n_layers, nullptr);
+    const size_t wb = (size_t)w_bytes(d->precision);
+    int w_in = d->in_w, c = d->in_c;
+    for (int l = 0; l < d->n_layers; ++l) {
+        const idf_volume_layer &L = d->layers[l];
+        if (L.c_in != c || L.c_out < 1) return fail(IDF_EINVAL, "layer %d: c_in %d does not follow %d channels", l, L.c_in, c);
+        if (L.k_d < 1 || L.k_h < 1 || L.k_w < 1 || L.s_d < 1 || L.s_h < 1 || L.s_w < 1 || L.p_d < 0 || L.p_h < 0 || L.p_w < 0)
+            return fail(IDF_EINVAL, "layer %d: bad kernel/stride/padding", l);
+        if (!weights || !weights[l]) return fail(IDF_EINVAL, "layer %d: no weights", l);
+        const int w_out = out_size(w_in, L.k_w, L.s_w, L.p_w);
+        if (w_out < 1) return fail(IDF_EINVAL, "layer %d: window larger than its input", l);
+        const int64_t ci_f = (int64_t)w_in * L.c_in, co_f = (int64_t)w_out * L.c_out;
+        if (ci_f > 4096 || co_f > 4096) return fail(IDF_EUNSUPPORTED, "layer %d: %lld x %lld folded channels", l, (long long)ci_f, (long long)co_f);
+        idf_layer &T = lt[l];
+        T = idf_layer{};
+        T.kind = IDF_CONV; T.c_in = (int)ci_f; T.c_out = (int)co_f;
+        T.k_h = L.k_d; T.k_w = L.k_h; T.s_h = L.s_d; T.s_w = L.s_h; T.p_h = L.p_d; T.p_w = L.p_h;
+        T.act = L.act; T.shr = L.shr; T.clamp_hi = L.clamp_hi;
+        wt[l].assign((size_t)co_f * ci_f * L.k_d * L.k_h * wb, 0);
+        const unsigned char *src = (const unsigned char *)weights[l];
+        for (int wo = 0; wo < w_out; ++wo)
+            for (int kw = 0; kw < L.k_w; ++kw) {
+                const int wi = wo * L.s_w - L.p_w + kw;
+                if (wi < 0 || wi >= w_in) continue;
+                for (int co = 0; co < L.c_out; ++co)
+                    for (int ci = 0; ci < L.c_in; ++ci)
+                        for (int kd = 0; kd < L.k_d; ++kd)
+                            for (int kh = 0; kh < L.k_h; ++kh) {
+                                const size_t s_idx = ((((size_t)co * L.c_in + ci) * L.k_d + kd) * L.k_h + kh) * L.k_w + kw;
+                                const size_t d_idx = ((((size_t)wo * L.c_out + co) * ci_f + (size_t)wi * L.c_in + ci) * L.k_d + kd) * L.k_h + kh;
+                                memcpy(&wt[l][d_idx * wb], src + s_idx * wb, wb);
+                            }
+            }
+        wp[l] = wt[l].data();
+        if (biases && biases[l]) {
+            bt[l].resize((size_t)co_f * 4);
+            for (int wo = 0; wo < w_out; ++wo) memcpy(&bt[l][(size_t)wo * L.c_out * 4], biases[l], (size_t)L.c_out * 4);
+            bp[l] = bt[l].data();
+        }
+        w_in = w_out; c = L.c_out;
+    }
+    idf_net_desc t{};
+    t.precision = d->precision; t.in_h = d->in_d; t.in_w = d->in_h; t.in_c = d->in_w * d->in_c;
+    t.n_layers = d->n_layers; t.layers = lt.data();
+    return idf_create_net(&t, wp.data(), biases ? bp.data() : nullptr, out);
+}
+
 int idf_destroy_net(idf_net *net)
 {
     if (!net) return IDF_OK;

@@ -1,0 +1,121 @@
+"""Volumes presented slab by slab (Sec. 3: inputs of more than two dimensions): idf_create_net_volume
+against the volume oracle, which knows nothing of how the library serves the third axis."""
+import numpy as np
+import pytest
+
+from oracle import volume as V
+from helpers import TOL, rel_err, elem_excess
+
+pytestmark = pytest.mark.gpu
+
+
+def _bf16_bits(a):
+    """float32 -> bfloat16 bit patterns (round to nearest even) and the values they stand for."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    r = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+    return r, (r.astype(np.uint32) << 16).view(np.float32)
+
+
+def _volume_net(prec, rng, shape, chans, ks, ss, ps, bias=True):
+    D, H, W = shape
+    n = len(ks)
+    layers, w_host, w_val, b_host = [], [], [], []
+    for i in range(n):
+        L = dict(c_in=chans[i], c_out=chans[i + 1], k=ks[i], s=ss[i], p=ps[i], act="relu")
+        if prec == "i8":
+            L = dict(L, act="relu_shr_clamp" if i < n - 1 else "relu", shr=3, clamp_hi=15)
+        layers.append(L)
+        wshape = (chans[i + 1], chans[i]) + tuple(ks[i])
+        if prec == "i8":
+            w = rng.integers(-4, 5, size=wshape).astype(np.int8)
+            w_host.append(w); w_val.append(w.astype(np.int64)); b_host.append(None)
+        else:
+            w = rng.normal(0, 1.0 / np.sqrt(chans[i] * np.prod(ks[i]) / 2), size=wshape).astype(np.float32)
+            if prec == "bf16":
+                bits, w = _bf16_bits(w)
+                w_host.append(bits)
+            else:
+                w_host.append(w)
+            w_val.append(w.astype(np.float64))
+            b_host.append(rng.normal(0, 0.1, size=chans[i + 1]).astype(np.float32) if bias else None)
+    B = 3
+    if prec == "i8":
+        x = rng.integers(0, 8, size=(B, D, H, W, chans[0])).astype(np.int8)
+    else:
+        x = rng.random((B, D, H, W, chans[0])).astype(np.float32)
+    x[rng.random((B, D, H, W)) < 0.5] = 0
+    x_val = x
+    x_host = x
+    if prec == "bf16":
+        x_host, x_val = _bf16_bits(x)
+    return layers, w_host, w_val, b_host, x_host, x_val
+
+
+CASES = [
+    # two 3x3x3 layers, same padding: folded channels (8*2, 8*8, 8*4) put both layers on the matrix-core kernel
+    ("f32", (6, 10, 8), [2, 8, 4], [(3, 3, 3)] * 2, [(1, 1, 1)] * 2, [(1, 1, 1)] * 2, 1),
+    ("i8", (6, 10, 8), [2, 8, 4], [(3, 3, 3)] * 2, [(1, 1, 1)] * 2, [(1, 1, 1)] * 2, 1),
+    ("bf16", (6, 10, 8), [2, 8, 4], [(3, 3, 3)] * 2, [(1, 1, 1)] * 2, [(1, 1, 1)] * 2, 1),
+    # strides, no padding on some axes, kernels that differ per axis, several slabs per push: the generic kernels
+    ("f32", (9, 7, 6), [3, 4, 5], [(2, 3, 1), (3, 1, 2)], [(1, 2, 1), (2, 1, 1)], [(0, 1, 0), (1, 0, 1)], 2),
+    ("i8", (9, 7, 6), [3, 4, 5], [(3, 2, 3), (2, 3, 2)], [(2, 1, 2), (1, 1, 1)], [(1, 0, 1), (0, 1, 0)], 3),
+]
+
+
+@pytest.mark.parametrize("prec,shape,chans,ks,ss,ps,seg", CASES)
+def test_volume_slab_by_slab_equals_conventional_network(prec, shape, chans, ks, ss, ps, seg):
+    import torch
+    from paper_1804_10727_amd.binding import VolumeNet, Streams
+    rng = np.random.default_rng(1000 * seg + 100 * shape[0] + {'f32': 0, 'i8': 1, 'bf16': 2}[prec])
+    layers, w_host, w_val, b_host, x_host, x_val = _volume_net(prec, rng, shape, chans, ks, ss, ps)
+    D, H, W = shape
+    net = VolumeNet(prec, D, H, W, chans[0], layers, w_host, b_host)
+    st = Streams(net, 3, max_seg_rows=seg)
+    Do, Ho, Wo, Co = V.shapes3d(layers, D, H, W)[-1]
+    assert (int(st.sizes.out_h), st.sizes.out_w, st.sizes.out_c) == (Do, Ho, Wo * Co)
+    tdt = {"f32": torch.float32, "i8": torch.int8, "bf16": torch.int16}[prec]
+    xt = torch.from_numpy(x_host.view(np.int16) if prec == "bf16" else x_host).to("cuda:0")
+    assert xt.dtype == tdt
+    got = [[] for _ in range(3)]
+    for z in range(0, D, seg):
+        n = min(seg, D - z)
+        st.push_segment(xt[:, z:z + n].contiguous().view(3, n, H, W * chans[0]))
+        out, first, cnt = st.read_outputs(Do)
+        o = out.cpu().numpy()
+        for b in range(3):
+            got[b].append(o[b, :cnt[b]])
+    integer = prec == "i8"
+    biases = None if integer else [None if b is None else b.astype(np.float64) for b in b_host]
+    for b in range(3):
+        g = np.concatenate(got[b]).reshape(Do, Ho, Wo, Co)
+        xv = x_val[b].astype(np.int64 if integer else np.float64)
+        want = V.dense3d(layers, xv, w_val, biases, integer=integer)
+        assert np.abs(want).max() > 0
+        if integer:
+            assert np.array_equal(g.astype(np.int64), want), b
+        elif prec == "f32":
+            assert rel_err(g, want) <= TOL["f32"], (b, rel_err(g, want))
+            assert elem_excess(g, want, "f32") <= 1.0
+        else:
+            emul = V.dense3d(layers, xv, w_val, biases, emit_round="bf16")
+            assert rel_err(g, emul) <= TOL["bf16_emul"], (b, rel_err(g, emul))
+            assert rel_err(g, want) <= TOL["bf16_true"], (b, rel_err(g, want))
+    # events are the non-zero values, layer by layer, as the scheme along the slab axis counts them
+    if integer:
+        _, ost = V.stream3d_run(layers, x_val[0].astype(np.int64), w_val, None, seg=seg, integer=True)
+        gst = st.get_stats(0)
+        assert np.array_equal(gst["events_in"].astype(np.int64), ost["events_in"])
+    st.close(); net.destroy()
+
+
+def test_state_of_a_volume_net_does_not_depend_on_the_number_of_slabs():
+    from paper_1804_10727_amd.binding import VolumeNet
+    rng = np.random.default_rng(5)
+    sizes = []
+    for D in (6, 12, 48):
+        layers, w_host, _, b_host, _, _ = _volume_net("f32", rng, (D, 10, 8), [2, 8, 4], [(3, 3, 3)] * 2, [(1, 1, 1)] * 2, [(1, 1, 1)] * 2)
+        net = VolumeNet("f32", D, 10, 8, 2, layers, w_host, b_host)
+        sizes.append(net.query_sizes(1).state_bytes_per_stream)
+        net.destroy()
+    # k_d slabs of c per layer: 3 * 10 * 8 * (8 + 4) values of 4 bytes
+    assert sizes[0] == sizes[1] == sizes[2] == 3 * 10 * 8 * (8 + 4) * 4
