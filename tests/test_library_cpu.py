@@ -203,3 +203,32 @@ def test_eager_rings_do_not_grow_with_the_sample_height():
     # announced + delta per level, state for conv levels; level 2 keeps one more row for the pool's window
     least = sum(4 * r * k * (3 if lv in (1, 2, 4, 5) else 2) for lv, (r, k) in enumerate(zip(row, cone))) - 4 * row[5] * cone[5]
     assert least <= a - oa <= 2 * least + 16 * 256
+
+
+def test_volume_net_description_and_sizes():
+    """idf_create_net_volume on the host: validation, output shape, and the state of k_d slabs per layer."""
+    from paper_1804_10727_amd.binding import VolumeNet
+    L = [dict(c_in=2, c_out=4, k=(3, 3, 3), s=(1, 1, 1), p=(1, 1, 1), act="relu"),
+         dict(c_in=4, c_out=6, k=(2, 3, 3), s=(1, 2, 2), p=(0, 1, 1), act="relu")]
+    w = [np.zeros((4, 2, 3, 3, 3), np.float32), np.zeros((6, 4, 2, 3, 3), np.float32)]
+    net = VolumeNet("f32", 9, 10, 8, 2, L, w)
+    sz = net.query_sizes(2)
+    # slabs 9 -> 9 -> 8; rows 10 -> 10 -> 5; columns 8 -> 8 -> 4, folded into the channels with c_out
+    assert (int(sz.out_h), sz.out_w, sz.out_c) == (8, 5, 4 * 6)
+    # k_d slabs of c per layer, 4 bytes a cell: 3 x (10 x 8 x 4) + 2 x (5 x 4 x 6)
+    assert sz.state_bytes_per_stream == (3 * 10 * 8 * 4 + 2 * 5 * 4 * 6) * 4
+    net.destroy()
+    with pytest.raises(idf.IdfError) as e:                  # channel chain
+        VolumeNet("f32", 9, 10, 8, 3, L, w)
+    assert e.value.code == binding.IDF_EINVAL
+    with pytest.raises(idf.IdfError) as e:                  # window wider than the volume along the column axis
+        VolumeNet("f32", 9, 10, 2, 2, [dict(L[0], p=(1, 1, 0))], w[:1])
+    assert e.value.code == binding.IDF_EINVAL
+    with pytest.raises(idf.IdfError) as e:                  # no slabs per sample given
+        VolumeNet("f32", 0, 10, 8, 2, L, w)
+    assert e.value.code == binding.IDF_EINVAL
+    with pytest.raises(idf.IdfError) as e:                  # too wide once the column axis is folded in
+        VolumeNet("f32", 9, 10, 4096, 2, [dict(L[0], k=(3, 3, 1), p=(1, 1, 0))], [np.zeros((4, 2, 3, 3, 1), np.float32)])
+    assert e.value.code == binding.IDF_EUNSUPPORTED
+    with pytest.raises(idf.IdfError):                       # missing weights
+        VolumeNet("f32", 9, 10, 8, 2, L, [w[0], None])
