@@ -28,7 +28,8 @@ def _volume_net(prec, rng, shape, chans, ks, ss, ps, bias=True):
         wshape = (chans[i + 1], chans[i]) + tuple(ks[i])
         if prec == "i8":
             w = rng.integers(-4, 5, size=wshape).astype(np.int8)
-            w_host.append(w); w_val.append(w.astype(np.int64)); b_host.append(None)
+            w_host.append(w); w_val.append(w.astype(np.int64))
+            b_host.append(rng.integers(-20, 21, size=chans[i + 1]).astype(np.int32) if bias else None)
         else:
             w = rng.normal(0, 1.0 / np.sqrt(chans[i] * np.prod(ks[i]) / 2), size=wshape).astype(np.float32)
             if prec == "bf16":
@@ -85,7 +86,7 @@ def test_volume_slab_by_slab_equals_conventional_network(prec, shape, chans, ks,
         for b in range(3):
             got[b].append(o[b, :cnt[b]])
     integer = prec == "i8"
-    biases = None if integer else [None if b is None else b.astype(np.float64) for b in b_host]
+    biases = [None if b is None else b.astype(np.int64 if integer else np.float64) for b in b_host]
     for b in range(3):
         g = np.concatenate(got[b]).reshape(Do, Ho, Wo, Co)
         xv = x_val[b].astype(np.int64 if integer else np.float64)
@@ -102,7 +103,7 @@ def test_volume_slab_by_slab_equals_conventional_network(prec, shape, chans, ks,
             assert rel_err(g, want) <= TOL["bf16_true"], (b, rel_err(g, want))
     # events are the non-zero values, layer by layer, as the scheme along the slab axis counts them
     if integer:
-        _, ost = V.stream3d_run(layers, x_val[0].astype(np.int64), w_val, None, seg=seg, integer=True)
+        _, ost = V.stream3d_run(layers, x_val[0].astype(np.int64), w_val, biases, seg=seg, integer=True)
         gst = st.get_stats(0)
         assert np.array_equal(gst["events_in"].astype(np.int64), ost["events_in"])
     st.close(); net.destroy()
