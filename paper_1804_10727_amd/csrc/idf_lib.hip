@@ -1379,13 +1379,15 @@ int idf_create_net_volume(const idf_volume_desc *d, const void *const *weights, 
         const int w_out = out_size(w_in, L.k_w, L.s_w, L.p_w);
         if (w_out < 1) return fail(IDF_EINVAL, "layer %d: window larger than its input", l);
         const int64_t ci_f = (int64_t)w_in * L.c_in, co_f = (int64_t)w_out * L.c_out;
-        if (ci_f > 4096 || co_f > 4096) return fail(IDF_EUNSUPPORTED, "layer %d: %lld x %lld folded channels", l, (long long)ci_f, (long long)co_f);
+        if (ci_f > 4096 || co_f > 4096 || ci_f * co_f * L.k_d * L.k_h > ((int64_t)1 << 26))
+            return fail(IDF_EUNSUPPORTED, "layer %d: %lld x %lld folded channels", l, (long long)ci_f, (long long)co_f);
         idf_layer &T = lt[l];
         T = idf_layer{};
         T.kind = IDF_CONV; T.c_in = (int)ci_f; T.c_out = (int)co_f;
         T.k_h = L.k_d; T.k_w = L.k_h; T.s_h = L.s_d; T.s_w = L.s_h; T.p_h = L.p_d; T.p_w = L.p_h;
         T.act = L.act; T.shr = L.shr; T.clamp_hi = L.clamp_hi;
-        wt[l].assign((size_t)co_f * ci_f * L.k_d * L.k_h * wb, 0);
+        try { wt[l].assign((size_t)co_f * ci_f * L.k_d * L.k_h * wb, 0); }
+        catch (const std::bad_alloc &) { return fail(IDF_ENOMEM, "out of host memory"); }
         const unsigned char *src = (const unsigned char *)weights[l];
         for (int wo = 0; wo < w_out; ++wo)
             for (int kw = 0; kw < L.k_w; ++kw) {
