@@ -211,7 +211,7 @@ def cpu_baseline(wl, budget_s=12.0):
                       f"scalar event-by-event fp64/int64, one stream per thread, {dt:.1f} s"}
 
 
-def run_workload(config, steps_arg=None, warmup_arg=None, eager=False, push_batch=1, event_path=0):
+def run_workload(config, steps_arg=None, warmup_arg=None, eager=False, push_batch=1, event_path=0, rows_per_push=None):
     """Times `steps` whole batches of one workload; returns (result dict, workload)."""
     import numpy as np
     import torch
@@ -223,6 +223,8 @@ def run_workload(config, steps_arg=None, warmup_arg=None, eager=False, push_batc
     dev = "cuda:0"
     wl = workloads.make(config)
     B, H, W, C0, seg = wl["streams"], wl["in_h"], wl["in_w"], wl["in_c"], wl["seg_rows"]
+    if rows_per_push:           # 2-D workloads with more rows per push than the configuration states (throughput mode)
+        seg = rows_per_push
     n_seg = (H + seg - 1) // seg
     assert H % seg == 0
     steps = steps_arg if steps_arg is not None else {1: 5, 2: 10, 3: 50, 4: 10, 5: 5}[config]
@@ -398,6 +400,9 @@ def main():
     ap.add_argument("--eager", action="store_true", help="eager emission (configs 3 and 4): output valid after every push")
     ap.add_argument("--push-batch", type=int, default=1,
                     help="1-D workloads: hold back up to this many pushes in step per launch (throughput mode; 1 = a launch per push)")
+    ap.add_argument("--rows-per-push", type=int, default=None,
+                    help="2-D workloads: push this many rows per call instead of the configuration's one (throughput mode: "
+                         "nets served by the matrix-core kernel then go through the layers two rows per launch)")
     ap.add_argument("--event-path", type=int, default=0,
                     help="int8 workloads: tiles with at most this many events per K-step take the event-list path (0 = off, the library's default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -428,7 +433,8 @@ def main():
 
     import torch
     assert torch.cuda.is_available(), "bench.py needs the GPU"
-    res, wl = run_workload(args.config, args.steps, args.warmup, eager=args.eager, push_batch=args.push_batch, event_path=args.event_path)
+    res, wl = run_workload(args.config, args.steps, args.warmup, eager=args.eager, push_batch=args.push_batch, event_path=args.event_path,
+                           rows_per_push=args.rows_per_push)
     if args.eager:
         print(json.dumps(res))
         return
@@ -446,9 +452,16 @@ def main():
             if c in (1, 2):     # the 1-D workloads also in throughput mode: up to 16 pushes in step per launch
                 t, _ = run_workload(c, None, 1, push_batch=16)
                 rec["throughput_mode_16_pushes_per_launch"] = {k: t[k] for k in ("value", "unit", "ms_per_step", "roofline")}
+            else:               # the 2-D workloads also with two rows per push: one launch per two rows
+                t, _ = run_workload(c, None, 1, rows_per_push=2)
+                rec["throughput_mode_2_rows_per_push"] = {k: t[k] for k in ("value", "unit", "ms_per_step", "roofline")}
             if not args.no_cpu_baseline:
                 rec["cpu_baseline"] = cpu_baseline(owl, budget_s=3.0)
             res["other_workloads"][o["config"]["workload"]] = rec
+    if args.others and args.config in (3, 4, 5) and not args.rows_per_push:
+        # the same workload pushed two rows per call (not the configuration's one): context, never `value`
+        t, _ = run_workload(args.config, None, 1, rows_per_push=2)
+        res["throughput_mode_2_rows_per_push"] = {k: t[k] for k in ("value", "unit", "ms_per_step", "roofline")}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(res))

@@ -211,6 +211,12 @@ int idf_open_streams_static(idf_net *net, int n_streams, int max_seg_rows, int64
  * idf_get_stats, idf_reset_streams, idf_close_streams and idf_profile_end first enqueue whatever
  * is still on its way, so what they return is always the result of every pushed row having gone
  * through every layer it can influence.  The last segment's dev_rows is read by the push itself.
+ * For 2-D nets served throughout by the matrix-core kernel a push of all streams in step is one
+ * launch per row -- or, when the push brings several rows (streams opened with max_seg_rows >= 2),
+ * one launch per two rows: a layer that finds two rows waiting takes both in one step and keeps
+ * the rows of c between them on chip instead of writing them to its rolling buffer and reading
+ * them back; values and counters are those of a launch per row, bit for bit (environment
+ * IDF_NO_ROW_PAIRS=1 switches it off).
  * IDF_EINVAL: bad id, duplicate id, n_rows out of range.  IDF_ESTATE: the rows would run past row
  * in_h-1 of the current sample, or the completed output rows would not fit the output area
  * (read first). */

@@ -221,7 +221,8 @@ enum { kEmitNone = 0,      // row not final: back to the rolling buffer
        kEmitDirect,        // final: activate and emit
        kEmitHold,          // final, even row of a pool pair: becomes the pool's held row
        kEmitPoolHeld,      // final, odd row of a pool pair: max with the held row, emit pooled row
-       kEmitPoolReg };     // final, odd row whose even partner became final in the same launch
+       kEmitPoolReg,       // final, odd row whose even partner became final in the same launch
+       kEmitKeep };        // not final, and the step's second input row follows at once: stays in the accumulators
 enum { kMfmaTile64x64 = 0, kMfmaTile128x32, kMfmaTile32x64, kMfmaTile32x32, kMfmaTile64x32 };
 
 struct MfmaTap {
@@ -244,6 +245,10 @@ struct MfmaStep {
     int skip_clear_tiles;              // tiles no given column reaches have nothing to do (no row starts or ends)
     int tile;                          // kMfmaTile*
     MfmaTap t[3];
+    int dbl;                           // the step takes a second input row straight after the first (batch launches only):
+    int taps_y2;                       //   its taps_y, its tap rows (rows y and y+1 arrive in the accumulators), its place
+    MfmaTap t2[3];
+    int64_t in_row_off2;
     const void *in;                    // input rows
     int64_t in_stream_stride, in_row_off;   // elements
     int in_by_position;

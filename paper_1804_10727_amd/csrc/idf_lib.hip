@@ -146,6 +146,8 @@ struct idf_streams {
     std::vector<int64_t> stg_seq;               // rows emitted by unit k so far
     int64_t stg_out_next = 0;                   // output slot of the next completed row
     int stg_tile = kMfmaTile64x64;              // tile shape of the staged launches
+    int stg_slots = 4;                          // rows of a hand-over ring (kStgSlots, twice that where a step may take two rows)
+    bool stg_pairs = false;                     // pushes of several rows go through the layers two rows per launch
     // eager emission: per stream and level (0 = input) rows of state, announced values and deltas in a
     // workspace of its own -- rings of the rows that can still change or be looked at (nets without
     // biases) or whole maps
@@ -289,7 +291,8 @@ int make_layout(const idf_net &net, int B, int max_seg, int64_t out_cap, Layout 
         const bool into_fused_pool = all_mfma && !getenv("IDF_NO_MFMA") && l + 1 < n && net.g[l + 1].kind == IDF_MAXPOOL;
         if (l < n - 1 && !L.cascade1d && !into_fused_pool) {
             // room for the hand-over ring when the layers are staged across pushes
-            const int rows = all_mfma ? std::max(cap, kStgSlots) : cap;
+            // (a step that takes two rows can complete three and reads two more meanwhile: twice the slots)
+            const int rows = all_mfma ? std::max(cap, max_seg >= 2 ? 2 * kStgSlots : kStgSlots) : cap;
             L.transit_stride[l] = (int64_t)rows * g.w_out * g.c_out;
             L.transit_off[l] = off; off = align_up(off + (size_t)L.transit_stride[l] * eb * B);
             transit_per_stream += (size_t)L.transit_stride[l] * eb;
@@ -776,7 +779,7 @@ void make_mfma_step(idf_streams *s, int l, int64_t y, int n_streams, MfmaStep &a
 // One launch for all streams: every conv layer that has a row waiting takes one step, layer 0 on
 // row j of the pushed segment (j < 0: no new row, the layers only move on).  What a step emits
 // waits for the next layer's step in a later launch.
-int stg_tick(idf_streams *s, const void *dev_rows, int n_rows, int j, int64_t r)
+int stg_tick(idf_streams *s, const void *dev_rows, int n_rows, int j, int64_t r, bool pairs = false)
 {
     const idf_net &net = *s->net;
     const int nu = (int)s->stg_unit.size();
@@ -788,38 +791,64 @@ int stg_tick(idf_streams *s, const void *dev_rows, int n_rows, int j, int64_t r)
     for (int k = nu - 1; k >= 0; --k) {         // deeper first: they take only rows that were there before
         const int l = s->stg_unit[k];
         const Geom &g = net.g[l];
-        int64_t y;
-        int slot = 0;
+        // the row the unit takes, and with pairs the one after it if that is there too (same sample)
+        int64_t y, y2 = -1;
+        int slot = 0, slot2 = 0;
         if (k == 0) {
             if (j < 0) continue;
             y = r + j;
+            if (pairs && j + 1 < n_rows) y2 = y + 1;
         } else {
-            if (s->stg_fifo[k].empty()) continue;
-            y = s->stg_fifo[k].front().y; slot = s->stg_fifo[k].front().slot;
-            s->stg_fifo[k].pop_front();
+            std::deque<idf_streams::StgRow> &f = s->stg_fifo[k];
+            if (f.empty()) continue;
+            y = f.front().y; slot = f.front().slot;
+            f.pop_front();
+            if (pairs && !f.empty() && f.front().y == y + 1) { y2 = y + 1; slot2 = f.front().slot; f.pop_front(); }
         }
         MfmaStep a;
-        int64_t rows_out[3];
+        int64_t rows_out[2][3];
         double bytes = 0;
-        make_mfma_step(s, l, y, s->B, a, rows_out, bytes);
+        make_mfma_step(s, l, y, s->B, a, rows_out[0], bytes);
+        const int lp = l - 1;                     // the layer whose rows this one reads: conv or fused pool before it
         if (k == 0) {
             a.in = dev_rows; a.in_stream_stride = (int64_t)n_rows * net.in_w * net.in_c; a.in_by_position = 1;
             a.in_row_off = (int64_t)j * g.w_in * g.c_in;
+            a.in_row_off2 = (int64_t)(j + 1) * g.w_in * g.c_in;
             if (s->part.on) { a.in_stream_stride = (int64_t)(s->part.x_hi - s->part.x_lo) * net.in_c; a.in_row_off = -(int64_t)s->part.x_lo * net.in_c; }
         } else {
-            const int lp = l - 1;                 // the layer whose rows this one reads: conv or fused pool before it
             a.in = s->ws + s->transit_off[lp]; a.in_stream_stride = s->transit_stride[lp]; a.in_by_position = 0;
             a.in_row_off = (int64_t)slot * g.w_in * g.c_in;
+            a.in_row_off2 = (int64_t)slot2 * g.w_in * g.c_in;
         }
-        for (int ky = 2; ky >= 0; --ky) {         // increasing row index
-            if (rows_out[ky] < 0) continue;
-            if (k == nu - 1) {
-                a.t[ky].dst_slot = s->stg_out_next;
-                s->stg_out_next = (s->stg_out_next + 1) % s->out_cap;
-            } else {
-                const int wslot = (int)(s->stg_seq[k]++ % kStgSlots);
-                a.t[ky].dst_slot = wslot;
-                s->stg_fifo[k + 1].push_back({rows_out[ky], wslot});
+        if (y2 >= 0) {
+            // The second row's step, folded into the first: rows y and y+1 of c stay in the accumulators in between,
+            // and a pool pair that the two rows complete between them keeps its even row in registers.
+            MfmaStep a2;
+            double bytes2 = 0;
+            make_mfma_step(s, l, y2, s->B, a2, rows_out[1], bytes2);
+            a.dbl = 1; a.taps_y2 = a2.taps_y;
+            for (int ky = 0; ky < 3; ++ky) a.t2[ky] = a2.t[ky];
+            for (int ky = 0; ky < 2; ++ky)
+                if (a.t[ky].valid && a.t[ky].emit == kEmitNone) a.t[ky].emit = kEmitKeep;
+            if (a.t[2].valid && a.t[2].emit == kEmitHold && a.t2[2].valid && a.t2[2].emit == kEmitPoolHeld) {
+                a.t[2].store_held = 0; a.t2[2].emit = kEmitPoolReg;
+            }
+            // what the pair has to move by the method: the two rows of c between the two input rows neither leave
+            // the chip nor come back (two rows written and two read fewer than two steps)
+            bytes += bytes2 - (double)s->B * 4.0 * g.w_out * g.c_out * 4.0;
+        }
+        for (int sub = 0; sub < (y2 >= 0 ? 2 : 1); ++sub) {
+            MfmaTap *t = sub ? a.t2 : a.t;
+            for (int ky = 2; ky >= 0; --ky) {     // increasing row index
+                if (rows_out[sub][ky] < 0) continue;
+                if (k == nu - 1) {
+                    t[ky].dst_slot = s->stg_out_next;
+                    s->stg_out_next = (s->stg_out_next + 1) % s->out_cap;
+                } else {
+                    const int wslot = (int)(s->stg_seq[k]++ % s->stg_slots);
+                    t[ky].dst_slot = wslot;
+                    s->stg_fifo[k + 1].push_back({rows_out[sub][ky], wslot});
+                }
             }
         }
         b.st[b.n++] = a;
@@ -870,11 +899,16 @@ int enqueue_cascade(idf_streams *s, const StreamSel &sel, const void *dev_rows, 
     if (s->stg2d) {
         if (sel.base == 0 && sel.pos0 == 0 && sel.n == s->B) {
             if (!stg_pending(s, 0)) s->stg_out_next = out_slot0;
-            for (int j = 0; j < n_rows; ++j) {
-                int rc = stg_tick(s, dev_rows, n_rows, j, r);
+            // A push of several rows goes through two rows per launch (every unit that finds two rows waiting takes both
+            // in one step); a push of one row, and the ticks that only move the layers on, take one.
+            const bool pairs = s->stg_pairs && !s->part.on && s->ev_per_step == 0;
+            for (int j = 0; j < n_rows;) {
+                const bool two = pairs && j + 1 < n_rows;
+                int rc = stg_tick(s, dev_rows, n_rows, j, r, two);
                 // the hand-over rings hold kStgSlots rows: never let more than kStgWait wait
                 while (rc == IDF_OK && stg_pending(s, kStgWait)) rc = stg_tick(s, nullptr, 0, -1, 0);
                 if (rc != IDF_OK) return rc;
+                j += two ? 2 : 1;
             }
             return IDF_OK;
         }
@@ -1554,6 +1588,8 @@ int open_on(idf_net *net, int n_streams, int max_seg_rows, int64_t out_cap_rows,
         for (int l : s->stg_unit) c_min = std::min(c_min, net->g[l].c_out);
         s->stg_tile = c_min > 32 ? kMfmaTile32x64 : kMfmaTile32x32;
         s->stg_seq.assign(s->stg_unit.size(), 0);
+        s->stg_slots = max_seg_rows >= 2 ? 2 * kStgSlots : kStgSlots;
+        s->stg_pairs = max_seg_rows >= 2 && !getenv("IDF_NO_ROW_PAIRS");
     }
     s->h.assign(n_streams, StreamHost{});
     s->stamp.assign(n_streams, 0);

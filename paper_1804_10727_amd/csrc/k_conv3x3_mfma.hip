@@ -152,7 +152,11 @@ constexpr int kEvCap = 256;                      // events (tile and halo) the e
 constexpr size_t event_lds_bytes(int mt, int nc, int c_in) { return (size_t)(2 * (mt + 4) + kEvCap + 3 * mt * nc + 3 * c_in * nc) * 4; }
 constexpr int kNzWords = (kMaxPos + 31) / 32 + 1;
 
-template <class T, int WM, int WN, bool COUNT, bool EV>
+// DBL: a step may take two consecutive input rows (MfmaStep::dbl): the second is worked on by the
+// same workgroup straight after the first, with the two rows of c that the first leaves unfinished
+// staying in the accumulators (they move up by one tap row) instead of going to the rolling buffer
+// and back -- every sum is formed in the same order as by two steps, so the values are the same.
+template <class T, int WM, int WN, bool COUNT, bool EV, bool DBL = false>
 __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &sel, const int bx, const int si)
 {
     using acc_t = typename T::acc_t; using st_t = typename T::st_t; using ev_t = typename T::ev_t;
@@ -203,7 +207,19 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
     const int co_c = co_ok ? co : C_out - 1;
     const bool small_c = C_in < VL;                // first layers: 1..4 input channels
     const int64_t in_idx = a.in_by_position ? (int64_t)(sel.pos0 + si) : (int64_t)stream;
-    const unsigned char *in_row = (const unsigned char *)a.in + (in_idx * a.in_stream_stride + a.in_row_off) * EB;
+    const unsigned char *in_base = (const unsigned char *)a.in + in_idx * a.in_stream_stride * EB;
+    acc_t acc[3];
+    ev_t hprev[16];                                   // activations of an even row of a pool pair whose partner follows in this launch
+#pragma unroll
+    for (int q = 0; q < 16; ++q) hprev[q] = 0;
+    const int n_sub = DBL ? (a.dbl ? 2 : 1) : 1;
+#pragma unroll
+    for (int sub = 0; sub < (DBL ? 2 : 1); ++sub) {           // two copies of the body: each is straight-line code for the compiler
+    if (sub >= n_sub) break;
+    const bool second = DBL && sub > 0;
+    auto tap = [&](int ky) -> const MfmaTap & { return second ? a.t2[ky] : a.t[ky]; };
+    const unsigned char *in_row = in_base + (second ? a.in_row_off2 : a.in_row_off) * EB;
+    if (second) lds_barrier();                     // the first row's stretch, bits and staged rows are done with
     for (int i = tid; i < chunks * kNzWords; i += NT) nz[i / kNzWords][i % kNzWords] = 0;
 
     // ---- (1) input row stretch [x0-1, x0+MT+1): first batch of 16-byte cells ------------------
@@ -249,17 +265,25 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
     st_t *ring = (st_t *)a.ring + (int64_t)stream * a.ring_stream_stride;
     // They are loaded straight into the accumulators (a row touched for the first time starts
     // from the bias there): the contraction then adds on top and the epilogue has nothing to add.
-    acc_t acc[3];
+    if (!second) {
 #pragma unroll
-    for (int ky = 0; ky < 3; ++ky) {
-        const st_t start = a.t[ky].valid ? bias_v : (st_t)0;
+        for (int ky = 0; ky < 3; ++ky) {
+            const st_t start = a.t[ky].valid ? bias_v : (st_t)0;
 #pragma unroll
-        for (int q = 0; q < 16; ++q) acc[ky][q] = start;
-        if (a.t[ky].valid && !a.t[ky].fresh) {
-            const st_t *rrow = ring + (int64_t)a.t[ky].ring_slot * W * C_out;
+            for (int q = 0; q < 16; ++q) acc[ky][q] = start;
+            if (a.t[ky].valid && !a.t[ky].fresh) {
+                const st_t *rrow = ring + (int64_t)a.t[ky].ring_slot * W * C_out;
 #pragma unroll
-            for (int q = 0; q < 16; ++q) acc[ky][q] = *at4(rrow, roff[q]);
+                for (int q = 0; q < 16; ++q) acc[ky][q] = *at4(rrow, roff[q]);
+            }
         }
+    } else {
+        // rows y and y+1 are in the accumulators already: one tap row up; row y+2 starts from the bias
+        acc[2] = acc[1];
+        acc[1] = acc[0];
+        const st_t start = a.t2[0].valid ? bias_v : (st_t)0;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) acc[0][q] = start;
     }
     ev_t *held = (ev_t *)a.held + (int64_t)stream * a.held_stream_stride;
 
@@ -349,7 +373,7 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
             for (int wv = 0; wv < WM * WN; ++wv) { e += red[0][wv]; t += red[1][wv]; }
             unsigned long long *dst = a.stats + ((int64_t)stream * a.n_layers + a.layer) * 2;
             if (e) atomicAdd(dst, e);
-            if (t) atomicAdd(dst + 1, t * (unsigned long long)(a.taps_y * C_out));
+            if (t) atomicAdd(dst + 1, t * (unsigned long long)((second ? a.taps_y2 : a.taps_y) * C_out));
         }
     }
 
@@ -606,12 +630,9 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
     };
     const int col = wn * 32 + (lane & 31);            // channel within the chunk
     const int prow = wm * 32 + row_lane;              // first of this lane's positions within the tile
-    ev_t hprev[16];                                   // activations of the even row finalised by tap 2
-#pragma unroll
-    for (int q = 0; q < 16; ++q) hprev[q] = 0;
     uint32_t heldv[16];                               // the pool's held row: one register each, nothing to pack
     {
-        const bool need = a.t[2].valid && a.t[2].emit == kEmitPoolHeld;   // only row y-1 can pair with the held row
+        const bool need = tap(2).valid && tap(2).emit == kEmitPoolHeld;   // only row y-1 can pair with the held row
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
             heldv[q] = 0;
@@ -621,8 +642,9 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
 #pragma unroll
     for (int kk = 0; kk < 3; ++kk) {
         const int ky = 2 - kk;                        // row y-1 first
-        const MfmaTap &t = a.t[ky];
+        const MfmaTap &t = tap(ky);
         if (!t.valid) continue;
+        if (DBL && t.emit == kEmitKeep) continue;     // stays in the accumulators for the second row
         st_t c[16];
 #pragma unroll
         for (int q = 0; q < 16; ++q) c[q] = acc[ky][q];
@@ -703,6 +725,7 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
                 flush((ev_t *)a.dst + (int64_t)stream * a.dst_stream_stride + t.dst_slot * Wp * C_out, Wp, x0 >> 1, MT / 2);
         }
     }
+    }   // rows of the step
 }
 
 template <class T, int WM, int WN, bool COUNT, bool EV>
@@ -723,10 +746,12 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) k_conv3x3_mfma(const MfmaStep
 // streams close in time, and every step is spread evenly.  (Stream by stream with the tiles inside was
 // measured 8 % slower on the VGG-style workload; one contiguous eighth of the order per XCD slower
 // still: the steps differ too much in length.)
-template <class T, int WM, int WN, bool COUNT, bool EV>
-__global__ void __launch_bounds__(64 * WM * WN, T::kOcc) k_conv3x3_mfma_batch(const MfmaBatch b, const StreamSel sel)
+// (the form that can take two rows per step keeps a pool's even row in registers across the second
+// row's contraction: compiled for two waves per SIMD)
+template <class T, int WM, int WN, bool COUNT, bool EV, bool DBL = false>
+__global__ void __launch_bounds__(64 * WM * WN, DBL ? 2 : T::kOcc) k_conv3x3_mfma_batch(const MfmaBatch b, const StreamSel sel)
 {
-    conv3x3_row<T, WM, WN, COUNT, EV>(b.st[blockIdx.z], sel, blockIdx.y, blockIdx.x);
+    conv3x3_row<T, WM, WN, COUNT, EV, DBL>(b.st[blockIdx.z], sel, blockIdx.y, blockIdx.x);
 }
 
 template <class T, int WM, int WN>
@@ -758,6 +783,16 @@ hipError_t launch_batch_shape(const MfmaBatch &b, const StreamSel &sel, const La
         if (any) {
             if (b.st[0].issued) return launch(k_conv3x3_mfma_batch<T, WM, WN, true, true>, grid, block, lds, lc, bb, sel);
             return launch(k_conv3x3_mfma_batch<T, WM, WN, false, true>, grid, block, lds, lc, bb, sel);
+        }
+    }
+    bool two_rows = false;                        // some step takes two input rows: the kernel that can
+    for (int k = 0; k < b.n; ++k) two_rows = two_rows || b.st[k].dbl;
+    if (two_rows) {
+        if constexpr (WM == 1) {                  // (the launches that pair rows use tiles of 32 positions only)
+            if (b.st[0].issued) return launch(k_conv3x3_mfma_batch<T, WM, WN, true, false, true>, grid, block, lds, lc, b, sel);
+            return launch(k_conv3x3_mfma_batch<T, WM, WN, false, false, true>, grid, block, lds, lc, b, sel);
+        } else {
+            return hipErrorInvalidValue;
         }
     }
     // the variant that adds up what it issues is a kernel of its own: the one that is timed carries none of it
