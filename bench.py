@@ -333,7 +333,8 @@ def run_workload(config, steps_arg=None, warmup_arg=None, eager=False, push_batc
     else:
         roof = {"bound": "hbm", "achieved": bytes_per_launch / avg_s / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = stored_traffic(WORKLOADS[config], dom["name"])
+    # (the counters were taken in the configuration's own mode: one push per launch, its rows per push)
+    roof["traffic"] = stored_traffic(WORKLOADS[config], dom["name"]) if push_batch == 1 and not rows_per_push and not eager else None
     roof.update({"kernel": dom["name"], "avg_launch_us": avg_s * 1e6, "launches_per_step": dom["launches"],
                  "algorithmic_bytes_per_launch": bytes_per_launch, "executed_flops_per_launch": flops_per_launch,
                  "kernel_time_share": dom["total_ms"] / sum(p["total_ms"] for p in prof),
