@@ -73,3 +73,50 @@ def test_two_rows_per_launch_equals_one(cfg, kw, seg):
     for b in range(wl["streams"]):                       # and the values are the conventional network's
         check_stream(wl, two[b][:H_o], b)
         check_stream(wl, two[b][H_o:], b)
+
+
+@pytest.mark.parametrize("cfg,kw", CASES[:3])
+def test_pairs_mixed_with_subsets_and_issued_counters(cfg, kw):
+    """Paired launches next to what interrupts them -- pushes of some streams only (a launch per layer) --
+    and the counters of issued multiply-adds, which the kernel that takes two rows must add up like the
+    one that takes one."""
+    import torch
+    import paper_1804_10727_amd as idf
+    from paper_1804_10727_amd.binding import input_tensor
+    wl = wl_mod.make(cfg, **kw)
+    B, H = wl["streams"], wl["in_h"]
+    x = input_tensor(wl, "cuda:0")
+    net = idf.net_from_workload(wl)
+
+    def run(seg, mixed):
+        st = idf.Streams(net, B, max_seg_rows=max(seg, 2))
+        st.count_issued_macs(True)
+        r, k = 0, 0
+        while r < H:
+            n = min(seg, H - r)
+            if mixed and k % 3 == 1 and B > 1:      # the same rows as two pushes of some streams each
+                ids_a, ids_b = list(range(0, B, 2)), list(range(1, B, 2))
+                st.push_segment(x[ids_a, r:r + n].contiguous(), stream_ids=ids_a)
+                st.push_segment(x[ids_b, r:r + n].contiguous(), stream_ids=ids_b)
+            else:
+                st.push_segment(x[:, r:r + n].contiguous())
+            r += n; k += 1
+        out, first, cnt = st.read_outputs(int(st.sizes.out_h))
+        torch.cuda.synchronize()
+        o = out.cpu().numpy()
+        res = [o[b, :cnt[b]].copy() for b in range(B)]
+        iss = [st.get_issued_macs(b) for b in range(B)]
+        stats = [st.get_stats(b) for b in range(B)]
+        st.close()
+        return res, iss, stats
+
+    one, iss_one, st_one = run(1, False)
+    two, iss_two, st_two = run(2, False)
+    for b in range(B):
+        assert np.array_equal(one[b], two[b])
+        assert np.array_equal(iss_one[b], iss_two[b])
+        assert np.array_equal(st_one[b]["macs"], st_two[b]["macs"])
+    mix, _, _ = run(2, True)
+    for b in range(B):
+        assert np.array_equal(one[b], mix[b]), b
+    net.destroy()
