@@ -271,6 +271,7 @@ struct MfmaBatch {
     int tile;                          // kMfmaTile* (not 128x32), the same for every step
     MfmaStep st[kMfmaBatchMax];
 };
+static_assert(sizeof(MfmaBatch) + sizeof(StreamSel) <= 4096, "a launch's arguments must fit the kernel-argument segment");
 
 struct CopyOut {
     const void *src;             // output area [stream][out_cap][row_elems]
