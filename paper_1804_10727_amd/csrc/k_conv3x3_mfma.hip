@@ -157,7 +157,8 @@ constexpr int kNzWords = (kMaxPos + 31) / 32 + 1;
 // staying in the accumulators (they move up by one tap row) instead of going to the rolling buffer
 // and back -- every sum is formed in the same order as by two steps, so the values are the same.
 template <class T, int WM, int WN, bool COUNT, bool EV, bool DBL = false>
-__device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &sel, const int bx, const int si)
+__device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &sel, const int bx, const int si,
+                                            const uint32_t a_at, const uint32_t sel_at)
 {
     using acc_t = typename T::acc_t; using st_t = typename T::st_t; using ev_t = typename T::ev_t;
     constexpr int VL = T::VL, EB = T::EB, KI = 2 * VL;
@@ -170,6 +171,25 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
     // Every argument the kernel uses is asked for here, in one batch of scalar loads with one
     // wait: left to first use, the loads end up behind conditions and cost one memory round
     // trip each, one after the other.
+    // Before that batch, one word of every 64-byte line of this step's arguments (they lie a_at
+    // bytes into the kernel-argument segment, the stream selection sel_at bytes) is asked for and
+    // never looked at: the compiler fetches some arguments again later rather than keep them in
+    // registers, and a launch's argument segment is new memory to every scalar cache -- with the
+    // lines all requested in the first round, those later fetches find them there instead of
+    // paying one miss after the other.  (The register the words land in stays reserved until the
+    // batch's own wait has passed: nothing else may be written to it while they are in flight.)
+    uint32_t line_touch;
+    {
+        typedef const __attribute__((address_space(4))) char *karg_ptr;
+        const karg_ptr ka = (karg_ptr)__builtin_amdgcn_kernarg_segment_ptr() + a_at;
+        const karg_ptr ks = (karg_ptr)__builtin_amdgcn_kernarg_segment_ptr() + sel_at;
+        static_assert(sizeof(MfmaStep) > 0x180 && sizeof(MfmaStep) <= 0x1c0, "one request per 64-byte line of a step's arguments");
+        asm volatile("s_load_dword %0, %1, 0x0\n\ts_load_dword %0, %1, 0x40\n\ts_load_dword %0, %1, 0x80\n\t"
+                     "s_load_dword %0, %1, 0xc0\n\ts_load_dword %0, %1, 0x100\n\ts_load_dword %0, %1, 0x140\n\t"
+                     "s_load_dword %0, %1, 0x180\n\ts_load_dword %0, %1, %3\n\ts_load_dword %0, %2, 0x0"
+                     : "=&s"(line_touch)
+                     : "s"(ka), "s"(ks), "n"(sizeof(MfmaStep) - 4));
+    }
     asm volatile("" ::"s"(a.w), "s"(a.c_in), "s"(a.c_out), "s"(a.c_out_pad), "s"(a.c_in_rcp), "s"(a.chunks_rcp), "s"(a.act), "s"(a.shr),
                  "s"(a.clamp_hi), "s"(a.x_lo), "s"(a.x_hi), "s"(a.skip_clear_tiles), "s"(a.layer), "s"(a.pool_layer), "s"(a.n_layers), "s"(a.taps_y), "s"(a.in_by_position),
                  "s"(a.to_output), "s"(a.in), "s"(a.in_stream_stride), "s"(a.in_row_off), "s"(a.ring),
@@ -179,6 +199,7 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
                  "s"(a.t[0].dst_slot), "s"(a.t[1].valid), "s"(a.t[1].fresh), "s"(a.t[1].emit), "s"(a.t[1].store_held),
                  "s"(a.t[1].ring_slot), "s"(a.t[1].dst_slot), "s"(a.t[2].valid), "s"(a.t[2].fresh), "s"(a.t[2].emit),
                  "s"(a.t[2].store_held), "s"(a.t[2].ring_slot), "s"(a.t[2].dst_slot), "s"(sel.n), "s"(sel.base), "s"(sel.pos0));
+    asm volatile("" ::"s"(line_touch));
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WM, wn = wave / WM;
     const int stream = sel_stream(sel, si);
@@ -731,7 +752,8 @@ __device__ __forceinline__ void conv3x3_row(const MfmaStep &a, const StreamSel &
 template <class T, int WM, int WN, bool COUNT, bool EV>
 __global__ void __launch_bounds__(64 * WM * WN, 2) k_conv3x3_mfma(const MfmaStep a, const StreamSel sel)
 {
-    conv3x3_row<T, WM, WN, COUNT, EV>(a, sel, blockIdx.z, blockIdx.x);      // tile by tile, the streams of a tile side by side
+    // tile by tile, the streams of a tile side by side
+    conv3x3_row<T, WM, WN, COUNT, EV>(a, sel, blockIdx.z, blockIdx.x, 0, (uint32_t)sizeof(MfmaStep));
 }
 
 // Several layers' steps in one launch (each on a row that was complete before the launch).  The grid
@@ -751,7 +773,8 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) k_conv3x3_mfma(const MfmaStep
 template <class T, int WM, int WN, bool COUNT, bool EV, bool DBL = false>
 __global__ void __launch_bounds__(64 * WM * WN, DBL ? 2 : T::kOcc) k_conv3x3_mfma_batch(const MfmaBatch b, const StreamSel sel)
 {
-    conv3x3_row<T, WM, WN, COUNT, EV, DBL>(b.st[blockIdx.z], sel, blockIdx.y, blockIdx.x);
+    conv3x3_row<T, WM, WN, COUNT, EV, DBL>(b.st[blockIdx.z], sel, blockIdx.y, blockIdx.x,
+                                           (uint32_t)(offsetof(MfmaBatch, st) + blockIdx.z * sizeof(MfmaStep)), (uint32_t)sizeof(MfmaBatch));
 }
 
 template <class T, int WM, int WN>
