@@ -398,6 +398,24 @@ typedef struct {
 int idf_profile_begin(idf_streams *s);
 int idf_profile_end(idf_streams *s, int max_kinds, idf_kernel_profile *out, int *n_kinds);
 
+/* What this machine delivers to a plain kernel, to be quoted next to the published peaks that
+ * the rooflines are priced against (for benchmarks and reports; nothing on the streaming path
+ * calls it, and the paper names no hardware).  kind selects the kernel:
+ *   IDF_PEAK_COPY       copies the first half of dev_buf to the second half in 16-byte pieces;
+ *                       *rate = bytes read + written per second, in GB/s.  Use a buffer well
+ *                       beyond the last-level cache (1 GiB or more) to see the memory itself.
+ *   IDF_PEAK_FMA_F32    independent chains of float32 multiply-adds on the vector units;
+ *   IDF_PEAK_MFMA_F32 / _BF16 / _I8   independent chains of the 32x32x2 float32, 32x32x16
+ *                       bfloat16 and 32x32x32 int8 matrix instructions, on every compute unit;
+ *                       *rate = operations per second (multiply and add counted separately), in
+ *                       tera-operations/s.
+ * dev_buf: device memory of at least 1 MiB (written); hip_stream: the hipStream_t to run on.
+ * The call launches the kernel once untimed and three times timed by HIP events stamped at the
+ * kernel's own start and end, synchronises the stream and reports the fastest of the three.
+ * Errors: IDF_EINVAL (null pointer, unknown kind, buffer too small), IDF_EDEVICE. */
+enum { IDF_PEAK_COPY = 0, IDF_PEAK_FMA_F32 = 1, IDF_PEAK_MFMA_F32 = 2, IDF_PEAK_MFMA_BF16 = 3, IDF_PEAK_MFMA_I8 = 4 };
+int idf_measure_peak(int kind, void *dev_buf, size_t bytes, void *hip_stream, double *rate);
+
 const char *idf_last_error(void);
 
 #ifdef __cplusplus

@@ -5,4 +5,4 @@ marshalling only -- every step of the method runs in the library's HIP kernels.
 PyTorch is used for device memory and streams.
 """
 from .binding import (IdfError, Net, Streams, create_net, lib_path, load_library,  # noqa: F401
-                      net_from_workload, open_streams)
+                      measure_peak, net_from_workload, open_streams)

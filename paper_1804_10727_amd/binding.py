@@ -17,7 +17,7 @@ ACT = {"none": 0, "relu": 1, "relu_shr_clamp": 2}
 EXPORTS = ["idf_create_net", "idf_create_net_columnwise", "idf_destroy_net", "idf_query_sizes", "idf_open_streams", "idf_open_streams_static", "idf_close_streams",
            "idf_push_segment", "idf_set_push_batching", "idf_read_outputs", "idf_reset_streams", "idf_get_stats", "idf_count_issued_macs", "idf_get_issued_macs", "idf_set_event_path", "idf_rows_pushed",
            "idf_layer_kernel", "idf_last_error", "idf_profile_begin", "idf_profile_end", "idf_enable_head",
-           "idf_read_head", "idf_query_head_units_bytes", "idf_enable_head_units", "idf_read_head_units", "idf_push_pixels", "idf_query_eager_bytes", "idf_enable_eager", "idf_read_announced", "idf_read_announced_rows", "idf_eager_state_bytes", "idf_snapshot_bytes", "idf_snapshot", "idf_restore", "idf_create_net_volume"]
+           "idf_read_head", "idf_query_head_units_bytes", "idf_enable_head_units", "idf_read_head_units", "idf_push_pixels", "idf_query_eager_bytes", "idf_enable_eager", "idf_read_announced", "idf_read_announced_rows", "idf_eager_state_bytes", "idf_snapshot_bytes", "idf_snapshot", "idf_restore", "idf_create_net_volume", "idf_measure_peak"]
 
 
 class IdfError(RuntimeError):
@@ -116,10 +116,23 @@ def load_library():
     L.idf_snapshot.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
     L.idf_restore.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
     L.idf_read_head.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+    L.idf_measure_peak.argtypes = [C.c_int, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_double)]
     L.idf_profile_begin.argtypes = [C.c_void_p]
     L.idf_profile_end.argtypes = [C.c_void_p, C.c_int, C.POINTER(KernelProfile), C.POINTER(C.c_int)]
     _LIB = L
     return L
+
+
+PEAK_KINDS = {"copy": 0, "fma_f32": 1, "mfma_f32": 2, "mfma_bf16": 3, "mfma_i8": 4}
+
+
+def measure_peak(kind, buf):
+    """idf_measure_peak on a torch uint8 device tensor: GB/s for "copy", tera-operations/s otherwise."""
+    import torch
+    rate = C.c_double()
+    _check(load_library().idf_measure_peak(PEAK_KINDS[kind], C.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(),
+                                           C.c_void_p(torch.cuda.current_stream(buf.device).cuda_stream), C.byref(rate)))
+    return rate.value
 
 
 def _check(rc):

@@ -77,6 +77,13 @@ int conv3x3_mfma_batch_resident(int prec, int tile);
 hipError_t launch_conv3x3_mfma(int prec, const MfmaStep &a, const StreamSel &sel, const LaunchCtx &lc);
 hipError_t launch_conv3x3_mfma_batch(int prec, const MfmaBatch &b, const StreamSel &sel, const LaunchCtx &lc);
 
+// Plain kernels that show what the machine delivers (copy, multiply-add chains, matrix-instruction
+// chains): bytes the compute kinds write for a launch of `blocks` workgroups, operations such a
+// launch performs, and the launch itself (copy: first half of buf to the second half).
+size_t peak_sink_bytes(int blocks);
+double peak_ops(int kind, int blocks, int iters);
+hipError_t launch_peak(int kind, void *buf, size_t bytes, int blocks, int iters, const LaunchCtx &lc);
+
 // Largest number of touched output rows one generic conv step can take for a layer with
 // c_out output channels (the host splits longer steps).
 int conv_generic_max_rows(int c_out);

@@ -2163,6 +2163,45 @@ int idf_read_head(idf_streams *s, const int32_t *stream_ids, int n_ids, double *
     return IDF_OK;
 }
 
+int idf_measure_peak(int kind, void *dev_buf, size_t bytes, void *hip_stream, double *rate)
+{
+    if (!dev_buf || !rate) return fail(IDF_EINVAL, "null argument");
+    if (kind < IDF_PEAK_COPY || kind > IDF_PEAK_MFMA_I8) return fail(IDF_EINVAL, "unknown kind %d", kind);
+    int dev = 0, cus = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess || cus < 1) return dev_fail(e, "measure_peak: device query");
+    const bool copy = kind == IDF_PEAK_COPY;
+    const int blocks = copy ? cus * 8 : cus * 2;             // two workgroups of four waves per compute unit: two waves per SIMD
+    const int iters = 2048;
+    if (bytes < ((size_t)1 << 20) || bytes < peak_sink_bytes(blocks))
+        return fail(IDF_EINVAL, "measure_peak: the buffer holds %zu bytes, at least %zu are needed", bytes,
+                    std::max<size_t>((size_t)1 << 20, peak_sink_bytes(blocks)));
+    hipStream_t st = (hipStream_t)hip_stream;
+    LaunchCtx lc;
+    lc.st = st;
+    e = launch_peak(kind, dev_buf, bytes, blocks, iters, lc);     // untimed: code and clocks warm
+    hipEvent_t a = nullptr, b = nullptr;
+    if (e == hipSuccess) e = hipEventCreate(&a);
+    if (e == hipSuccess) e = hipEventCreate(&b);
+    float best = 0.f;
+    for (int rep = 0; rep < 3 && e == hipSuccess; ++rep) {
+        lc.start = a; lc.stop = b;
+        e = launch_peak(kind, dev_buf, bytes, blocks, iters, lc);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
+        if (e == hipSuccess && (best == 0.f || ms < best)) best = ms;
+    }
+    if (a) (void)hipEventDestroy(a);
+    if (b) (void)hipEventDestroy(b);
+    if (e != hipSuccess) return dev_fail(e, "measure_peak");
+    if (best <= 0.f) return fail(IDF_EDEVICE, "measure_peak: no time was measured");
+    const double work = copy ? 2.0 * (double)(bytes / 32 * 16) : peak_ops(kind, blocks, iters);
+    *rate = work / ((double)best * 1e-3) / (copy ? 1e9 : 1e12);
+    return IDF_OK;
+}
+
 int idf_profile_begin(idf_streams *s)
 {
     if (!s) return fail(IDF_EINVAL, "null argument");
