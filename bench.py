@@ -463,6 +463,11 @@ def main():
         # the same workload pushed two rows per call (not the configuration's one): context, never `value`
         t, _ = run_workload(args.config, None, 1, rows_per_push=2)
         res["throughput_mode_2_rows_per_push"] = {k: t[k] for k in ("value", "unit", "ms_per_step", "roofline")}
+    if args.others:
+        # what this GPU gives plain copy / multiply-add / matrix-instruction kernels, next to the published
+        # peaks the rooflines are priced against (idf_measure_peak; about a second)
+        from paper_1804_10727_amd import peaks
+        res["machine"] = {k: {kk: (round(vv, 4) if isinstance(vv, float) else vv) for kk, vv in v.items()} for k, v in peaks.measure().items()}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(res))
